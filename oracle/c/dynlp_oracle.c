@@ -1,0 +1,207 @@
+/*
+ * CPU oracle for DynLP in plain C, float64.  TEST INFRASTRUCTURE ONLY: it exists so that
+ * tests, the smoke check and the benchmark's cpu_baseline leg can evaluate the definitions on
+ * graphs that are too large for the Python loops.  It shares no code with the GPU library.
+ *
+ * What each function states:
+ *   oracle_itlp_sweep    one Jacobi sweep of Eq. (1): every unlabelled row with d(u) > 0 becomes
+ *                        (1/d(u)) sum_v w(u,v) F_v, read from F_in, written to F_out; seed rows
+ *                        and isolated rows are copied.
+ *   oracle_itlp_solve    repeat the sweep until max_u max_c |F_new - F| <= tol (ItLP).
+ *   oracle_affected_set  V_aff after Step 1 of Alg. 2 for an insertion batch.
+ *   oracle_step3         Step 3 of Alg. 2 in synchronous rounds over V_aff.
+ *
+ * Graph: CSR over n vertices, row_ptr (int64, n+1), col (int32), w (double).  Parallel edges
+ * may appear as separate entries (everything is linear in w).  seed_class[u] >= 0 marks a
+ * vertex of V^L and gives its class; -1 marks V^U.  F is n x C row-major.
+ * The loops over rows are independent (Jacobi), so the OpenMP pragma changes no result.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void oracle_set_num_threads(int t) {
+#ifdef _OPENMP
+    if (t > 0) omp_set_num_threads(t);
+#else
+    (void)t;
+#endif
+}
+
+/* F_out[u,:] for one unlabelled row with at least one edge: the weighted mean of Eq. (1). */
+static void weighted_mean_row(const int64_t* row_ptr, const int32_t* col, const double* w, int C,
+                              const double* F, int64_t u, double* out) {
+    double d = 0.0;
+    for (int c = 0; c < C; ++c) out[c] = 0.0;
+    for (int64_t j = row_ptr[u]; j < row_ptr[u + 1]; ++j) {
+        const double* Fv = F + (int64_t)col[j] * C;
+        d += w[j];
+        for (int c = 0; c < C; ++c) out[c] += w[j] * Fv[c];
+    }
+    for (int c = 0; c < C; ++c) out[c] /= d;
+}
+
+double oracle_itlp_sweep(int64_t n, const int64_t* row_ptr, const int32_t* col, const double* w, int C,
+                         const int32_t* seed_class, const double* F_in, double* F_out) {
+    double change = 0.0;
+#pragma omp parallel for schedule(dynamic, 1024) reduction(max : change)
+    for (int64_t u = 0; u < n; ++u) {
+        double* out = F_out + u * C;
+        const double* old = F_in + u * C;
+        if (seed_class[u] >= 0 || row_ptr[u + 1] == row_ptr[u]) {
+            for (int c = 0; c < C; ++c) out[c] = old[c];
+            continue;
+        }
+        weighted_mean_row(row_ptr, col, w, C, F_in, u, out);
+        for (int c = 0; c < C; ++c) {
+            double r = fabs(out[c] - old[c]);
+            if (r > change) change = r;
+        }
+    }
+    return change;
+}
+
+/* F is read and overwritten with the result; tmp is caller-provided scratch of n*C doubles. */
+int64_t oracle_itlp_solve(int64_t n, const int64_t* row_ptr, const int32_t* col, const double* w, int C,
+                          const int32_t* seed_class, double* F, double* tmp, double tol, int64_t max_iter,
+                          double* last_change) {
+    double* a = F;
+    double* b = tmp;
+    int64_t it = 0;
+    double change = INFINITY;
+    while (it < max_iter) {
+        change = oracle_itlp_sweep(n, row_ptr, col, w, C, seed_class, a, b);
+        double* t = a;
+        a = b;
+        b = t;
+        ++it;
+        if (change <= tol) break;
+    }
+    if (a != F) memcpy(F, a, (size_t)n * C * sizeof(double));
+    if (last_change) *last_change = change;
+    return it;
+}
+
+/*
+ * V_aff for an insertion batch applied to a graph that now has n vertices (CSR already
+ * updated): inserted vertices n_old..n-1 and their neighbours, both endpoints of every new
+ * edge, and the neighbours of every vertex that has just become a seed; minus seeds and
+ * isolated vertices.  flag is n bytes of scratch.  Writes ascending ids to out (capacity n);
+ * returns the count.
+ */
+int64_t oracle_affected_set(int64_t n, const int64_t* row_ptr, const int32_t* col, const int32_t* seed_class,
+                            int64_t n_old, int64_t m, const int32_t* eu, const int32_t* ev, int64_t s,
+                            const int32_t* new_seed_vertex, uint8_t* flag, int32_t* out) {
+    memset(flag, 0, (size_t)n);
+    for (int64_t u = n_old; u < n; ++u) {
+        flag[u] = 1;
+        for (int64_t j = row_ptr[u]; j < row_ptr[u + 1]; ++j) flag[col[j]] = 1;
+    }
+    for (int64_t e = 0; e < m; ++e) {
+        flag[eu[e]] = 1;
+        flag[ev[e]] = 1;
+    }
+    for (int64_t i = 0; i < s; ++i) {
+        int64_t u = new_seed_vertex[i];
+        for (int64_t j = row_ptr[u]; j < row_ptr[u + 1]; ++j) flag[col[j]] = 1;
+    }
+    int64_t cnt = 0;
+    for (int64_t u = 0; u < n; ++u)
+        if (flag[u] && seed_class[u] < 0 && row_ptr[u + 1] > row_ptr[u]) out[cnt++] = (int32_t)u;
+    return cnt;
+}
+
+/*
+ * Alg. 2 Step 3.  Round t: for every u in V_aff compute F'_u (weighted mean of the round-start
+ * F), commit all of them, then V_aff <- union over {u : change(u) > tol} of {u} U N(u), minus
+ * seeds and isolated vertices.  change(u) = max_c |F'_u[c] - F_u[c]|; with decide_fp32 the two
+ * rows are rounded to binary32 and the subtraction and comparison are done in binary32 (the
+ * precision in which the GPU kernel takes the same decision).  Stops when V_aff is empty or
+ * after max_iter rounds.  frontier_sizes / max_changes (capacity cap, may be NULL) receive the
+ * first cap rounds.  totals[0] = rows updated, totals[1] = CSR entries traversed.
+ * Returns the number of rounds; *remaining = |V_aff| at exit (0 if it emptied).
+ */
+int64_t oracle_step3(int64_t n, const int64_t* row_ptr, const int32_t* col, const double* w, int C,
+                     const int32_t* seed_class, double* F, const int32_t* frontier0, int64_t n0, double tol,
+                     int64_t max_iter, int decide_fp32, int64_t* frontier_sizes, double* max_changes,
+                     int64_t cap, int64_t* totals, int64_t* remaining) {
+    int32_t* A = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    uint8_t* flag = (uint8_t*)calloc((size_t)(n > 0 ? n : 1), 1);
+    uint8_t* big = (uint8_t*)malloc((size_t)(n > 0 ? n : 1));
+    double* stage = (double*)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * C);
+    int64_t na = n0;
+    memcpy(A, frontier0, sizeof(int32_t) * (size_t)n0);
+    int64_t rounds = 0, rows = 0, edges = 0;
+    const float tolf = (float)tol;
+    while (na > 0 && rounds < max_iter) {
+        double mx = 0.0;
+#pragma omp parallel for schedule(dynamic, 256) reduction(max : mx)
+        for (int64_t i = 0; i < na; ++i) {
+            int64_t u = A[i];
+            double* out = stage + i * C;
+            weighted_mean_row(row_ptr, col, w, C, F, u, out);
+            double r = 0.0;
+            if (decide_fp32) {
+                float rf = 0.0f;
+                for (int c = 0; c < C; ++c) {
+                    float df = fabsf((float)out[c] - (float)F[u * C + c]);
+                    if (df > rf) rf = df;
+                }
+                big[i] = rf > tolf;
+                r = rf;
+            } else {
+                for (int c = 0; c < C; ++c) {
+                    double dd = fabs(out[c] - F[u * C + c]);
+                    if (dd > r) r = dd;
+                }
+                big[i] = r > tol;
+            }
+            if (r > mx) mx = r;
+        }
+        for (int64_t i = 0; i < na; ++i) {
+            int64_t u = A[i];
+            memcpy(F + u * C, stage + i * C, sizeof(double) * C);
+            rows += 1;
+            edges += row_ptr[u + 1] - row_ptr[u];
+            if (big[i]) {
+                flag[u] = 1;
+                for (int64_t j = row_ptr[u]; j < row_ptr[u + 1]; ++j) flag[col[j]] = 1;
+            }
+        }
+        if (rounds < cap) {
+            if (frontier_sizes) frontier_sizes[rounds] = na;
+            if (max_changes) max_changes[rounds] = mx;
+        }
+        int64_t nn = 0;
+        for (int64_t u = 0; u < n; ++u) {
+            if (flag[u]) {
+                flag[u] = 0;
+                if (seed_class[u] < 0 && row_ptr[u + 1] > row_ptr[u]) A[nn++] = (int32_t)u;
+            }
+        }
+        na = nn;
+        ++rounds;
+    }
+    if (totals) {
+        totals[0] = rows;
+        totals[1] = edges;
+    }
+    if (remaining) *remaining = na;
+    free(A);
+    free(flag);
+    free(big);
+    free(stage);
+    return rounds;
+}

@@ -1,0 +1,120 @@
+"""ctypes access to the plain-C oracle (``c/dynlp_oracle.c``).  TEST INFRASTRUCTURE ONLY.
+
+``build()`` compiles the C file with gcc into ``oracle/_dynlp_oracle.so``; ``lib()`` loads it
+(building it first if it is absent).  The wrappers only marshal numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes as ct
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "c", "dynlp_oracle.c")
+_SO = os.path.join(_HERE, "_dynlp_oracle.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-std=c11", "-shared", "-fPIC", "-o", _SO, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _SO
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        L = ct.CDLL(_SO)
+        i64, f64, p = ct.c_int64, ct.c_double, ct.c_void_p
+        L.oracle_num_threads.restype = ct.c_int
+        L.oracle_set_num_threads.argtypes = [ct.c_int]
+        L.oracle_itlp_sweep.restype = f64
+        L.oracle_itlp_sweep.argtypes = [i64, p, p, p, ct.c_int, p, p, p]
+        L.oracle_itlp_solve.restype = i64
+        L.oracle_itlp_solve.argtypes = [i64, p, p, p, ct.c_int, p, p, p, f64, i64, p]
+        L.oracle_affected_set.restype = i64
+        L.oracle_affected_set.argtypes = [i64, p, p, p, i64, i64, p, p, i64, p, p, p]
+        L.oracle_step3.restype = i64
+        L.oracle_step3.argtypes = [i64, p, p, p, ct.c_int, p, p, p, i64, f64, i64, ct.c_int, p, p, i64, p, p]
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return a.ctypes.data_as(ct.c_void_p)
+
+
+def _csr(row_ptr, col, w):
+    return (np.ascontiguousarray(row_ptr, dtype=np.int64), np.ascontiguousarray(col, dtype=np.int32),
+            np.ascontiguousarray(w, dtype=np.float64))
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def set_num_threads(t: int) -> None:
+    lib().oracle_set_num_threads(int(t))
+
+
+def itlp_sweep(row_ptr, col, w, F, seed_class):
+    """One Jacobi sweep of Eq. (1).  Returns (F_new, max_change)."""
+    rp, cl, ww = _csr(row_ptr, col, w)
+    F = np.ascontiguousarray(F, dtype=np.float64)
+    sc = np.ascontiguousarray(seed_class, dtype=np.int32)
+    out = np.empty_like(F)
+    ch = lib().oracle_itlp_sweep(F.shape[0], _ptr(rp), _ptr(cl), _ptr(ww), F.shape[1], _ptr(sc), _ptr(F), _ptr(out))
+    return out, float(ch)
+
+
+def itlp_solve(row_ptr, col, w, seed_class, C, tol=1e-10, max_iter=1_000_000, F0=None):
+    """ItLP to convergence.  Returns (F, sweeps, last_change)."""
+    from .reference import initial_labels
+
+    rp, cl, ww = _csr(row_ptr, col, w)
+    sc = np.ascontiguousarray(seed_class, dtype=np.int32)
+    F = initial_labels(sc, C) if F0 is None else np.array(F0, dtype=np.float64, order="C")
+    tmp = np.empty_like(F)
+    last = ct.c_double(0.0)
+    it = lib().oracle_itlp_solve(F.shape[0], _ptr(rp), _ptr(cl), _ptr(ww), C, _ptr(sc), _ptr(F), _ptr(tmp),
+                                 float(tol), int(max_iter), ct.byref(last))
+    return F, int(it), float(last.value)
+
+
+def affected_set(row_ptr, col, seed_class, n_old, eu, ev, new_seed_vertex):
+    """V_aff of an insertion batch on the already-updated CSR; ascending int32 ids."""
+    rp = np.ascontiguousarray(row_ptr, dtype=np.int64)
+    cl = np.ascontiguousarray(col, dtype=np.int32)
+    sc = np.ascontiguousarray(seed_class, dtype=np.int32)
+    n = sc.shape[0]
+    eu = np.ascontiguousarray(eu, dtype=np.int32)
+    ev = np.ascontiguousarray(ev, dtype=np.int32)
+    sv = np.ascontiguousarray(new_seed_vertex, dtype=np.int32)
+    flag = np.empty(max(n, 1), dtype=np.uint8)
+    out = np.empty(max(n, 1), dtype=np.int32)
+    cnt = lib().oracle_affected_set(n, _ptr(rp), _ptr(cl), _ptr(sc), int(n_old), eu.shape[0], _ptr(eu), _ptr(ev),
+                                    sv.shape[0], _ptr(sv), _ptr(flag), _ptr(out))
+    return out[:cnt].copy()
+
+
+def step3_propagate(row_ptr, col, w, F, seed_class, V_aff, tol, max_iter, decide_fp32=True, record=4096):
+    """Alg. 2 Step 3.  Returns dict(F, rounds, frontier_sizes, max_changes, rows_updated,
+    edges_traversed, remaining)."""
+    rp, cl, ww = _csr(row_ptr, col, w)
+    F = np.array(F, dtype=np.float64, order="C")
+    sc = np.ascontiguousarray(seed_class, dtype=np.int32)
+    A0 = np.ascontiguousarray(V_aff, dtype=np.int32)
+    sizes = np.zeros(record, dtype=np.int64)
+    changes = np.zeros(record, dtype=np.float64)
+    totals = np.zeros(2, dtype=np.int64)
+    rem = ct.c_int64(0)
+    rounds = lib().oracle_step3(F.shape[0], _ptr(rp), _ptr(cl), _ptr(ww), F.shape[1], _ptr(sc), _ptr(F), _ptr(A0),
+                                A0.shape[0], float(tol), int(max_iter), int(bool(decide_fp32)), _ptr(sizes),
+                                _ptr(changes), record, _ptr(totals), ct.byref(rem))
+    k = min(int(rounds), record)
+    return dict(F=F, rounds=int(rounds), frontier_sizes=sizes[:k].copy(), max_changes=changes[:k].copy(),
+                rows_updated=int(totals[0]), edges_traversed=int(totals[1]), remaining=int(rem.value))
