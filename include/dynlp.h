@@ -1,0 +1,185 @@
+/*
+ * dynlp.h — C ABI of libdynlp: dynamic batched label propagation (DynLP) on one AMD MI355X.
+ *
+ * The library keeps, in device memory, a weighted undirected graph G=(V,E) in a mutable CSR
+ * with per-row slack, the set V^L of labelled (seed) vertices with their classes, and the
+ * n x C label matrix F (row u = class distribution of vertex u; the paper's binary scalar label
+ * is column 1 of the C=2 case).  It offers
+ *   - the static iterative label propagation ItLP (paper Eq. (1)) as the cold start, and
+ *   - the batch update of Alg. 2 ("DynLP Update"): insert the batch's vertices and edges
+ *     (Step 1), mark the affected set V_aff, and run the frontier-restricted propagation of
+ *     Step 3 until V_aff is empty.
+ * Every step runs in hand-written HIP kernels for gfx950; there is no CPU fallback: without a
+ * usable GPU every call that needs one returns DYNLP_ERR_DEVICE.
+ *
+ * Conventions
+ *   - All functions are thread-compatible: one context must not be used from two threads at
+ *     once; different contexts are independent.
+ *   - Pointer arguments are HOST pointers unless the context was created with
+ *     dynlp_options.ptrs_on_device = 1, in which case every array argument of every call
+ *     (inputs and outputs) is a DEVICE pointer on the context's device.  Scalars, the options
+ *     and the stats struct are always host memory.
+ *   - The caller owns every buffer it passes; the library copies what it needs and keeps no
+ *     caller pointer after a call returns.
+ *   - Work is enqueued on dynlp_options.stream (a hipStream_t; NULL = the default stream).  Each
+ *     call returns after that work has completed, so outputs are readable on return.
+ *   - No C++ exception crosses this boundary.  A failed call leaves the context as it was
+ *     before the call (arguments are validated before anything is changed), except for
+ *     DYNLP_ERR_OOM / DYNLP_ERR_DEVICE, after which the context may only be destroyed.
+ *   - Indices are int32 vertex ids; sizes are int64.  Weights and labels are IEEE binary32.
+ */
+#ifndef DYNLP_H
+#define DYNLP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DYNLP_MAX_CLASSES 64 /* largest num_classes the row-update kernel is laid out for */
+
+typedef struct dynlp_ctx dynlp_ctx; /* opaque; owns all device memory it allocates */
+
+typedef enum dynlp_status {
+    DYNLP_OK = 0,
+    DYNLP_NOT_CONVERGED = 1,    /* max_iter reached; labels are valid but not converged */
+    DYNLP_ERR_INVALID_ARG = -1, /* see dynlp_last_error for which argument and why */
+    DYNLP_ERR_OOM = -2,         /* device or host allocation failed */
+    DYNLP_ERR_DEVICE = -3,      /* no usable GPU, or a HIP call failed */
+    DYNLP_ERR_STATE = -4        /* call not allowed in the context's current state */
+} dynlp_status;
+
+/* Counters and timings of the last dynlp_static_solve / dynlp_apply_batch (host memory). */
+typedef struct dynlp_stats {
+    int32_t iterations;       /* propagation rounds executed */
+    int32_t converged;        /* 1 if the stop rule was met, 0 if max_iter cut it */
+    float final_max_delta;    /* max_u max_c |F'_u - F_u| of the last round */
+    int64_t rows_updated;     /* sum over rounds of |V_aff| */
+    int64_t edges_traversed;  /* sum over rounds and frontier rows of the row length */
+    int64_t frontier_initial; /* |V_aff| after Step 1 (static solve: number of updatable rows) */
+    int64_t frontier_peak;
+    int64_t rows_relocated;   /* rows moved to the pool tail because their slack ran out */
+    int64_t update_launches;  /* launches of the row-update kernel */
+    float ms_update_kernel;   /* summed device time of those launches (HIP events on the stream);
+                                 0 unless dynlp_options.time_kernels is set */
+    float ms_insert;          /* validation + edge insertion + degree update */
+    float ms_seed;            /* seed clamping + frontier seeding + first compaction */
+    float ms_iterate;         /* the propagation loop */
+    float ms_total;           /* whole call, host wall clock */
+} dynlp_stats;
+
+typedef struct dynlp_options {
+    int32_t device;          /* HIP device ordinal */
+    void* stream;            /* hipStream_t to enqueue on; NULL = default stream */
+    int32_t ptrs_on_device;  /* 0: array arguments are host pointers; 1: device pointers */
+    float slack_factor;      /* row capacity = max(ceil(len*slack_factor), len+4), rounded up to 8
+                                entries; <= 1 selects the default 1.25 */
+    int64_t reserve_vertices; /* room for this many vertices beyond n before arrays regrow */
+    int64_t reserve_edges;    /* room for this many extra undirected edges at the pool tail */
+    int32_t time_kernels;    /* 1: bracket every row-update launch with HIP events */
+    int32_t group_lanes;     /* lanes cooperating on one frontier row: 0 = choose from the mean
+                                row length, else 4, 8, 16, 32 or 64 (tuning knob) */
+    /* Optional allocator for device memory (e.g. a caching allocator); all three NULL selects
+       hipMalloc/hipFree.  alloc returns NULL on failure. */
+    void* (*alloc)(size_t bytes, void* user);
+    void (*dealloc)(void* ptr, void* user);
+    void* alloc_user;
+} dynlp_options;
+
+/* Fill *opt with the defaults (device 0, default stream, host pointers). */
+void dynlp_default_options(dynlp_options* opt);
+
+/*
+ * Build a context from a weighted undirected graph, a seed set and a class count
+ * (the inputs of Alg. 2: G_t, F^L; problem statement in "Preliminaries").
+ *   n            number of vertices (>= 0)
+ *   row_ptr      n+1 ascending offsets, row_ptr[0] = 0           (CSR, both directions of every
+ *   col, w       row_ptr[n] neighbour ids and positive weights    edge present: the graph is
+ *                                                                undirected; not verified)
+ *   num_classes  C, 1 <= C <= DYNLP_MAX_CLASSES
+ *   seed_vertex, seed_class   num_seeds labelled vertices and their classes in [0, C)
+ *   opt          NULL = defaults
+ * Seed rows of F start one-hot, all other rows uniform 1/C.  The CSR is copied into the slack
+ * layout; the caller's arrays are not referenced afterwards.
+ * DYNLP_ERR_INVALID_ARG on: NULL required pointer, n < 0, n > 2^31-2, C out of range,
+ * non-monotone row_ptr, neighbour id outside [0,n), self loop, weight not finite or <= 0,
+ * seed vertex / class out of range, the same vertex listed with two different classes.
+ * On failure *out is NULL and dynlp_last_error(NULL) describes the problem.
+ */
+dynlp_status dynlp_create(dynlp_ctx** out, int64_t n, const int64_t* row_ptr, const int32_t* col, const float* w,
+                          int32_t num_classes, int64_t num_seeds, const int32_t* seed_vertex,
+                          const int32_t* seed_class, const dynlp_options* opt);
+
+/*
+ * Static ItLP (Eq. (1)): Jacobi sweeps over all unlabelled rows with d(u) > 0, starting from the
+ * current F, until max_u max_c |F^(k+1) - F^(k)| <= tol or max_iter sweeps.  Also stores tol and
+ * max_iter for later dynlp_apply_batch calls.  tol >= 0, max_iter >= 0.  stats may be NULL.
+ */
+dynlp_status dynlp_static_solve(dynlp_ctx* ctx, float tol, int32_t max_iter, dynlp_stats* stats);
+
+/* Set the threshold delta and the round cap used by dynlp_apply_batch (defaults 1e-4, 100000). */
+dynlp_status dynlp_set_params(dynlp_ctx* ctx, float tol, int32_t max_iter);
+
+/*
+ * DynLP update for one insertion batch (Alg. 2 Steps 1 and 3).
+ *   num_new_vertices   they receive ids n .. n+k-1 in order; rows start uniform 1/C
+ *   eu, ev, ew         num_new_edges undirected edges, each listed once, endpoints in [0, n+k),
+ *                      eu != ev, weight finite and > 0; an edge that already exists is legal
+ *                      and adds its weight (parallel edge)
+ *   seed_vertex/class  num_new_seeds vertices (old or new) that are labelled from now on
+ * Step 1: both directions of every edge are appended to their rows (rows whose slack is
+ * exhausted move to the pool tail with fresh slack); degrees are updated; new seeds are clamped
+ * one-hot; V_aff = inserted vertices, endpoints of inserted edges and neighbours of new seeds,
+ * without seeds and isolated vertices.  Step 3: rounds of F'_u = sum_v w(u,v) F_v / d(u) for
+ * u in V_aff from the round-start F; every F'_u is stored; u with max_c |F'_u - F_u| > tol
+ * puts itself and N(u) into the next V_aff; stops when V_aff is empty (DYNLP_OK) or after
+ * max_iter rounds (DYNLP_NOT_CONVERGED).
+ * DYNLP_ERR_INVALID_ARG (context unchanged) on: negative counts, NULL array with a positive
+ * count, endpoint out of range, self loop, bad weight, seed vertex/class out of range, a vertex
+ * given two different classes, relabelling an existing seed with another class.
+ */
+dynlp_status dynlp_apply_batch(dynlp_ctx* ctx, int64_t num_new_vertices, int64_t num_new_edges, const int32_t* eu,
+                               const int32_t* ev, const float* ew, int64_t num_new_seeds,
+                               const int32_t* seed_vertex, const int32_t* seed_class, dynlp_stats* stats);
+
+/*
+ * Current labels.  soft: n*C floats row-major (no padding), or NULL.  hard: n int32 =
+ * argmax_c F[u][c] with the lowest class index winning ties (for C=2 the paper's 0.5 cut-off), or
+ * NULL.  Seed rows are exactly one-hot.
+ */
+dynlp_status dynlp_get_labels(dynlp_ctx* ctx, float* soft, int32_t* hard);
+
+/* Current number of vertices / directed CSR entries (2x the undirected edge count); -1 on NULL. */
+int64_t dynlp_num_vertices(const dynlp_ctx* ctx);
+int64_t dynlp_num_entries(const dynlp_ctx* ctx);
+int32_t dynlp_num_classes(const dynlp_ctx* ctx);
+
+/*
+ * Copy the graph out as a compact CSR (inspection and tests): row_ptr n+1 offsets, col/w
+ * dynlp_num_entries() entries in stored order (within a row: creation order, then insertion
+ * order, which for edges of one batch is unspecified); degree: n floats d(u) as maintained by the
+ * insertion step, or NULL; seed_class: n int32, -1 for unlabelled, or NULL.
+ */
+dynlp_status dynlp_export_graph(dynlp_ctx* ctx, int64_t* row_ptr, int32_t* col, float* w, float* degree,
+                                int32_t* seed_class);
+
+/*
+ * Per-round log of the last solve / batch: frontier size and max change of round i, for the first
+ * min(rounds, cap) rounds (HOST pointers regardless of ptrs_on_device; either may be NULL).
+ * Returns the number of rounds the last call executed.
+ */
+int64_t dynlp_round_log(const dynlp_ctx* ctx, int64_t cap, int64_t* frontier_size, float* max_delta);
+
+/* Message for the last failed call on ctx (or, with ctx NULL, the last failed dynlp_create on this
+ * thread).  Valid until the next call on the same context / thread.  Never NULL. */
+const char* dynlp_last_error(const dynlp_ctx* ctx);
+
+/* Release the context and all device memory it owns.  NULL is allowed. */
+void dynlp_destroy(dynlp_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DYNLP_H */

@@ -1,0 +1,1017 @@
+// libdynlp: host side of the DynLP library (context, memory, launch sequencing, C ABI).
+// Every step of the path runs in the kernels of dynlp_kernels.h; there is no CPU fallback.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "dynlp.h"
+#include "dynlp_kernels.h"
+
+using namespace dynlp;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
+
+int padded_classes(int C) {
+    if (C <= 1) return 1;
+    if (C <= 2) return 2;
+    if (C <= 4) return 4;
+    if (C <= 8) return 8;
+    if (C <= 16) return 16;
+    if (C <= 32) return 32;
+    return 64;
+}
+
+const char* validation_message(int code) {
+    switch (code) {
+        case kErrRowPtr: return "row_ptr must start at 0, be non-decreasing and end at the entry count (row index %lld)";
+        case kErrColRange: return "neighbour id out of range (entry %lld)";
+        case kErrSelfLoop: return "self loop (item %lld)";
+        case kErrWeight: return "weight must be finite and > 0 (item %lld)";
+        case kErrSeedVertex: return "seed vertex out of range (seed %lld)";
+        case kErrSeedClass: return "seed class out of range (seed %lld)";
+        case kErrSeedConflict: return "one vertex listed with two different classes (seed %lld)";
+        case kErrEndpoint: return "edge endpoint out of range (edge %lld)";
+        case kErrRelabel: return "vertex is already a seed of another class (seed %lld)";
+        default: return "validation error %lld";
+    }
+}
+
+using Clock = std::chrono::steady_clock;
+inline float ms_since(Clock::time_point t0) {
+    return std::chrono::duration<float, std::milli>(Clock::now() - t0).count();
+}
+
+}  // namespace
+
+struct dynlp_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    bool dev_ptrs = false;
+    float slack = 1.25f;
+    bool time_kernels = false;
+    int group_lanes = 0;
+    void* (*alloc_fn)(size_t, void*) = nullptr;
+    void (*dealloc_fn)(void*, void*) = nullptr;
+    void* alloc_user = nullptr;
+    int num_cu = 256;
+
+    int C = 0, CP = 0;
+    int64_t n = 0, n_cap = 0, flag_cap = 0;
+    int64_t entries = 0;  // directed CSR entries stored
+    RowMeta* meta = nullptr;
+    Edge* pool = nullptr;
+    int64_t pool_cap = 0, pool_tail = 0;
+    float* F = nullptr;   // current labels, n_cap x CP
+    float* F2 = nullptr;  // second buffer: ping-pong partner (static) / staging by queue position (dynamic)
+    int32_t* seed_class = nullptr;
+    uint8_t* flag = nullptr;
+    int32_t* queue[2] = {nullptr, nullptr};
+    int32_t* add_cnt = nullptr;
+    float* deg = nullptr;
+
+    int32_t* touched = nullptr;
+    int64_t* reloc_off = nullptr;
+    int64_t touched_cap = 0;
+    int32_t *b_eu = nullptr, *b_ev = nullptr, *b_sv = nullptr, *b_sc = nullptr;
+    float* b_ew = nullptr;
+    int64_t b_edge_cap = 0, b_seed_cap = 0;
+
+    RoundCtr* ring = nullptr;  // kRing slots
+    BatchCtr* bc = nullptr;
+    RoundCtr* h_slot = nullptr;  // pinned
+    BatchCtr* h_bc = nullptr;    // pinned
+
+    float tol = 1e-4f;
+    int32_t max_iter = 100000;
+    std::vector<int64_t> log_sizes;
+    std::vector<float> log_delta;
+    std::vector<hipEvent_t> events;
+    size_t events_used = 0;
+    hipEvent_t phase_ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    std::string err;
+    bool poisoned = false;
+};
+
+namespace {
+
+struct Fail {
+    dynlp_status st;
+};
+
+#define HIPCHK(ctx, expr)                                                                              \
+    do {                                                                                               \
+        hipError_t _e = (expr);                                                                        \
+        if (_e != hipSuccess) {                                                                        \
+            (ctx)->err = std::string("HIP error: ") + hipGetErrorString(_e) + " in " #expr;            \
+            (ctx)->poisoned = true;                                                                    \
+            throw Fail{_e == hipErrorOutOfMemory ? DYNLP_ERR_OOM : DYNLP_ERR_DEVICE};                   \
+        }                                                                                              \
+    } while (0)
+
+void* dev_alloc(dynlp_ctx* c, size_t bytes) {
+    if (bytes == 0) bytes = 256;
+    void* p = nullptr;
+    if (c->alloc_fn) {
+        p = c->alloc_fn(bytes, c->alloc_user);
+    } else if (hipMalloc(&p, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        p = nullptr;
+    }
+    if (!p) {
+        c->err = "device allocation of " + std::to_string(bytes) + " bytes failed";
+        c->poisoned = true;
+        throw Fail{DYNLP_ERR_OOM};
+    }
+    return p;
+}
+
+void dev_free(dynlp_ctx* c, void* p) {
+    if (!p) return;
+    if (c->dealloc_fn) c->dealloc_fn(p, c->alloc_user);
+    else (void)hipFree(p);
+}
+
+template <typename T>
+T* dev_alloc_n(dynlp_ctx* c, int64_t count) {
+    return static_cast<T*>(dev_alloc(c, (size_t)std::max<int64_t>(count, 1) * sizeof(T)));
+}
+
+inline unsigned int grid_for(int64_t items) { return (unsigned int)std::max<int64_t>(1, ceil_div(items, kBlock)); }
+
+// A device array argument: either the caller's device pointer, or a temporary device copy of the
+// caller's host array (freed by the destructor).
+template <typename T>
+struct DevIn {
+    dynlp_ctx* c;
+    const T* ptr = nullptr;
+    T* owned = nullptr;
+    DevIn(dynlp_ctx* ctx, const T* src, int64_t count) : c(ctx) {
+        if (count <= 0 || !src) return;
+        if (c->dev_ptrs) {
+            ptr = src;
+        } else {
+            owned = dev_alloc_n<T>(c, count);
+            HIPCHK(c, hipMemcpyAsync(owned, src, (size_t)count * sizeof(T), hipMemcpyHostToDevice, c->stream));
+            ptr = owned;
+        }
+    }
+    ~DevIn() {
+        if (owned) {
+            (void)hipStreamSynchronize(c->stream);
+            dev_free(c, owned);
+        }
+    }
+};
+
+void read_bc(dynlp_ctx* c) {
+    HIPCHK(c, hipMemcpyAsync(c->h_bc, c->bc, sizeof(BatchCtr), hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+}
+
+void write_bc(dynlp_ctx* c) {
+    HIPCHK(c, hipMemcpyAsync(c->bc, c->h_bc, sizeof(BatchCtr), hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+}
+
+std::string format_validation(int code, long long index) {
+    char buf[256];
+    std::snprintf(buf, sizeof buf, validation_message(code), index);
+    return buf;
+}
+
+// ---- vertex-indexed arrays --------------------------------------------------------------------
+void alloc_vertex_arrays(dynlp_ctx* c, int64_t new_cap) {
+    const int64_t old_n = c->n;
+    const int64_t flag_cap = round_up(new_cap, kFlagsPerBlock) + kFlagsPerBlock;
+    RowMeta* meta = dev_alloc_n<RowMeta>(c, new_cap);
+    float* F = dev_alloc_n<float>(c, new_cap * c->CP);
+    float* F2 = dev_alloc_n<float>(c, new_cap * c->CP);
+    int32_t* sc = dev_alloc_n<int32_t>(c, new_cap);
+    uint8_t* flag = dev_alloc_n<uint8_t>(c, flag_cap);
+    int32_t* q0 = dev_alloc_n<int32_t>(c, new_cap);
+    int32_t* q1 = dev_alloc_n<int32_t>(c, new_cap);
+    int32_t* add = dev_alloc_n<int32_t>(c, new_cap);
+    float* deg = dev_alloc_n<float>(c, new_cap);
+    HIPCHK(c, hipMemsetAsync(flag, 0, (size_t)flag_cap, c->stream));
+    HIPCHK(c, hipMemsetAsync(add, 0, (size_t)new_cap * sizeof(int32_t), c->stream));
+    if (old_n > 0 && c->meta) {
+        HIPCHK(c, hipMemcpyAsync(meta, c->meta, (size_t)old_n * sizeof(RowMeta), hipMemcpyDeviceToDevice, c->stream));
+        HIPCHK(c, hipMemcpyAsync(F, c->F, (size_t)old_n * c->CP * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
+        HIPCHK(c, hipMemcpyAsync(sc, c->seed_class, (size_t)old_n * sizeof(int32_t), hipMemcpyDeviceToDevice, c->stream));
+        HIPCHK(c, hipMemcpyAsync(deg, c->deg, (size_t)old_n * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
+    }
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    dev_free(c, c->meta);
+    dev_free(c, c->F);
+    dev_free(c, c->F2);
+    dev_free(c, c->seed_class);
+    dev_free(c, c->flag);
+    dev_free(c, c->queue[0]);
+    dev_free(c, c->queue[1]);
+    dev_free(c, c->add_cnt);
+    dev_free(c, c->deg);
+    c->meta = meta;
+    c->F = F;
+    c->F2 = F2;
+    c->seed_class = sc;
+    c->flag = flag;
+    c->queue[0] = q0;
+    c->queue[1] = q1;
+    c->add_cnt = add;
+    c->deg = deg;
+    c->n_cap = new_cap;
+    c->flag_cap = flag_cap;
+}
+
+void grow_pool(dynlp_ctx* c, int64_t min_cap) {
+    int64_t new_cap = std::max<int64_t>(min_cap, c->pool_cap + c->pool_cap / 2);
+    new_cap = round_up(new_cap, kRowAlign);
+    Edge* p = dev_alloc_n<Edge>(c, new_cap);
+    if (c->pool && c->pool_tail > 0)
+        HIPCHK(c, hipMemcpyAsync(p, c->pool, (size_t)c->pool_tail * sizeof(Edge), hipMemcpyDeviceToDevice, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    dev_free(c, c->pool);
+    c->pool = p;
+    c->pool_cap = new_cap;
+}
+
+void ensure_batch_scratch(dynlp_ctx* c, int64_t m, int64_t s) {
+    const int64_t need_t = std::max<int64_t>(1, std::min<int64_t>(2 * m, c->n_cap));
+    if (need_t > c->touched_cap) {
+        dev_free(c, c->touched);
+        dev_free(c, c->reloc_off);
+        c->touched = nullptr;
+        c->reloc_off = nullptr;
+        const int64_t cap = need_t + need_t / 2;
+        c->touched = dev_alloc_n<int32_t>(c, cap);
+        c->reloc_off = dev_alloc_n<int64_t>(c, cap);
+        c->touched_cap = cap;
+    }
+    if (!c->dev_ptrs) {
+        if (m > c->b_edge_cap) {
+            dev_free(c, c->b_eu);
+            dev_free(c, c->b_ev);
+            dev_free(c, c->b_ew);
+            c->b_eu = c->b_ev = nullptr;
+            c->b_ew = nullptr;
+            const int64_t cap = m + m / 2;
+            c->b_eu = dev_alloc_n<int32_t>(c, cap);
+            c->b_ev = dev_alloc_n<int32_t>(c, cap);
+            c->b_ew = dev_alloc_n<float>(c, cap);
+            c->b_edge_cap = cap;
+        }
+        if (s > c->b_seed_cap) {
+            dev_free(c, c->b_sv);
+            dev_free(c, c->b_sc);
+            c->b_sv = c->b_sc = nullptr;
+            const int64_t cap = s + s / 2;
+            c->b_sv = dev_alloc_n<int32_t>(c, cap);
+            c->b_sc = dev_alloc_n<int32_t>(c, cap);
+            c->b_seed_cap = cap;
+        }
+    }
+}
+
+// ---- row-update launch ---------------------------------------------------------------------------
+int lanes_per_neighbour(int CP) { return CP >= 4 ? CP / 4 : 1; }
+
+int choose_group(const dynlp_ctx* c, double avg_len) {
+    const int lpn = lanes_per_neighbour(c->CP);
+    if (c->group_lanes) return std::max(c->group_lanes, lpn);
+    int slots = 1;
+    while (slots * 2 <= avg_len * 0.75 && slots * lpn < kWave) slots *= 2;
+    return std::max(4, std::min(kWave, slots * lpn));
+}
+
+template <int CP, int G, bool STATIC>
+void launch_update_inst(dynlp_ctx* c, const int32_t* queue, unsigned int nq, const float* F_in, float* F_out,
+                        float tol, RoundCtr* ctr, RoundCtr* ctr_zero) {
+    constexpr int GPB = kBlock / G;
+    const int64_t want = ceil_div(nq, GPB);
+    const unsigned int blocks = (unsigned int)std::max<int64_t>(1, std::min<int64_t>(want, (int64_t)c->num_cu * 8));
+    hipLaunchKernelGGL((k_row_update<CP, G, STATIC>), dim3(blocks), dim3(kBlock), 0, c->stream, queue, nq, c->meta,
+                       c->pool, F_in, F_out, c->flag, tol, ctr, ctr_zero);
+}
+
+template <int CP, bool STATIC>
+void launch_update_cp(dynlp_ctx* c, int G, const int32_t* queue, unsigned int nq, const float* F_in, float* F_out,
+                      float tol, RoundCtr* ctr, RoundCtr* ctr_zero) {
+    constexpr int LPN = CP >= 4 ? CP / 4 : 1;
+#define DYNLP_CASE(GV)                                                                            \
+    case GV:                                                                                      \
+        if constexpr (GV >= LPN) {                                                                \
+            launch_update_inst<CP, GV, STATIC>(c, queue, nq, F_in, F_out, tol, ctr, ctr_zero);    \
+            return;                                                                               \
+        }                                                                                         \
+        break;
+    switch (G) {
+        DYNLP_CASE(4)
+        DYNLP_CASE(8)
+        DYNLP_CASE(16)
+        DYNLP_CASE(32)
+        DYNLP_CASE(64)
+        default: break;
+    }
+#undef DYNLP_CASE
+    launch_update_inst<CP, 64, STATIC>(c, queue, nq, F_in, F_out, tol, ctr, ctr_zero);
+}
+
+template <bool STATIC>
+void launch_update(dynlp_ctx* c, int G, const int32_t* queue, unsigned int nq, const float* F_in, float* F_out,
+                   float tol, RoundCtr* ctr, RoundCtr* ctr_zero) {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (c->time_kernels) {
+        while (c->events.size() < c->events_used + 2) {
+            hipEvent_t e;
+            HIPCHK(c, hipEventCreate(&e));
+            c->events.push_back(e);
+        }
+        e0 = c->events[c->events_used++];
+        e1 = c->events[c->events_used++];
+        HIPCHK(c, hipEventRecord(e0, c->stream));
+    }
+    switch (c->CP) {
+        case 1: launch_update_cp<1, STATIC>(c, G, queue, nq, F_in, F_out, tol, ctr, ctr_zero); break;
+        case 2: launch_update_cp<2, STATIC>(c, G, queue, nq, F_in, F_out, tol, ctr, ctr_zero); break;
+        case 4: launch_update_cp<4, STATIC>(c, G, queue, nq, F_in, F_out, tol, ctr, ctr_zero); break;
+        case 8: launch_update_cp<8, STATIC>(c, G, queue, nq, F_in, F_out, tol, ctr, ctr_zero); break;
+        case 16: launch_update_cp<16, STATIC>(c, G, queue, nq, F_in, F_out, tol, ctr, ctr_zero); break;
+        case 32: launch_update_cp<32, STATIC>(c, G, queue, nq, F_in, F_out, tol, ctr, ctr_zero); break;
+        default: launch_update_cp<64, STATIC>(c, G, queue, nq, F_in, F_out, tol, ctr, ctr_zero); break;
+    }
+    HIPCHK(c, hipGetLastError());
+    if (c->time_kernels) HIPCHK(c, hipEventRecord(e1, c->stream));
+}
+
+float collect_kernel_ms(dynlp_ctx* c) {
+    float total = 0.f;
+    for (size_t i = 0; i + 1 < c->events_used; i += 2) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, c->events[i], c->events[i + 1]) == hipSuccess) total += ms;
+    }
+    c->events_used = 0;
+    return total;
+}
+
+// Compaction launch; commit_nq > 0 also commits the staged rows of queue_cur.
+void launch_commit_compact(dynlp_ctx* c, const int32_t* queue_cur, unsigned int commit_nq, int32_t* queue_next,
+                           unsigned int* next_count, int all_rows) {
+    unsigned int commit_blocks = 0;
+    if (commit_nq) {
+        const int64_t items = (int64_t)commit_nq * (c->CP >= 4 ? c->CP / 4 : c->CP);
+        commit_blocks = (unsigned int)std::min<int64_t>(ceil_div(items, kBlock), (int64_t)c->num_cu * 8);
+    }
+    const unsigned int compact_blocks = (unsigned int)ceil_div(std::max<int64_t>(c->n, 1), kFlagsPerBlock);
+    hipLaunchKernelGGL(k_commit_compact, dim3(commit_blocks + compact_blocks), dim3(kBlock), 0, c->stream, queue_cur,
+                       commit_nq, c->F2, c->F, c->CP, commit_blocks, (unsigned int)c->n, c->flag, c->seed_class,
+                       c->meta, queue_next, next_count, all_rows);
+    HIPCHK(c, hipGetLastError());
+}
+
+void zero_ring(dynlp_ctx* c) {
+    HIPCHK(c, hipMemsetAsync(c->ring, 0, sizeof(RoundCtr) * kRing, c->stream));
+}
+
+RoundCtr read_slot(dynlp_ctx* c, int t) {
+    HIPCHK(c, hipMemcpyAsync(c->h_slot, c->ring + (t % kRing), sizeof(RoundCtr), hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    return *c->h_slot;
+}
+
+void fill_stats_zero(dynlp_stats* s) {
+    if (s) std::memset(s, 0, sizeof *s);
+}
+
+// ---- host-side argument checks (host-pointer mode): errors without touching the device ----------
+bool host_check_seeds(std::string& err, int64_t s, int64_t n_total, int C, const int32_t* sv, const int32_t* sc) {
+    std::unordered_map<int32_t, int32_t> seen;
+    for (int64_t i = 0; i < s; ++i) {
+        if (sv[i] < 0 || sv[i] >= n_total) { err = format_validation(kErrSeedVertex, i); return false; }
+        if (sc[i] < 0 || sc[i] >= C) { err = format_validation(kErrSeedClass, i); return false; }
+        auto it = seen.find(sv[i]);
+        if (it != seen.end() && it->second != sc[i]) { err = format_validation(kErrSeedConflict, i); return false; }
+        seen[sv[i]] = sc[i];
+    }
+    return true;
+}
+
+bool host_check_csr(std::string& err, int64_t n, const int64_t* row_ptr, const int32_t* col, const float* w) {
+    if (row_ptr[0] != 0) { err = format_validation(kErrRowPtr, 0); return false; }
+    for (int64_t u = 0; u < n; ++u)
+        if (row_ptr[u + 1] < row_ptr[u]) { err = format_validation(kErrRowPtr, u); return false; }
+    for (int64_t u = 0; u < n; ++u) {
+        for (int64_t j = row_ptr[u]; j < row_ptr[u + 1]; ++j) {
+            if (col[j] < 0 || col[j] >= n) { err = format_validation(kErrColRange, j); return false; }
+            if (col[j] == u) { err = format_validation(kErrSelfLoop, j); return false; }
+            if (!(w[j] > 0.f) || !std::isfinite(w[j])) { err = format_validation(kErrWeight, j); return false; }
+        }
+    }
+    return true;
+}
+
+bool host_check_edges(std::string& err, int64_t m, int64_t n_total, const int32_t* eu, const int32_t* ev,
+                      const float* ew) {
+    for (int64_t i = 0; i < m; ++i) {
+        if (eu[i] < 0 || eu[i] >= n_total || ev[i] < 0 || ev[i] >= n_total) {
+            err = format_validation(kErrEndpoint, i);
+            return false;
+        }
+        if (eu[i] == ev[i]) { err = format_validation(kErrSelfLoop, i); return false; }
+        if (!(ew[i] > 0.f) || !std::isfinite(ew[i])) { err = format_validation(kErrWeight, i); return false; }
+    }
+    return true;
+}
+
+void destroy_ctx(dynlp_ctx* c) {
+    if (!c) return;
+    (void)hipSetDevice(c->device);
+    if (c->stream || c->meta) (void)hipStreamSynchronize(c->stream);
+    void* ptrs[] = {c->meta, c->pool, c->F, c->F2, c->seed_class, c->flag, c->queue[0], c->queue[1], c->add_cnt,
+                    c->deg, c->touched, c->reloc_off, c->b_eu, c->b_ev, c->b_ew, c->b_sv, c->b_sc};
+    for (void* p : ptrs) dev_free(c, p);
+    if (c->ring) (void)hipFree(c->ring);
+    if (c->bc) (void)hipFree(c->bc);
+    if (c->h_slot) (void)hipHostFree(c->h_slot);
+    if (c->h_bc) (void)hipHostFree(c->h_bc);
+    for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->phase_ev)
+        if (e) (void)hipEventDestroy(e);
+    delete c;
+}
+
+// Prefix offsets of per-row values already stored (caps in meta / lens in an array) need the
+// scanned block sums; this runs the middle step and returns the grand total.
+int64_t scan_block_sums(dynlp_ctx* c, int64_t nb, int64_t* sums) {
+    hipLaunchKernelGGL(k_scan_block_sums, dim3(1), dim3(kBlock), 0, c->stream, nb, sums, &c->bc->scan_total);
+    HIPCHK(c, hipGetLastError());
+    read_bc(c);
+    return (int64_t)c->h_bc->scan_total;
+}
+
+}  // namespace
+
+// =================================================================================================
+// C ABI
+// =================================================================================================
+extern "C" {
+
+void dynlp_default_options(dynlp_options* opt) {
+    if (!opt) return;
+    std::memset(opt, 0, sizeof *opt);
+    opt->slack_factor = 1.25f;
+}
+
+const char* dynlp_last_error(const dynlp_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+int64_t dynlp_num_vertices(const dynlp_ctx* ctx) { return ctx ? ctx->n : -1; }
+int64_t dynlp_num_entries(const dynlp_ctx* ctx) { return ctx ? ctx->entries : -1; }
+int32_t dynlp_num_classes(const dynlp_ctx* ctx) { return ctx ? ctx->C : -1; }
+
+void dynlp_destroy(dynlp_ctx* ctx) { destroy_ctx(ctx); }
+
+dynlp_status dynlp_create(dynlp_ctx** out, int64_t n, const int64_t* row_ptr, const int32_t* col, const float* w,
+                          int32_t num_classes, int64_t num_seeds, const int32_t* seed_vertex,
+                          const int32_t* seed_class, const dynlp_options* opt) {
+    if (out) *out = nullptr;
+    g_create_error.clear();
+    auto bad = [&](const std::string& msg) {
+        g_create_error = msg;
+        return DYNLP_ERR_INVALID_ARG;
+    };
+    if (!out) return bad("out is NULL");
+    if (n < 0 || n > 0x7ffffffeLL) return bad("n must be in [0, 2^31-2]");
+    if (num_classes < 1 || num_classes > DYNLP_MAX_CLASSES) return bad("num_classes must be in [1, DYNLP_MAX_CLASSES]");
+    if (!row_ptr) return bad("row_ptr is NULL");
+    if (num_seeds < 0) return bad("num_seeds is negative");
+    if (num_seeds > 0 && (!seed_vertex || !seed_class)) return bad("seed arrays are NULL");
+    dynlp_options o;
+    dynlp_default_options(&o);
+    if (opt) o = *opt;
+    if (!(o.slack_factor > 1.0f)) o.slack_factor = 1.25f;
+    if (o.slack_factor > 8.0f) return bad("slack_factor must be <= 8");
+    if (o.reserve_vertices < 0 || o.reserve_edges < 0) return bad("reserve counts must be >= 0");
+    if ((o.alloc == nullptr) != (o.dealloc == nullptr)) return bad("alloc and dealloc must be given together");
+    const int CP = padded_classes(num_classes);
+    if (o.group_lanes != 0) {
+        const int g = o.group_lanes;
+        if (!(g == 4 || g == 8 || g == 16 || g == 32 || g == 64) || g < lanes_per_neighbour(CP))
+            return bad("group_lanes must be 0 or one of 4, 8, 16, 32, 64 and at least padded_classes/4");
+    }
+    // Host-pointer mode: everything that can be checked without a GPU is checked first.
+    int64_t nnz = -1;
+    if (!o.ptrs_on_device) {
+        nnz = row_ptr[n];
+        if (nnz < 0) return bad(format_validation(kErrRowPtr, n));
+        if (nnz > 0 && (!col || !w)) return bad("col / w are NULL");
+        std::string e;
+        if (!host_check_csr(e, n, row_ptr, col, w)) return bad(e);
+        if (!host_check_seeds(e, num_seeds, n, num_classes, seed_vertex, seed_class)) return bad(e);
+    }
+
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0 || o.device < 0 || o.device >= ndev) {
+        (void)hipGetLastError();
+        g_create_error = "no usable GPU (hipGetDeviceCount found " + std::to_string(ndev) + " devices, device " +
+                         std::to_string(o.device) + " requested); libdynlp has no CPU path";
+        return DYNLP_ERR_DEVICE;
+    }
+    dynlp_ctx* c = new (std::nothrow) dynlp_ctx;
+    if (!c) {
+        g_create_error = "host allocation failed";
+        return DYNLP_ERR_OOM;
+    }
+    dynlp_status result = DYNLP_OK;
+    int64_t* block_sums = nullptr;
+    try {
+        c->device = o.device;
+        c->stream = static_cast<hipStream_t>(o.stream);
+        c->dev_ptrs = o.ptrs_on_device != 0;
+        c->slack = o.slack_factor;
+        c->time_kernels = o.time_kernels != 0;
+        c->group_lanes = o.group_lanes;
+        c->alloc_fn = o.alloc;
+        c->dealloc_fn = o.dealloc;
+        c->alloc_user = o.alloc_user;
+        c->C = num_classes;
+        c->CP = CP;
+        HIPCHK(c, hipSetDevice(c->device));
+        hipDeviceProp_t prop;
+        HIPCHK(c, hipGetDeviceProperties(&prop, c->device));
+        c->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->ring), sizeof(RoundCtr) * kRing));
+        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->bc), sizeof(BatchCtr)));
+        HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_slot), sizeof(RoundCtr), hipHostMallocDefault));
+        HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_bc), sizeof(BatchCtr), hipHostMallocDefault));
+        for (auto& e : c->phase_ev) HIPCHK(c, hipEventCreate(&e));
+        std::memset(c->h_bc, 0, sizeof(BatchCtr));
+        write_bc(c);
+        zero_ring(c);
+
+        if (c->dev_ptrs) {
+            HIPCHK(c, hipMemcpyAsync(&nnz, row_ptr + n, sizeof(int64_t), hipMemcpyDeviceToHost, c->stream));
+            HIPCHK(c, hipStreamSynchronize(c->stream));
+            if (nnz < 0) {
+                c->err = format_validation(kErrRowPtr, n);
+                throw Fail{DYNLP_ERR_INVALID_ARG};
+            }
+            if (nnz > 0 && (!col || !w)) {
+                c->err = "col / w are NULL";
+                throw Fail{DYNLP_ERR_INVALID_ARG};
+            }
+        }
+        const int64_t reserve_v = o.reserve_vertices > 0 ? o.reserve_vertices : std::max<int64_t>(1024, n / 8);
+        c->n = 0;  // nothing to preserve while the arrays are first allocated
+        alloc_vertex_arrays(c, n + reserve_v);
+        c->n = n;
+
+        DevIn<int64_t> d_rp(c, row_ptr, n + 1);
+        DevIn<int32_t> d_col(c, col, nnz);
+        DevIn<float> d_w(c, w, nnz);
+        DevIn<int32_t> d_sv(c, seed_vertex, num_seeds);
+        DevIn<int32_t> d_sc(c, seed_class, num_seeds);
+
+        // validate row_ptr and the seed list
+        if (n > 0)
+            hipLaunchKernelGGL(k_validate_row_ptr, dim3(grid_for(n)), dim3(kBlock), 0, c->stream, n, d_rp.ptr, nnz, c->bc);
+        if (num_seeds > 0) {
+            hipLaunchKernelGGL(k_validate_seeds, dim3(grid_for(num_seeds)), dim3(kBlock), 0, c->stream, num_seeds, n,
+                               (int64_t)0, c->C, d_sv.ptr, d_sc.ptr, c->seed_class, c->add_cnt, c->bc);
+            hipLaunchKernelGGL(k_clear_seed_tmp, dim3(grid_for(num_seeds)), dim3(kBlock), 0, c->stream, num_seeds, n,
+                               d_sv.ptr, c->add_cnt);
+        }
+        HIPCHK(c, hipGetLastError());
+        read_bc(c);
+        if (c->h_bc->err_code) {
+            c->err = format_validation(c->h_bc->err_code, c->h_bc->err_index);
+            throw Fail{DYNLP_ERR_INVALID_ARG};
+        }
+
+        // slack layout: capacities, offsets (scan), entries
+        const int64_t nb = grid_for(n);
+        block_sums = dev_alloc_n<int64_t>(c, nb);
+        int64_t tail = 0;
+        if (n > 0) {
+            hipLaunchKernelGGL(k_row_caps, dim3(nb), dim3(kBlock), 0, c->stream, n, d_rp.ptr, c->slack, c->meta, block_sums);
+            HIPCHK(c, hipGetLastError());
+            tail = scan_block_sums(c, nb, block_sums);
+            hipLaunchKernelGGL(k_row_offsets, dim3(nb), dim3(kBlock), 0, c->stream, n, c->meta, block_sums);
+            HIPCHK(c, hipGetLastError());
+        }
+        c->pool_tail = tail;
+        const int64_t extra = tail / 4 + 4 * o.reserve_edges + (1 << 16);
+        c->pool_cap = 0;
+        grow_pool(c, tail + extra);
+        c->h_bc->pool_tail = (unsigned long long)tail;
+        c->h_bc->err_code = 0;
+        write_bc(c);
+        if (nnz > 0) {
+            hipLaunchKernelGGL(k_scatter_entries, dim3(grid_for(nnz)), dim3(kBlock), 0, c->stream, nnz, n, d_rp.ptr,
+                               d_col.ptr, d_w.ptr, c->meta, c->pool, c->bc);
+            HIPCHK(c, hipGetLastError());
+        }
+        read_bc(c);
+        if (c->h_bc->err_code) {
+            c->err = format_validation(c->h_bc->err_code, c->h_bc->err_index);
+            throw Fail{DYNLP_ERR_INVALID_ARG};
+        }
+        c->entries = nnz;
+
+        // labels
+        hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(c->n_cap)), dim3(kBlock), 0, c->stream, (int64_t)0, c->n_cap,
+                           c->seed_class, -1);
+        if (num_seeds > 0)
+            hipLaunchKernelGGL(k_set_seed_class, dim3(grid_for(num_seeds)), dim3(kBlock), 0, c->stream, num_seeds,
+                               d_sv.ptr, d_sc.ptr, c->seed_class);
+        if (n > 0) {
+            hipLaunchKernelGGL(k_init_labels, dim3(grid_for(n * c->CP)), dim3(kBlock), 0, c->stream, (int64_t)0, n, c->C,
+                               c->CP, c->seed_class, c->F);
+            hipLaunchKernelGGL(k_row_degree, dim3(grid_for(n * 16)), dim3(kBlock), 0, c->stream, n, c->meta, c->pool,
+                               c->deg);
+        }
+        HIPCHK(c, hipGetLastError());
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+    } catch (const Fail& f) {
+        result = f.st;
+    } catch (const std::bad_alloc&) {
+        c->err = "host allocation failed";
+        result = DYNLP_ERR_OOM;
+    }
+    if (block_sums) dev_free(c, block_sums);
+    if (result != DYNLP_OK) {
+        g_create_error = c->err;
+        destroy_ctx(c);
+        return result;
+    }
+    *out = c;
+    return DYNLP_OK;
+}
+
+dynlp_status dynlp_set_params(dynlp_ctx* ctx, float tol, int32_t max_iter) {
+    if (!ctx) return DYNLP_ERR_INVALID_ARG;
+    if (!(tol >= 0.f) || !std::isfinite(tol) || max_iter < 0) {
+        ctx->err = "tol must be finite and >= 0, max_iter >= 0";
+        return DYNLP_ERR_INVALID_ARG;
+    }
+    ctx->tol = tol;
+    ctx->max_iter = max_iter;
+    return DYNLP_OK;
+}
+
+dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp_stats* stats) {
+    if (!c) return DYNLP_ERR_INVALID_ARG;
+    fill_stats_zero(stats);
+    if (c->poisoned) {
+        c->err = "context is unusable after an earlier device or memory error";
+        return DYNLP_ERR_STATE;
+    }
+    dynlp_status st = dynlp_set_params(c, tol, max_iter);
+    if (st != DYNLP_OK) return st;
+    const auto t0 = Clock::now();
+    try {
+        HIPCHK(c, hipSetDevice(c->device));
+        c->log_sizes.clear();
+        c->log_delta.clear();
+        c->events_used = 0;
+        // the partner buffer must agree on the rows no sweep writes (seeds, isolated vertices)
+        if (c->n > 0)
+            HIPCHK(c, hipMemcpyAsync(c->F2, c->F, (size_t)c->n * c->CP * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
+        zero_ring(c);
+        c->h_bc->init_count = 0;
+        HIPCHK(c, hipMemsetAsync(&c->bc->init_count, 0, sizeof(unsigned int), c->stream));
+        launch_commit_compact(c, nullptr, 0, c->queue[0], &c->bc->init_count, 1);
+        read_bc(c);
+        const unsigned int nq = c->h_bc->init_count;
+        int it = 0;
+        float last = 0.f;
+        bool converged = nq == 0;
+        int64_t edges = 0;
+        const int G = choose_group(c, c->n > 0 ? (double)c->entries / (double)std::max<int64_t>(1, nq) : 1.0);
+        const auto t_it = Clock::now();
+        while (!converged && it < max_iter) {
+            launch_update<true>(c, G, c->queue[0], nq, c->F, c->F2, tol, c->ring + (it % kRing),
+                                c->ring + ((it + 1) % kRing));
+            const RoundCtr r = read_slot(c, it);
+            std::swap(c->F, c->F2);
+            std::memcpy(&last, &r.resid_bits, sizeof(float));
+            edges += (int64_t)r.edges;
+            c->log_sizes.push_back(nq);
+            c->log_delta.push_back(last);
+            ++it;
+            if (last <= tol) converged = true;
+        }
+        if (stats) {
+            stats->iterations = it;
+            stats->converged = converged ? 1 : 0;
+            stats->final_max_delta = last;
+            stats->rows_updated = (int64_t)nq * it;
+            stats->edges_traversed = edges;
+            stats->frontier_initial = nq;
+            stats->frontier_peak = nq;
+            stats->update_launches = it;
+            stats->ms_iterate = ms_since(t_it);
+            stats->ms_update_kernel = c->time_kernels ? collect_kernel_ms(c) : 0.f;
+            stats->ms_total = ms_since(t0);
+        }
+        c->events_used = 0;
+        return converged ? DYNLP_OK : DYNLP_NOT_CONVERGED;
+    } catch (const Fail& f) {
+        return f.st;
+    } catch (const std::bad_alloc&) {
+        c->err = "host allocation failed";
+        return DYNLP_ERR_OOM;
+    }
+}
+
+dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t* eu, const int32_t* ev,
+                               const float* ew, int64_t s, const int32_t* sv, const int32_t* sc, dynlp_stats* stats) {
+    if (!c) return DYNLP_ERR_INVALID_ARG;
+    fill_stats_zero(stats);
+    if (c->poisoned) {
+        c->err = "context is unusable after an earlier device or memory error";
+        return DYNLP_ERR_STATE;
+    }
+    auto bad = [&](const std::string& msg) {
+        c->err = msg;
+        return DYNLP_ERR_INVALID_ARG;
+    };
+    if (k < 0 || m < 0 || s < 0) return bad("counts must be >= 0");
+    if (m > 0 && (!eu || !ev || !ew)) return bad("edge arrays are NULL");
+    if (s > 0 && (!sv || !sc)) return bad("seed arrays are NULL");
+    const int64_t n0 = c->n, n1 = c->n + k;
+    if (n1 > 0x7ffffffeLL) return bad("vertex count would exceed 2^31-2");
+    if (m > 0x3fffffffLL) return bad("too many edges in one batch");
+    if (!c->dev_ptrs) {
+        std::string e;
+        if (!host_check_edges(e, m, n1, eu, ev, ew)) return bad(e);
+        if (!host_check_seeds(e, s, n1, c->C, sv, sc)) return bad(e);
+    }
+    const auto t0 = Clock::now();
+    bool mutated = false;
+    try {
+        HIPCHK(c, hipSetDevice(c->device));
+        c->log_sizes.clear();
+        c->log_delta.clear();
+        c->events_used = 0;
+        // ---- capacity for new vertices; their rows start empty, unlabelled, uniform ----
+        if (n1 > c->n_cap) alloc_vertex_arrays(c, n1 + std::max<int64_t>(n1 / 2, 1024));
+        ensure_batch_scratch(c, m, s);
+        const int32_t *d_eu = eu, *d_ev = ev, *d_sv = sv, *d_sc = sc;
+        const float* d_ew = ew;
+        if (!c->dev_ptrs) {
+            if (m > 0) {
+                HIPCHK(c, hipMemcpyAsync(c->b_eu, eu, (size_t)m * 4, hipMemcpyHostToDevice, c->stream));
+                HIPCHK(c, hipMemcpyAsync(c->b_ev, ev, (size_t)m * 4, hipMemcpyHostToDevice, c->stream));
+                HIPCHK(c, hipMemcpyAsync(c->b_ew, ew, (size_t)m * 4, hipMemcpyHostToDevice, c->stream));
+            }
+            if (s > 0) {
+                HIPCHK(c, hipMemcpyAsync(c->b_sv, sv, (size_t)s * 4, hipMemcpyHostToDevice, c->stream));
+                HIPCHK(c, hipMemcpyAsync(c->b_sc, sc, (size_t)s * 4, hipMemcpyHostToDevice, c->stream));
+            }
+            d_eu = c->b_eu;
+            d_ev = c->b_ev;
+            d_ew = c->b_ew;
+            d_sv = c->b_sv;
+            d_sc = c->b_sc;
+        }
+        HIPCHK(c, hipEventRecord(c->phase_ev[0], c->stream));
+
+        // ---- validate, count entries per row, plan relocations: one read-back for all three ----
+        std::memset(c->h_bc, 0, sizeof(BatchCtr));
+        c->h_bc->pool_tail = (unsigned long long)c->pool_tail;
+        HIPCHK(c, hipMemcpyAsync(c->bc, c->h_bc, sizeof(BatchCtr), hipMemcpyHostToDevice, c->stream));
+        if (m > 0)
+            hipLaunchKernelGGL(k_validate_edges, dim3(grid_for(m)), dim3(kBlock), 0, c->stream, m, n1, d_eu, d_ev, d_ew, c->bc);
+        if (s > 0) {
+            hipLaunchKernelGGL(k_validate_seeds, dim3(grid_for(s)), dim3(kBlock), 0, c->stream, s, n1, n0, c->C, d_sv,
+                               d_sc, c->seed_class, c->add_cnt, c->bc);
+            hipLaunchKernelGGL(k_clear_seed_tmp, dim3(grid_for(s)), dim3(kBlock), 0, c->stream, s, n1, d_sv, c->add_cnt);
+        }
+        if (k > 0) {  // empty rows for the new ids (scratch state only until n is advanced)
+            hipLaunchKernelGGL(k_init_meta, dim3(grid_for(k)), dim3(kBlock), 0, c->stream, n0, n1, c->meta, c->deg);
+            hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(k)), dim3(kBlock), 0, c->stream, n0, n1, c->seed_class, -1);
+        }
+        if (m > 0)
+            hipLaunchKernelGGL(k_count_halfedges, dim3(grid_for(2 * m)), dim3(kBlock), 0, c->stream, m, n1, d_eu, d_ev,
+                               c->add_cnt, c->touched, c->bc);
+        HIPCHK(c, hipGetLastError());
+        read_bc(c);
+        unsigned int nt = c->h_bc->touched;
+        if (c->h_bc->err_code) {
+            if (nt) hipLaunchKernelGGL(k_clear_counts, dim3(grid_for(nt)), dim3(kBlock), 0, c->stream, nt, c->touched, c->add_cnt);
+            HIPCHK(c, hipStreamSynchronize(c->stream));
+            return bad(format_validation(c->h_bc->err_code, c->h_bc->err_index));
+        }
+        if (nt) {
+            hipLaunchKernelGGL(k_plan_sum, dim3(grid_for(nt)), dim3(kBlock), 0, c->stream, nt, c->touched, c->meta,
+                               c->add_cnt, c->slack, c->bc);
+            HIPCHK(c, hipGetLastError());
+            read_bc(c);
+            const int64_t need = (int64_t)c->h_bc->reloc_need;
+            if (c->pool_tail + need > c->pool_cap) grow_pool(c, c->pool_tail + need + need / 2);
+        }
+        // ---- from here on the graph changes ----
+        mutated = true;
+        if (k > 0)
+            hipLaunchKernelGGL(k_init_labels, dim3(grid_for(k * c->CP)), dim3(kBlock), 0, c->stream, n0, n1, c->C, c->CP,
+                               c->seed_class, c->F);
+        if (nt) {
+            hipLaunchKernelGGL(k_plan_reserve, dim3(grid_for(nt)), dim3(kBlock), 0, c->stream, nt, c->touched, c->meta,
+                               c->add_cnt, c->slack, c->reloc_off, c->bc);
+            hipLaunchKernelGGL(k_relocate, dim3(grid_for((int64_t)nt * 16)), dim3(kBlock), 0, c->stream, nt, c->touched,
+                               c->meta, c->add_cnt, c->slack, c->reloc_off, c->pool);
+            hipLaunchKernelGGL(k_write_halfedges, dim3(grid_for(2 * m)), dim3(kBlock), 0, c->stream, m, d_eu, d_ev, d_ew,
+                               c->meta, c->pool);
+            hipLaunchKernelGGL(k_finish_rows, dim3(grid_for((int64_t)nt * 16)), dim3(kBlock), 0, c->stream, nt, c->touched,
+                               c->meta, c->pool, c->add_cnt, c->deg, c->flag);
+            HIPCHK(c, hipGetLastError());
+        }
+        c->n = n1;
+        c->entries += 2 * m;
+        HIPCHK(c, hipEventRecord(c->phase_ev[1], c->stream));
+        // ---- seeds: clamp one-hot, their neighbours join V_aff; first compaction ----
+        if (s > 0)
+            hipLaunchKernelGGL(k_apply_seeds, dim3(grid_for(s * 16)), dim3(kBlock), 0, c->stream, s, d_sv, d_sc, c->C, c->CP,
+                               c->seed_class, c->F, c->meta, c->pool, c->flag);
+        zero_ring(c);
+        launch_commit_compact(c, nullptr, 0, c->queue[0], &c->bc->init_count, 0);
+        read_bc(c);
+        c->pool_tail = (int64_t)c->h_bc->pool_tail;
+        const int64_t relocated = c->h_bc->relocated;
+        unsigned int nq = c->h_bc->init_count;
+        HIPCHK(c, hipEventRecord(c->phase_ev[2], c->stream));
+
+        // ---- Step 3: rounds over V_aff ----
+        const int64_t frontier_initial = nq;
+        int64_t peak = nq, rows = 0, edges = 0;
+        int it = 0, cur = 0;
+        float last = 0.f;
+        double avg_len = c->n > 0 ? (double)c->entries / (double)c->n : 1.0;
+        while (nq > 0 && it < c->max_iter) {
+            const int G = choose_group(c, avg_len);
+            RoundCtr* slot = c->ring + (it % kRing);
+            launch_update<false>(c, G, c->queue[cur], nq, c->F, c->F2, c->tol, slot, c->ring + ((it + 1) % kRing));
+            launch_commit_compact(c, c->queue[cur], nq, c->queue[cur ^ 1], &slot->next_count, 0);
+            const RoundCtr r = read_slot(c, it);
+            std::memcpy(&last, &r.resid_bits, sizeof(float));
+            rows += nq;
+            edges += (int64_t)r.edges;
+            avg_len = nq ? (double)r.edges / (double)nq : avg_len;
+            c->log_sizes.push_back(nq);
+            c->log_delta.push_back(last);
+            nq = r.next_count;
+            peak = std::max<int64_t>(peak, nq);
+            cur ^= 1;
+            ++it;
+        }
+        HIPCHK(c, hipEventRecord(c->phase_ev[3], c->stream));
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        if (nq > 0) {  // cut by max_iter: the flags were consumed by the last compaction; nothing is pending
+        }
+        if (stats) {
+            stats->iterations = it;
+            stats->converged = nq == 0 ? 1 : 0;
+            stats->final_max_delta = last;
+            stats->rows_updated = rows;
+            stats->edges_traversed = edges;
+            stats->frontier_initial = frontier_initial;
+            stats->frontier_peak = peak;
+            stats->rows_relocated = relocated;
+            stats->update_launches = it;
+            stats->ms_update_kernel = c->time_kernels ? collect_kernel_ms(c) : 0.f;
+            (void)hipEventElapsedTime(&stats->ms_insert, c->phase_ev[0], c->phase_ev[1]);
+            (void)hipEventElapsedTime(&stats->ms_seed, c->phase_ev[1], c->phase_ev[2]);
+            (void)hipEventElapsedTime(&stats->ms_iterate, c->phase_ev[2], c->phase_ev[3]);
+            stats->ms_total = ms_since(t0);
+        }
+        c->events_used = 0;
+        return nq == 0 ? DYNLP_OK : DYNLP_NOT_CONVERGED;
+    } catch (const Fail& f) {
+        if (mutated) c->poisoned = true;
+        return f.st;
+    } catch (const std::bad_alloc&) {
+        c->err = "host allocation failed";
+        if (mutated) c->poisoned = true;
+        return DYNLP_ERR_OOM;
+    }
+}
+
+dynlp_status dynlp_get_labels(dynlp_ctx* c, float* soft, int32_t* hard) {
+    if (!c) return DYNLP_ERR_INVALID_ARG;
+    if (c->poisoned) {
+        c->err = "context is unusable after an earlier device or memory error";
+        return DYNLP_ERR_STATE;
+    }
+    const int64_t n = c->n;
+    if (n == 0 || (!soft && !hard)) return DYNLP_OK;
+    float* d_soft = nullptr;
+    int32_t* d_hard = nullptr;
+    dynlp_status st = DYNLP_OK;
+    try {
+        HIPCHK(c, hipSetDevice(c->device));
+        if (soft) {
+            float* dst = c->dev_ptrs ? soft : (d_soft = dev_alloc_n<float>(c, n * c->C));
+            hipLaunchKernelGGL(k_pack_soft, dim3(grid_for(n * c->C)), dim3(kBlock), 0, c->stream, n, c->C, c->CP, c->F, dst);
+            HIPCHK(c, hipGetLastError());
+            if (!c->dev_ptrs)
+                HIPCHK(c, hipMemcpyAsync(soft, dst, (size_t)n * c->C * sizeof(float), hipMemcpyDeviceToHost, c->stream));
+        }
+        if (hard) {
+            int32_t* dst = c->dev_ptrs ? hard : (d_hard = dev_alloc_n<int32_t>(c, n));
+            hipLaunchKernelGGL(k_argmax, dim3(grid_for(n)), dim3(kBlock), 0, c->stream, n, c->C, c->CP, c->F, dst);
+            HIPCHK(c, hipGetLastError());
+            if (!c->dev_ptrs)
+                HIPCHK(c, hipMemcpyAsync(hard, dst, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+        }
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+    } catch (const Fail& f) {
+        st = f.st;
+    }
+    dev_free(c, d_soft);
+    dev_free(c, d_hard);
+    return st;
+}
+
+dynlp_status dynlp_export_graph(dynlp_ctx* c, int64_t* row_ptr, int32_t* col, float* w, float* degree,
+                                int32_t* seed_class) {
+    if (!c) return DYNLP_ERR_INVALID_ARG;
+    if (c->poisoned) {
+        c->err = "context is unusable after an earlier device or memory error";
+        return DYNLP_ERR_STATE;
+    }
+    if (!row_ptr || (c->entries > 0 && (!col || !w))) {
+        c->err = "row_ptr / col / w are NULL";
+        return DYNLP_ERR_INVALID_ARG;
+    }
+    const int64_t n = c->n, nnz = c->entries;
+    int64_t *d_rp = nullptr, *sums = nullptr;
+    int32_t* d_col = nullptr;
+    float* d_w = nullptr;
+    dynlp_status st = DYNLP_OK;
+    const hipMemcpyKind kind = c->dev_ptrs ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost;
+    try {
+        HIPCHK(c, hipSetDevice(c->device));
+        const int64_t nb = grid_for(n);
+        d_rp = dev_alloc_n<int64_t>(c, n + 1);
+        sums = dev_alloc_n<int64_t>(c, nb);
+        int64_t total = 0;
+        if (n > 0) {
+            hipLaunchKernelGGL(k_row_lens, dim3(nb), dim3(kBlock), 0, c->stream, n, c->meta, d_rp, sums);
+            HIPCHK(c, hipGetLastError());
+            total = scan_block_sums(c, nb, sums);
+            hipLaunchKernelGGL(k_lens_to_row_ptr, dim3(nb), dim3(kBlock), 0, c->stream, n, d_rp, sums);
+            HIPCHK(c, hipGetLastError());
+        }
+        HIPCHK(c, hipMemcpyAsync(d_rp + n, &total, sizeof(int64_t), hipMemcpyHostToDevice, c->stream));
+        if (total != nnz) {
+            c->err = "internal: entry count mismatch";
+            throw Fail{DYNLP_ERR_STATE};
+        }
+        if (nnz > 0) {
+            int32_t* ocol = c->dev_ptrs ? col : (d_col = dev_alloc_n<int32_t>(c, nnz));
+            float* ow = c->dev_ptrs ? w : (d_w = dev_alloc_n<float>(c, nnz));
+            hipLaunchKernelGGL(k_export_rows, dim3(grid_for(n * 16)), dim3(kBlock), 0, c->stream, n, c->meta, c->pool, d_rp,
+                               ocol, ow);
+            HIPCHK(c, hipGetLastError());
+            if (!c->dev_ptrs) {
+                HIPCHK(c, hipMemcpyAsync(col, ocol, (size_t)nnz * 4, hipMemcpyDeviceToHost, c->stream));
+                HIPCHK(c, hipMemcpyAsync(w, ow, (size_t)nnz * 4, hipMemcpyDeviceToHost, c->stream));
+            }
+        }
+        HIPCHK(c, hipMemcpyAsync(row_ptr, d_rp, (size_t)(n + 1) * sizeof(int64_t), kind, c->stream));
+        if (degree && n > 0) HIPCHK(c, hipMemcpyAsync(degree, c->deg, (size_t)n * sizeof(float), kind, c->stream));
+        if (seed_class && n > 0)
+            HIPCHK(c, hipMemcpyAsync(seed_class, c->seed_class, (size_t)n * sizeof(int32_t), kind, c->stream));
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+    } catch (const Fail& f) {
+        st = f.st;
+    }
+    dev_free(c, d_rp);
+    dev_free(c, sums);
+    dev_free(c, d_col);
+    dev_free(c, d_w);
+    return st;
+}
+
+int64_t dynlp_round_log(const dynlp_ctx* ctx, int64_t cap, int64_t* frontier_size, float* max_delta) {
+    if (!ctx) return -1;
+    const int64_t rounds = (int64_t)ctx->log_sizes.size();
+    const int64_t k = std::max<int64_t>(0, std::min(cap, rounds));
+    if (frontier_size) std::copy(ctx->log_sizes.begin(), ctx->log_sizes.begin() + k, frontier_size);
+    if (max_delta) std::copy(ctx->log_delta.begin(), ctx->log_delta.begin() + k, max_delta);
+    return rounds;
+}
+
+}  // extern "C"

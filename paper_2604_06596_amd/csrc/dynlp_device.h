@@ -1,0 +1,183 @@
+// Device-side building blocks shared by the DynLP kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dynlp {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;       // threads per workgroup for every kernel here
+constexpr int kRowAlign = 8;      // row capacities are multiples of 8 entries = 64 bytes
+constexpr int kRing = 64;         // per-round counter slots
+
+// One CSR entry of the slack pool: neighbour id and weight side by side, so that a single
+// 8-byte load brings both.
+struct __attribute__((aligned(8))) Edge {
+    int32_t col;
+    float w;
+};
+
+// Where row u lives in the pool: entries [off, off+len) are valid, [off+len, off+cap) is slack.
+struct __attribute__((aligned(16))) RowMeta {
+    int64_t off;
+    int32_t len;
+    int32_t cap;
+};
+
+// Counters one propagation round leaves for the host (one slot of a small ring).
+struct __attribute__((aligned(32))) RoundCtr {
+    unsigned int next_count;   // |V_aff| for the next round (written by compaction)
+    unsigned int resid_bits;   // max change of this round, float bits (non-negative floats order as uints)
+    unsigned int changed;      // rows whose change exceeded tol
+    unsigned int pad0;
+    unsigned long long edges;  // CSR entries traversed by the row update
+    unsigned long long pad1;
+};
+
+// Scalars of the insertion step and error reporting.
+struct __attribute__((aligned(64))) BatchCtr {
+    unsigned long long pool_tail;    // first free pool entry
+    unsigned long long reloc_need;   // pool entries the planned relocations will take
+    unsigned int touched;            // rows that receive at least one new entry
+    unsigned int relocated;          // rows moved by the last insertion
+    int err_code;                    // 0 = none; first validation error wins
+    int err_pad;
+    long long err_index;             // index of the offending item
+    unsigned int init_count;         // size of the first frontier
+    unsigned int pad0;
+    unsigned long long scan_total;   // grand total of the last block-sum scan
+    unsigned long long pad1;
+};
+
+enum ValidationError : int {
+    kErrNone = 0,
+    kErrRowPtr = 1,
+    kErrColRange = 2,
+    kErrSelfLoop = 3,
+    kErrWeight = 4,
+    kErrSeedVertex = 5,
+    kErrSeedClass = 6,
+    kErrSeedConflict = 7,
+    kErrEndpoint = 8,
+    kErrRelabel = 9,
+};
+
+__device__ inline void report_error(BatchCtr* bc, int code, long long index) {
+    if (atomicCAS(&bc->err_code, 0, code) == 0) bc->err_index = index;
+}
+
+__device__ inline int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
+
+// ---- wave / block reductions and scans --------------------------------------------------------
+template <typename T>
+__device__ inline T wave_sum(T v) {
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) v += __shfl_xor(v, d, kWave);
+    return v;
+}
+
+__device__ inline float wave_max(float v) {
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) v = fmaxf(v, __shfl_xor(v, d, kWave));
+    return v;
+}
+
+// Inclusive scan across the 64 lanes of a wave.
+template <typename T>
+__device__ inline T wave_inclusive_scan(T v) {
+    const int lane = lane_id();
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        T o = __shfl_up(v, d, kWave);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+// Exclusive scan over the kBlock threads of a workgroup; *total receives the block sum.
+// smem must hold kBlock / kWave + 1 elements.  Contains barriers: call from all threads.
+template <typename T>
+__device__ inline T block_exclusive_scan(T v, T* smem, T* total) {
+    const int lane = lane_id();
+    const int wave = threadIdx.x / kWave;
+    constexpr int nw = kBlock / kWave;
+    T inc = wave_inclusive_scan(v);
+    if (lane == kWave - 1) smem[wave] = inc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        T run = 0;
+        for (int i = 0; i < nw; ++i) {
+            T t = smem[i];
+            smem[i] = run;
+            run += t;
+        }
+        smem[nw] = run;
+    }
+    __syncthreads();
+    T res = inc - v + smem[wave];
+    *total = smem[nw];
+    __syncthreads();
+    return res;
+}
+
+// Append-slot reservation with one atomic per wave: lanes with pred get consecutive slots.
+__device__ inline unsigned int wave_reserve(unsigned int* counter, bool pred) {
+    const unsigned long long mask = __ballot(pred);
+    const int lane = lane_id();
+    unsigned int base = 0;
+    const int leader = __ffsll((long long)mask) - 1;
+    if (pred && lane == leader) base = atomicAdd(counter, (unsigned int)__popcll(mask));
+    base = __shfl(base, leader < 0 ? 0 : leader, kWave);
+    return base + (unsigned int)__popcll(mask & ((1ull << lane) - 1ull));
+}
+
+// ---- small vectors of floats for row chunks ---------------------------------------------------
+template <int V>
+struct Vec {
+    float v[V];
+};
+
+template <int V>
+__device__ inline Vec<V> load_vec(const float* p);
+template <>
+__device__ inline Vec<1> load_vec<1>(const float* p) {
+    Vec<1> r;
+    r.v[0] = *p;
+    return r;
+}
+template <>
+__device__ inline Vec<2> load_vec<2>(const float* p) {
+    float2 t = *reinterpret_cast<const float2*>(p);
+    Vec<2> r;
+    r.v[0] = t.x;
+    r.v[1] = t.y;
+    return r;
+}
+template <>
+__device__ inline Vec<4> load_vec<4>(const float* p) {
+    float4 t = *reinterpret_cast<const float4*>(p);
+    Vec<4> r;
+    r.v[0] = t.x;
+    r.v[1] = t.y;
+    r.v[2] = t.z;
+    r.v[3] = t.w;
+    return r;
+}
+
+template <int V>
+__device__ inline void store_vec(float* p, const Vec<V>& a);
+template <>
+__device__ inline void store_vec<1>(float* p, const Vec<1>& a) {
+    *p = a.v[0];
+}
+template <>
+__device__ inline void store_vec<2>(float* p, const Vec<2>& a) {
+    *reinterpret_cast<float2*>(p) = make_float2(a.v[0], a.v[1]);
+}
+template <>
+__device__ inline void store_vec<4>(float* p, const Vec<4>& a) {
+    *reinterpret_cast<float4*>(p) = make_float4(a.v[0], a.v[1], a.v[2], a.v[3]);
+}
+
+}  // namespace dynlp

@@ -1,0 +1,441 @@
+"""GPU parity: libdynlp (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Tolerances (derivation in DESIGN.md, "Numerical tolerances"):
+* one sweep / one round, float32 vs float64:                         max-abs <= 1e-6
+* converged labels vs exact harmonic labels (O1) at tol = 1e-6:      max-abs <= 1e-4
+* batch update vs the oracle's Step-3 loop (O2) at the same tol:     max-abs <= 2e-5
+* hard labels: exact wherever the oracle's top-2 margin exceeds the soft tolerance.
+"""
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import native as ON
+from oracle import reference as R
+import paper_2604_06596_amd as P
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-6
+SWEEP_ATOL = 1e-6
+O1_ATOL = 1e-4
+O2_ATOL = 2e-5
+
+
+def _oracle_graph(p):
+    return R.Graph(p.n, p.row_ptr, p.col, p.w, p.C, p.seed_vertex, p.seed_class)
+
+
+def _make(p, **kw):
+    return P.DynLP(p.n, p.row_ptr, p.col, p.w, p.C, p.seed_vertex, p.seed_class, **kw)
+
+
+def _rows_as_sorted_pairs(rp, col, w):
+    out = []
+    for u in range(len(rp) - 1):
+        seg = sorted(zip(col[rp[u]:rp[u + 1]].tolist(), w[rp[u]:rp[u + 1]].tolist()))
+        out.append(seg)
+    return out
+
+
+def _check_graph_equals_oracle(d, g):
+    rp, col, w, deg, sc = d.export_graph()
+    orp, ocol, ow = g.csr()
+    assert rp.tolist() == orp.tolist()
+    assert _rows_as_sorted_pairs(rp, col, w) == _rows_as_sorted_pairs(orp, ocol.astype(np.int32), ow.astype(np.float32))
+    assert sc.tolist() == g.seed_class.tolist()
+    d64 = np.bincount(g.src, weights=g.w, minlength=g.n)
+    np.testing.assert_allclose(deg, d64, rtol=1e-5, atol=0)
+
+
+def _check_hard(hard, F_oracle, atol):
+    oh = R.hard_labels(F_oracle)
+    clear = R.top2_margin(F_oracle) > 2 * atol
+    assert np.array_equal(hard[clear], oh[clear])
+
+
+def _apply_oracle_batch(g, F_before, b):
+    """Oracle side of one batch: graph update, O2 (frontier loop) and O1 (exact recompute)."""
+    n_old = g.n
+    g.insert(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+    F = np.concatenate([F_before, np.full((b.num_new_vertices, g.C), 1.0 / g.C)])
+    s = np.asarray(b.seed_vertex, dtype=np.int64)
+    F[s] = 0
+    F[s, np.asarray(b.seed_class, dtype=np.int64)] = 1
+    rp, col, w = g.csr()
+    A0 = ON.affected_set(rp, col, g.seed_class, n_old, b.eu, b.ev, b.seed_vertex)
+    return rp, col, w, F, A0
+
+
+# ---------------------------------------------------------------------------------------------
+# mutable CSR (create / export / insert / relocate)
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,deg,C", [(1, 0.0, 2), (50, 3.0, 3), (700, 5.0, 4), (5000, 20.0, 10)])
+def test_create_and_export_round_trip(n, deg, C):
+    p = W.small_random(n, C, deg, max(1, n // 20), 100 + n, connected=n > 1)
+    with _make(p) as d:
+        assert d.num_vertices == n and d.num_entries == p.nnz and d.num_classes == C
+        _check_graph_equals_oracle(d, _oracle_graph(p))
+        soft, hard = d.get_labels()
+        np.testing.assert_array_equal(soft, R.initial_labels(_oracle_graph(p).seed_class, C).astype(np.float32))
+
+
+def test_empty_graph_and_growth_from_nothing():
+    rp = np.zeros(1, dtype=np.int64)
+    with P.DynLP(0, rp, None, None, 3, None, None) as d:
+        st, s = d.static_solve(TOL, 10)
+        assert st == 0 and s.iterations == 0
+        soft, hard = d.get_labels()
+        assert soft.shape == (0, 3)
+        # grow: 4 vertices in a path, the ends labelled
+        st, s = d.apply_batch(4, [0, 1, 2], [1, 2, 3], [1.0, 1.0, 1.0], [0, 3], [0, 2])
+        assert st == 0
+        soft, hard = d.get_labels()
+        np.testing.assert_allclose(soft[1], [2 / 3, 0, 1 / 3], atol=1e-5)
+        np.testing.assert_allclose(soft[2], [1 / 3, 0, 2 / 3], atol=1e-5)
+        assert hard.tolist() == [0, 0, 2, 2]
+
+
+@pytest.mark.parametrize("slack,reserve_v", [(1.25, 0), (1.01, 16)])
+def test_insertion_matches_model_including_relocation_and_regrowth(slack, reserve_v):
+    p = W.small_random(600, 3, 4.0, 30, 7)
+    g = _oracle_graph(p)
+    with _make(p, slack_factor=slack, reserve_vertices=reserve_v) as d:
+        d.set_params(1e-3, 5)
+        relocated = 0
+        for i in range(4):
+            # many new vertices (forces the vertex arrays to regrow when reserve is small) and many
+            # extra edges onto old vertices (forces rows out of their slack)
+            b = W.small_random_batch(p, 700 if i == 1 else 60, 6, 3, num_extra_edges=900, num_revealed=4)
+            st, s = d.apply_batch(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+            g.insert(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+            relocated += s.rows_relocated
+            assert d.num_vertices == g.n and d.num_entries == g.src.shape[0]
+            _check_graph_equals_oracle(d, g)
+        assert relocated > 0
+
+
+def test_hub_row_receives_many_edges_in_one_batch():
+    p = W.small_random(300, 2, 3.0, 10, 9)
+    g = _oracle_graph(p)
+    with _make(p) as d:
+        d.set_params(1e-3, 3)
+        hub = 5
+        others = np.array([v for v in range(300) if v != hub], dtype=np.int32)
+        eu = np.full(others.shape, hub, dtype=np.int32)
+        ew = np.linspace(0.1, 1.0, others.shape[0]).astype(np.float32)
+        d.apply_batch(0, eu, others, ew)
+        g.insert(0, eu, others, ew, [], [])
+        _check_graph_equals_oracle(d, g)
+
+
+# ---------------------------------------------------------------------------------------------
+# row update: one sweep, static solve
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("C", [1, 2, 3, 4, 7, 10, 16, 17, 33, 50, 64])
+@pytest.mark.parametrize("group_lanes", [0, 64])
+def test_one_sweep_equals_oracle_sweep(C, group_lanes):
+    p = W.small_random(3000, C, 9.0, 150, 200 + C, connected=False)
+    g = _oracle_graph(p)
+    rp, col, w = g.csr()
+    with _make(p, group_lanes=group_lanes) as d:
+        F = R.initial_labels(g.seed_class, C)
+        for sweep in range(3):
+            st, s = d.static_solve(0.0, 1)
+            assert s.iterations == 1
+            F_new, change = ON.itlp_sweep(rp, col, w, F, g.seed_class)
+            soft, _ = d.get_labels()
+            assert np.max(np.abs(soft - F_new)) <= SWEEP_ATOL
+            assert abs(s.final_max_delta - change) <= SWEEP_ATOL
+            updatable = int(((g.seed_class < 0) & (np.diff(rp) > 0)).sum())
+            assert s.frontier_initial == updatable and s.edges_traversed == int(np.diff(rp)[(g.seed_class < 0)].sum())
+            F = soft.astype(np.float64)  # follow the GPU trajectory so that sweeps stay comparable
+
+
+@pytest.mark.parametrize("gl", [4, 8, 16, 32, 64])
+def test_every_group_width_gives_the_same_sweep(gl):
+    p = W.small_random(2000, 10, 25.0, 60, 77)
+    g = _oracle_graph(p)
+    rp, col, w = g.csr()
+    with _make(p, group_lanes=gl) as d:
+        d.static_solve(0.0, 1)
+        soft, _ = d.get_labels()
+    F_new, _ = ON.itlp_sweep(rp, col, w, R.initial_labels(g.seed_class, p.C), g.seed_class)
+    assert np.max(np.abs(soft - F_new)) <= SWEEP_ATOL
+
+
+def test_long_rows_span_many_chunks():
+    # a star-heavy graph: a few rows with thousands of entries next to short rows
+    n, C = 6000, 5
+    rng = np.random.default_rng(3)
+    hubs = np.arange(4)
+    eu = np.repeat(hubs, 3000)
+    ev = rng.integers(4, n, size=eu.shape[0])
+    extra_u = rng.integers(0, n, size=8000)
+    extra_v = rng.integers(0, n, size=8000)
+    key = np.unique(np.minimum(np.concatenate([eu, extra_u]), np.concatenate([ev, extra_v])) * n +
+                    np.maximum(np.concatenate([eu, extra_u]), np.concatenate([ev, extra_v])))
+    lo, hi = key // n, key % n
+    keep = lo != hi
+    lo, hi = lo[keep], hi[keep]
+    ew = rng.uniform(0.1, 1.0, size=lo.shape[0]).astype(np.float32)
+    rp, col, w = W.edges_to_csr(n, lo, hi, ew)
+    sv = np.arange(10, 310, dtype=np.int32)
+    sc = (sv % C).astype(np.int32)
+    seed_class = np.full(n, -1, dtype=np.int64)
+    seed_class[sv] = sc
+    with P.DynLP(n, rp, col, w, C, sv, sc) as d:
+        d.static_solve(0.0, 1)
+        soft, _ = d.get_labels()
+        F_new, _ = ON.itlp_sweep(rp, col, w.astype(np.float64), R.initial_labels(seed_class, C), seed_class)
+        assert np.max(np.abs(soft - F_new)) <= SWEEP_ATOL
+        st, s = d.static_solve(TOL, 5000)
+        assert st == 0
+        soft, hard = d.get_labels()
+        exact, _, _ = ON.itlp_solve(rp, col, w.astype(np.float64), seed_class, C, tol=1e-12)
+        reach = R.seed_reachable(rp, col, seed_class)
+        assert np.max(np.abs(soft - exact)[reach]) <= O1_ATOL
+
+
+def test_static_solve_cfg1_matches_closed_form_and_oracle():
+    p = W.make_config("cfg1")
+    cfg = W.CONFIGS["cfg1"]
+    g = _oracle_graph(p)
+    rp, col, w = g.csr()
+    with _make(p) as d:
+        st, s = d.static_solve(cfg["tol"], cfg["max_iter"])
+        soft, hard = d.get_labels()
+        sizes, deltas = d.round_log()
+    assert st == 0 and s.converged == 1 and s.final_max_delta <= cfg["tol"]
+    exact, _, _ = ON.itlp_solve(rp, col, w, g.seed_class, p.C, tol=1e-13, max_iter=2_000_000)
+    _, it_oracle, _ = ON.itlp_solve(rp, col, w, g.seed_class, p.C, tol=cfg["tol"])
+    reach = R.seed_reachable(rp, col, g.seed_class)
+    err = np.max(np.abs(soft - exact)[reach])
+    print(f"cfg1 static: {s.iterations} sweeps (oracle {it_oracle}), max|F-F*| = {err:.2e}")
+    assert err <= O1_ATOL
+    assert abs(s.iterations - it_oracle) <= max(2, it_oracle // 50)
+    if reach.all():
+        closed = R.harmonic_closed_form(rp, col, w, g.seed_class, p.C)
+        assert np.max(np.abs(soft - closed)) <= O1_ATOL
+    _check_hard(hard[reach], exact[reach], O1_ATOL)
+    # invariants: seeds exactly one-hot, rows are distributions
+    s_idx = np.flatnonzero(g.seed_class >= 0)
+    assert np.array_equal(soft[s_idx], R.initial_labels(g.seed_class, p.C)[s_idx].astype(np.float32))
+    assert soft.min() >= 0 and np.max(np.abs(soft.sum(1) - 1)) < 1e-5
+    assert len(sizes) == s.iterations and np.all(np.diff(deltas[5:]) <= 1e-6)
+
+
+def test_static_solve_respects_max_iter_and_reports_not_converged():
+    p = W.small_random(2000, 3, 4.0, 20, 5)
+    with _make(p) as d:
+        st, s = d.static_solve(1e-7, 3)
+        assert st == 1 and s.iterations == 3 and s.converged == 0
+        st, s = d.static_solve(1e-7, 0)
+        assert st == 1 and s.iterations == 0
+
+
+# ---------------------------------------------------------------------------------------------
+# full batch update (Alg. 2) vs O2 and O1
+# ---------------------------------------------------------------------------------------------
+def _batch_parity(p, batches, tol=TOL, max_iter=20000, **kw):
+    g = _oracle_graph(p)
+    rp, col, w = g.csr()
+    reports = []
+    with _make(p, **kw) as d:
+        st, s = d.static_solve(tol, max_iter)
+        assert st == 0
+        soft, _ = d.get_labels()
+        F_o2 = soft.astype(np.float64)  # O2 continues from the same state the GPU holds
+        for b in batches:
+            st, s = d.apply_batch(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+            assert st == 0 and s.converged == 1
+            soft, hard = d.get_labels()
+            sizes, deltas = d.round_log()
+            rp, col, w, F_start, A0 = _apply_oracle_batch(g, F_o2, b)
+            o2 = ON.step3_propagate(rp, col, w, F_start, g.seed_class, A0, tol, max_iter)
+            exact, _, _ = ON.itlp_solve(rp, col, w, g.seed_class, g.C, tol=1e-12, max_iter=5_000_000)
+            reach = R.seed_reachable(rp, col, g.seed_class)
+            e2 = float(np.max(np.abs(soft - o2["F"])))
+            e1 = float(np.max(np.abs(soft - exact)[reach]))
+            reports.append(dict(e_o2=e2, e_o1=e1, rounds=s.iterations, rounds_o2=o2["rounds"],
+                                A0=int(s.frontier_initial), A0_o2=len(A0)))
+            print(reports[-1])
+            assert s.frontier_initial == len(A0)
+            assert e2 <= O2_ATOL
+            assert e1 <= O1_ATOL
+            assert abs(s.iterations - o2["rounds"]) <= max(2, o2["rounds"] // 20)
+            k = min(len(sizes), len(o2["frontier_sizes"]), 5)
+            assert sizes[:k].tolist() == o2["frontier_sizes"][:k].tolist() or \
+                np.max(np.abs(sizes[:k] - o2["frontier_sizes"][:k]) / np.maximum(1, o2["frontier_sizes"][:k])) < 0.01
+            assert s.rows_updated == int(sizes.sum())
+            _check_hard(hard[reach], exact[reach], O1_ATOL)
+            s_idx = np.flatnonzero(g.seed_class >= 0)
+            assert np.array_equal(soft[s_idx], R.initial_labels(g.seed_class, g.C)[s_idx].astype(np.float32))
+            assert soft.min() >= 0 and np.max(np.abs(soft.sum(1) - 1)) < 1e-5
+            _check_graph_equals_oracle(d, g)
+            F_o2 = soft.astype(np.float64)
+    return reports
+
+
+def test_cfg1_batch_update_matches_oracle():
+    p = W.make_config("cfg1")
+    b = W.knn_mixture_batch(p, 100, 5)
+    p0 = W.make_config("cfg1")  # pristine copy for create (p was advanced by the batch generator)
+    _batch_parity(p0, [b])
+
+
+@pytest.mark.parametrize("C,gl", [(2, 0), (10, 0), (10, 16), (50, 0)])
+def test_vertex_batches_on_random_graphs(C, gl):
+    p = W.small_random(4000, C, 8.0, 200, 300 + C)
+    p0 = W.small_random(4000, C, 8.0, 200, 300 + C)
+    batches = [W.small_random_batch(p, 200, 8, 4), W.small_random_batch(p, 37, 5, 1, num_extra_edges=50)]
+    _batch_parity(p0, batches, group_lanes=gl)
+
+
+def test_edge_only_batches_with_revealed_seeds():
+    p = W.sbm(20000, 10, 20.0, 8.0, 0.01, 4242)
+    p0 = W.sbm(20000, 10, 20.0, 8.0, 0.01, 4242)
+    batches = [W.sbm_edge_batch(p, 2000, 0.5, 20) for _ in range(3)]
+    _batch_parity(p0, batches)
+
+
+def test_degenerate_batches():
+    p = W.small_random(500, 3, 4.0, 25, 11)
+    g = _oracle_graph(p)
+    with _make(p) as d:
+        d.static_solve(TOL, 20000)
+        before, _ = d.get_labels()
+        # nothing at all
+        st, s = d.apply_batch(0, None, None, None)
+        assert st == 0 and s.iterations == 0 and s.frontier_initial == 0
+        # vertices without edges: isolated rows stay uniform and are never updated
+        st, s = d.apply_batch(3, None, None, None)
+        assert st == 0 and s.frontier_initial == 0 and d.num_vertices == 503
+        soft, hard = d.get_labels()
+        np.testing.assert_array_equal(soft[:500], before)
+        np.testing.assert_allclose(soft[500:], 1.0 / 3, rtol=1e-7)
+        assert hard[500:].tolist() == [0, 0, 0]
+        # re-announcing an existing seed with the same class is a no-op for that row
+        sv, sc = p.seed_vertex[:2], p.seed_class[:2]
+        st, s = d.apply_batch(0, None, None, None, sv, sc)
+        assert st == 0
+        # an isolated new vertex that is a seed, and an edge between two isolated vertices
+        st, s = d.apply_batch(1, [500], [501], [0.5], [503], [2])
+        assert st == 0
+        soft, _ = d.get_labels()
+        np.testing.assert_array_equal(soft[503], [0, 0, 1])
+        np.testing.assert_allclose(soft[[500, 501]], 1.0 / 3, atol=1e-6)
+
+
+def test_max_iter_cut_returns_not_converged_with_valid_labels():
+    p = W.small_random(3000, 3, 4.0, 30, 13)
+    p0 = W.small_random(3000, 3, 4.0, 30, 13)
+    b = W.small_random_batch(p, 300, 4, 3)
+    with _make(p0) as d:
+        d.static_solve(TOL, 20000)
+        d.set_params(1e-7, 2)
+        st, s = d.apply_batch(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+        assert st == 1 and s.iterations == 2 and s.converged == 0
+        soft, _ = d.get_labels()
+        assert np.max(np.abs(soft.sum(1) - 1)) < 1e-5
+        # and the context keeps working
+        d.set_params(TOL, 20000)
+        st, s = d.apply_batch(0, [0], [1], [0.3])
+        assert st == 0
+
+
+def test_rejected_batch_leaves_context_unchanged():
+    p = W.small_random(400, 3, 4.0, 20, 17)
+    with _make(p) as d:
+        d.static_solve(1e-5, 5000)
+        before, _ = d.get_labels()
+        graph_before = d.export_graph()
+        free = int(np.setdiff1d(np.arange(400), p.seed_vertex)[0])
+        other_class = (int(p.seed_class[0]) + 1) % 3
+        bad = [
+            dict(k=1, eu=[0], ev=[401], ew=[1.0]),                      # endpoint out of range
+            dict(k=0, eu=[3], ev=[3], ew=[1.0]),                        # self loop
+            dict(k=0, eu=[3], ev=[4], ew=[-1.0]),                       # bad weight
+            dict(k=0, eu=[3], ev=[4], ew=[float("nan")]),
+            dict(k=0, sv=[400], sc=[0]),                                # seed vertex out of range
+            dict(k=0, sv=[free], sc=[3]),                               # class out of range
+            dict(k=0, sv=[free, free], sc=[0, 1]),                      # two classes for one vertex
+            dict(k=0, sv=[int(p.seed_vertex[0])], sc=[other_class]),    # relabel an existing seed
+            dict(k=-1),
+        ]
+        for a in bad:
+            with pytest.raises(P.DynLPError) as ei:
+                d.apply_batch(a.get("k", 0), a.get("eu"), a.get("ev"), a.get("ew"), a.get("sv"), a.get("sc"))
+            assert ei.value.status == -1
+            assert d.num_vertices == 400
+        after, _ = d.get_labels()
+        np.testing.assert_array_equal(before, after)
+        for x, y in zip(graph_before, d.export_graph()):
+            np.testing.assert_array_equal(x, y)
+        # still usable, scratch state intact
+        st, s = d.apply_batch(1, [400], [0], [0.7])
+        assert st == 0 and d.num_vertices == 401
+
+
+def test_device_pointer_mode_matches_host_mode():
+    import torch
+
+    p = W.small_random(3000, 10, 8.0, 100, 19)
+    p2 = W.small_random(3000, 10, 8.0, 100, 19)
+    b = W.small_random_batch(p2, 150, 6, 3, num_extra_edges=40, num_revealed=2)
+    with _make(p) as dh:
+        dh.static_solve(TOL, 20000)
+        dh.apply_batch(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+        soft_h, hard_h = dh.get_labels()
+    dev = torch.device("cuda:0")
+    t = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a)).to(dt).to(dev)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        d = P.DynLP(p.n, t(p.row_ptr, torch.int64), t(p.col, torch.int32), t(p.w, torch.float32), p.C,
+                    t(p.seed_vertex, torch.int32), t(p.seed_class, torch.int32), device_ptrs=True,
+                    stream=stream.cuda_stream)
+        d.static_solve(TOL, 20000)
+        d.apply_batch(b.num_new_vertices, t(b.eu, torch.int32), t(b.ev, torch.int32), t(b.ew, torch.float32),
+                      t(b.seed_vertex, torch.int32), t(b.seed_class, torch.int32))
+        soft_d, hard_d = d.get_labels()
+        rp, col, w, deg, sc = d.export_graph()
+        d.destroy()
+    stream.synchronize()
+    # same kernels, same inputs; only the order of one batch's entries inside a row may differ
+    assert np.max(np.abs(soft_d.cpu().numpy() - soft_h)) <= 1e-6
+    assert (hard_d.cpu().numpy() != hard_h).mean() < 1e-3
+    assert int(rp[-1]) == col.numel()
+
+
+def test_device_mode_validation_errors_come_from_the_gpu_checks():
+    import torch
+
+    dev = torch.device("cuda:0")
+    t = lambda a, dt: torch.tensor(a, dtype=dt, device=dev)
+    rp, col, w = [0, 1, 3, 4], [1, 0, 2, 1], [1.0, 1.0, 2.0, 2.0]
+    cases = [
+        (dict(rp=[0, 2, 1, 4]), "row_ptr"),
+        (dict(col=[1, 0, 3, 1]), "neighbour id"),
+        (dict(col=[0, 0, 2, 1]), "self loop"),
+        (dict(w=[1.0, 0.0, 2.0, 2.0]), "weight"),
+        (dict(sv=[5]), "seed vertex"),
+        (dict(sv=[0, 0], sc=[0, 1]), "two different"),
+    ]
+    for mut, needle in cases:
+        a = dict(rp=rp, col=col, w=w, sv=[0], sc=[1])
+        a.update(mut)
+        with pytest.raises(P.DynLPError) as ei:
+            P.DynLP(3, t(a["rp"], torch.int64), t(a["col"], torch.int32), t(a["w"], torch.float32), 2,
+                    t(a["sv"], torch.int32), t(a["sc"], torch.int32), device_ptrs=True)
+        assert ei.value.status == -1 and needle in ei.value.message
+    d = P.DynLP(3, t(rp, torch.int64), t(col, torch.int32), t(w, torch.float32), 2, t([0], torch.int32),
+                t([1], torch.int32), device_ptrs=True)
+    with pytest.raises(P.DynLPError) as ei:
+        d.apply_batch(0, t([0], torch.int32), t([7], torch.int32), t([1.0], torch.float32))
+    assert "endpoint" in ei.value.message
+    with pytest.raises(P.DynLPError) as ei:
+        d.apply_batch(0, None, None, None, t([0], torch.int32), t([0], torch.int32))
+    assert "already a seed" in ei.value.message
+    st, s = d.apply_batch(1, t([3], torch.int32), t([2], torch.int32), t([1.0], torch.float32))
+    assert st == 0 and d.num_vertices == 4
+    d.destroy()
