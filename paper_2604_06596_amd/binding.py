@@ -62,6 +62,13 @@ def load_library(path: str | None = None):
     if not os.path.exists(path):
         raise FileNotFoundError(f"{path} is missing: build it with `python -m paper_2604_06596_amd.build` "
                                 "(or __graft_entry__.build()); DynLP has no CPU fallback")
+    # PyTorch ships its own libamdhip64.so.7.  A process must not run two HIP runtimes, so torch is
+    # imported first: the loader then binds libdynlp's libamdhip64.so.7 dependency to the copy that
+    # is already resident, and tensors, streams and this library share one runtime.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = ct.CDLL(path)
     p, i32, i64, f32 = ct.c_void_p, ct.c_int32, ct.c_int64, ct.c_float
     L.dynlp_default_options.argtypes = [ct.POINTER(Options)]
