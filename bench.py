@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the DynLP batch-update path on one MI355X.
+
+A *step* is one pass of the whole hot path over one synthetic insertion batch:
+dynlp_apply_batch (edge insertion + degree update, seed clamping, frontier seeding, the
+frontier-restricted propagation loop to an empty frontier) followed by dynlp_get_labels (argmax).
+All inputs are resident in HBM before the timed region (device-pointer mode of the C ABI).
+
+Prints ONE JSON line: metric = inserted undirected edges per second over the timed steps, plus
+  "roofline"     algorithmic bytes of the frontier row-update kernel / its device time (HIP events
+                 on the launch stream, collected inside the library), against the 8 TB/s HBM peak;
+  "cpu_baseline" the CPU oracle (plain C, OpenMP over rows) timed on a bounded sample of the same
+                 batch on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(rows: int, edges: int, C: int) -> int:
+    """Per frontier row of length k: queue entry + row meta (20) + k (col, w) pairs (8k) + k gathered
+    neighbour rows (4C each) + own old row and new row (8C).  Summed over rows: edges = sum of k."""
+    return 8 * edges + 4 * C * (edges + 2 * rows) + 20 * rows
+
+
+def build_workload(name: str, batch_frac: float, num_batches: int):
+    import workloads as W
+
+    cfg = W.CONFIGS[name]
+    p = W.make_config(name)
+    base = dict(n=p.n, C=p.C, row_ptr=p.row_ptr, col=p.col, w=p.w, seed_vertex=p.seed_vertex,
+                seed_class=p.seed_class)
+    batches = []
+    if cfg["kind"] == "sbm":
+        k = max(1, int(round(batch_frac * cfg["n"])))
+        for _ in range(num_batches):
+            batches.append(W.sbm_vertex_batch(p, k, cfg["batch_degree"], cfg["seed_frac"]))
+        label = f"{name}: SBM n={cfg['n']} C={cfg['C']} mean degree {cfg['mean_degree']:g}, batches of {k} new vertices x degree {cfg['batch_degree']}"
+    elif cfg["kind"] == "sbm-edge-stream":
+        for _ in range(num_batches):
+            batches.append(W.sbm_edge_batch(p, cfg["edges_per_batch"], cfg["intra_frac"], cfg["revealed_per_batch"]))
+        label = f"{name}: SBM n={cfg['n']} C={cfg['C']}, edge-only batches of {cfg['edges_per_batch']} edges + {cfg['revealed_per_batch']} revealed seeds"
+    elif cfg["kind"] == "knn":
+        k = max(1, int(round(batch_frac * cfg["n"])))
+        for _ in range(num_batches):
+            batches.append(W.knn_mixture_batch(p, k, max(1, int(round(cfg["seed_frac"] * k)))))
+        label = f"{name}: kNN mixture n={cfg['n']} C={cfg['C']} k={cfg['k']}, batches of {k} new points"
+    elif cfg["kind"] == "chung_lu":
+        k = max(1, int(round(batch_frac * cfg["n"])))
+        for _ in range(num_batches):
+            batches.append(W.chung_lu_vertex_batch(p, k, cfg["seed_frac"]))
+        label = f"{name}: Chung-Lu n={cfg['n']} C={cfg['C']} mean degree {cfg['mean_degree']:g}, batches of {k} new vertices"
+    else:
+        raise KeyError(name)
+    return cfg, base, batches, label
+
+
+def cpu_baseline(base, batches_applied, batch, F_before, tol, gpu_edges_traversed, budget_s):
+    """Oracle Step 3 on the host cores for the first rounds of ``batch`` (bounded by budget_s),
+    scaled to the metric's unit with the total work the GPU needed for the same batch."""
+    from oracle import native as ON
+    from oracle import reference as R
+
+    g = R.Graph(base["n"], base["row_ptr"], base["col"], base["w"], base["C"], base["seed_vertex"], base["seed_class"])
+    for b in batches_applied:
+        g.insert(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+    n_old = g.n
+    g.insert(batch.num_new_vertices, batch.eu, batch.ev, batch.ew, batch.seed_vertex, batch.seed_class)
+    rp, col, w = g.csr()
+    F = np.concatenate([F_before.astype(np.float64), np.full((batch.num_new_vertices, g.C), 1.0 / g.C)])
+    s = np.asarray(batch.seed_vertex, dtype=np.int64)
+    F[s] = 0
+    F[s, np.asarray(batch.seed_class, dtype=np.int64)] = 1
+    A0 = ON.affected_set(rp, col, g.seed_class, n_old, batch.eu, batch.ev, batch.seed_vertex)
+    # probe two rounds to size the sample, then one run of as many rounds as the budget allows
+    t0 = time.perf_counter()
+    out = ON.step3_propagate(rp, col, w, F, g.seed_class, A0, tol, 2, record=16)
+    probe = time.perf_counter() - t0
+    want = int(max(2, min(100000, 0.8 * budget_s / max(probe / 2, 1e-4))))
+    t0 = time.perf_counter()
+    out = ON.step3_propagate(rp, col, w, F, g.seed_class, A0, tol, want, record=16)
+    t_used = time.perf_counter() - t0
+    rounds, edges = out["rounds"], out["edges_traversed"]
+    edges_per_s = edges / max(t_used, 1e-9)
+    est_latency = gpu_edges_traversed / max(edges_per_s, 1e-9)
+    return dict(value=batch.num_edges / est_latency, unit="edges/s", cores=ON.num_threads(), kind="oracle",
+                sample=f"oracle Step 3 (float64, C + OpenMP) on the first {rounds} rounds of one batch: "
+                       f"{edges} CSR entries traversed in {t_used:.2f} s = {edges_per_s / 1e6:.1f} M entries/s; "
+                       f"whole-batch latency extrapolated to the {gpu_edges_traversed} entries the full update traverses "
+                       f"= {est_latency:.1f} s",
+                traversed_entries_per_s=edges_per_s)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--batch-frac", type=float, default=0.01, help="new vertices per batch as a fraction of n")
+    ap.add_argument("--tol", type=float, default=None, help="threshold delta (default: the workload's)")
+    ap.add_argument("--group-lanes", type=int, default=0)
+    ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of CPU oracle work (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (one process, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2604_06596_amd as P
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU: libdynlp has no CPU path", file=sys.stderr)
+        sys.exit(3)
+    if not os.path.exists(P.library_path()):
+        P.build()
+    dev = torch.device("cuda:0")
+    t_gen = time.perf_counter()
+    cfg, base, batches, label = build_workload(args.workload, args.batch_frac, args.warmup + args.steps)
+    tol = float(args.tol if args.tol is not None else cfg["tol"])
+    t_gen = time.perf_counter() - t_gen
+
+    def dv(a, dt):
+        return torch.from_numpy(np.ascontiguousarray(a)).to(dt).to(dev)
+
+    d_batches = [dict(k=b.num_new_vertices, eu=dv(b.eu, torch.int32), ev=dv(b.ev, torch.int32),
+                      ew=dv(b.ew, torch.float32), sv=dv(b.seed_vertex, torch.int32), sc=dv(b.seed_class, torch.int32))
+                 for b in batches]
+    tot_v = sum(b.num_new_vertices for b in batches)
+    tot_e = sum(b.num_edges for b in batches)
+    d = P.DynLP(base["n"], dv(base["row_ptr"], torch.int64), dv(base["col"], torch.int32), dv(base["w"], torch.float32),
+                base["C"], dv(base["seed_vertex"], torch.int32), dv(base["seed_class"], torch.int32),
+                device_ptrs=True, reserve_vertices=tot_v + 1024, reserve_edges=2 * tot_e + 1024, time_kernels=True,
+                group_lanes=args.group_lanes)
+    st, s0 = d.static_solve(tol, cfg["max_iter"])
+    cold = dict(status=st, sweeps=s0.iterations, ms=s0.ms_total, ms_update_kernel=s0.ms_update_kernel,
+                algorithmic_gbs=algorithmic_bytes(s0.rows_updated, s0.edges_traversed, base["C"]) / 1e6 /
+                max(s0.ms_update_kernel, 1e-9))
+    F_before = None
+    per_step = []
+    for i, b in enumerate(d_batches):
+        timed = i >= args.warmup
+        if i == args.warmup and args.cpu_budget > 0:
+            F_before = d.get_labels(soft=True, hard=False)[0].cpu().numpy()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        st, s = d.apply_batch(b["k"], b["eu"], b["ev"], b["ew"], b["sv"], b["sc"])
+        _, hard = d.get_labels(soft=False, hard=True)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        if timed:
+            per_step.append(dict(ms=dt * 1e3, status=st, edges=batches[i].num_edges, **s.as_dict()))
+    total_s = sum(x["ms"] for x in per_step) / 1e3
+    edges_inserted = sum(x["edges"] for x in per_step)
+    rows = sum(x["rows_updated"] for x in per_step)
+    trav = sum(x["edges_traversed"] for x in per_step)
+    k_ms = sum(x["ms_update_kernel"] for x in per_step)
+    launches = sum(x["update_launches"] for x in per_step)
+    alg_bytes = algorithmic_bytes(rows, trav, base["C"])
+    achieved = alg_bytes / 1e6 / max(k_ms, 1e-9)  # GB/s
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"row_update_{args.workload}_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+    out = {
+        "metric": "dynlp_batch_update_inserted_edges_per_s",
+        "value": edges_inserted / total_s,
+        "unit": "edges/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": total_s * 1e3 / max(1, len(per_step)),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": label, "tol": tol, "edges_per_batch": edges_inserted // max(1, len(per_step)),
+                   "vertices_after": d.num_vertices, "directed_entries_after": d.num_entries},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "k_row_update (frontier row update)", "launches": launches,
+                     "avg_launch_us": k_ms * 1e3 / max(1, launches),
+                     "algorithmic_bytes_per_launch": alg_bytes / max(1, launches)},
+        "detail": {"rounds_per_step": [x["iterations"] for x in per_step],
+                   "frontier_initial": [x["frontier_initial"] for x in per_step],
+                   "frontier_peak": [x["frontier_peak"] for x in per_step],
+                   "traversed_entries_per_s": trav / total_s,
+                   "ms_insert": [round(x["ms_insert"], 3) for x in per_step],
+                   "ms_seed": [round(x["ms_seed"], 3) for x in per_step],
+                   "ms_iterate": [round(x["ms_iterate"], 3) for x in per_step],
+                   "ms_update_kernel": [round(x["ms_update_kernel"], 3) for x in per_step],
+                   "status": [x["status"] for x in per_step],
+                   "cold_start": cold, "gen_s": round(t_gen, 1)},
+    }
+    if args.cpu_budget > 0 and per_step:
+        out["cpu_baseline"] = cpu_baseline(base, batches[:args.warmup], batches[args.warmup], F_before, tol,
+                                           per_step[0]["edges_traversed"], args.cpu_budget)
+    else:
+        out["cpu_baseline"] = None
+    d.destroy()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
