@@ -14,6 +14,7 @@
 
 #include "dynlp.h"
 #include "dynlp_kernels.h"
+#include "dynlp_frontier.h"
 
 using namespace dynlp;
 
@@ -78,7 +79,10 @@ struct dynlp_ctx {
     float* F2 = nullptr;  // second buffer: ping-pong partner (static) / staging by queue position (dynamic)
     int32_t* seed_class = nullptr;
     uint8_t* flag = nullptr;
-    int32_t* queue[2] = {nullptr, nullptr};
+    int32_t* queue[2] = {nullptr, nullptr};  // frontier storage, two parities (see dynlp_frontier.h)
+    uint8_t* changed = nullptr;               // per frontier position: row moved by more than tol
+    int64_t updatable = -1;                   // vertices that can be updated (unlabelled, >= 1 edge)
+    bool f2_synced = false;                   // F2 agrees with F on all rows a full sweep skips
     int32_t* add_cnt = nullptr;
     float* deg = nullptr;
 
@@ -203,6 +207,7 @@ void alloc_vertex_arrays(dynlp_ctx* c, int64_t new_cap) {
     uint8_t* flag = dev_alloc_n<uint8_t>(c, flag_cap);
     int32_t* q0 = dev_alloc_n<int32_t>(c, new_cap);
     int32_t* q1 = dev_alloc_n<int32_t>(c, new_cap);
+    uint8_t* chg = dev_alloc_n<uint8_t>(c, new_cap);
     int32_t* add = dev_alloc_n<int32_t>(c, new_cap);
     float* deg = dev_alloc_n<float>(c, new_cap);
     HIPCHK(c, hipMemsetAsync(flag, 0, (size_t)flag_cap, c->stream));
@@ -221,8 +226,11 @@ void alloc_vertex_arrays(dynlp_ctx* c, int64_t new_cap) {
     dev_free(c, c->flag);
     dev_free(c, c->queue[0]);
     dev_free(c, c->queue[1]);
+    dev_free(c, c->changed);
     dev_free(c, c->add_cnt);
     dev_free(c, c->deg);
+    c->changed = chg;
+    c->f2_synced = false;
     c->meta = meta;
     c->F = F;
     c->F2 = F2;
@@ -285,37 +293,67 @@ void ensure_batch_scratch(dynlp_ctx* c, int64_t m, int64_t s) {
     }
 }
 
-// ---- row-update launch ---------------------------------------------------------------------------
+// ---- frontier launches ---------------------------------------------------------------------------
 int lanes_per_neighbour(int CP) { return CP >= 4 ? CP / 4 : 1; }
 
 int choose_group(const dynlp_ctx* c, double avg_len) {
     const int lpn = lanes_per_neighbour(c->CP);
     if (c->group_lanes) return std::max(c->group_lanes, lpn);
-    int slots = 1;
-    while (slots * 2 <= avg_len * 0.75 && slots * lpn < kWave) slots *= 2;
-    return std::max(4, std::min(kWave, slots * lpn));
+    // Measured on MI355X (1M-vertex graph, mean row length 20, C = 4 .. 50): 16 lanes per row is the
+    // fastest or within 2% of it for every padded class count; wider groups only pay off when the
+    // typical row fills several 16-entry chunks.
+    int g = 16;
+    if (avg_len >= 96.0) g = 32;
+    if (avg_len >= 384.0) g = 64;
+    return std::max(g, lpn);
 }
 
-template <int CP, int G, bool STATIC>
-void launch_update_inst(dynlp_ctx* c, const int32_t* queue, unsigned int nq, const float* F_in, float* F_out,
-                        float tol, RoundCtr* ctr, RoundCtr* ctr_zero) {
+// One propagation round's frontier: ns short rows at front[0..ns), nl long rows at back[0..-nl).
+struct Frontier {
+    int32_t* front = nullptr;
+    int32_t* back = nullptr;
+    unsigned int ns = 0, nl = 0;
+    unsigned int size() const { return ns + nl; }
+};
+
+Frontier frontier_of(dynlp_ctx* c, int parity, unsigned int ns = 0, unsigned int nl = 0) {
+    Frontier f;
+    f.front = c->queue[parity];
+    f.back = c->queue[parity] + (c->n_cap - 1);
+    f.ns = ns;
+    f.nl = nl;
+    return f;
+}
+
+struct UpdateArgs {
+    const float* F_in;
+    float* F_out;
+    uint8_t* changed;  // NULL in static sweeps and staged rounds
+    float tol;
+    RoundCtr* ctr;
+    RoundCtr* ctr_zero;
+};
+
+template <int CP, int G, bool STAGED>
+void launch_short_inst(dynlp_ctx* c, const Frontier& f, const UpdateArgs& a) {
     constexpr int GPB = kBlock / G;
-    const int64_t want = ceil_div(nq, GPB);
+    const int64_t want = ceil_div(f.ns, GPB);
     const unsigned int blocks = (unsigned int)std::max<int64_t>(1, std::min<int64_t>(want, (int64_t)c->num_cu * 8));
-    hipLaunchKernelGGL((k_row_update<CP, G, STATIC>), dim3(blocks), dim3(kBlock), 0, c->stream, queue, nq, c->meta,
-                       c->pool, F_in, F_out, c->flag, tol, ctr, ctr_zero);
+    hipLaunchKernelGGL((k_row_update<CP, G, STAGED>), dim3(blocks), dim3(kBlock), 0, c->stream, f.front, f.ns, c->meta,
+                       c->pool, a.F_in, a.F_out, c->flag, a.changed, a.tol, a.ctr, a.ctr_zero);
 }
 
-template <int CP, bool STATIC>
-void launch_update_cp(dynlp_ctx* c, int G, const int32_t* queue, unsigned int nq, const float* F_in, float* F_out,
-                      float tol, RoundCtr* ctr, RoundCtr* ctr_zero) {
+template <int CP, bool STAGED>
+void launch_update_cp(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& a) {
     constexpr int LPN = CP >= 4 ? CP / 4 : 1;
-#define DYNLP_CASE(GV)                                                                            \
-    case GV:                                                                                      \
-        if constexpr (GV >= LPN) {                                                                \
-            launch_update_inst<CP, GV, STATIC>(c, queue, nq, F_in, F_out, tol, ctr, ctr_zero);    \
-            return;                                                                               \
-        }                                                                                         \
+    // the short-row kernel always runs (it also clears the next counter slot)
+    bool done = false;
+#define DYNLP_CASE(GV)                                              \
+    case GV:                                                        \
+        if constexpr (GV >= LPN) {                                  \
+            launch_short_inst<CP, GV, STAGED>(c, f, a);             \
+            done = true;                                            \
+        }                                                           \
         break;
     switch (G) {
         DYNLP_CASE(4)
@@ -326,12 +364,18 @@ void launch_update_cp(dynlp_ctx* c, int G, const int32_t* queue, unsigned int nq
         default: break;
     }
 #undef DYNLP_CASE
-    launch_update_inst<CP, 64, STATIC>(c, queue, nq, F_in, F_out, tol, ctr, ctr_zero);
+    if (!done) launch_short_inst<CP, 64, STAGED>(c, f, a);
+    if (f.nl) {
+        const unsigned int blocks = (unsigned int)std::min<int64_t>(f.nl, (int64_t)c->num_cu * 8);
+        hipLaunchKernelGGL((k_row_update_long<CP, STAGED>), dim3(blocks), dim3(kBlock), 0, c->stream, f.back, f.nl,
+                           f.ns, c->meta, c->pool, a.F_in, a.F_out, c->flag, a.changed, a.tol, a.ctr);
+    }
 }
 
-template <bool STATIC>
-void launch_update(dynlp_ctx* c, int G, const int32_t* queue, unsigned int nq, const float* F_in, float* F_out,
-                   float tol, RoundCtr* ctr, RoundCtr* ctr_zero) {
+// Row update of one frontier (short-row launch + long-row launch), bracketed by events when
+// kernel timing is on.
+template <bool STAGED>
+void launch_update(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& a) {
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (c->time_kernels) {
         while (c->events.size() < c->events_used + 2) {
@@ -344,13 +388,13 @@ void launch_update(dynlp_ctx* c, int G, const int32_t* queue, unsigned int nq, c
         HIPCHK(c, hipEventRecord(e0, c->stream));
     }
     switch (c->CP) {
-        case 1: launch_update_cp<1, STATIC>(c, G, queue, nq, F_in, F_out, tol, ctr, ctr_zero); break;
-        case 2: launch_update_cp<2, STATIC>(c, G, queue, nq, F_in, F_out, tol, ctr, ctr_zero); break;
-        case 4: launch_update_cp<4, STATIC>(c, G, queue, nq, F_in, F_out, tol, ctr, ctr_zero); break;
-        case 8: launch_update_cp<8, STATIC>(c, G, queue, nq, F_in, F_out, tol, ctr, ctr_zero); break;
-        case 16: launch_update_cp<16, STATIC>(c, G, queue, nq, F_in, F_out, tol, ctr, ctr_zero); break;
-        case 32: launch_update_cp<32, STATIC>(c, G, queue, nq, F_in, F_out, tol, ctr, ctr_zero); break;
-        default: launch_update_cp<64, STATIC>(c, G, queue, nq, F_in, F_out, tol, ctr, ctr_zero); break;
+        case 1: launch_update_cp<1, STAGED>(c, G, f, a); break;
+        case 2: launch_update_cp<2, STAGED>(c, G, f, a); break;
+        case 4: launch_update_cp<4, STAGED>(c, G, f, a); break;
+        case 8: launch_update_cp<8, STAGED>(c, G, f, a); break;
+        case 16: launch_update_cp<16, STAGED>(c, G, f, a); break;
+        case 32: launch_update_cp<32, STAGED>(c, G, f, a); break;
+        default: launch_update_cp<64, STAGED>(c, G, f, a); break;
     }
     HIPCHK(c, hipGetLastError());
     if (c->time_kernels) HIPCHK(c, hipEventRecord(e1, c->stream));
@@ -366,19 +410,48 @@ float collect_kernel_ms(dynlp_ctx* c) {
     return total;
 }
 
-// Compaction launch; commit_nq > 0 also commits the staged rows of queue_cur.
-void launch_commit_compact(dynlp_ctx* c, const int32_t* queue_cur, unsigned int commit_nq, int32_t* queue_next,
-                           unsigned int* next_count, int all_rows) {
-    unsigned int commit_blocks = 0;
-    if (commit_nq) {
-        const int64_t items = (int64_t)commit_nq * (c->CP >= 4 ? c->CP / 4 : c->CP);
-        commit_blocks = (unsigned int)std::min<int64_t>(ceil_div(items, kBlock), (int64_t)c->num_cu * 8);
-    }
-    const unsigned int compact_blocks = (unsigned int)ceil_div(std::max<int64_t>(c->n, 1), kFlagsPerBlock);
-    hipLaunchKernelGGL(k_commit_compact, dim3(commit_blocks + compact_blocks), dim3(kBlock), 0, c->stream, queue_cur,
-                       commit_nq, c->F2, c->F, c->CP, commit_blocks, (unsigned int)c->n, c->flag, c->seed_class,
-                       c->meta, queue_next, next_count, all_rows);
+// flag bytes (or, with all_rows, every updatable vertex) -> frontier `out`; the two counts land in
+// *count_short / *count_long, which must be zero beforehand.
+void launch_compact(dynlp_ctx* c, const Frontier& out, unsigned int* count_short, unsigned int* count_long,
+                    int all_rows) {
+    const unsigned int blocks = (unsigned int)ceil_div(std::max<int64_t>(c->n, 1), kFlagsPerBlock);
+    hipLaunchKernelGGL(k_compact, dim3(blocks), dim3(kBlock), 0, c->stream, (unsigned int)c->n, c->flag, c->seed_class,
+                       c->meta, all_rows, out.front, out.back, count_short, count_long);
     HIPCHK(c, hipGetLastError());
+}
+
+void launch_commit(dynlp_ctx* c, const Frontier& f) {
+    const int64_t items = (int64_t)f.size() * (c->CP >= 4 ? c->CP / 4 : c->CP);
+    const unsigned int blocks = (unsigned int)std::max<int64_t>(1, std::min<int64_t>(ceil_div(items, kBlock), (int64_t)c->num_cu * 8));
+    hipLaunchKernelGGL(k_commit, dim3(blocks), dim3(kBlock), 0, c->stream, f.ns, f.nl, f.front, f.back, c->F2, c->F, c->CP);
+    HIPCHK(c, hipGetLastError());
+}
+
+void launch_expand(dynlp_ctx* c, const Frontier& f) {
+    const unsigned int blocks = (unsigned int)std::max<int64_t>(1, std::min<int64_t>(ceil_div(f.size(), kBlock / 16), (int64_t)c->num_cu * 8));
+    hipLaunchKernelGGL(k_expand, dim3(blocks), dim3(kBlock), 0, c->stream, f.ns, f.nl, f.front, f.back, c->changed,
+                       c->meta, c->pool, c->flag);
+    HIPCHK(c, hipGetLastError());
+}
+
+// The ping-pong partner must agree with F on every row a full sweep does not write (seeds,
+// isolated vertices) before it can receive one.
+void sync_partner(dynlp_ctx* c) {
+    if (c->f2_synced) return;
+    if (c->n > 0)
+        HIPCHK(c, hipMemcpyAsync(c->F2, c->F, (size_t)c->n * c->CP * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
+    c->f2_synced = true;
+}
+
+// Every updatable vertex (unlabelled, at least one edge) into the frontier of the given parity.
+Frontier all_updatable(dynlp_ctx* c, int parity) {
+    Frontier f = frontier_of(c, parity);
+    HIPCHK(c, hipMemsetAsync(&c->bc->init_count, 0, 2 * sizeof(unsigned int), c->stream));
+    launch_compact(c, f, &c->bc->init_count, &c->bc->init_long, 1);
+    read_bc(c);
+    f.ns = c->h_bc->init_count;
+    f.nl = c->h_bc->init_long;
+    return f;
 }
 
 void zero_ring(dynlp_ctx* c) {
@@ -439,7 +512,7 @@ void destroy_ctx(dynlp_ctx* c) {
     if (!c) return;
     (void)hipSetDevice(c->device);
     if (c->stream || c->meta) (void)hipStreamSynchronize(c->stream);
-    void* ptrs[] = {c->meta, c->pool, c->F, c->F2, c->seed_class, c->flag, c->queue[0], c->queue[1], c->add_cnt,
+    void* ptrs[] = {c->meta, c->pool, c->F, c->F2, c->seed_class, c->flag, c->queue[0], c->queue[1], c->changed, c->add_cnt,
                     c->deg, c->touched, c->reloc_off, c->b_eu, c->b_ev, c->b_ew, c->b_sv, c->b_sc};
     for (void* p : ptrs) dev_free(c, p);
     if (c->ring) (void)hipFree(c->ring);
@@ -685,15 +758,11 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
         c->log_sizes.clear();
         c->log_delta.clear();
         c->events_used = 0;
-        // the partner buffer must agree on the rows no sweep writes (seeds, isolated vertices)
-        if (c->n > 0)
-            HIPCHK(c, hipMemcpyAsync(c->F2, c->F, (size_t)c->n * c->CP * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
+        sync_partner(c);
         zero_ring(c);
-        c->h_bc->init_count = 0;
-        HIPCHK(c, hipMemsetAsync(&c->bc->init_count, 0, sizeof(unsigned int), c->stream));
-        launch_commit_compact(c, nullptr, 0, c->queue[0], &c->bc->init_count, 1);
-        read_bc(c);
-        const unsigned int nq = c->h_bc->init_count;
+        const Frontier f = all_updatable(c, 0);
+        c->updatable = f.size();
+        const unsigned int nq = f.size();
         int it = 0;
         float last = 0.f;
         bool converged = nq == 0;
@@ -701,8 +770,8 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
         const int G = choose_group(c, c->n > 0 ? (double)c->entries / (double)std::max<int64_t>(1, nq) : 1.0);
         const auto t_it = Clock::now();
         while (!converged && it < max_iter) {
-            launch_update<true>(c, G, c->queue[0], nq, c->F, c->F2, tol, c->ring + (it % kRing),
-                                c->ring + ((it + 1) % kRing));
+            const UpdateArgs a{c->F, c->F2, nullptr, tol, c->ring + (it % kRing), c->ring + ((it + 1) % kRing)};
+            launch_update<false>(c, G, f, a);
             const RoundCtr r = read_slot(c, it);
             std::swap(c->F, c->F2);
             std::memcpy(&last, &r.resid_bits, sizeof(float));
@@ -846,40 +915,82 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
             hipLaunchKernelGGL(k_apply_seeds, dim3(grid_for(s * 16)), dim3(kBlock), 0, c->stream, s, d_sv, d_sc, c->C, c->CP,
                                c->seed_class, c->F, c->meta, c->pool, c->flag);
         zero_ring(c);
-        launch_commit_compact(c, nullptr, 0, c->queue[0], &c->bc->init_count, 0);
+        // first frontier from the flags; and the census of updatable vertices (into the other parity,
+        // as scratch) that tells later rounds when the frontier is "everything"
+        Frontier f = frontier_of(c, 0);
+        launch_compact(c, f, &c->bc->init_count, &c->bc->init_long, 0);
+        launch_compact(c, frontier_of(c, 1), &c->bc->upd_short, &c->bc->upd_long, 1);
         read_bc(c);
         c->pool_tail = (int64_t)c->h_bc->pool_tail;
         const int64_t relocated = c->h_bc->relocated;
-        unsigned int nq = c->h_bc->init_count;
+        f.ns = c->h_bc->init_count;
+        f.nl = c->h_bc->init_long;
+        c->updatable = (int64_t)c->h_bc->upd_short + (int64_t)c->h_bc->upd_long;
+        if (k > 0 || s > 0) c->f2_synced = false;  // rows no sweep writes have changed in F
         HIPCHK(c, hipEventRecord(c->phase_ev[2], c->stream));
 
         // ---- Step 3: rounds over V_aff ----
-        const int64_t frontier_initial = nq;
-        int64_t peak = nq, rows = 0, edges = 0;
+        const int64_t frontier_initial = f.size();
+        int64_t peak = f.size(), rows = 0, edges = 0;
         int it = 0, cur = 0;
         float last = 0.f;
         double avg_len = c->n > 0 ? (double)c->entries / (double)c->n : 1.0;
-        while (nq > 0 && it < c->max_iter) {
+        while (f.size() > 0 && it < c->max_iter) {
+            const unsigned int nq = f.size();
             const int G = choose_group(c, avg_len);
             RoundCtr* slot = c->ring + (it % kRing);
-            launch_update<false>(c, G, c->queue[cur], nq, c->F, c->F2, c->tol, slot, c->ring + ((it + 1) % kRing));
-            launch_commit_compact(c, c->queue[cur], nq, c->queue[cur ^ 1], &slot->next_count, 0);
-            const RoundCtr r = read_slot(c, it);
+            RoundCtr* next_slot = c->ring + ((it + 1) % kRing);
+            RoundCtr r;
+            bool same_frontier = false;
+            if ((int64_t)nq == c->updatable) {
+                // Full round: every updatable row is in V_aff, so the new rows go straight into the
+                // ping-pong partner (no staging, no commit).  If every row moved by more than tol the
+                // next V_aff is the same set again and nothing else has to run.
+                sync_partner(c);
+                const UpdateArgs a{c->F, c->F2, c->changed, c->tol, slot, next_slot};
+                launch_update<false>(c, G, f, a);
+                std::swap(c->F, c->F2);
+                r = read_slot(c, it);
+                if (r.changed == nq) {
+                    same_frontier = true;
+                } else {
+                    launch_expand(c, f);
+                    Frontier nf = frontier_of(c, cur ^ 1);
+                    launch_compact(c, nf, &slot->next_count, &slot->next_long, 0);
+                    const RoundCtr r2 = read_slot(c, it);
+                    nf.ns = r2.next_count;
+                    nf.nl = r2.next_long;
+                    f = nf;
+                    cur ^= 1;
+                }
+            } else {
+                // Partial round: rows are staged by frontier position, committed after the kernel, and
+                // the rows that moved mark themselves and their neighbours for the next round.
+                const UpdateArgs a{c->F, c->F2, nullptr, c->tol, slot, next_slot};
+                launch_update<true>(c, G, f, a);
+                c->f2_synced = false;
+                launch_commit(c, f);
+                Frontier nf = frontier_of(c, cur ^ 1);
+                launch_compact(c, nf, &slot->next_count, &slot->next_long, 0);
+                r = read_slot(c, it);
+                nf.ns = r.next_count;
+                nf.nl = r.next_long;
+                f = nf;
+                cur ^= 1;
+            }
+            (void)same_frontier;
             std::memcpy(&last, &r.resid_bits, sizeof(float));
             rows += nq;
             edges += (int64_t)r.edges;
             avg_len = nq ? (double)r.edges / (double)nq : avg_len;
             c->log_sizes.push_back(nq);
             c->log_delta.push_back(last);
-            nq = r.next_count;
-            peak = std::max<int64_t>(peak, nq);
-            cur ^= 1;
+            peak = std::max<int64_t>(peak, f.size());
             ++it;
         }
+        const unsigned int nq = f.size();
         HIPCHK(c, hipEventRecord(c->phase_ev[3], c->stream));
         HIPCHK(c, hipStreamSynchronize(c->stream));
-        if (nq > 0) {  // cut by max_iter: the flags were consumed by the last compaction; nothing is pending
-        }
         if (stats) {
             stats->iterations = it;
             stats->converged = nq == 0 ? 1 : 0;

@@ -27,10 +27,10 @@ struct __attribute__((aligned(16))) RowMeta {
 
 // Counters one propagation round leaves for the host (one slot of a small ring).
 struct __attribute__((aligned(32))) RoundCtr {
-    unsigned int next_count;   // |V_aff| for the next round (written by compaction)
+    unsigned int next_count;   // short rows of V_aff for the next round (written by compaction)
     unsigned int resid_bits;   // max change of this round, float bits (non-negative floats order as uints)
     unsigned int changed;      // rows whose change exceeded tol
-    unsigned int pad0;
+    unsigned int next_long;    // long rows of V_aff for the next round
     unsigned long long edges;  // CSR entries traversed by the row update
     unsigned long long pad1;
 };
@@ -44,10 +44,11 @@ struct __attribute__((aligned(64))) BatchCtr {
     int err_code;                    // 0 = none; first validation error wins
     int err_pad;
     long long err_index;             // index of the offending item
-    unsigned int init_count;         // size of the first frontier
-    unsigned int pad0;
+    unsigned int init_count;         // first frontier: short rows
+    unsigned int init_long;          //                 long rows
     unsigned long long scan_total;   // grand total of the last block-sum scan
-    unsigned long long pad1;
+    unsigned int upd_short;          // updatable vertices (unlabelled, >= 1 edge): short rows
+    unsigned int upd_long;           //                                              long rows
 };
 
 enum ValidationError : int {

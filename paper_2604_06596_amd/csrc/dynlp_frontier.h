@@ -1,0 +1,401 @@
+// Frontier kernels of DynLP for gfx950: compaction of V_aff into queues, the frontier row update
+// (the hot kernel), the Jacobi commit of staged rows and the expansion of V_aff (Alg. 2 Step 3).
+#pragma once
+
+#include "dynlp_device.h"
+
+namespace dynlp {
+
+constexpr int kFlagsPerThread = 16;
+constexpr int kFlagsPerBlock = kBlock * kFlagsPerThread;  // 4096
+constexpr int kLongRow = 512;  // rows longer than this get a whole workgroup
+
+#ifndef DYNLP_UN_CAP
+#define DYNLP_UN_CAP 8
+#endif
+
+// A frontier is stored in one int32 array of n_cap entries: "short" rows (len <= kLongRow) from
+// the front, position i at front[i]; "long" rows from the back, position j at back[-j] with
+// back = front + n_cap - 1.  The two never meet because a frontier has at most n entries.
+// Row i of the frontier (short rows first, then long rows) has *position* i; staged label rows
+// and changed-bytes are indexed by position.
+__device__ inline int32_t frontier_vertex(const int32_t* front, const int32_t* back, unsigned int ns,
+                                          unsigned int pos) {
+    return pos < ns ? front[pos] : back[-(long long)(pos - ns)];
+}
+
+// =================================================================================================
+// Compaction: flag bytes -> next frontier
+// =================================================================================================
+// Each workgroup scans kFlagsPerBlock flag bytes, keeps the vertices that may be updated
+// (unlabelled, at least one edge), reserves ranges of the short and the long queue with one atomic
+// each, writes the ids in ascending order inside its ranges, and clears the flags it read.
+// all_rows != 0 ignores the flags and lists every updatable vertex (static solve, and the count of
+// updatable vertices).
+__global__ void __launch_bounds__(kBlock) k_compact(unsigned int n, uint8_t* __restrict__ flag,
+                                                   const int32_t* __restrict__ seed_class,
+                                                   const RowMeta* __restrict__ meta, int all_rows,
+                                                   int32_t* __restrict__ front, int32_t* __restrict__ back,
+                                                   unsigned int* __restrict__ count_short,
+                                                   unsigned int* __restrict__ count_long) {
+    __shared__ unsigned long long sm[kBlock / kWave + 1];
+    __shared__ unsigned int sbase[2];
+    const unsigned int v0 = blockIdx.x * kFlagsPerBlock + threadIdx.x * kFlagsPerThread;
+    unsigned int keep = 0, is_long = 0;  // bit k: vertex v0+k enters the frontier / as a long row
+    if (v0 < n) {
+        unsigned int cand = 0;
+        if (all_rows) {
+            cand = 0xffffu;
+        } else {
+            const uint4 f = *reinterpret_cast<const uint4*>(flag + v0);
+            if ((f.x | f.y | f.z | f.w) != 0) {
+                const unsigned int wds[4] = {f.x, f.y, f.z, f.w};
+#pragma unroll
+                for (int k = 0; k < kFlagsPerThread; ++k)
+                    if ((wds[k >> 2] >> ((k & 3) * 8)) & 0xffu) cand |= 1u << k;
+                *reinterpret_cast<uint4*>(flag + v0) = make_uint4(0, 0, 0, 0);
+            }
+        }
+        while (cand) {
+            const int k = __ffs(cand) - 1;
+            cand &= cand - 1;
+            const unsigned int v = v0 + k;
+            if (v < n && seed_class[v] < 0) {
+                const int len = meta[v].len;
+                if (len > 0) {
+                    keep |= 1u << k;
+                    if (len > kLongRow) is_long |= 1u << k;
+                }
+            }
+        }
+    }
+    const unsigned long long cnt =
+        (unsigned long long)__popc(keep & ~is_long) | ((unsigned long long)__popc(is_long) << 32);
+    unsigned long long total;
+    const unsigned long long ex = block_exclusive_scan<unsigned long long>(cnt, sm, &total);
+    if (threadIdx.x == 0) {
+        const unsigned int ts = (unsigned int)total, tl = (unsigned int)(total >> 32);
+        sbase[0] = ts ? atomicAdd(count_short, ts) : 0u;
+        sbase[1] = tl ? atomicAdd(count_long, tl) : 0u;
+    }
+    __syncthreads();
+    unsigned int ps = sbase[0] + (unsigned int)ex;
+    unsigned int pl = sbase[1] + (unsigned int)(ex >> 32);
+    while (keep) {
+        const int k = __ffs(keep) - 1;
+        keep &= keep - 1;
+        if ((is_long >> k) & 1u) back[-(long long)(pl++)] = (int32_t)(v0 + k);
+        else front[ps++] = (int32_t)(v0 + k);
+    }
+}
+
+// =================================================================================================
+// Commit of staged rows (partial rounds) and expansion from changed-bytes (full rounds)
+// =================================================================================================
+// F[vertex at position i] = Fq[i] for all positions: the Jacobi commit of a staged round.
+__global__ void __launch_bounds__(kBlock) k_commit(unsigned int ns, unsigned int nl,
+                                                  const int32_t* __restrict__ front,
+                                                  const int32_t* __restrict__ back,
+                                                  const float* __restrict__ Fq, float* __restrict__ F, int CP) {
+    const unsigned int nq = ns + nl;
+    if (CP >= 4) {
+        const unsigned int vpr = CP / 4;
+        const unsigned long long total = (unsigned long long)nq * vpr;
+        const float4* src = reinterpret_cast<const float4*>(Fq);
+        float4* dst = reinterpret_cast<float4*>(F);
+        for (unsigned long long i = (unsigned long long)blockIdx.x * kBlock + threadIdx.x; i < total;
+             i += (unsigned long long)gridDim.x * kBlock) {
+            const unsigned int pos = (unsigned int)(i / vpr);
+            const unsigned int ch = (unsigned int)(i % vpr);
+            dst[(unsigned long long)frontier_vertex(front, back, ns, pos) * vpr + ch] = src[i];
+        }
+    } else {
+        const unsigned long long total = (unsigned long long)nq * CP;
+        for (unsigned long long i = (unsigned long long)blockIdx.x * kBlock + threadIdx.x; i < total;
+             i += (unsigned long long)gridDim.x * kBlock) {
+            const unsigned int pos = (unsigned int)(i / CP);
+            F[(unsigned long long)frontier_vertex(front, back, ns, pos) * CP + (i % CP)] = Fq[i];
+        }
+    }
+}
+
+__device__ inline void mark(uint8_t* __restrict__ flag, int32_t v) {
+    if (!flag[v]) flag[v] = 1;
+}
+
+// V_aff <- union over changed rows u of {u} U N(u), from the changed-bytes a full round left
+// (16 lanes per frontier position).
+__global__ void __launch_bounds__(kBlock) k_expand(unsigned int ns, unsigned int nl,
+                                                  const int32_t* __restrict__ front,
+                                                  const int32_t* __restrict__ back,
+                                                  const uint8_t* __restrict__ changed,
+                                                  const RowMeta* __restrict__ meta,
+                                                  const Edge* __restrict__ pool, uint8_t* __restrict__ flag) {
+    constexpr int G = 16;
+    const unsigned int nq = ns + nl;
+    const int gl = threadIdx.x % G;
+    for (unsigned int pos = blockIdx.x * (kBlock / G) + threadIdx.x / G; pos < nq; pos += gridDim.x * (kBlock / G)) {
+        if (!changed[pos]) continue;
+        const int32_t u = frontier_vertex(front, back, ns, pos);
+        const RowMeta m = meta[u];
+        if (gl == 0) flag[u] = 1;
+        for (int j = gl; j < m.len; j += G) mark(flag, pool[m.off + j].col);
+    }
+}
+
+// =================================================================================================
+// Frontier row update: the hot kernels (Alg. 2 Step 3 inner loop / one ItLP sweep of Eq. (1))
+// =================================================================================================
+// G lanes cooperate on one frontier row u.  A neighbour row of CP floats is read by LPN = CP/VEC
+// adjacent lanes (VEC = 4 floats = 16 bytes per lane), so the group gathers SLOTS = G/LPN neighbour
+// rows at once, each as one contiguous CP*4-byte segment.  The row's (col, w) pairs are read G at
+// a time with one coalesced 8-byte load per lane and handed round with lane shuffles; UN gathers
+// are issued back to back before their values are used.  Every lane keeps the partial sums of its
+// slot; a butterfly over the slot bits finishes acc = sum_j w_j F[col_j] and s = sum_j w_j.
+template <int CP>
+struct RowShape {
+    static constexpr int VEC = CP >= 4 ? 4 : CP;
+    static constexpr int LPN = CP / VEC;
+};
+
+// Accumulate the chunks first_chunk, first_chunk + chunk_step, ... (G entries each) of one row.
+// Lanes past the end of the row carry a stand-in entry (own row, weight 0).  On return e holds the
+// last chunk this group loaded (or the stand-in if it loaded none).
+template <int CP, int G>
+__device__ inline void accumulate_row(const Edge* __restrict__ row, int len, int first_chunk, int chunk_step,
+                                      int32_t u, const float* __restrict__ F_in, int gl,
+                                      Vec<RowShape<CP>::VEC>& acc, float& s, Edge& e) {
+    constexpr int VEC = RowShape<CP>::VEC;
+    constexpr int LPN = RowShape<CP>::LPN;
+    constexpr int SLOTS = G / LPN;
+    constexpr int UN = LPN < DYNLP_UN_CAP ? LPN : DYNLP_UN_CAP;
+    static_assert(G % LPN == 0 && SLOTS >= 1, "group must hold whole neighbour rows");
+    static_assert(G % (SLOTS * UN) == 0, "a chunk of G entries is a whole number of gather blocks");
+    const int slot = gl / LPN;
+    const int chunk = gl % LPN;
+    for (int base = first_chunk * G; base < len; base += chunk_step * G) {
+        const int idx = base + gl;
+        if (idx < len) {
+            e = row[idx];
+        } else {
+            e.col = u;
+            e.w = 0.f;
+        }
+        const int cnt = len - base;
+#pragma unroll
+        for (int j0 = 0; j0 < G; j0 += SLOTS * UN) {
+            if (j0 < cnt) {  // uniform across the group
+                int32_t c[UN];
+                float w[UN];
+                Vec<VEC> f[UN];
+#pragma unroll
+                for (int t = 0; t < UN; ++t) {
+                    c[t] = __shfl(e.col, j0 + t * SLOTS + slot, G);
+                    w[t] = __shfl(e.w, j0 + t * SLOTS + slot, G);
+                }
+#pragma unroll
+                for (int t = 0; t < UN; ++t) f[t] = load_vec<VEC>(F_in + (size_t)c[t] * CP + chunk * VEC);
+#pragma unroll
+                for (int t = 0; t < UN; ++t) {
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) acc.v[k] = fmaf(w[t], f[t].v[k], acc.v[k]);
+                    s += w[t];
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int d = LPN; d < G; d <<= 1) {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) acc.v[k] += __shfl_xor(acc.v[k], d, G);
+        s += __shfl_xor(s, d, G);
+    }
+}
+
+// Per-workgroup totals -> one set of atomics on the round's counters.
+__device__ inline void flush_round_counters(float rmax, unsigned long long edges, unsigned int changed,
+                                            RoundCtr* __restrict__ ctr) {
+    __shared__ float sm_r[kBlock / kWave];
+    __shared__ unsigned long long sm_e[kBlock / kWave];
+    __shared__ unsigned int sm_c[kBlock / kWave];
+    rmax = wave_max(rmax);
+    edges = wave_sum(edges);
+    changed = wave_sum(changed);
+    if (lane_id() == 0) {
+        sm_r[threadIdx.x / kWave] = rmax;
+        sm_e[threadIdx.x / kWave] = edges;
+        sm_c[threadIdx.x / kWave] = changed;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 1; i < kBlock / kWave; ++i) {
+            rmax = fmaxf(rmax, sm_r[i]);
+            edges += sm_e[i];
+            changed += sm_c[i];
+        }
+        atomicMax(&ctr->resid_bits, __float_as_uint(rmax));
+        if (edges) atomicAdd(&ctr->edges, edges);
+        if (changed) atomicAdd(&ctr->changed, changed);
+    }
+}
+
+// Short rows: G lanes per row, grid-strided.
+//   STAGED = false (static sweep / full round): F'_u is written to row u of F_out, the ping-pong
+//            partner of F_in; changed[pos] (if not NULL) records whether the row moved by > tol.
+//   STAGED = true (partial round): F'_u is staged at row pos of F_out so that every row of this
+//            round reads the round-start F (Jacobi); a row that moved by > tol marks itself and
+//            its neighbours in flag[] for the next round.
+template <int CP, int G, bool STAGED>
+__global__ void __launch_bounds__(kBlock) k_row_update(const int32_t* __restrict__ front, unsigned int ns,
+                                                      const RowMeta* __restrict__ meta,
+                                                      const Edge* __restrict__ pool,
+                                                      const float* __restrict__ F_in, float* __restrict__ F_out,
+                                                      uint8_t* __restrict__ flag, uint8_t* __restrict__ changed_out,
+                                                      float tol, RoundCtr* __restrict__ ctr,
+                                                      RoundCtr* __restrict__ ctr_zero) {
+    constexpr int VEC = RowShape<CP>::VEC;
+    constexpr int LPN = RowShape<CP>::LPN;
+    constexpr int GPB = kBlock / G;
+    if (ctr_zero && blockIdx.x == 0 && threadIdx.x == 0) {
+        ctr_zero->next_count = 0;
+        ctr_zero->next_long = 0;
+        ctr_zero->resid_bits = 0;
+        ctr_zero->changed = 0;
+        ctr_zero->edges = 0;
+    }
+    const int gl = threadIdx.x % G;
+    const int slot = gl / LPN;
+    const int chunk = gl % LPN;
+    float rmax = 0.f;
+    unsigned long long edges = 0;
+    unsigned int nchanged = 0;
+
+    for (unsigned int g = blockIdx.x * GPB + threadIdx.x / G; g < ns; g += gridDim.x * GPB) {
+        const int32_t u = front[g];
+        const RowMeta m = meta[u];
+        const Edge* __restrict__ row = pool + m.off;
+        Vec<VEC> acc;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) acc.v[k] = 0.f;
+        float s = 0.f;
+        Edge e;
+        e.col = u;
+        e.w = 0.f;
+        accumulate_row<CP, G>(row, m.len, 0, 1, u, F_in, gl, acc, s, e);
+        const Vec<VEC> old = load_vec<VEC>(F_in + (size_t)u * CP + chunk * VEC);
+        Vec<VEC> fn;
+        float r = 0.f;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            fn.v[k] = acc.v[k] / s;
+            r = fmaxf(r, fabsf(fn.v[k] - old.v[k]));
+        }
+#pragma unroll
+        for (int d = 1; d < LPN; d <<= 1) r = fmaxf(r, __shfl_xor(r, d, G));
+        if (slot == 0) store_vec<VEC>(F_out + (size_t)(STAGED ? g : (unsigned int)u) * CP + chunk * VEC, fn);
+        const bool big = r > tol;
+        if (STAGED) {
+            if (big) {  // V_aff <- V_aff U {u} U N(u); the last chunk of the row is still in registers
+                if (gl == 0) flag[u] = 1;
+                if (e.w != 0.f) mark(flag, e.col);
+                const int last_base = ((m.len - 1) / G) * G;
+                for (int idx = gl; idx < last_base; idx += G) mark(flag, row[idx].col);
+            }
+        } else if (changed_out && gl == 0) {
+            changed_out[g] = big ? 1 : 0;
+        }
+        if (gl == 0) {
+            rmax = fmaxf(rmax, r);
+            edges += (unsigned long long)m.len;
+            nchanged += big ? 1u : 0u;
+        }
+    }
+    flush_round_counters(rmax, edges, nchanged, ctr);
+}
+
+// Long rows: one workgroup per row.  Its kBlock/G groups take the row's chunks round-robin; their
+// partial sums meet in LDS and are added in group order (a fixed order: results do not depend on
+// timing).  Position of long row j is pos_base + j.
+template <int CP, bool STAGED>
+__global__ void __launch_bounds__(kBlock) k_row_update_long(const int32_t* __restrict__ back, unsigned int nl,
+                                                           unsigned int pos_base,
+                                                           const RowMeta* __restrict__ meta,
+                                                           const Edge* __restrict__ pool,
+                                                           const float* __restrict__ F_in,
+                                                           float* __restrict__ F_out, uint8_t* __restrict__ flag,
+                                                           uint8_t* __restrict__ changed_out, float tol,
+                                                           RoundCtr* __restrict__ ctr) {
+    constexpr int VEC = RowShape<CP>::VEC;
+    constexpr int LPN = RowShape<CP>::LPN;
+    constexpr int G = LPN > 16 ? LPN : 16;
+    constexpr int NG = kBlock / G;
+    __shared__ float part[NG][CP + 1];
+    __shared__ float part_s[NG];
+    __shared__ int sh_big;
+    const int gi = threadIdx.x / G;
+    const int gl = threadIdx.x % G;
+    const int slot = gl / LPN;
+    const int chunk = gl % LPN;
+    float rmax = 0.f;
+    unsigned long long edges = 0;
+    unsigned int nchanged = 0;
+
+    for (unsigned int j = blockIdx.x; j < nl; j += gridDim.x) {
+        const int32_t u = back[-(long long)j];
+        const RowMeta m = meta[u];
+        const Edge* __restrict__ row = pool + m.off;
+        Vec<VEC> acc;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) acc.v[k] = 0.f;
+        float s = 0.f;
+        Edge e;
+        e.col = u;
+        e.w = 0.f;
+        accumulate_row<CP, G>(row, m.len, gi, NG, u, F_in, gl, acc, s, e);
+        if (slot == 0) {
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) part[gi][chunk * VEC + k] = acc.v[k];
+            if (gl == 0) part_s[gi] = s;
+        }
+        __syncthreads();
+        if (gi == 0 && slot == 0) {
+            Vec<VEC> tot;
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) tot.v[k] = 0.f;
+            float st = 0.f;
+            for (int q = 0; q < NG; ++q) {
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) tot.v[k] += part[q][chunk * VEC + k];
+                st += part_s[q];
+            }
+            const Vec<VEC> old = load_vec<VEC>(F_in + (size_t)u * CP + chunk * VEC);
+            Vec<VEC> fn;
+            float r = 0.f;
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) {
+                fn.v[k] = tot.v[k] / st;
+                r = fmaxf(r, fabsf(fn.v[k] - old.v[k]));
+            }
+#pragma unroll
+            for (int d = 1; d < LPN; d <<= 1) r = fmaxf(r, __shfl_xor(r, d, G));
+            store_vec<VEC>(F_out + (size_t)(STAGED ? pos_base + j : (unsigned int)u) * CP + chunk * VEC, fn);
+            if (gl == 0) {
+                const bool big = r > tol;
+                sh_big = big ? 1 : 0;
+                if (!STAGED && changed_out) changed_out[pos_base + j] = big ? 1 : 0;
+                rmax = fmaxf(rmax, r);
+                edges += (unsigned long long)m.len;
+                nchanged += big ? 1u : 0u;
+            }
+        }
+        __syncthreads();
+        if (STAGED && sh_big) {
+            if (threadIdx.x == 0) flag[u] = 1;
+            for (int idx = threadIdx.x; idx < m.len; idx += kBlock) mark(flag, row[idx].col);
+        }
+        __syncthreads();
+    }
+    flush_round_counters(rmax, edges, nchanged, ctr);
+}
+
+}  // namespace dynlp

@@ -364,220 +364,6 @@ __global__ void __launch_bounds__(kBlock) k_clear_counts(unsigned int nt, const 
 }
 
 // =================================================================================================
-// Frontier compaction (+ commit of the staged rows of the round that just ran)
-// =================================================================================================
-constexpr int kFlagsPerThread = 16;
-constexpr int kFlagsPerBlock = kBlock * kFlagsPerThread;  // 4096
-
-// Blocks [0, commit_blocks): copy staged rows Fq[i] -> F[queue_cur[i]] (the Jacobi commit).
-// Blocks [commit_blocks, ...): each scans kFlagsPerBlock flag bytes, keeps the vertices that
-// may be updated (unlabelled, at least one edge), reserves a range of the next queue with one
-// atomic, writes the ids in ascending order inside the range, and clears the flags it read.
-// all_rows != 0 ignores the flags and lists every updatable vertex (static solve).
-__global__ void __launch_bounds__(kBlock) k_commit_compact(const int32_t* __restrict__ queue_cur, unsigned int nq,
-                                                          const float* __restrict__ Fq, float* __restrict__ F, int CP,
-                                                          unsigned int commit_blocks, unsigned int n,
-                                                          uint8_t* __restrict__ flag,
-                                                          const int32_t* __restrict__ seed_class,
-                                                          const RowMeta* __restrict__ meta,
-                                                          int32_t* __restrict__ queue_next,
-                                                          unsigned int* __restrict__ next_count, int all_rows) {
-    if (blockIdx.x < commit_blocks) {
-        if (CP >= 4) {
-            const unsigned int vpr = CP / 4;
-            const unsigned long long total = (unsigned long long)nq * vpr;
-            const float4* src = reinterpret_cast<const float4*>(Fq);
-            float4* dst = reinterpret_cast<float4*>(F);
-            for (unsigned long long i = (unsigned long long)blockIdx.x * kBlock + threadIdx.x; i < total;
-                 i += (unsigned long long)commit_blocks * kBlock) {
-                const unsigned int qi = (unsigned int)(i / vpr);
-                const unsigned int ch = (unsigned int)(i % vpr);
-                dst[(unsigned long long)queue_cur[qi] * vpr + ch] = src[i];
-            }
-        } else {
-            const unsigned long long total = (unsigned long long)nq * CP;
-            for (unsigned long long i = (unsigned long long)blockIdx.x * kBlock + threadIdx.x; i < total;
-                 i += (unsigned long long)commit_blocks * kBlock) {
-                const unsigned int qi = (unsigned int)(i / CP);
-                F[(unsigned long long)queue_cur[qi] * CP + (i % CP)] = Fq[i];
-            }
-        }
-        return;
-    }
-    __shared__ unsigned int sm[kBlock / kWave + 1];
-    __shared__ unsigned int sbase;
-    const unsigned int b = blockIdx.x - commit_blocks;
-    const unsigned int v0 = b * kFlagsPerBlock + threadIdx.x * kFlagsPerThread;
-    unsigned int keep = 0;  // bit k: vertex v0+k enters the queue
-    bool any = false;
-    if (v0 < n) {
-        if (all_rows) {
-            for (int k = 0; k < kFlagsPerThread; ++k) {
-                const unsigned int v = v0 + k;
-                if (v < n && seed_class[v] < 0 && meta[v].len > 0) keep |= 1u << k;
-            }
-        } else {
-            const uint4 f = *reinterpret_cast<const uint4*>(flag + v0);
-            const unsigned int wds[4] = {f.x, f.y, f.z, f.w};
-            any = (f.x | f.y | f.z | f.w) != 0;
-            if (any) {
-#pragma unroll
-                for (int k = 0; k < kFlagsPerThread; ++k) {
-                    if ((wds[k >> 2] >> ((k & 3) * 8)) & 0xffu) {
-                        const unsigned int v = v0 + k;
-                        if (v < n && seed_class[v] < 0 && meta[v].len > 0) keep |= 1u << k;
-                    }
-                }
-                *reinterpret_cast<uint4*>(flag + v0) = make_uint4(0, 0, 0, 0);
-            }
-        }
-    }
-    const unsigned int cnt = __popc(keep);
-    unsigned int total;
-    const unsigned int ex = block_exclusive_scan<unsigned int>(cnt, sm, &total);
-    if (threadIdx.x == 0) sbase = total ? atomicAdd(next_count, total) : 0u;
-    __syncthreads();
-    unsigned int pos = sbase + ex;
-    while (keep) {
-        const int k = __ffs(keep) - 1;
-        keep &= keep - 1;
-        queue_next[pos++] = (int32_t)(v0 + k);
-    }
-}
-
-// =================================================================================================
-// Frontier row update: the hot kernel (Alg. 2 Step 3 inner loop / one ItLP sweep of Eq. (1))
-// =================================================================================================
-// G lanes cooperate on one frontier row u.  A neighbour row of CP floats is read by LPN = CP/VEC
-// adjacent lanes (VEC = 4 floats = 16 bytes per lane), so the group gathers SLOTS = G/LPN
-// neighbour rows at once, each as one contiguous CP*4-byte segment.  The row's (col, w) pairs
-// are first read G at a time with one coalesced 8-byte load per lane and handed round with
-// lane shuffles.  Every lane keeps the partial sums of its slot; a butterfly over the slot bits
-// finishes acc = sum_j w_j F[col_j] and s = sum_j w_j; F'_u = acc / s.
-//   STATIC : F' is written to row u of F_out (ping-pong buffer); no frontier bookkeeping.
-//   dynamic: F' is staged at row g of F_out (g = position in the queue) so that every row of
-//            this round reads the round-start F (Jacobi); if max_c |F'_u - F_u| > tol the row
-//            marks itself and its neighbours in flag[] for the next round (Alg. 2 Step 3).
-// The kernel is grid-strided so that each workgroup issues one set of counter atomics.
-template <int CP, int G, bool STATIC>
-__global__ void __launch_bounds__(kBlock) k_row_update(const int32_t* __restrict__ queue, unsigned int nq,
-                                                      const RowMeta* __restrict__ meta,
-                                                      const Edge* __restrict__ pool,
-                                                      const float* __restrict__ F_in, float* __restrict__ F_out,
-                                                      uint8_t* __restrict__ flag, float tol,
-                                                      RoundCtr* __restrict__ ctr, RoundCtr* __restrict__ ctr_zero) {
-    constexpr int VEC = CP >= 4 ? 4 : CP;
-    constexpr int LPN = CP / VEC;
-    constexpr int SLOTS = G / LPN;
-    constexpr int GPB = kBlock / G;
-    static_assert(G % LPN == 0 && SLOTS >= 1, "group must hold whole neighbour rows");
-
-    if (ctr_zero && blockIdx.x == 0 && threadIdx.x == 0) {
-        ctr_zero->next_count = 0;
-        ctr_zero->resid_bits = 0;
-        ctr_zero->changed = 0;
-        ctr_zero->edges = 0;
-    }
-
-    const int gl = threadIdx.x % G;
-    const int slot = gl / LPN;
-    const int chunk = gl % LPN;
-    float rmax = 0.f;
-    unsigned long long edges = 0;
-    unsigned int changed = 0;
-
-    for (unsigned int g = blockIdx.x * GPB + threadIdx.x / G; g < nq; g += gridDim.x * GPB) {
-        const int32_t u = queue[g];
-        const RowMeta m = meta[u];
-        const Edge* __restrict__ row = pool + m.off;
-        Vec<VEC> acc;
-#pragma unroll
-        for (int k = 0; k < VEC; ++k) acc.v[k] = 0.f;
-        float s = 0.f;
-        Edge e;
-        e.col = u;
-        e.w = 0.f;
-        for (int base = 0; base < m.len; base += G) {
-            const int idx = base + gl;
-            if (idx < m.len) {
-                e = row[idx];
-            } else {  // a harmless stand-in: own row, weight 0
-                e.col = u;
-                e.w = 0.f;
-            }
-            const int cnt = m.len - base;
-#pragma unroll
-            for (int j0 = 0; j0 < G; j0 += SLOTS) {
-                if (j0 < cnt) {  // uniform across the group
-                    const int32_t c = __shfl(e.col, j0 + slot, G);
-                    const float w = __shfl(e.w, j0 + slot, G);
-                    const Vec<VEC> f = load_vec<VEC>(F_in + (size_t)c * CP + chunk * VEC);
-#pragma unroll
-                    for (int k = 0; k < VEC; ++k) acc.v[k] = fmaf(w, f.v[k], acc.v[k]);
-                    s += w;
-                }
-            }
-        }
-#pragma unroll
-        for (int d = LPN; d < G; d <<= 1) {
-#pragma unroll
-            for (int k = 0; k < VEC; ++k) acc.v[k] += __shfl_xor(acc.v[k], d, G);
-            s += __shfl_xor(s, d, G);
-        }
-        const Vec<VEC> old = load_vec<VEC>(F_in + (size_t)u * CP + chunk * VEC);
-        Vec<VEC> fn;
-        float r = 0.f;
-#pragma unroll
-        for (int k = 0; k < VEC; ++k) {
-            fn.v[k] = acc.v[k] / s;
-            r = fmaxf(r, fabsf(fn.v[k] - old.v[k]));
-        }
-#pragma unroll
-        for (int d = 1; d < LPN; d <<= 1) r = fmaxf(r, __shfl_xor(r, d, G));
-        if (slot == 0) store_vec<VEC>(F_out + (size_t)(STATIC ? (unsigned int)u : g) * CP + chunk * VEC, fn);
-        const bool big = r > tol;
-        if (!STATIC && big) {
-            // V_aff <- V_aff U {u} U N(u); the last chunk of the row is still in registers
-            if (gl == 0) flag[u] = 1;
-            if (e.w != 0.f && !flag[e.col]) flag[e.col] = 1;
-            const int last_base = ((m.len - 1) / G) * G;
-            for (int idx = gl; idx < last_base; idx += G) {
-                const int32_t c = row[idx].col;
-                if (!flag[c]) flag[c] = 1;
-            }
-        }
-        if (gl == 0) {
-            rmax = fmaxf(rmax, r);
-            edges += (unsigned long long)m.len;
-            changed += big ? 1u : 0u;
-        }
-    }
-
-    __shared__ float sm_r[kBlock / kWave];
-    __shared__ unsigned long long sm_e[kBlock / kWave];
-    __shared__ unsigned int sm_c[kBlock / kWave];
-    rmax = wave_max(rmax);
-    edges = wave_sum(edges);
-    changed = wave_sum(changed);
-    if (lane_id() == 0) {
-        sm_r[threadIdx.x / kWave] = rmax;
-        sm_e[threadIdx.x / kWave] = edges;
-        sm_c[threadIdx.x / kWave] = changed;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        for (int i = 1; i < kBlock / kWave; ++i) {
-            rmax = fmaxf(rmax, sm_r[i]);
-            edges += sm_e[i];
-            changed += sm_c[i];
-        }
-        atomicMax(&ctr->resid_bits, __float_as_uint(rmax));
-        if (edges) atomicAdd(&ctr->edges, edges);
-        if (changed) atomicAdd(&ctr->changed, changed);
-    }
-}
-
-// =================================================================================================
 // Export (inspection / tests)
 // =================================================================================================
 __global__ void __launch_bounds__(kBlock) k_row_lens(int64_t n, const RowMeta* __restrict__ meta,

@@ -480,3 +480,74 @@ def test_device_mode_validation_errors_come_from_the_gpu_checks():
     st, s = d.apply_batch(1, t([3], torch.int32), t([2], torch.int32), t([1.0], torch.float32))
     assert st == 0 and d.num_vertices == 4
     d.destroy()
+
+
+def _hub_problem(n=8000, C=5, hubs=6, hub_deg=2500, seed=5):
+    """Short rows next to a few rows with thousands of entries (these take the long-row kernel)."""
+    rng = np.random.default_rng(seed)
+    eu = np.repeat(np.arange(hubs), hub_deg)
+    ev = rng.integers(hubs, n, size=eu.shape[0])
+    xu = rng.integers(0, n, size=4 * n)
+    xv = rng.integers(0, n, size=4 * n)
+    a = np.concatenate([eu, xu])
+    b = np.concatenate([ev, xv])
+    key = np.unique(np.minimum(a, b) * n + np.maximum(a, b))
+    lo, hi = key // n, key % n
+    keep = lo != hi
+    lo, hi = lo[keep], hi[keep]
+    ew = rng.uniform(0.1, 1.0, size=lo.shape[0]).astype(np.float32)
+    rp, col, w = W.edges_to_csr(n, lo, hi, ew)
+    sv = np.sort(rng.choice(np.arange(hubs, n), size=n // 25, replace=False)).astype(np.int32)
+    sc = (sv % C).astype(np.int32)
+    cls = rng.integers(0, C, size=n).astype(np.int32)
+    is_seed = np.zeros(n, dtype=bool)
+    is_seed[sv] = True
+    return W.Problem(n, C, rp, col, w, sv, sc, cls, dict(kind="small", rng=rng, is_seed=is_seed))
+
+
+@pytest.mark.parametrize("R_", [1, 3, 12])
+def test_hub_rows_first_rounds_match_the_oracle(R_):
+    p = _hub_problem()
+    p0 = _hub_problem()
+    assert np.diff(p.row_ptr).max() > 2000
+    b = W.small_random_batch(p, 120, 6, 3, num_extra_edges=40, num_revealed=2)
+    # a new vertex that is itself a hub, and new edges onto an old hub
+    extra_u = np.concatenate([np.full(900, p.n - 1), np.full(300, 0)]).astype(np.int32)
+    extra_v = np.concatenate([np.arange(100, 1000), np.arange(2000, 2300)]).astype(np.int32)
+    extra_w = np.linspace(0.1, 1.0, extra_u.shape[0]).astype(np.float32)
+    b.eu = np.concatenate([b.eu, extra_u])
+    b.ev = np.concatenate([b.ev, extra_v])
+    b.ew = np.concatenate([b.ew, extra_w])
+    g = _oracle_graph(p0)
+    with _make(p0) as d:
+        st, _ = d.static_solve(TOL, 20000)
+        assert st == 0
+        soft0, _ = d.get_labels()
+        d.set_params(TOL, R_)
+        st, s = d.apply_batch(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+        soft, _ = d.get_labels()
+        sizes, deltas = d.round_log()
+        _check_graph_equals_oracle(d, g_after := _apply_and_return(g, b))
+    rp, col, w = g_after.csr()
+    F_start = np.concatenate([soft0.astype(np.float64), np.full((b.num_new_vertices, g.C), 1.0 / g.C)])
+    sidx = np.asarray(b.seed_vertex, dtype=np.int64)
+    F_start[sidx] = 0
+    F_start[sidx, np.asarray(b.seed_class, dtype=np.int64)] = 1
+    A0 = ON.affected_set(rp, col, g_after.seed_class, p0.n, b.eu, b.ev, b.seed_vertex)
+    o2 = ON.step3_propagate(rp, col, w, F_start, g_after.seed_class, A0, TOL, R_)
+    assert s.iterations == o2["rounds"] == R_
+    assert sizes.tolist() == o2["frontier_sizes"].tolist()
+    assert np.max(np.abs(soft - o2["F"])) <= ROUNDS_ATOL
+    assert s.edges_traversed == o2["edges_traversed"]
+
+
+def _apply_and_return(g, b):
+    g.insert(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+    return g
+
+
+def test_hub_graph_converged_batch_matches_exact_labels():
+    p = _hub_problem(seed=6)
+    p0 = _hub_problem(seed=6)
+    b = W.small_random_batch(p, 200, 8, 4, num_extra_edges=100, num_revealed=3)
+    _batch_parity(p0, [b])

@@ -55,6 +55,46 @@ class Batch:
 
 
 # --------------------------------------------------------------------------------------
+# heavy deterministic array steps: numpy, or torch on the GPU for the 10M-vertex build
+# (same results either way: sorting/searching integers and float64 keys is exact)
+# --------------------------------------------------------------------------------------
+_BIG = 20_000_000
+
+
+def _gpu():
+    try:
+        import torch
+
+        return torch if torch.cuda.is_available() else None
+    except ImportError:
+        return None
+
+
+def _argsort(keys: np.ndarray) -> np.ndarray:
+    t = _gpu() if keys.shape[0] >= _BIG else None
+    if t is None:
+        return np.argsort(keys, kind="stable")
+    k = t.from_numpy(keys).cuda()
+    order = t.sort(k, stable=True).indices
+    del k
+    return order.cpu().numpy()
+
+
+def _unique(keys: np.ndarray) -> np.ndarray:
+    t = _gpu() if keys.shape[0] >= _BIG else None
+    if t is None:
+        return np.unique(keys)
+    return t.unique(t.from_numpy(keys).cuda(), sorted=True).cpu().numpy()
+
+
+def _searchsorted_right(cum: np.ndarray, vals: np.ndarray) -> np.ndarray:
+    t = _gpu() if vals.shape[0] >= _BIG else None
+    if t is None:
+        return np.searchsorted(cum, vals, side="right")
+    return t.searchsorted(t.from_numpy(cum).cuda(), t.from_numpy(vals).cuda(), right=True).cpu().numpy()
+
+
+# --------------------------------------------------------------------------------------
 # plumbing helpers
 # --------------------------------------------------------------------------------------
 def edges_to_csr(n: int, eu, ev, ew):
@@ -65,7 +105,7 @@ def edges_to_csr(n: int, eu, ev, ew):
     src = np.concatenate([eu, ev])
     dst = np.concatenate([ev, eu])
     ww = np.concatenate([ew, ew])
-    order = np.argsort(src * np.int64(n) + dst, kind="stable")
+    order = _argsort(src * np.int64(n) + dst)
     src = src[order]
     col = dst[order].astype(np.int32)
     ww = ww[order]
@@ -83,7 +123,7 @@ def _dedupe_undirected(n_total: int, a, b):
     a, b = a[keep], b[keep]
     lo = np.minimum(a, b)
     hi = np.maximum(a, b)
-    key = np.unique(lo * np.int64(n_total) + hi)
+    key = _unique(lo * np.int64(n_total) + hi)
     return key // n_total, key % n_total
 
 
@@ -299,12 +339,12 @@ def _chung_lu_partners(rng, src_cls: np.ndarray, theta_cum_all, order_cls, start
     n = theta_cum_all.shape[0]
     intra = rng.random(m) < intra_frac
     r = rng.random(m)
-    dst = np.searchsorted(theta_cum_all, r * theta_cum_all[-1], side="right").astype(np.int64)
+    dst = _searchsorted_right(theta_cum_all, r * theta_cum_all[-1]).astype(np.int64)
     np.minimum(dst, n - 1, out=dst)
     c = src_cls[intra].astype(np.int64)
     base = np.where(start_cls[c] > 0, theta_cum_cls[np.maximum(start_cls[c] - 1, 0)], 0.0)
     top = theta_cum_cls[start_cls[c + 1] - 1]
-    pos = np.searchsorted(theta_cum_cls, base + r[intra] * (top - base), side="right")
+    pos = _searchsorted_right(theta_cum_cls, base + r[intra] * (top - base))
     pos = np.clip(pos, start_cls[c], start_cls[c + 1] - 1)
     dst[intra] = order_cls[pos]
     return dst
@@ -324,7 +364,7 @@ def chung_lu(n: int, C: int, mean_degree: float, exponent: float, d_max: int, in
     theta_cum_cls = np.cumsum(theta[order_cls])
     m = int(round(n * mean_degree / 2))
     r = rng.random(m)
-    src = np.minimum(np.searchsorted(theta_cum_all, r * theta_cum_all[-1], side="right"), n - 1).astype(np.int64)
+    src = np.minimum(_searchsorted_right(theta_cum_all, r * theta_cum_all[-1]), n - 1).astype(np.int64)
     dst = _chung_lu_partners(rng, cls[src], theta_cum_all, order_cls, start_cls, theta_cum_cls, intra_frac)
     lo, hi = _dedupe_undirected(n, src, dst)
     ew = rng.uniform(0.1, 1.0, size=lo.shape[0]).astype(np.float32)
