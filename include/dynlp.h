@@ -166,11 +166,13 @@ dynlp_status dynlp_export_graph(dynlp_ctx* ctx, int64_t* row_ptr, int32_t* col, 
                                 int32_t* seed_class);
 
 /*
- * Per-round log of the last solve / batch: frontier size and max change of round i, for the first
- * min(rounds, cap) rounds (HOST pointers regardless of ptrs_on_device; either may be NULL).
+ * Per-round log of the last solve / batch: frontier size, max change and (with time_kernels) the
+ * device time in ms of the row-update launches of round i, for the first min(rounds, cap) rounds
+ * (HOST pointers regardless of ptrs_on_device; each may be NULL).
  * Returns the number of rounds the last call executed.
  */
-int64_t dynlp_round_log(const dynlp_ctx* ctx, int64_t cap, int64_t* frontier_size, float* max_delta);
+int64_t dynlp_round_log(const dynlp_ctx* ctx, int64_t cap, int64_t* frontier_size, float* max_delta,
+                        float* kernel_ms);
 
 /* Message for the last failed call on ctx (or, with ctx NULL, the last failed dynlp_create on this
  * thread).  Valid until the next call on the same context / thread.  Never NULL. */

@@ -90,7 +90,7 @@ def load_library(path: str | None = None):
     L.dynlp_num_classes.restype = i32
     L.dynlp_export_graph.argtypes = [p, p, p, p, p, p]
     L.dynlp_export_graph.restype = ct.c_int
-    L.dynlp_round_log.argtypes = [p, i64, p, p]
+    L.dynlp_round_log.argtypes = [p, i64, p, p, p]
     L.dynlp_round_log.restype = i64
     L.dynlp_last_error.argtypes = [p]
     L.dynlp_last_error.restype = ct.c_char_p
@@ -222,15 +222,17 @@ class DynLP:
         self._check(self._L.dynlp_export_graph(self._h, rpp, colp, wp, degp, scp))
         return rp, col, w, deg, sc
 
-    def round_log(self):
-        """dynlp_round_log.  Returns (frontier_sizes int64, max_delta float32) of the last call."""
-        rounds = int(self._L.dynlp_round_log(self._h, 0, None, None))
+    def round_log(self, kernel_ms=False):
+        """dynlp_round_log.  Returns (frontier_sizes int64, max_delta float32) of the last call;
+        with kernel_ms=True also the per-round device time of the row-update launches."""
+        rounds = int(self._L.dynlp_round_log(self._h, 0, None, None, None))
         sizes = np.zeros(rounds, dtype=np.int64)
         delta = np.zeros(rounds, dtype=np.float32)
+        kms = np.zeros(rounds, dtype=np.float32)
         if rounds:
             self._L.dynlp_round_log(self._h, rounds, sizes.ctypes.data_as(ct.c_void_p),
-                                    delta.ctypes.data_as(ct.c_void_p))
-        return sizes, delta
+                                    delta.ctypes.data_as(ct.c_void_p), kms.ctypes.data_as(ct.c_void_p))
+        return (sizes, delta, kms) if kernel_ms else (sizes, delta)
 
     def destroy(self):
         if self._h:

@@ -80,9 +80,6 @@ struct dynlp_ctx {
     int32_t* seed_class = nullptr;
     uint8_t* flag = nullptr;
     int32_t* queue[2] = {nullptr, nullptr};  // frontier storage, two parities (see dynlp_frontier.h)
-    uint8_t* changed = nullptr;               // per frontier position: row moved by more than tol
-    int64_t updatable = -1;                   // vertices that can be updated (unlabelled, >= 1 edge)
-    bool f2_synced = false;                   // F2 agrees with F on all rows a full sweep skips
     int32_t* add_cnt = nullptr;
     float* deg = nullptr;
 
@@ -102,6 +99,7 @@ struct dynlp_ctx {
     int32_t max_iter = 100000;
     std::vector<int64_t> log_sizes;
     std::vector<float> log_delta;
+    std::vector<float> log_kernel_ms;  // per round, filled when kernel timing is on
     std::vector<hipEvent_t> events;
     size_t events_used = 0;
     hipEvent_t phase_ev[4] = {nullptr, nullptr, nullptr, nullptr};
@@ -207,7 +205,6 @@ void alloc_vertex_arrays(dynlp_ctx* c, int64_t new_cap) {
     uint8_t* flag = dev_alloc_n<uint8_t>(c, flag_cap);
     int32_t* q0 = dev_alloc_n<int32_t>(c, new_cap);
     int32_t* q1 = dev_alloc_n<int32_t>(c, new_cap);
-    uint8_t* chg = dev_alloc_n<uint8_t>(c, new_cap);
     int32_t* add = dev_alloc_n<int32_t>(c, new_cap);
     float* deg = dev_alloc_n<float>(c, new_cap);
     HIPCHK(c, hipMemsetAsync(flag, 0, (size_t)flag_cap, c->stream));
@@ -226,11 +223,8 @@ void alloc_vertex_arrays(dynlp_ctx* c, int64_t new_cap) {
     dev_free(c, c->flag);
     dev_free(c, c->queue[0]);
     dev_free(c, c->queue[1]);
-    dev_free(c, c->changed);
     dev_free(c, c->add_cnt);
     dev_free(c, c->deg);
-    c->changed = chg;
-    c->f2_synced = false;
     c->meta = meta;
     c->F = F;
     c->F2 = F2;
@@ -328,7 +322,6 @@ Frontier frontier_of(dynlp_ctx* c, int parity, unsigned int ns = 0, unsigned int
 struct UpdateArgs {
     const float* F_in;
     float* F_out;
-    uint8_t* changed;  // NULL in static sweeps and staged rounds
     float tol;
     RoundCtr* ctr;
     RoundCtr* ctr_zero;
@@ -340,7 +333,7 @@ void launch_short_inst(dynlp_ctx* c, const Frontier& f, const UpdateArgs& a) {
     const int64_t want = ceil_div(f.ns, GPB);
     const unsigned int blocks = (unsigned int)std::max<int64_t>(1, std::min<int64_t>(want, (int64_t)c->num_cu * 8));
     hipLaunchKernelGGL((k_row_update<CP, G, STAGED>), dim3(blocks), dim3(kBlock), 0, c->stream, f.front, f.ns, c->meta,
-                       c->pool, a.F_in, a.F_out, c->flag, a.changed, a.tol, a.ctr, a.ctr_zero);
+                       c->pool, a.F_in, a.F_out, c->flag, a.tol, a.ctr, a.ctr_zero);
 }
 
 template <int CP, bool STAGED>
@@ -368,7 +361,7 @@ void launch_update_cp(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& 
     if (f.nl) {
         const unsigned int blocks = (unsigned int)std::min<int64_t>(f.nl, (int64_t)c->num_cu * 8);
         hipLaunchKernelGGL((k_row_update_long<CP, STAGED>), dim3(blocks), dim3(kBlock), 0, c->stream, f.back, f.nl,
-                           f.ns, c->meta, c->pool, a.F_in, a.F_out, c->flag, a.changed, a.tol, a.ctr);
+                           f.ns, c->meta, c->pool, a.F_in, a.F_out, c->flag, a.tol, a.ctr);
     }
 }
 
@@ -402,9 +395,11 @@ void launch_update(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& a) 
 
 float collect_kernel_ms(dynlp_ctx* c) {
     float total = 0.f;
+    c->log_kernel_ms.clear();
     for (size_t i = 0; i + 1 < c->events_used; i += 2) {
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, c->events[i], c->events[i + 1]) == hipSuccess) total += ms;
+        c->log_kernel_ms.push_back(ms);
     }
     c->events_used = 0;
     return total;
@@ -429,18 +424,17 @@ void launch_commit(dynlp_ctx* c, const Frontier& f) {
 
 void launch_expand(dynlp_ctx* c, const Frontier& f) {
     const unsigned int blocks = (unsigned int)std::max<int64_t>(1, std::min<int64_t>(ceil_div(f.size(), kBlock / 16), (int64_t)c->num_cu * 8));
-    hipLaunchKernelGGL(k_expand, dim3(blocks), dim3(kBlock), 0, c->stream, f.ns, f.nl, f.front, f.back, c->changed,
-                       c->meta, c->pool, c->flag);
+    // called after the buffers were swapped: F holds the new rows, F2 the round-start rows
+    hipLaunchKernelGGL(k_expand, dim3(blocks), dim3(kBlock), 0, c->stream, f.ns, f.nl, f.front, f.back, c->F, c->F2,
+                       c->CP, c->tol, c->meta, c->pool, c->flag);
     HIPCHK(c, hipGetLastError());
 }
 
 // The ping-pong partner must agree with F on every row a full sweep does not write (seeds,
 // isolated vertices) before it can receive one.
 void sync_partner(dynlp_ctx* c) {
-    if (c->f2_synced) return;
     if (c->n > 0)
         HIPCHK(c, hipMemcpyAsync(c->F2, c->F, (size_t)c->n * c->CP * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
-    c->f2_synced = true;
 }
 
 // Every updatable vertex (unlabelled, at least one edge) into the frontier of the given parity.
@@ -512,7 +506,7 @@ void destroy_ctx(dynlp_ctx* c) {
     if (!c) return;
     (void)hipSetDevice(c->device);
     if (c->stream || c->meta) (void)hipStreamSynchronize(c->stream);
-    void* ptrs[] = {c->meta, c->pool, c->F, c->F2, c->seed_class, c->flag, c->queue[0], c->queue[1], c->changed, c->add_cnt,
+    void* ptrs[] = {c->meta, c->pool, c->F, c->F2, c->seed_class, c->flag, c->queue[0], c->queue[1], c->add_cnt,
                     c->deg, c->touched, c->reloc_off, c->b_eu, c->b_ev, c->b_ew, c->b_sv, c->b_sc};
     for (void* p : ptrs) dev_free(c, p);
     if (c->ring) (void)hipFree(c->ring);
@@ -761,7 +755,6 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
         sync_partner(c);
         zero_ring(c);
         const Frontier f = all_updatable(c, 0);
-        c->updatable = f.size();
         const unsigned int nq = f.size();
         int it = 0;
         float last = 0.f;
@@ -770,7 +763,7 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
         const int G = choose_group(c, c->n > 0 ? (double)c->entries / (double)std::max<int64_t>(1, nq) : 1.0);
         const auto t_it = Clock::now();
         while (!converged && it < max_iter) {
-            const UpdateArgs a{c->F, c->F2, nullptr, tol, c->ring + (it % kRing), c->ring + ((it + 1) % kRing)};
+            const UpdateArgs a{c->F, c->F2, tol, c->ring + (it % kRing), c->ring + ((it + 1) % kRing)};
             launch_update<false>(c, G, f, a);
             const RoundCtr r = read_slot(c, it);
             std::swap(c->F, c->F2);
@@ -781,6 +774,7 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
             ++it;
             if (last <= tol) converged = true;
         }
+        const float kernel_ms_total = c->time_kernels ? collect_kernel_ms(c) : 0.f;
         if (stats) {
             stats->iterations = it;
             stats->converged = converged ? 1 : 0;
@@ -791,7 +785,7 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
             stats->frontier_peak = nq;
             stats->update_launches = it;
             stats->ms_iterate = ms_since(t_it);
-            stats->ms_update_kernel = c->time_kernels ? collect_kernel_ms(c) : 0.f;
+            stats->ms_update_kernel = kernel_ms_total;
             stats->ms_total = ms_since(t0);
         }
         c->events_used = 0;
@@ -915,18 +909,14 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
             hipLaunchKernelGGL(k_apply_seeds, dim3(grid_for(s * 16)), dim3(kBlock), 0, c->stream, s, d_sv, d_sc, c->C, c->CP,
                                c->seed_class, c->F, c->meta, c->pool, c->flag);
         zero_ring(c);
-        // first frontier from the flags; and the census of updatable vertices (into the other parity,
-        // as scratch) that tells later rounds when the frontier is "everything"
+        // first frontier from the flags
         Frontier f = frontier_of(c, 0);
         launch_compact(c, f, &c->bc->init_count, &c->bc->init_long, 0);
-        launch_compact(c, frontier_of(c, 1), &c->bc->upd_short, &c->bc->upd_long, 1);
         read_bc(c);
         c->pool_tail = (int64_t)c->h_bc->pool_tail;
         const int64_t relocated = c->h_bc->relocated;
         f.ns = c->h_bc->init_count;
         f.nl = c->h_bc->init_long;
-        c->updatable = (int64_t)c->h_bc->upd_short + (int64_t)c->h_bc->upd_long;
-        if (k > 0 || s > 0) c->f2_synced = false;  // rows no sweep writes have changed in F
         HIPCHK(c, hipEventRecord(c->phase_ev[2], c->stream));
 
         // ---- Step 3: rounds over V_aff ----
@@ -935,50 +925,59 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
         int it = 0, cur = 0;
         float last = 0.f;
         double avg_len = c->n > 0 ? (double)c->entries / (double)c->n : 1.0;
+        bool pingpong = false, closed = false, prev_all_changed = false;
         while (f.size() > 0 && it < c->max_iter) {
             const unsigned int nq = f.size();
             const int G = choose_group(c, avg_len);
             RoundCtr* slot = c->ring + (it % kRing);
             RoundCtr* next_slot = c->ring + ((it + 1) % kRing);
             RoundCtr r;
-            bool same_frontier = false;
-            if ((int64_t)nq == c->updatable) {
-                // Full round: every updatable row is in V_aff, so the new rows go straight into the
-                // ping-pong partner (no staging, no commit).  If every row moved by more than tol the
-                // next V_aff is the same set again and nothing else has to run.
+            // A stretch of ping-pong rounds may start when V_aff is large and still moving as a whole;
+            // it costs one copy of F so that the partner agrees on every row outside V_aff.
+            if (!pingpong && prev_all_changed && (int64_t)nq * 8 >= c->n) {
                 sync_partner(c);
-                const UpdateArgs a{c->F, c->F2, c->changed, c->tol, slot, next_slot};
+                pingpong = true;
+                closed = false;
+            }
+            if (pingpong) {
+                // Ping-pong round: new rows go straight into the partner buffer (no staging, no commit).
+                // Valid because V_aff only grows while every row of it keeps moving by more than tol,
+                // so the partner is stale only on rows this round rewrites.
+                const UpdateArgs a{c->F, c->F2, c->tol, slot, next_slot};
                 launch_update<false>(c, G, f, a);
                 std::swap(c->F, c->F2);
                 r = read_slot(c, it);
-                if (r.changed == nq) {
-                    same_frontier = true;
-                } else {
+                prev_all_changed = r.changed == nq;
+                if (!(prev_all_changed && closed)) {
+                    // next V_aff from the rows that moved (all of them, or the stretch ends here)
                     launch_expand(c, f);
                     Frontier nf = frontier_of(c, cur ^ 1);
                     launch_compact(c, nf, &slot->next_count, &slot->next_long, 0);
                     const RoundCtr r2 = read_slot(c, it);
                     nf.ns = r2.next_count;
                     nf.nl = r2.next_long;
+                    // all rows moved and V_aff did not grow: it is closed under taking neighbours and
+                    // stays the same set until some row stops moving
+                    closed = prev_all_changed && nf.size() == nq;
+                    pingpong = prev_all_changed;
                     f = nf;
                     cur ^= 1;
                 }
             } else {
-                // Partial round: rows are staged by frontier position, committed after the kernel, and
+                // Staged round: rows are staged by frontier position, committed after the kernel, and
                 // the rows that moved mark themselves and their neighbours for the next round.
-                const UpdateArgs a{c->F, c->F2, nullptr, c->tol, slot, next_slot};
+                const UpdateArgs a{c->F, c->F2, c->tol, slot, next_slot};
                 launch_update<true>(c, G, f, a);
-                c->f2_synced = false;
                 launch_commit(c, f);
                 Frontier nf = frontier_of(c, cur ^ 1);
                 launch_compact(c, nf, &slot->next_count, &slot->next_long, 0);
                 r = read_slot(c, it);
+                prev_all_changed = r.changed == nq;
                 nf.ns = r.next_count;
                 nf.nl = r.next_long;
                 f = nf;
                 cur ^= 1;
             }
-            (void)same_frontier;
             std::memcpy(&last, &r.resid_bits, sizeof(float));
             rows += nq;
             edges += (int64_t)r.edges;
@@ -991,6 +990,7 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
         const unsigned int nq = f.size();
         HIPCHK(c, hipEventRecord(c->phase_ev[3], c->stream));
         HIPCHK(c, hipStreamSynchronize(c->stream));
+        const float kernel_ms_total = c->time_kernels ? collect_kernel_ms(c) : 0.f;
         if (stats) {
             stats->iterations = it;
             stats->converged = nq == 0 ? 1 : 0;
@@ -1001,7 +1001,7 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
             stats->frontier_peak = peak;
             stats->rows_relocated = relocated;
             stats->update_launches = it;
-            stats->ms_update_kernel = c->time_kernels ? collect_kernel_ms(c) : 0.f;
+            stats->ms_update_kernel = kernel_ms_total;
             (void)hipEventElapsedTime(&stats->ms_insert, c->phase_ev[0], c->phase_ev[1]);
             (void)hipEventElapsedTime(&stats->ms_seed, c->phase_ev[1], c->phase_ev[2]);
             (void)hipEventElapsedTime(&stats->ms_iterate, c->phase_ev[2], c->phase_ev[3]);
@@ -1116,12 +1116,17 @@ dynlp_status dynlp_export_graph(dynlp_ctx* c, int64_t* row_ptr, int32_t* col, fl
     return st;
 }
 
-int64_t dynlp_round_log(const dynlp_ctx* ctx, int64_t cap, int64_t* frontier_size, float* max_delta) {
+int64_t dynlp_round_log(const dynlp_ctx* ctx, int64_t cap, int64_t* frontier_size, float* max_delta,
+                        float* kernel_ms) {
     if (!ctx) return -1;
     const int64_t rounds = (int64_t)ctx->log_sizes.size();
     const int64_t k = std::max<int64_t>(0, std::min(cap, rounds));
     if (frontier_size) std::copy(ctx->log_sizes.begin(), ctx->log_sizes.begin() + k, frontier_size);
     if (max_delta) std::copy(ctx->log_delta.begin(), ctx->log_delta.begin() + k, max_delta);
+    if (kernel_ms) {
+        for (int64_t i = 0; i < k; ++i)
+            kernel_ms[i] = i < (int64_t)ctx->log_kernel_ms.size() ? ctx->log_kernel_ms[(size_t)i] : 0.f;
+    }
     return rounds;
 }
 

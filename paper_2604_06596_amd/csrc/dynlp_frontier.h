@@ -18,7 +18,7 @@ constexpr int kLongRow = 512;  // rows longer than this get a whole workgroup
 // the front, position i at front[i]; "long" rows from the back, position j at back[-j] with
 // back = front + n_cap - 1.  The two never meet because a frontier has at most n entries.
 // Row i of the frontier (short rows first, then long rows) has *position* i; staged label rows
-// and changed-bytes are indexed by position.
+// are indexed by position.
 __device__ inline int32_t frontier_vertex(const int32_t* front, const int32_t* back, unsigned int ns,
                                           unsigned int pos) {
     return pos < ns ? front[pos] : back[-(long long)(pos - ns)];
@@ -90,7 +90,7 @@ __global__ void __launch_bounds__(kBlock) k_compact(unsigned int n, uint8_t* __r
 }
 
 // =================================================================================================
-// Commit of staged rows (partial rounds) and expansion from changed-bytes (full rounds)
+// Commit of staged rows (staged rounds) and expansion after a ping-pong round
 // =================================================================================================
 // F[vertex at position i] = Fq[i] for all positions: the Jacobi commit of a staged round.
 __global__ void __launch_bounds__(kBlock) k_commit(unsigned int ns, unsigned int nl,
@@ -123,20 +123,27 @@ __device__ inline void mark(uint8_t* __restrict__ flag, int32_t v) {
     if (!flag[v]) flag[v] = 1;
 }
 
-// V_aff <- union over changed rows u of {u} U N(u), from the changed-bytes a full round left
-// (16 lanes per frontier position).
+// V_aff <- union over changed rows u of {u} U N(u) after a full round.  A full round leaves the new
+// rows in F_new and the round-start rows untouched in F_old (the ping-pong partner), so whether row
+// u moved by more than tol is recomputed here from the two stored rows: the same float32 values,
+// hence the same decision the update kernel counted (16 lanes per frontier position).
 __global__ void __launch_bounds__(kBlock) k_expand(unsigned int ns, unsigned int nl,
                                                   const int32_t* __restrict__ front,
                                                   const int32_t* __restrict__ back,
-                                                  const uint8_t* __restrict__ changed,
+                                                  const float* __restrict__ F_new,
+                                                  const float* __restrict__ F_old, int CP, float tol,
                                                   const RowMeta* __restrict__ meta,
                                                   const Edge* __restrict__ pool, uint8_t* __restrict__ flag) {
     constexpr int G = 16;
     const unsigned int nq = ns + nl;
     const int gl = threadIdx.x % G;
     for (unsigned int pos = blockIdx.x * (kBlock / G) + threadIdx.x / G; pos < nq; pos += gridDim.x * (kBlock / G)) {
-        if (!changed[pos]) continue;
         const int32_t u = frontier_vertex(front, back, ns, pos);
+        float r = 0.f;
+        for (int k = gl; k < CP; k += G) r = fmaxf(r, fabsf(F_new[(size_t)u * CP + k] - F_old[(size_t)u * CP + k]));
+#pragma unroll
+        for (int d = G / 2; d > 0; d >>= 1) r = fmaxf(r, __shfl_xor(r, d, G));
+        if (!(r > tol)) continue;
         const RowMeta m = meta[u];
         if (gl == 0) flag[u] = 1;
         for (int j = gl; j < m.len; j += G) mark(flag, pool[m.off + j].col);
@@ -240,8 +247,8 @@ __device__ inline void flush_round_counters(float rmax, unsigned long long edges
 }
 
 // Short rows: G lanes per row, grid-strided.
-//   STAGED = false (static sweep / full round): F'_u is written to row u of F_out, the ping-pong
-//            partner of F_in; changed[pos] (if not NULL) records whether the row moved by > tol.
+//   STAGED = false (static sweep / ping-pong round): F'_u is written to row u of F_out, the
+//            ping-pong partner of F_in.
 //   STAGED = true (partial round): F'_u is staged at row pos of F_out so that every row of this
 //            round reads the round-start F (Jacobi); a row that moved by > tol marks itself and
 //            its neighbours in flag[] for the next round.
@@ -250,8 +257,8 @@ __global__ void __launch_bounds__(kBlock) k_row_update(const int32_t* __restrict
                                                       const RowMeta* __restrict__ meta,
                                                       const Edge* __restrict__ pool,
                                                       const float* __restrict__ F_in, float* __restrict__ F_out,
-                                                      uint8_t* __restrict__ flag, uint8_t* __restrict__ changed_out,
-                                                      float tol, RoundCtr* __restrict__ ctr,
+                                                      uint8_t* __restrict__ flag, float tol,
+                                                      RoundCtr* __restrict__ ctr,
                                                       RoundCtr* __restrict__ ctr_zero) {
     constexpr int VEC = RowShape<CP>::VEC;
     constexpr int LPN = RowShape<CP>::LPN;
@@ -301,8 +308,6 @@ __global__ void __launch_bounds__(kBlock) k_row_update(const int32_t* __restrict
                 const int last_base = ((m.len - 1) / G) * G;
                 for (int idx = gl; idx < last_base; idx += G) mark(flag, row[idx].col);
             }
-        } else if (changed_out && gl == 0) {
-            changed_out[g] = big ? 1 : 0;
         }
         if (gl == 0) {
             rmax = fmaxf(rmax, r);
@@ -323,7 +328,7 @@ __global__ void __launch_bounds__(kBlock) k_row_update_long(const int32_t* __res
                                                            const Edge* __restrict__ pool,
                                                            const float* __restrict__ F_in,
                                                            float* __restrict__ F_out, uint8_t* __restrict__ flag,
-                                                           uint8_t* __restrict__ changed_out, float tol,
+                                                           float tol,
                                                            RoundCtr* __restrict__ ctr) {
     constexpr int VEC = RowShape<CP>::VEC;
     constexpr int LPN = RowShape<CP>::LPN;
@@ -382,7 +387,6 @@ __global__ void __launch_bounds__(kBlock) k_row_update_long(const int32_t* __res
             if (gl == 0) {
                 const bool big = r > tol;
                 sh_big = big ? 1 : 0;
-                if (!STAGED && changed_out) changed_out[pos_base + j] = big ? 1 : 0;
                 rmax = fmaxf(rmax, r);
                 edges += (unsigned long long)m.len;
                 nchanged += big ? 1u : 0u;
