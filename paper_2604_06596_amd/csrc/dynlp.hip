@@ -79,7 +79,8 @@ struct dynlp_ctx {
     float* F2 = nullptr;  // second buffer: ping-pong partner (static) / staging by queue position (dynamic)
     int32_t* seed_class = nullptr;
     uint8_t* flag = nullptr;
-    int32_t* queue[2] = {nullptr, nullptr};  // frontier storage, two parities (see dynlp_frontier.h)
+    int32_t* queue[3] = {nullptr, nullptr, nullptr};  // frontier storage: two parities + the list of all
+                                                      // updatable vertices (see dynlp_frontier.h)
     int32_t* add_cnt = nullptr;
     float* deg = nullptr;
 
@@ -205,6 +206,7 @@ void alloc_vertex_arrays(dynlp_ctx* c, int64_t new_cap) {
     uint8_t* flag = dev_alloc_n<uint8_t>(c, flag_cap);
     int32_t* q0 = dev_alloc_n<int32_t>(c, new_cap);
     int32_t* q1 = dev_alloc_n<int32_t>(c, new_cap);
+    int32_t* q2 = dev_alloc_n<int32_t>(c, new_cap);
     int32_t* add = dev_alloc_n<int32_t>(c, new_cap);
     float* deg = dev_alloc_n<float>(c, new_cap);
     HIPCHK(c, hipMemsetAsync(flag, 0, (size_t)flag_cap, c->stream));
@@ -223,6 +225,7 @@ void alloc_vertex_arrays(dynlp_ctx* c, int64_t new_cap) {
     dev_free(c, c->flag);
     dev_free(c, c->queue[0]);
     dev_free(c, c->queue[1]);
+    dev_free(c, c->queue[2]);
     dev_free(c, c->add_cnt);
     dev_free(c, c->deg);
     c->meta = meta;
@@ -232,6 +235,7 @@ void alloc_vertex_arrays(dynlp_ctx* c, int64_t new_cap) {
     c->flag = flag;
     c->queue[0] = q0;
     c->queue[1] = q1;
+    c->queue[2] = q2;
     c->add_cnt = add;
     c->deg = deg;
     c->n_cap = new_cap;
@@ -422,13 +426,19 @@ void launch_commit(dynlp_ctx* c, const Frontier& f) {
     HIPCHK(c, hipGetLastError());
 }
 
-void launch_expand(dynlp_ctx* c, const Frontier& f) {
-    const unsigned int blocks = (unsigned int)std::max<int64_t>(1, std::min<int64_t>(ceil_div(f.size(), kBlock / 16), (int64_t)c->num_cu * 8));
-    // called after the buffers were swapped: F holds the new rows, F2 the round-start rows
-    hipLaunchKernelGGL(k_expand, dim3(blocks), dim3(kBlock), 0, c->stream, f.ns, f.nl, f.front, f.back, c->F, c->F2,
-                       c->CP, c->tol, c->meta, c->pool, c->flag);
+// Pull the next V_aff out of the two label buffers (called after they were swapped: F holds the new
+// rows, F2 the round-start rows); `universe` lists every updatable vertex.
+void launch_next_frontier(dynlp_ctx* c, const Frontier& universe) {
+    const unsigned int blocks = (unsigned int)std::max<int64_t>(
+        1, std::min<int64_t>(ceil_div(universe.size(), kBlock / 16), (int64_t)c->num_cu * 16));
+    hipLaunchKernelGGL(k_next_frontier, dim3(blocks), dim3(kBlock), 0, c->stream, universe.ns, universe.nl,
+                       universe.front, universe.back, c->F, c->F2, c->CP, c->tol, c->meta, c->pool, c->flag);
     HIPCHK(c, hipGetLastError());
 }
+
+// Ping-pong stretches begin when V_aff holds at least kDenseEnter of the updatable vertices and end
+// when it falls below kDenseLeave (the pull over all updatable vertices stops paying off).
+constexpr double kDenseEnter = 0.90, kDenseLeave = 0.75;
 
 // The ping-pong partner must agree with F on every row a full sweep does not write (seeds,
 // isolated vertices) before it can receive one.
@@ -506,7 +516,7 @@ void destroy_ctx(dynlp_ctx* c) {
     if (!c) return;
     (void)hipSetDevice(c->device);
     if (c->stream || c->meta) (void)hipStreamSynchronize(c->stream);
-    void* ptrs[] = {c->meta, c->pool, c->F, c->F2, c->seed_class, c->flag, c->queue[0], c->queue[1], c->add_cnt,
+    void* ptrs[] = {c->meta, c->pool, c->F, c->F2, c->seed_class, c->flag, c->queue[0], c->queue[1], c->queue[2], c->add_cnt,
                     c->deg, c->touched, c->reloc_off, c->b_eu, c->b_ev, c->b_ew, c->b_sv, c->b_sc};
     for (void* p : ptrs) dev_free(c, p);
     if (c->ring) (void)hipFree(c->ring);
@@ -909,10 +919,14 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
             hipLaunchKernelGGL(k_apply_seeds, dim3(grid_for(s * 16)), dim3(kBlock), 0, c->stream, s, d_sv, d_sc, c->C, c->CP,
                                c->seed_class, c->F, c->meta, c->pool, c->flag);
         zero_ring(c);
-        // first frontier from the flags
+        // first frontier from the flags, and the list of all updatable vertices
         Frontier f = frontier_of(c, 0);
         launch_compact(c, f, &c->bc->init_count, &c->bc->init_long, 0);
+        Frontier universe = frontier_of(c, 2);
+        launch_compact(c, universe, &c->bc->upd_short, &c->bc->upd_long, 1);
         read_bc(c);
+        universe.ns = c->h_bc->upd_short;
+        universe.nl = c->h_bc->upd_long;
         c->pool_tail = (int64_t)c->h_bc->pool_tail;
         const int64_t relocated = c->h_bc->relocated;
         f.ns = c->h_bc->init_count;
@@ -925,59 +939,40 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
         int it = 0, cur = 0;
         float last = 0.f;
         double avg_len = c->n > 0 ? (double)c->entries / (double)c->n : 1.0;
-        bool pingpong = false, closed = false, prev_all_changed = false;
+        bool pingpong = false;
         while (f.size() > 0 && it < c->max_iter) {
             const unsigned int nq = f.size();
             const int G = choose_group(c, avg_len);
             RoundCtr* slot = c->ring + (it % kRing);
             RoundCtr* next_slot = c->ring + ((it + 1) % kRing);
-            RoundCtr r;
-            // A stretch of ping-pong rounds may start when V_aff is large and still moving as a whole;
-            // it costs one copy of F so that the partner agrees on every row outside V_aff.
-            if (!pingpong && prev_all_changed && (int64_t)nq * 8 >= c->n) {
+            // A stretch of ping-pong rounds starts when V_aff covers nearly every updatable vertex; it
+            // costs one copy of F so that the partner buffer agrees on every row outside V_aff.
+            if (!pingpong && (double)nq >= kDenseEnter * (double)universe.size()) {
                 sync_partner(c);
                 pingpong = true;
-                closed = false;
             }
             if (pingpong) {
-                // Ping-pong round: new rows go straight into the partner buffer (no staging, no commit).
-                // Valid because V_aff only grows while every row of it keeps moving by more than tol,
-                // so the partner is stale only on rows this round rewrites.
+                // Ping-pong round: new rows go straight into the partner buffer (no staging, no commit,
+                // no marking); the next V_aff is pulled from the two buffers over all updatable vertices.
                 const UpdateArgs a{c->F, c->F2, c->tol, slot, next_slot};
                 launch_update<false>(c, G, f, a);
                 std::swap(c->F, c->F2);
-                r = read_slot(c, it);
-                prev_all_changed = r.changed == nq;
-                if (!(prev_all_changed && closed)) {
-                    // next V_aff from the rows that moved (all of them, or the stretch ends here)
-                    launch_expand(c, f);
-                    Frontier nf = frontier_of(c, cur ^ 1);
-                    launch_compact(c, nf, &slot->next_count, &slot->next_long, 0);
-                    const RoundCtr r2 = read_slot(c, it);
-                    nf.ns = r2.next_count;
-                    nf.nl = r2.next_long;
-                    // all rows moved and V_aff did not grow: it is closed under taking neighbours and
-                    // stays the same set until some row stops moving
-                    closed = prev_all_changed && nf.size() == nq;
-                    pingpong = prev_all_changed;
-                    f = nf;
-                    cur ^= 1;
-                }
+                launch_next_frontier(c, universe);
+                if ((double)nq < kDenseLeave * (double)universe.size()) pingpong = false;
             } else {
                 // Staged round: rows are staged by frontier position, committed after the kernel, and
                 // the rows that moved mark themselves and their neighbours for the next round.
                 const UpdateArgs a{c->F, c->F2, c->tol, slot, next_slot};
                 launch_update<true>(c, G, f, a);
                 launch_commit(c, f);
-                Frontier nf = frontier_of(c, cur ^ 1);
-                launch_compact(c, nf, &slot->next_count, &slot->next_long, 0);
-                r = read_slot(c, it);
-                prev_all_changed = r.changed == nq;
-                nf.ns = r.next_count;
-                nf.nl = r.next_long;
-                f = nf;
-                cur ^= 1;
             }
+            Frontier nf = frontier_of(c, cur ^ 1);
+            launch_compact(c, nf, &slot->next_count, &slot->next_long, 0);
+            const RoundCtr r = read_slot(c, it);
+            nf.ns = r.next_count;
+            nf.nl = r.next_long;
+            f = nf;
+            cur ^= 1;
             std::memcpy(&last, &r.resid_bits, sizeof(float));
             rows += nq;
             edges += (int64_t)r.edges;

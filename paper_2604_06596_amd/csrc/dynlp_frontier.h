@@ -90,7 +90,7 @@ __global__ void __launch_bounds__(kBlock) k_compact(unsigned int n, uint8_t* __r
 }
 
 // =================================================================================================
-// Commit of staged rows (staged rounds) and expansion after a ping-pong round
+// Commit of staged rows (staged rounds) and the next frontier after a ping-pong round
 // =================================================================================================
 // F[vertex at position i] = Fq[i] for all positions: the Jacobi commit of a staged round.
 __global__ void __launch_bounds__(kBlock) k_commit(unsigned int ns, unsigned int nl,
@@ -123,17 +123,22 @@ __device__ inline void mark(uint8_t* __restrict__ flag, int32_t v) {
     if (!flag[v]) flag[v] = 1;
 }
 
-// V_aff <- union over changed rows u of {u} U N(u) after a full round.  A full round leaves the new
-// rows in F_new and the round-start rows untouched in F_old (the ping-pong partner), so whether row
-// u moved by more than tol is recomputed here from the two stored rows: the same float32 values,
-// hence the same decision the update kernel counted (16 lanes per frontier position).
-__global__ void __launch_bounds__(kBlock) k_expand(unsigned int ns, unsigned int nl,
-                                                  const int32_t* __restrict__ front,
-                                                  const int32_t* __restrict__ back,
-                                                  const float* __restrict__ F_new,
-                                                  const float* __restrict__ F_old, int CP, float tol,
-                                                  const RowMeta* __restrict__ meta,
-                                                  const Edge* __restrict__ pool, uint8_t* __restrict__ flag) {
+// Next V_aff after a ping-pong round, computed by *pulling* instead of marking.  During a stretch of
+// ping-pong rounds F_new holds the rows just written, F_old the round-start rows, and the two agree
+// on every row outside the round's V_aff.  Hence "row x moved by more than tol in this round" is
+// max_c |F_new[x][c] - F_old[x][c]| > tol for ANY vertex x (it is false for seeds, for rows outside
+// V_aff, and it is the same float32 comparison the update kernel made).  Alg. 2 Step 3 puts u into
+// the next V_aff iff u moved or one of its neighbours moved; this kernel evaluates exactly that for
+// every updatable vertex u (the universe list), scanning N(u) only when u itself did not move and
+// stopping at the first neighbour that did.  Rows that leave V_aff get their new value copied into
+// F_old so that the two buffers keep agreeing outside V_aff.  16 lanes per vertex.
+__global__ void __launch_bounds__(kBlock) k_next_frontier(unsigned int ns, unsigned int nl,
+                                                         const int32_t* __restrict__ front,
+                                                         const int32_t* __restrict__ back,
+                                                         const float* __restrict__ F_new,
+                                                         float* __restrict__ F_old, int CP, float tol,
+                                                         const RowMeta* __restrict__ meta,
+                                                         const Edge* __restrict__ pool, uint8_t* __restrict__ flag) {
     constexpr int G = 16;
     const unsigned int nq = ns + nl;
     const int gl = threadIdx.x % G;
@@ -143,10 +148,28 @@ __global__ void __launch_bounds__(kBlock) k_expand(unsigned int ns, unsigned int
         for (int k = gl; k < CP; k += G) r = fmaxf(r, fabsf(F_new[(size_t)u * CP + k] - F_old[(size_t)u * CP + k]));
 #pragma unroll
         for (int d = G / 2; d > 0; d >>= 1) r = fmaxf(r, __shfl_xor(r, d, G));
-        if (!(r > tol)) continue;
-        const RowMeta m = meta[u];
-        if (gl == 0) flag[u] = 1;
-        for (int j = gl; j < m.len; j += G) mark(flag, pool[m.off + j].col);
+        bool keep = r > tol;
+        if (!keep) {
+            const RowMeta m = meta[u];
+            const Edge* __restrict__ row = pool + m.off;
+            for (int j = 0; j < m.len; ++j) {  // uniform across the group
+                const int32_t v = row[j].col;
+                float rv = 0.f;
+                for (int k = gl; k < CP; k += G)
+                    rv = fmaxf(rv, fabsf(F_new[(size_t)v * CP + k] - F_old[(size_t)v * CP + k]));
+#pragma unroll
+                for (int d = G / 2; d > 0; d >>= 1) rv = fmaxf(rv, __shfl_xor(rv, d, G));
+                if (rv > tol) {
+                    keep = true;
+                    break;
+                }
+            }
+        }
+        if (keep) {
+            if (gl == 0) flag[u] = 1;
+        } else if (r > 0.f) {  // u was in V_aff and leaves it: bring the partner buffer up to date
+            for (int k = gl; k < CP; k += G) F_old[(size_t)u * CP + k] = F_new[(size_t)u * CP + k];
+        }
     }
 }
 
