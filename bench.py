@@ -176,6 +176,7 @@ def main():
     F_before = None
     per_step = []
     round_profile = []
+    buckets = {}
     for i, b in enumerate(d_batches):
         timed = i >= args.warmup
         if i == args.warmup and args.cpu_budget > 0:
@@ -188,21 +189,44 @@ def main():
         dt = time.perf_counter() - t0
         if timed:
             per_step.append(dict(ms=dt * 1e3, status=st, edges=batches[i].num_edges, **s.as_dict()))
-            if len(per_step) == 1:  # how the row-update kernel behaves as V_aff grows and shrinks
-                sizes, _, kms = d.round_log(kernel_ms=True)
-                pick = sorted(set(np.linspace(0, len(sizes) - 1, num=min(16, len(sizes))).astype(int).tolist()))
-                round_profile = [dict(round=int(j), frontier=int(sizes[j]), kernel_us=round(float(kms[j]) * 1e3, 1))
-                                 for j in pick]
+            info = d.round_log_full()
+            for r in info:  # per kernel: launches, rows, entries, device ms
+                for kind, rws, ent, ms in (("short", r.rows_short, r.entries_short, r.ms_short),
+                                           ("long", r.rows_long, r.entries_long, r.ms_long)):
+                    if rws > 0:
+                        b = buckets.setdefault((kind, int(r.staged), int(r.group_lanes) if kind == "short" else 0), [0, 0, 0, 0.0])
+                        b[0] += 1
+                        b[1] += int(rws)
+                        b[2] += int(ent)
+                        b[3] += float(ms)
+            if len(per_step) == 1:  # how the row-update kernels behave as V_aff grows and shrinks
+                pick = sorted(set(np.linspace(0, len(info) - 1, num=min(16, len(info))).astype(int).tolist()))
+                round_profile = [dict(round=int(j), frontier=int(info[j].rows_short + info[j].rows_long),
+                                      staged=int(info[j].staged),
+                                      kernel_us=round(float(info[j].ms_short + info[j].ms_long) * 1e3, 1)) for j in pick]
     total_s = sum(x["ms"] for x in per_step) / 1e3
     edges_inserted = sum(x["edges"] for x in per_step)
     rows = sum(x["rows_updated"] for x in per_step)
     trav = sum(x["edges_traversed"] for x in per_step)
-    k_ms = sum(x["ms_update_kernel"] for x in per_step)
-    launches = sum(x["update_launches"] for x in per_step)
-    alg_bytes = algorithmic_bytes(rows, trav, base["C"])
+    # The roofline entry is for the kernel that takes the most device time in the timed region.
+    CP = next(c for c in (1, 2, 4, 8, 16, 32, 64) if c >= base["C"])
+    kstats = {}
+    for (kind, staged, glanes), (cnt, rws, ent, ms) in buckets.items():
+        name = (f"k_row_update<{CP}, {glanes}, {'true' if staged else 'false'}>" if kind == "short"
+                else f"k_row_update_long<{CP}, {'true' if staged else 'false'}>")
+        ab = algorithmic_bytes(rws, ent, base["C"])
+        kstats[name] = dict(launches=cnt, rows=rws, entries=ent, device_ms=round(ms, 3),
+                            avg_launch_us=round(ms * 1e3 / max(1, cnt), 1),
+                            algorithmic_GBs=round(ab / 1e6 / max(ms, 1e-9), 1), algorithmic_bytes=ab)
+    dom = max(kstats, key=lambda k: kstats[k]["device_ms"])
+    launches = kstats[dom]["launches"]
+    k_ms = kstats[dom]["device_ms"]
+    alg_bytes = kstats[dom]["algorithmic_bytes"]
     achieved = alg_bytes / 1e6 / max(k_ms, 1e-9)  # GB/s
+    all_ms = sum(v["device_ms"] for v in kstats.values())
+    all_bytes = sum(v["algorithmic_bytes"] for v in kstats.values())
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"row_update_{args.workload}_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", f"row_update_{args.workload}_traffic.json")  # from rocprofv3 --pmc runs
     if os.path.exists(tpath):
         try:
             traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
@@ -225,7 +249,7 @@ def main():
                    "vertices_after": d.num_vertices, "directed_entries_after": d.num_entries},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "k_row_update (frontier row update)", "launches": launches,
+                     "kernel": dom, "launches": launches,
                      "avg_launch_us": k_ms * 1e3 / max(1, launches),
                      "algorithmic_bytes_per_launch": alg_bytes / max(1, launches)},
         "detail": {"rounds_per_step": [x["iterations"] for x in per_step],
@@ -237,6 +261,9 @@ def main():
                    "ms_iterate": [round(x["ms_iterate"], 3) for x in per_step],
                    "ms_update_kernel": [round(x["ms_update_kernel"], 3) for x in per_step],
                    "status": [x["status"] for x in per_step],
+                   "row_update_kernels": {k: {kk: vv for kk, vv in v.items() if kk != "algorithmic_bytes"}
+                                          for k, v in kstats.items()},
+                   "row_update_all_kernels_algorithmic_GBs": round(all_bytes / 1e6 / max(all_ms, 1e-9), 1),
                    "round_profile_first_step": round_profile,
                    "cold_start": cold, "gen_s": round(t_gen, 1)},
     }

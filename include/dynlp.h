@@ -165,14 +165,26 @@ int32_t dynlp_num_classes(const dynlp_ctx* ctx);
 dynlp_status dynlp_export_graph(dynlp_ctx* ctx, int64_t* row_ptr, int32_t* col, float* w, float* degree,
                                 int32_t* seed_class);
 
+/* One propagation round of the last dynlp_static_solve / dynlp_apply_batch. */
+typedef struct dynlp_round_info {
+    int64_t rows_short;    /* |V_aff| of the round, split by the kernel that updated the row: rows of */
+    int64_t rows_long;     /* at most 512 entries (short-row kernel) and longer rows (long-row kernel) */
+    int64_t entries_short; /* CSR entries those rows hold */
+    int64_t entries_long;
+    int64_t rows_moved;    /* rows with max_c |F'_u - F_u| > tol */
+    float max_delta;       /* max_u max_c |F'_u - F_u| */
+    float ms_short;        /* device time of the short-row launch (0 unless time_kernels) */
+    float ms_long;         /* device time of the long-row launch (0 unless time_kernels) */
+    int32_t staged;        /* 1: rows staged and committed after the kernel; 0: written straight into
+                              the second label buffer (static sweeps, ping-pong rounds) */
+    int32_t group_lanes;   /* lanes per row the short-row kernel ran with */
+} dynlp_round_info;
+
 /*
- * Per-round log of the last solve / batch: frontier size, max change and (with time_kernels) the
- * device time in ms of the row-update launches of round i, for the first min(rounds, cap) rounds
- * (HOST pointers regardless of ptrs_on_device; each may be NULL).
- * Returns the number of rounds the last call executed.
+ * Per-round log of the last solve / batch: copies the first min(rounds, cap) entries to out (HOST
+ * memory regardless of ptrs_on_device; may be NULL).  Returns the number of rounds executed.
  */
-int64_t dynlp_round_log(const dynlp_ctx* ctx, int64_t cap, int64_t* frontier_size, float* max_delta,
-                        float* kernel_ms);
+int64_t dynlp_round_log(const dynlp_ctx* ctx, int64_t cap, dynlp_round_info* out);
 
 /* Message for the last failed call on ctx (or, with ctx NULL, the last failed dynlp_create on this
  * thread).  Valid until the next call on the same context / thread.  Never NULL. */

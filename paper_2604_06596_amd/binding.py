@@ -35,6 +35,12 @@ class Stats(ct.Structure):
         return {k: getattr(self, k) for k, _ in self._fields_}
 
 
+class RoundInfo(ct.Structure):
+    _fields_ = [("rows_short", ct.c_int64), ("rows_long", ct.c_int64), ("entries_short", ct.c_int64),
+                ("entries_long", ct.c_int64), ("rows_moved", ct.c_int64), ("max_delta", ct.c_float),
+                ("ms_short", ct.c_float), ("ms_long", ct.c_float), ("staged", ct.c_int32), ("group_lanes", ct.c_int32)]
+
+
 _ALLOC_FN = ct.CFUNCTYPE(ct.c_void_p, ct.c_size_t, ct.c_void_p)
 _DEALLOC_FN = ct.CFUNCTYPE(None, ct.c_void_p, ct.c_void_p)
 
@@ -90,7 +96,7 @@ def load_library(path: str | None = None):
     L.dynlp_num_classes.restype = i32
     L.dynlp_export_graph.argtypes = [p, p, p, p, p, p]
     L.dynlp_export_graph.restype = ct.c_int
-    L.dynlp_round_log.argtypes = [p, i64, p, p, p]
+    L.dynlp_round_log.argtypes = [p, i64, ct.POINTER(RoundInfo)]
     L.dynlp_round_log.restype = i64
     L.dynlp_last_error.argtypes = [p]
     L.dynlp_last_error.restype = ct.c_char_p
@@ -222,17 +228,23 @@ class DynLP:
         self._check(self._L.dynlp_export_graph(self._h, rpp, colp, wp, degp, scp))
         return rp, col, w, deg, sc
 
+    def round_log_full(self):
+        """dynlp_round_log.  Returns the list of RoundInfo structures of the last solve / batch."""
+        rounds = int(self._L.dynlp_round_log(self._h, 0, None))
+        if rounds <= 0:
+            return []
+        buf = (RoundInfo * rounds)()
+        self._L.dynlp_round_log(self._h, rounds, buf)
+        return list(buf)
+
     def round_log(self, kernel_ms=False):
-        """dynlp_round_log.  Returns (frontier_sizes int64, max_delta float32) of the last call;
-        with kernel_ms=True also the per-round device time of the row-update launches."""
-        rounds = int(self._L.dynlp_round_log(self._h, 0, None, None, None))
-        sizes = np.zeros(rounds, dtype=np.int64)
-        delta = np.zeros(rounds, dtype=np.float32)
-        kms = np.zeros(rounds, dtype=np.float32)
-        if rounds:
-            self._L.dynlp_round_log(self._h, rounds, sizes.ctypes.data_as(ct.c_void_p),
-                                    delta.ctypes.data_as(ct.c_void_p), kms.ctypes.data_as(ct.c_void_p))
-        return (sizes, delta, kms) if kernel_ms else (sizes, delta)
+        """Per-round (frontier sizes int64, max change float32[, row-update device time in ms])."""
+        info = self.round_log_full()
+        sizes = np.array([r.rows_short + r.rows_long for r in info], dtype=np.int64)
+        delta = np.array([r.max_delta for r in info], dtype=np.float32)
+        if kernel_ms:
+            return sizes, delta, np.array([r.ms_short + r.ms_long for r in info], dtype=np.float32)
+        return sizes, delta
 
     def destroy(self):
         if self._h:

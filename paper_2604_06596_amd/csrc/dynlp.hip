@@ -98,9 +98,7 @@ struct dynlp_ctx {
 
     float tol = 1e-4f;
     int32_t max_iter = 100000;
-    std::vector<int64_t> log_sizes;
-    std::vector<float> log_delta;
-    std::vector<float> log_kernel_ms;  // per round, filled when kernel timing is on
+    std::vector<dynlp_round_info> log;  // one entry per round of the last solve / batch
     std::vector<hipEvent_t> events;
     size_t events_used = 0;
     hipEvent_t phase_ev[4] = {nullptr, nullptr, nullptr, nullptr};
@@ -341,7 +339,7 @@ void launch_short_inst(dynlp_ctx* c, const Frontier& f, const UpdateArgs& a) {
 }
 
 template <int CP, bool STAGED>
-void launch_update_cp(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& a) {
+void launch_update_cp(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& a, hipEvent_t mid) {
     constexpr int LPN = CP >= 4 ? CP / 4 : 1;
     // the short-row kernel always runs (it also clears the next counter slot)
     bool done = false;
@@ -362,6 +360,7 @@ void launch_update_cp(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& 
     }
 #undef DYNLP_CASE
     if (!done) launch_short_inst<CP, 64, STAGED>(c, f, a);
+    if (mid) (void)hipEventRecord(mid, c->stream);
     if (f.nl) {
         const unsigned int blocks = (unsigned int)std::min<int64_t>(f.nl, (int64_t)c->num_cu * 8);
         hipLaunchKernelGGL((k_row_update_long<CP, STAGED>), dim3(blocks), dim3(kBlock), 0, c->stream, f.back, f.nl,
@@ -369,44 +368,63 @@ void launch_update_cp(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& 
     }
 }
 
-// Row update of one frontier (short-row launch + long-row launch), bracketed by events when
-// kernel timing is on.
+// Row update of one frontier: the short-row launch, then the long-row launch.  With kernel timing
+// on, three events per round bracket the two launches separately.
 template <bool STAGED>
 void launch_update(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& a) {
-    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipEvent_t e0 = nullptr, emid = nullptr, e1 = nullptr;
     if (c->time_kernels) {
-        while (c->events.size() < c->events_used + 2) {
+        while (c->events.size() < c->events_used + 3) {
             hipEvent_t e;
             HIPCHK(c, hipEventCreate(&e));
             c->events.push_back(e);
         }
         e0 = c->events[c->events_used++];
+        emid = c->events[c->events_used++];
         e1 = c->events[c->events_used++];
         HIPCHK(c, hipEventRecord(e0, c->stream));
     }
     switch (c->CP) {
-        case 1: launch_update_cp<1, STAGED>(c, G, f, a); break;
-        case 2: launch_update_cp<2, STAGED>(c, G, f, a); break;
-        case 4: launch_update_cp<4, STAGED>(c, G, f, a); break;
-        case 8: launch_update_cp<8, STAGED>(c, G, f, a); break;
-        case 16: launch_update_cp<16, STAGED>(c, G, f, a); break;
-        case 32: launch_update_cp<32, STAGED>(c, G, f, a); break;
-        default: launch_update_cp<64, STAGED>(c, G, f, a); break;
+        case 1: launch_update_cp<1, STAGED>(c, G, f, a, emid); break;
+        case 2: launch_update_cp<2, STAGED>(c, G, f, a, emid); break;
+        case 4: launch_update_cp<4, STAGED>(c, G, f, a, emid); break;
+        case 8: launch_update_cp<8, STAGED>(c, G, f, a, emid); break;
+        case 16: launch_update_cp<16, STAGED>(c, G, f, a, emid); break;
+        case 32: launch_update_cp<32, STAGED>(c, G, f, a, emid); break;
+        default: launch_update_cp<64, STAGED>(c, G, f, a, emid); break;
     }
     HIPCHK(c, hipGetLastError());
     if (c->time_kernels) HIPCHK(c, hipEventRecord(e1, c->stream));
 }
 
+// Resolve the per-round events into the round log; returns the summed device time of all
+// row-update launches.
 float collect_kernel_ms(dynlp_ctx* c) {
     float total = 0.f;
-    c->log_kernel_ms.clear();
-    for (size_t i = 0; i + 1 < c->events_used; i += 2) {
-        float ms = 0.f;
-        if (hipEventElapsedTime(&ms, c->events[i], c->events[i + 1]) == hipSuccess) total += ms;
-        c->log_kernel_ms.push_back(ms);
+    for (size_t i = 0, round = 0; i + 2 < c->events_used + 0 && round < c->log.size(); i += 3, ++round) {
+        float a = 0.f, b = 0.f;
+        (void)hipEventElapsedTime(&a, c->events[i], c->events[i + 1]);
+        (void)hipEventElapsedTime(&b, c->events[i + 1], c->events[i + 2]);
+        c->log[round].ms_short = a;
+        c->log[round].ms_long = b;
+        total += a + b;
     }
     c->events_used = 0;
     return total;
+}
+
+dynlp_round_info round_info(const Frontier& f, const RoundCtr& r, bool staged, int G) {
+    dynlp_round_info ri;
+    std::memset(&ri, 0, sizeof ri);
+    ri.rows_short = f.ns;
+    ri.rows_long = f.nl;
+    ri.entries_short = (int64_t)r.edges;
+    ri.entries_long = (int64_t)r.edges_long;
+    std::memcpy(&ri.max_delta, &r.resid_bits, sizeof(float));
+    ri.rows_moved = r.changed;
+    ri.staged = staged ? 1 : 0;
+    ri.group_lanes = G;
+    return ri;
 }
 
 // flag bytes (or, with all_rows, every updatable vertex) -> frontier `out`; the two counts land in
@@ -759,8 +777,7 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
     const auto t0 = Clock::now();
     try {
         HIPCHK(c, hipSetDevice(c->device));
-        c->log_sizes.clear();
-        c->log_delta.clear();
+        c->log.clear();
         c->events_used = 0;
         sync_partner(c);
         zero_ring(c);
@@ -778,9 +795,8 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
             const RoundCtr r = read_slot(c, it);
             std::swap(c->F, c->F2);
             std::memcpy(&last, &r.resid_bits, sizeof(float));
-            edges += (int64_t)r.edges;
-            c->log_sizes.push_back(nq);
-            c->log_delta.push_back(last);
+            edges += (int64_t)(r.edges + r.edges_long);
+            c->log.push_back(round_info(f, r, false, G));
             ++it;
             if (last <= tol) converged = true;
         }
@@ -835,8 +851,7 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
     bool mutated = false;
     try {
         HIPCHK(c, hipSetDevice(c->device));
-        c->log_sizes.clear();
-        c->log_delta.clear();
+        c->log.clear();
         c->events_used = 0;
         // ---- capacity for new vertices; their rows start empty, unlabelled, uniform ----
         if (n1 > c->n_cap) alloc_vertex_arrays(c, n1 + std::max<int64_t>(n1 / 2, 1024));
@@ -951,6 +966,7 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
                 sync_partner(c);
                 pingpong = true;
             }
+            const bool pingpong_round = pingpong;
             if (pingpong) {
                 // Ping-pong round: new rows go straight into the partner buffer (no staging, no commit,
                 // no marking); the next V_aff is pulled from the two buffers over all updatable vertices.
@@ -966,19 +982,19 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
                 launch_update<true>(c, G, f, a);
                 launch_commit(c, f);
             }
+            const bool staged = !pingpong_round;
             Frontier nf = frontier_of(c, cur ^ 1);
             launch_compact(c, nf, &slot->next_count, &slot->next_long, 0);
             const RoundCtr r = read_slot(c, it);
+            c->log.push_back(round_info(f, r, staged, G));
             nf.ns = r.next_count;
             nf.nl = r.next_long;
             f = nf;
             cur ^= 1;
             std::memcpy(&last, &r.resid_bits, sizeof(float));
             rows += nq;
-            edges += (int64_t)r.edges;
-            avg_len = nq ? (double)r.edges / (double)nq : avg_len;
-            c->log_sizes.push_back(nq);
-            c->log_delta.push_back(last);
+            edges += (int64_t)(r.edges + r.edges_long);
+            avg_len = nq ? (double)(r.edges + r.edges_long) / (double)nq : avg_len;
             peak = std::max<int64_t>(peak, f.size());
             ++it;
         }
@@ -1111,17 +1127,11 @@ dynlp_status dynlp_export_graph(dynlp_ctx* c, int64_t* row_ptr, int32_t* col, fl
     return st;
 }
 
-int64_t dynlp_round_log(const dynlp_ctx* ctx, int64_t cap, int64_t* frontier_size, float* max_delta,
-                        float* kernel_ms) {
+int64_t dynlp_round_log(const dynlp_ctx* ctx, int64_t cap, dynlp_round_info* out) {
     if (!ctx) return -1;
-    const int64_t rounds = (int64_t)ctx->log_sizes.size();
+    const int64_t rounds = (int64_t)ctx->log.size();
     const int64_t k = std::max<int64_t>(0, std::min(cap, rounds));
-    if (frontier_size) std::copy(ctx->log_sizes.begin(), ctx->log_sizes.begin() + k, frontier_size);
-    if (max_delta) std::copy(ctx->log_delta.begin(), ctx->log_delta.begin() + k, max_delta);
-    if (kernel_ms) {
-        for (int64_t i = 0; i < k; ++i)
-            kernel_ms[i] = i < (int64_t)ctx->log_kernel_ms.size() ? ctx->log_kernel_ms[(size_t)i] : 0.f;
-    }
+    if (out && k > 0) std::copy(ctx->log.begin(), ctx->log.begin() + k, out);
     return rounds;
 }
 

@@ -31,8 +31,8 @@ struct __attribute__((aligned(32))) RoundCtr {
     unsigned int resid_bits;   // max change of this round, float bits (non-negative floats order as uints)
     unsigned int changed;      // rows whose change exceeded tol
     unsigned int next_long;    // long rows of V_aff for the next round
-    unsigned long long edges;  // CSR entries traversed by the row update
-    unsigned long long pad1;
+    unsigned long long edges;  // CSR entries traversed by the short-row update kernel
+    unsigned long long edges_long;  // CSR entries traversed by the long-row update kernel
 };
 
 // Scalars of the insertion step and error reporting.

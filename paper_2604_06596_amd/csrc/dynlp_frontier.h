@@ -244,7 +244,7 @@ __device__ inline void accumulate_row(const Edge* __restrict__ row, int len, int
 
 // Per-workgroup totals -> one set of atomics on the round's counters.
 __device__ inline void flush_round_counters(float rmax, unsigned long long edges, unsigned int changed,
-                                            RoundCtr* __restrict__ ctr) {
+                                            RoundCtr* __restrict__ ctr, unsigned long long* edges_field) {
     __shared__ float sm_r[kBlock / kWave];
     __shared__ unsigned long long sm_e[kBlock / kWave];
     __shared__ unsigned int sm_c[kBlock / kWave];
@@ -264,7 +264,7 @@ __device__ inline void flush_round_counters(float rmax, unsigned long long edges
             changed += sm_c[i];
         }
         atomicMax(&ctr->resid_bits, __float_as_uint(rmax));
-        if (edges) atomicAdd(&ctr->edges, edges);
+        if (edges) atomicAdd(edges_field, edges);
         if (changed) atomicAdd(&ctr->changed, changed);
     }
 }
@@ -292,6 +292,7 @@ __global__ void __launch_bounds__(kBlock) k_row_update(const int32_t* __restrict
         ctr_zero->resid_bits = 0;
         ctr_zero->changed = 0;
         ctr_zero->edges = 0;
+        ctr_zero->edges_long = 0;
     }
     const int gl = threadIdx.x % G;
     const int slot = gl / LPN;
@@ -338,7 +339,7 @@ __global__ void __launch_bounds__(kBlock) k_row_update(const int32_t* __restrict
             nchanged += big ? 1u : 0u;
         }
     }
-    flush_round_counters(rmax, edges, nchanged, ctr);
+    flush_round_counters(rmax, edges, nchanged, ctr, &ctr->edges);
 }
 
 // Long rows: one workgroup per row.  Its kBlock/G groups take the row's chunks round-robin; their
@@ -422,7 +423,7 @@ __global__ void __launch_bounds__(kBlock) k_row_update_long(const int32_t* __res
         }
         __syncthreads();
     }
-    flush_round_counters(rmax, edges, nchanged, ctr);
+    flush_round_counters(rmax, edges, nchanged, ctr, &ctr->edges_long);
 }
 
 }  // namespace dynlp
