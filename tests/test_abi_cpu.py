@@ -118,3 +118,8 @@ def test_product_does_not_import_the_oracle():
         if f.endswith(".py"):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert not re.search(r"^\s*(from|import)\s+paper_2604_06596_amd", text, flags=re.M), f
+
+
+def test_round_info_layout_matches_header():
+    assert ct.sizeof(B.RoundInfo) == 5 * 8 + 3 * 4 + 2 * 4
+    assert B.RoundInfo.max_delta.offset == 40 and B.RoundInfo.group_lanes.offset == 56
