@@ -24,5 +24,6 @@ from .graphs import (  # noqa: F401
     small_random,
     small_random_batch,
     CONFIGS,
+    csr_with_batch,
     make_config,
 )

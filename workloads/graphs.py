@@ -492,3 +492,14 @@ def make_config(name: str, scale: float = 1.0) -> Problem:
         return chung_lu(n, cfg["C"], cfg["mean_degree"], cfg["exponent"], d_max, cfg["intra_frac"],
                         cfg["seed_frac"], seed)
     raise KeyError(name)
+
+
+def csr_with_batch(n_old: int, row_ptr, col, w, batch: Batch):
+    """Symmetric CSR of the graph after an insertion batch (plumbing for large cases: same sort
+    path as the generators; parallel edges stay separate entries)."""
+    src = np.repeat(np.arange(n_old, dtype=np.int64), np.diff(row_ptr))
+    up = src < col
+    eu = np.concatenate([src[up], batch.eu.astype(np.int64)])
+    ev = np.concatenate([col[up].astype(np.int64), batch.ev.astype(np.int64)])
+    ew = np.concatenate([w[up], batch.ew])
+    return edges_to_csr(n_old + batch.num_new_vertices, eu, ev, ew)
