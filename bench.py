@@ -195,20 +195,17 @@ def main():
         if timed:
             per_step.append(dict(ms=dt * 1e3, status=st, edges=batches[i].num_edges, **s.as_dict()))
             info = d.round_log_full()
-            for r in info:  # per kernel: launches, rows, entries, device ms
-                for kind, rws, ent, ms in (("short", r.rows_short, r.entries_short, r.ms_short),
-                                           ("long", r.rows_long, r.entries_long, r.ms_long)):
-                    if rws > 0:
-                        b = buckets.setdefault((kind, int(r.staged), int(r.group_lanes) if kind == "short" else 0), [0, 0, 0, 0.0])
-                        b[0] += 1
-                        b[1] += int(rws)
-                        b[2] += int(ent)
-                        b[3] += float(ms)
+            for r in info:  # per kernel instantiation: launches, rows, entries, device ms
+                b = buckets.setdefault((int(r.staged), int(r.group_lanes)), [0, 0, 0, 0.0])
+                b[0] += 1
+                b[1] += int(r.rows_short + r.rows_long)
+                b[2] += int(r.entries_short + r.entries_long)
+                b[3] += float(r.ms_update)
             if len(per_step) == 1:  # how the row-update kernels behave as V_aff grows and shrinks
                 pick = sorted(set(np.linspace(0, len(info) - 1, num=min(16, len(info))).astype(int).tolist()))
                 round_profile = [dict(round=int(j), frontier=int(info[j].rows_short + info[j].rows_long),
                                       staged=int(info[j].staged),
-                                      kernel_us=round(float(info[j].ms_short + info[j].ms_long) * 1e3, 1)) for j in pick]
+                                      kernel_us=round(float(info[j].ms_update) * 1e3, 1)) for j in pick]
     total_s = sum(x["ms"] for x in per_step) / 1e3
     edges_inserted = sum(x["edges"] for x in per_step)
     rows = sum(x["rows_updated"] for x in per_step)
@@ -216,9 +213,8 @@ def main():
     # The roofline entry is for the kernel that takes the most device time in the timed region.
     CP = next(c for c in (1, 2, 4, 8, 16, 32, 64) if c >= base["C"])
     kstats = {}
-    for (kind, staged, glanes), (cnt, rws, ent, ms) in buckets.items():
-        name = (f"k_row_update<{CP}, {glanes}, {'true' if staged else 'false'}>" if kind == "short"
-                else f"k_row_update_long<{CP}, {'true' if staged else 'false'}>")
+    for (staged, glanes), (cnt, rws, ent, ms) in buckets.items():
+        name = f"k_row_update<{CP}, {glanes}, {'true' if staged else 'false'}>"
         ab = algorithmic_bytes(rws, ent, base["C"])
         kstats[name] = dict(launches=cnt, rows=rws, entries=ent, device_ms=round(ms, 3),
                             avg_launch_us=round(ms * 1e3 / max(1, cnt), 1),

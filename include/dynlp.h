@@ -167,14 +167,14 @@ dynlp_status dynlp_export_graph(dynlp_ctx* ctx, int64_t* row_ptr, int32_t* col, 
 
 /* One propagation round of the last dynlp_static_solve / dynlp_apply_batch. */
 typedef struct dynlp_round_info {
-    int64_t rows_short;    /* |V_aff| of the round, split by the kernel that updated the row: rows of */
-    int64_t rows_long;     /* at most 512 entries (short-row kernel) and longer rows (long-row kernel) */
+    int64_t rows_short;    /* |V_aff| of the round, split by how the row was updated: rows of at most 512 */
+    int64_t rows_long;     /* entries (a few lanes per row) and longer rows (a workgroup per row)        */
     int64_t entries_short; /* CSR entries those rows hold */
     int64_t entries_long;
     int64_t rows_moved;    /* rows with max_c |F'_u - F_u| > tol */
     float max_delta;       /* max_u max_c |F'_u - F_u| */
-    float ms_short;        /* device time of the short-row launch (0 unless time_kernels) */
-    float ms_long;         /* device time of the long-row launch (0 unless time_kernels) */
+    float ms_update;       /* device time of the round's row-update launch (0 unless time_kernels) */
+    float reserved;
     int32_t staged;        /* 1: rows staged and committed after the kernel; 0: written straight into
                               the second label buffer (static sweeps, ping-pong rounds) */
     int32_t group_lanes;   /* lanes per row the short-row kernel ran with */

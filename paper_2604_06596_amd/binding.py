@@ -38,7 +38,7 @@ class Stats(ct.Structure):
 class RoundInfo(ct.Structure):
     _fields_ = [("rows_short", ct.c_int64), ("rows_long", ct.c_int64), ("entries_short", ct.c_int64),
                 ("entries_long", ct.c_int64), ("rows_moved", ct.c_int64), ("max_delta", ct.c_float),
-                ("ms_short", ct.c_float), ("ms_long", ct.c_float), ("staged", ct.c_int32), ("group_lanes", ct.c_int32)]
+                ("ms_update", ct.c_float), ("reserved", ct.c_float), ("staged", ct.c_int32), ("group_lanes", ct.c_int32)]
 
 
 _ALLOC_FN = ct.CFUNCTYPE(ct.c_void_p, ct.c_size_t, ct.c_void_p)
@@ -243,7 +243,7 @@ class DynLP:
         sizes = np.array([r.rows_short + r.rows_long for r in info], dtype=np.int64)
         delta = np.array([r.max_delta for r in info], dtype=np.float32)
         if kernel_ms:
-            return sizes, delta, np.array([r.ms_short + r.ms_long for r in info], dtype=np.float32)
+            return sizes, delta, np.array([r.ms_update for r in info], dtype=np.float32)
         return sizes, delta
 
     def destroy(self):

@@ -83,6 +83,8 @@ struct dynlp_ctx {
                                                       // updatable vertices (see dynlp_frontier.h)
     int32_t* add_cnt = nullptr;
     float* deg = nullptr;
+    unsigned int* stamp = nullptr;  // per-vertex round stamps of ping-pong rounds (see k_next_frontier)
+    unsigned int round_id = 0;      // id of the last ping-pong round; 0 is never used as a stamp
 
     int32_t* touched = nullptr;
     int64_t* reloc_off = nullptr;
@@ -207,6 +209,8 @@ void alloc_vertex_arrays(dynlp_ctx* c, int64_t new_cap) {
     int32_t* q2 = dev_alloc_n<int32_t>(c, new_cap);
     int32_t* add = dev_alloc_n<int32_t>(c, new_cap);
     float* deg = dev_alloc_n<float>(c, new_cap);
+    unsigned int* stamp = dev_alloc_n<unsigned int>(c, new_cap);
+    HIPCHK(c, hipMemsetAsync(stamp, 0, (size_t)new_cap * sizeof(unsigned int), c->stream));
     HIPCHK(c, hipMemsetAsync(flag, 0, (size_t)flag_cap, c->stream));
     HIPCHK(c, hipMemsetAsync(add, 0, (size_t)new_cap * sizeof(int32_t), c->stream));
     if (old_n > 0 && c->meta) {
@@ -226,6 +230,9 @@ void alloc_vertex_arrays(dynlp_ctx* c, int64_t new_cap) {
     dev_free(c, c->queue[2]);
     dev_free(c, c->add_cnt);
     dev_free(c, c->deg);
+    dev_free(c, c->stamp);
+    c->stamp = stamp;
+    c->round_id = 0;
     c->meta = meta;
     c->F = F;
     c->F2 = F2;
@@ -324,30 +331,32 @@ Frontier frontier_of(dynlp_ctx* c, int parity, unsigned int ns = 0, unsigned int
 struct UpdateArgs {
     const float* F_in;
     float* F_out;
+    unsigned int* stamp;  // per-vertex round stamps (ping-pong rounds), NULL otherwise
+    unsigned int round_id;
     float tol;
     RoundCtr* ctr;
     RoundCtr* ctr_zero;
 };
 
 template <int CP, int G, bool STAGED>
-void launch_short_inst(dynlp_ctx* c, const Frontier& f, const UpdateArgs& a) {
+void launch_update_inst(dynlp_ctx* c, const Frontier& f, const UpdateArgs& a) {
     constexpr int GPB = kBlock / G;
-    const int64_t want = ceil_div(f.ns, GPB);
-    const unsigned int blocks = (unsigned int)std::max<int64_t>(1, std::min<int64_t>(want, (int64_t)c->num_cu * 8));
-    hipLaunchKernelGGL((k_row_update<CP, G, STAGED>), dim3(blocks), dim3(kBlock), 0, c->stream, f.front, f.ns, c->meta,
-                       c->pool, a.F_in, a.F_out, c->flag, a.tol, a.ctr, a.ctr_zero);
+    const int64_t cap = (int64_t)c->num_cu * 8;
+    const unsigned int long_blocks = (unsigned int)std::min<int64_t>(f.nl, cap / 2);
+    const unsigned int short_blocks = (unsigned int)std::max<int64_t>(1, std::min<int64_t>(ceil_div(f.ns, GPB), cap));
+    hipLaunchKernelGGL((k_row_update<CP, G, STAGED>), dim3(long_blocks + short_blocks), dim3(kBlock), 0, c->stream,
+                       f.front, f.ns, f.back, f.nl, long_blocks, c->meta, c->pool, a.F_in, a.F_out, c->flag, a.stamp,
+                       a.round_id, a.tol, a.ctr, a.ctr_zero);
 }
 
 template <int CP, bool STAGED>
-void launch_update_cp(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& a, hipEvent_t mid) {
+void launch_update_cp(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& a) {
     constexpr int LPN = CP >= 4 ? CP / 4 : 1;
-    // the short-row kernel always runs (it also clears the next counter slot)
-    bool done = false;
 #define DYNLP_CASE(GV)                                              \
     case GV:                                                        \
         if constexpr (GV >= LPN) {                                  \
-            launch_short_inst<CP, GV, STAGED>(c, f, a);             \
-            done = true;                                            \
+            launch_update_inst<CP, GV, STAGED>(c, f, a);            \
+            return;                                                 \
         }                                                           \
         break;
     switch (G) {
@@ -359,39 +368,32 @@ void launch_update_cp(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& 
         default: break;
     }
 #undef DYNLP_CASE
-    if (!done) launch_short_inst<CP, 64, STAGED>(c, f, a);
-    if (mid) (void)hipEventRecord(mid, c->stream);
-    if (f.nl) {
-        const unsigned int blocks = (unsigned int)std::min<int64_t>(f.nl, (int64_t)c->num_cu * 8);
-        hipLaunchKernelGGL((k_row_update_long<CP, STAGED>), dim3(blocks), dim3(kBlock), 0, c->stream, f.back, f.nl,
-                           f.ns, c->meta, c->pool, a.F_in, a.F_out, c->flag, a.tol, a.ctr);
-    }
+    launch_update_inst<CP, 64, STAGED>(c, f, a);
 }
 
-// Row update of one frontier: the short-row launch, then the long-row launch.  With kernel timing
-// on, three events per round bracket the two launches separately.
+// Row update of one frontier: one launch (long rows and short rows share the grid).  With kernel
+// timing on, two events per round bracket it.
 template <bool STAGED>
 void launch_update(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& a) {
-    hipEvent_t e0 = nullptr, emid = nullptr, e1 = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
     if (c->time_kernels) {
-        while (c->events.size() < c->events_used + 3) {
+        while (c->events.size() < c->events_used + 2) {
             hipEvent_t e;
             HIPCHK(c, hipEventCreate(&e));
             c->events.push_back(e);
         }
         e0 = c->events[c->events_used++];
-        emid = c->events[c->events_used++];
         e1 = c->events[c->events_used++];
         HIPCHK(c, hipEventRecord(e0, c->stream));
     }
     switch (c->CP) {
-        case 1: launch_update_cp<1, STAGED>(c, G, f, a, emid); break;
-        case 2: launch_update_cp<2, STAGED>(c, G, f, a, emid); break;
-        case 4: launch_update_cp<4, STAGED>(c, G, f, a, emid); break;
-        case 8: launch_update_cp<8, STAGED>(c, G, f, a, emid); break;
-        case 16: launch_update_cp<16, STAGED>(c, G, f, a, emid); break;
-        case 32: launch_update_cp<32, STAGED>(c, G, f, a, emid); break;
-        default: launch_update_cp<64, STAGED>(c, G, f, a, emid); break;
+        case 1: launch_update_cp<1, STAGED>(c, G, f, a); break;
+        case 2: launch_update_cp<2, STAGED>(c, G, f, a); break;
+        case 4: launch_update_cp<4, STAGED>(c, G, f, a); break;
+        case 8: launch_update_cp<8, STAGED>(c, G, f, a); break;
+        case 16: launch_update_cp<16, STAGED>(c, G, f, a); break;
+        case 32: launch_update_cp<32, STAGED>(c, G, f, a); break;
+        default: launch_update_cp<64, STAGED>(c, G, f, a); break;
     }
     HIPCHK(c, hipGetLastError());
     if (c->time_kernels) HIPCHK(c, hipEventRecord(e1, c->stream));
@@ -401,13 +403,11 @@ void launch_update(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& a) 
 // row-update launches.
 float collect_kernel_ms(dynlp_ctx* c) {
     float total = 0.f;
-    for (size_t i = 0, round = 0; i + 2 < c->events_used + 0 && round < c->log.size(); i += 3, ++round) {
-        float a = 0.f, b = 0.f;
+    for (size_t i = 0, round = 0; i + 1 < c->events_used && round < c->log.size(); i += 2, ++round) {
+        float a = 0.f;
         (void)hipEventElapsedTime(&a, c->events[i], c->events[i + 1]);
-        (void)hipEventElapsedTime(&b, c->events[i + 1], c->events[i + 2]);
-        c->log[round].ms_short = a;
-        c->log[round].ms_long = b;
-        total += a + b;
+        c->log[round].ms_update = a;
+        total += a;
     }
     c->events_used = 0;
     return total;
@@ -450,7 +450,7 @@ void launch_next_frontier(dynlp_ctx* c, const Frontier& universe) {
     const unsigned int blocks = (unsigned int)std::max<int64_t>(
         1, std::min<int64_t>(ceil_div(universe.size(), kBlock / 16), (int64_t)c->num_cu * 16));
     hipLaunchKernelGGL(k_next_frontier, dim3(blocks), dim3(kBlock), 0, c->stream, universe.ns, universe.nl,
-                       universe.front, universe.back, c->F, c->F2, c->CP, c->tol, c->meta, c->pool, c->flag);
+                       universe.front, universe.back, c->stamp, c->round_id, c->F, c->F2, c->CP, c->meta, c->pool, c->flag);
     HIPCHK(c, hipGetLastError());
 }
 
@@ -534,7 +534,7 @@ void destroy_ctx(dynlp_ctx* c) {
     if (!c) return;
     (void)hipSetDevice(c->device);
     if (c->stream || c->meta) (void)hipStreamSynchronize(c->stream);
-    void* ptrs[] = {c->meta, c->pool, c->F, c->F2, c->seed_class, c->flag, c->queue[0], c->queue[1], c->queue[2], c->add_cnt,
+    void* ptrs[] = {c->meta, c->pool, c->F, c->F2, c->seed_class, c->flag, c->queue[0], c->queue[1], c->queue[2], c->stamp, c->add_cnt,
                     c->deg, c->touched, c->reloc_off, c->b_eu, c->b_ev, c->b_ew, c->b_sv, c->b_sc};
     for (void* p : ptrs) dev_free(c, p);
     if (c->ring) (void)hipFree(c->ring);
@@ -790,7 +790,7 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
         const int G = choose_group(c, c->n > 0 ? (double)c->entries / (double)std::max<int64_t>(1, nq) : 1.0);
         const auto t_it = Clock::now();
         while (!converged && it < max_iter) {
-            const UpdateArgs a{c->F, c->F2, tol, c->ring + (it % kRing), c->ring + ((it + 1) % kRing)};
+            const UpdateArgs a{c->F, c->F2, nullptr, 0u, tol, c->ring + (it % kRing), c->ring + ((it + 1) % kRing)};
             launch_update<false>(c, G, f, a);
             const RoundCtr r = read_slot(c, it);
             std::swap(c->F, c->F2);
@@ -970,7 +970,12 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
             if (pingpong) {
                 // Ping-pong round: new rows go straight into the partner buffer (no staging, no commit,
                 // no marking); the next V_aff is pulled from the two buffers over all updatable vertices.
-                const UpdateArgs a{c->F, c->F2, c->tol, slot, next_slot};
+                c->round_id = (c->round_id + 1u) & 0x7fffffffu;
+                if (c->round_id == 0u) {  // stamps wrapped: forget the old ones
+                    HIPCHK(c, hipMemsetAsync(c->stamp, 0, (size_t)c->n_cap * sizeof(unsigned int), c->stream));
+                    c->round_id = 1u;
+                }
+                const UpdateArgs a{c->F, c->F2, c->stamp, c->round_id, c->tol, slot, next_slot};
                 launch_update<false>(c, G, f, a);
                 std::swap(c->F, c->F2);
                 launch_next_frontier(c, universe);
@@ -978,7 +983,7 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
             } else {
                 // Staged round: rows are staged by frontier position, committed after the kernel, and
                 // the rows that moved mark themselves and their neighbours for the next round.
-                const UpdateArgs a{c->F, c->F2, c->tol, slot, next_slot};
+                const UpdateArgs a{c->F, c->F2, nullptr, 0u, c->tol, slot, next_slot};
                 launch_update<true>(c, G, f, a);
                 launch_commit(c, f);
             }

@@ -123,43 +123,41 @@ __device__ inline void mark(uint8_t* __restrict__ flag, int32_t v) {
     if (!flag[v]) flag[v] = 1;
 }
 
-// Next V_aff after a ping-pong round, computed by *pulling* instead of marking.  During a stretch of
-// ping-pong rounds F_new holds the rows just written, F_old the round-start rows, and the two agree
-// on every row outside the round's V_aff.  Hence "row x moved by more than tol in this round" is
-// max_c |F_new[x][c] - F_old[x][c]| > tol for ANY vertex x (it is false for seeds, for rows outside
-// V_aff, and it is the same float32 comparison the update kernel made).  Alg. 2 Step 3 puts u into
-// the next V_aff iff u moved or one of its neighbours moved; this kernel evaluates exactly that for
-// every updatable vertex u (the universe list), scanning N(u) only when u itself did not move and
-// stopping at the first neighbour that did.  Rows that leave V_aff get their new value copied into
-// F_old so that the two buffers keep agreeing outside V_aff.  16 lanes per vertex.
+// Next V_aff after a ping-pong round, computed by *pulling* instead of marking.  The update kernels
+// of a ping-pong round leave a stamp per updated row: stamp[u] = round id if the row moved by more
+// than tol, round id | kStampStill if it was updated but did not move.  Alg. 2 Step 3 puts u into the
+// next V_aff iff u moved or one of its neighbours moved; this kernel evaluates exactly that for every
+// updatable vertex u (the universe list): one stamp read, and only when u itself did not move a scan
+// of N(u)'s stamps, 16 neighbours at a time, that stops at the first chunk with a hit.  A row that was
+// updated in this round and now leaves V_aff gets its new value copied into F_old, so that the two
+// label buffers keep agreeing on every row outside V_aff (the invariant ping-pong rounds rely on).
+// 16 lanes per vertex.
+constexpr unsigned int kStampStill = 0x80000000u;
+
 __global__ void __launch_bounds__(kBlock) k_next_frontier(unsigned int ns, unsigned int nl,
                                                          const int32_t* __restrict__ front,
                                                          const int32_t* __restrict__ back,
-                                                         const float* __restrict__ F_new,
-                                                         float* __restrict__ F_old, int CP, float tol,
+                                                         const unsigned int* __restrict__ stamp,
+                                                         unsigned int round_id, const float* __restrict__ F_new,
+                                                         float* __restrict__ F_old, int CP,
                                                          const RowMeta* __restrict__ meta,
                                                          const Edge* __restrict__ pool, uint8_t* __restrict__ flag) {
     constexpr int G = 16;
     const unsigned int nq = ns + nl;
     const int gl = threadIdx.x % G;
+    const int group_in_wave = (threadIdx.x % kWave) / G;
     for (unsigned int pos = blockIdx.x * (kBlock / G) + threadIdx.x / G; pos < nq; pos += gridDim.x * (kBlock / G)) {
         const int32_t u = frontier_vertex(front, back, ns, pos);
-        float r = 0.f;
-        for (int k = gl; k < CP; k += G) r = fmaxf(r, fabsf(F_new[(size_t)u * CP + k] - F_old[(size_t)u * CP + k]));
-#pragma unroll
-        for (int d = G / 2; d > 0; d >>= 1) r = fmaxf(r, __shfl_xor(r, d, G));
-        bool keep = r > tol;
+        const unsigned int su = stamp[u];
+        bool keep = su == round_id;
         if (!keep) {
             const RowMeta m = meta[u];
             const Edge* __restrict__ row = pool + m.off;
-            for (int j = 0; j < m.len; ++j) {  // uniform across the group
-                const int32_t v = row[j].col;
-                float rv = 0.f;
-                for (int k = gl; k < CP; k += G)
-                    rv = fmaxf(rv, fabsf(F_new[(size_t)v * CP + k] - F_old[(size_t)v * CP + k]));
-#pragma unroll
-                for (int d = G / 2; d > 0; d >>= 1) rv = fmaxf(rv, __shfl_xor(rv, d, G));
-                if (rv > tol) {
+            for (int base = 0; base < m.len; base += G) {  // uniform across the group
+                const int j = base + gl;
+                const bool hit = j < m.len && stamp[row[j].col] == round_id;
+                const unsigned long long b = __ballot(hit);
+                if ((b >> (group_in_wave * G)) & 0xffffull) {
                     keep = true;
                     break;
                 }
@@ -167,7 +165,7 @@ __global__ void __launch_bounds__(kBlock) k_next_frontier(unsigned int ns, unsig
         }
         if (keep) {
             if (gl == 0) flag[u] = 1;
-        } else if (r > 0.f) {  // u was in V_aff and leaves it: bring the partner buffer up to date
+        } else if (su == (round_id | kStampStill)) {  // updated in this round, leaves V_aff
             for (int k = gl; k < CP; k += G) F_old[(size_t)u * CP + k] = F_new[(size_t)u * CP + k];
         }
     }
@@ -269,31 +267,23 @@ __device__ inline void flush_round_counters(float rmax, unsigned long long edges
     }
 }
 
-// Short rows: G lanes per row, grid-strided.
+// Short rows: G lanes per row, grid-strided (body; k_row_update dispatches to it).
 //   STAGED = false (static sweep / ping-pong round): F'_u is written to row u of F_out, the
-//            ping-pong partner of F_in.
+//            ping-pong partner of F_in; stamp[u] (if not NULL) records the round id and whether
+//            the row moved by more than tol (see k_next_frontier).
 //   STAGED = true (partial round): F'_u is staged at row pos of F_out so that every row of this
 //            round reads the round-start F (Jacobi); a row that moved by > tol marks itself and
 //            its neighbours in flag[] for the next round.
 template <int CP, int G, bool STAGED>
-__global__ void __launch_bounds__(kBlock) k_row_update(const int32_t* __restrict__ front, unsigned int ns,
-                                                      const RowMeta* __restrict__ meta,
-                                                      const Edge* __restrict__ pool,
-                                                      const float* __restrict__ F_in, float* __restrict__ F_out,
-                                                      uint8_t* __restrict__ flag, float tol,
-                                                      RoundCtr* __restrict__ ctr,
-                                                      RoundCtr* __restrict__ ctr_zero) {
+__device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, const int32_t* __restrict__ front,
+                                        unsigned int ns, const RowMeta* __restrict__ meta,
+                                        const Edge* __restrict__ pool, const float* __restrict__ F_in,
+                                        float* __restrict__ F_out, uint8_t* __restrict__ flag,
+                                        unsigned int* __restrict__ stamp, unsigned int round_id, float tol,
+                                        RoundCtr* __restrict__ ctr) {
     constexpr int VEC = RowShape<CP>::VEC;
     constexpr int LPN = RowShape<CP>::LPN;
     constexpr int GPB = kBlock / G;
-    if (ctr_zero && blockIdx.x == 0 && threadIdx.x == 0) {
-        ctr_zero->next_count = 0;
-        ctr_zero->next_long = 0;
-        ctr_zero->resid_bits = 0;
-        ctr_zero->changed = 0;
-        ctr_zero->edges = 0;
-        ctr_zero->edges_long = 0;
-    }
     const int gl = threadIdx.x % G;
     const int slot = gl / LPN;
     const int chunk = gl % LPN;
@@ -301,7 +291,7 @@ __global__ void __launch_bounds__(kBlock) k_row_update(const int32_t* __restrict
     unsigned long long edges = 0;
     unsigned int nchanged = 0;
 
-    for (unsigned int g = blockIdx.x * GPB + threadIdx.x / G; g < ns; g += gridDim.x * GPB) {
+    for (unsigned int g = bid * GPB + threadIdx.x / G; g < ns; g += nblocks * GPB) {
         const int32_t u = front[g];
         const RowMeta m = meta[u];
         const Edge* __restrict__ row = pool + m.off;
@@ -332,6 +322,8 @@ __global__ void __launch_bounds__(kBlock) k_row_update(const int32_t* __restrict
                 const int last_base = ((m.len - 1) / G) * G;
                 for (int idx = gl; idx < last_base; idx += G) mark(flag, row[idx].col);
             }
+        } else if (stamp && gl == 0) {
+            stamp[u] = big ? round_id : (round_id | 0x80000000u);
         }
         if (gl == 0) {
             rmax = fmaxf(rmax, r);
@@ -342,18 +334,16 @@ __global__ void __launch_bounds__(kBlock) k_row_update(const int32_t* __restrict
     flush_round_counters(rmax, edges, nchanged, ctr, &ctr->edges);
 }
 
-// Long rows: one workgroup per row.  Its kBlock/G groups take the row's chunks round-robin; their
+// Long rows: one workgroup per row (body; k_row_update dispatches to it).  Its kBlock/G groups take the row's chunks round-robin; their
 // partial sums meet in LDS and are added in group order (a fixed order: results do not depend on
 // timing).  Position of long row j is pos_base + j.
 template <int CP, bool STAGED>
-__global__ void __launch_bounds__(kBlock) k_row_update_long(const int32_t* __restrict__ back, unsigned int nl,
-                                                           unsigned int pos_base,
-                                                           const RowMeta* __restrict__ meta,
-                                                           const Edge* __restrict__ pool,
-                                                           const float* __restrict__ F_in,
-                                                           float* __restrict__ F_out, uint8_t* __restrict__ flag,
-                                                           float tol,
-                                                           RoundCtr* __restrict__ ctr) {
+__device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, const int32_t* __restrict__ back,
+                                       unsigned int nl, unsigned int pos_base, const RowMeta* __restrict__ meta,
+                                       const Edge* __restrict__ pool, const float* __restrict__ F_in,
+                                       float* __restrict__ F_out, uint8_t* __restrict__ flag,
+                                       unsigned int* __restrict__ stamp, unsigned int round_id, float tol,
+                                       RoundCtr* __restrict__ ctr) {
     constexpr int VEC = RowShape<CP>::VEC;
     constexpr int LPN = RowShape<CP>::LPN;
     constexpr int G = LPN > 16 ? LPN : 16;
@@ -369,7 +359,7 @@ __global__ void __launch_bounds__(kBlock) k_row_update_long(const int32_t* __res
     unsigned long long edges = 0;
     unsigned int nchanged = 0;
 
-    for (unsigned int j = blockIdx.x; j < nl; j += gridDim.x) {
+    for (unsigned int j = bid; j < nl; j += nblocks) {
         const int32_t u = back[-(long long)j];
         const RowMeta m = meta[u];
         const Edge* __restrict__ row = pool + m.off;
@@ -411,6 +401,7 @@ __global__ void __launch_bounds__(kBlock) k_row_update_long(const int32_t* __res
             if (gl == 0) {
                 const bool big = r > tol;
                 sh_big = big ? 1 : 0;
+                if (!STAGED && stamp) stamp[u] = big ? round_id : (round_id | 0x80000000u);
                 rmax = fmaxf(rmax, r);
                 edges += (unsigned long long)m.len;
                 nchanged += big ? 1u : 0u;
@@ -424,6 +415,35 @@ __global__ void __launch_bounds__(kBlock) k_row_update_long(const int32_t* __res
         __syncthreads();
     }
     flush_round_counters(rmax, edges, nchanged, ctr, &ctr->edges_long);
+}
+
+// One launch per round: workgroups [0, long_blocks) take the long rows (started first, they are the
+// long poles), the remaining workgroups take the short rows.  Workgroup 0 also clears the counter
+// slot of the next round.
+template <int CP, int G, bool STAGED>
+__global__ void __launch_bounds__(kBlock) k_row_update(const int32_t* __restrict__ front, unsigned int ns,
+                                                      const int32_t* __restrict__ back, unsigned int nl,
+                                                      unsigned int long_blocks, const RowMeta* __restrict__ meta,
+                                                      const Edge* __restrict__ pool,
+                                                      const float* __restrict__ F_in, float* __restrict__ F_out,
+                                                      uint8_t* __restrict__ flag, unsigned int* __restrict__ stamp,
+                                                      unsigned int round_id, float tol,
+                                                      RoundCtr* __restrict__ ctr,
+                                                      RoundCtr* __restrict__ ctr_zero) {
+    if (ctr_zero && blockIdx.x == 0 && threadIdx.x == 0) {
+        ctr_zero->next_count = 0;
+        ctr_zero->next_long = 0;
+        ctr_zero->resid_bits = 0;
+        ctr_zero->changed = 0;
+        ctr_zero->edges = 0;
+        ctr_zero->edges_long = 0;
+    }
+    if (blockIdx.x < long_blocks)
+        row_update_long<CP, STAGED>(blockIdx.x, long_blocks, back, nl, ns, meta, pool, F_in, F_out, flag, stamp,
+                                    round_id, tol, ctr);
+    else
+        row_update_short<CP, G, STAGED>(blockIdx.x - long_blocks, gridDim.x - long_blocks, front, ns, meta, pool, F_in,
+                                        F_out, flag, stamp, round_id, tol, ctr);
 }
 
 }  // namespace dynlp
