@@ -93,9 +93,9 @@ struct dynlp_ctx {
     float* b_ew = nullptr;
     int64_t b_edge_cap = 0, b_seed_cap = 0;
 
-    RoundCtr* ring = nullptr;  // kRing slots
+    RoundCtr* ring = nullptr;  // kRing round slots + the start slot
     BatchCtr* bc = nullptr;
-    RoundCtr* h_slot = nullptr;  // pinned
+    RoundCtr* h_slot = nullptr;  // pinned, kRing slots
     BatchCtr* h_bc = nullptr;    // pinned
 
     float tol = 1e-4f;
@@ -311,11 +311,12 @@ int choose_group(const dynlp_ctx* c, double avg_len) {
     return std::max(g, lpn);
 }
 
-// One propagation round's frontier: ns short rows at front[0..ns), nl long rows at back[0..-nl).
+// One propagation round's frontier lives in the array of one parity: short rows from the front,
+// long rows from the back.  Its size is only on the device (the previous round's counter slot).
 struct Frontier {
     int32_t* front = nullptr;
     int32_t* back = nullptr;
-    unsigned int ns = 0, nl = 0;
+    unsigned int ns = 0, nl = 0;  // only meaningful for lists whose size the host has read
     unsigned int size() const { return ns + nl; }
 };
 
@@ -329,6 +330,8 @@ Frontier frontier_of(dynlp_ctx* c, int parity, unsigned int ns = 0, unsigned int
 }
 
 struct UpdateArgs {
+    const RoundCtr* prev;  // slot that holds the size of the frontier to work on
+    int static_stop;       // 0: frontier round; 1: static sweep; 2: static sweep that checks prev's stop rule
     const float* F_in;
     float* F_out;
     unsigned int* stamp;  // per-vertex round stamps (ping-pong rounds), NULL otherwise
@@ -336,17 +339,19 @@ struct UpdateArgs {
     float tol;
     RoundCtr* ctr;
     RoundCtr* ctr_zero;
+    int64_t rows_bound;  // upper bound of the frontier size (sizes the grid)
 };
 
 template <int CP, int G, bool STAGED>
 void launch_update_inst(dynlp_ctx* c, const Frontier& f, const UpdateArgs& a) {
     constexpr int GPB = kBlock / G;
     const int64_t cap = (int64_t)c->num_cu * 8;
-    const unsigned int long_blocks = (unsigned int)std::min<int64_t>(f.nl, cap / 2);
-    const unsigned int short_blocks = (unsigned int)std::max<int64_t>(1, std::min<int64_t>(ceil_div(f.ns, GPB), cap));
-    hipLaunchKernelGGL((k_row_update<CP, G, STAGED>), dim3(long_blocks + short_blocks), dim3(kBlock), 0, c->stream,
-                       f.front, f.ns, f.back, f.nl, long_blocks, c->meta, c->pool, a.F_in, a.F_out, c->flag, a.stamp,
-                       a.round_id, a.tol, a.ctr, a.ctr_zero);
+    const unsigned int blocks = (unsigned int)std::max<int64_t>(4, std::min<int64_t>(ceil_div(a.rows_bound, GPB) + 4, cap));
+    unsigned int stop_bits;
+    std::memcpy(&stop_bits, &a.tol, sizeof stop_bits);
+    hipLaunchKernelGGL((k_row_update<CP, G, STAGED>), dim3(blocks), dim3(kBlock), 0, c->stream, a.prev, a.static_stop,
+                       stop_bits, f.front, f.back, c->meta, c->pool, a.F_in, a.F_out, c->flag, a.stamp, a.round_id, a.tol,
+                       a.ctr, a.ctr_zero);
 }
 
 template <int CP, bool STAGED>
@@ -413,11 +418,11 @@ float collect_kernel_ms(dynlp_ctx* c) {
     return total;
 }
 
-dynlp_round_info round_info(const Frontier& f, const RoundCtr& r, bool staged, int G) {
+dynlp_round_info round_info(const RoundCtr& r, bool staged, int G) {
     dynlp_round_info ri;
     std::memset(&ri, 0, sizeof ri);
-    ri.rows_short = f.ns;
-    ri.rows_long = f.nl;
+    ri.rows_short = r.rows_short;
+    ri.rows_long = r.rows_long;
     ri.entries_short = (int64_t)r.edges;
     ri.entries_long = (int64_t)r.edges_long;
     std::memcpy(&ri.max_delta, &r.resid_bits, sizeof(float));
@@ -437,20 +442,21 @@ void launch_compact(dynlp_ctx* c, const Frontier& out, unsigned int* count_short
     HIPCHK(c, hipGetLastError());
 }
 
-void launch_commit(dynlp_ctx* c, const Frontier& f) {
-    const int64_t items = (int64_t)f.size() * (c->CP >= 4 ? c->CP / 4 : c->CP);
+void launch_commit(dynlp_ctx* c, const Frontier& f, const RoundCtr* prev, int64_t rows_bound) {
+    const int64_t items = rows_bound * (c->CP >= 4 ? c->CP / 4 : c->CP);
     const unsigned int blocks = (unsigned int)std::max<int64_t>(1, std::min<int64_t>(ceil_div(items, kBlock), (int64_t)c->num_cu * 8));
-    hipLaunchKernelGGL(k_commit, dim3(blocks), dim3(kBlock), 0, c->stream, f.ns, f.nl, f.front, f.back, c->F2, c->F, c->CP);
+    hipLaunchKernelGGL(k_commit, dim3(blocks), dim3(kBlock), 0, c->stream, prev, f.front, f.back, c->F2, c->F, c->CP);
     HIPCHK(c, hipGetLastError());
 }
 
-// Pull the next V_aff out of the two label buffers (called after they were swapped: F holds the new
-// rows, F2 the round-start rows); `universe` lists every updatable vertex.
-void launch_next_frontier(dynlp_ctx* c, const Frontier& universe) {
+// Pull the next V_aff out of the round stamps; F_new holds the rows just written, F_old the
+// round-start rows; `universe` lists every updatable vertex.
+void launch_next_frontier(dynlp_ctx* c, const Frontier& universe, const float* F_new, float* F_old) {
     const unsigned int blocks = (unsigned int)std::max<int64_t>(
         1, std::min<int64_t>(ceil_div(universe.size(), kBlock / 16), (int64_t)c->num_cu * 16));
     hipLaunchKernelGGL(k_next_frontier, dim3(blocks), dim3(kBlock), 0, c->stream, universe.ns, universe.nl,
-                       universe.front, universe.back, c->stamp, c->round_id, c->F, c->F2, c->CP, c->meta, c->pool, c->flag);
+                       universe.front, universe.back, c->stamp, c->round_id, F_new, F_old, c->CP, c->meta, c->pool,
+                       c->flag);
     HIPCHK(c, hipGetLastError());
 }
 
@@ -465,25 +471,30 @@ void sync_partner(dynlp_ctx* c) {
         HIPCHK(c, hipMemcpyAsync(c->F2, c->F, (size_t)c->n * c->CP * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
 }
 
-// Every updatable vertex (unlabelled, at least one edge) into the frontier of the given parity.
-Frontier all_updatable(dynlp_ctx* c, int parity) {
-    Frontier f = frontier_of(c, parity);
-    HIPCHK(c, hipMemsetAsync(&c->bc->init_count, 0, 2 * sizeof(unsigned int), c->stream));
-    launch_compact(c, f, &c->bc->init_count, &c->bc->init_long, 1);
-    read_bc(c);
-    f.ns = c->h_bc->init_count;
-    f.nl = c->h_bc->init_long;
-    return f;
-}
-
 void zero_ring(dynlp_ctx* c) {
-    HIPCHK(c, hipMemsetAsync(c->ring, 0, sizeof(RoundCtr) * kRing, c->stream));
+    HIPCHK(c, hipMemsetAsync(c->ring, 0, sizeof(RoundCtr) * (kRing + 1), c->stream));
 }
 
-RoundCtr read_slot(dynlp_ctx* c, int t) {
-    HIPCHK(c, hipMemcpyAsync(c->h_slot, c->ring + (t % kRing), sizeof(RoundCtr), hipMemcpyDeviceToHost, c->stream));
+// Slot of round t; round -1 is the start slot that holds the size of the first frontier.
+RoundCtr* slot_of(dynlp_ctx* c, int t) { return t < 0 ? c->ring + kRing : c->ring + (t % kRing); }
+
+// Copy the slots of rounds [t0, t0 + count) to the host (count <= kRing) and wait for them.
+void read_slots(dynlp_ctx* c, int t0, int count) {
+    for (int i = 0; i < count;) {
+        const int idx = (t0 + i) % kRing;
+        const int run = std::min(count - i, kRing - idx);
+        HIPCHK(c, hipMemcpyAsync(c->h_slot + i, c->ring + idx, sizeof(RoundCtr) * (size_t)run, hipMemcpyDeviceToHost, c->stream));
+        i += run;
+    }
     HIPCHK(c, hipStreamSynchronize(c->stream));
-    return *c->h_slot;
+}
+
+// Rounds queued per host round trip.
+constexpr int kChain = 8;
+
+void read_slots_start(dynlp_ctx* c) {
+    HIPCHK(c, hipMemcpyAsync(c->h_slot, c->ring + kRing, sizeof(RoundCtr), hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
 }
 
 void fill_stats_zero(dynlp_stats* s) {
@@ -646,9 +657,9 @@ dynlp_status dynlp_create(dynlp_ctx** out, int64_t n, const int64_t* row_ptr, co
         hipDeviceProp_t prop;
         HIPCHK(c, hipGetDeviceProperties(&prop, c->device));
         c->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->ring), sizeof(RoundCtr) * kRing));
+        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->ring), sizeof(RoundCtr) * (kRing + 1)));
         HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->bc), sizeof(BatchCtr)));
-        HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_slot), sizeof(RoundCtr), hipHostMallocDefault));
+        HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_slot), sizeof(RoundCtr) * kRing, hipHostMallocDefault));
         HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_bc), sizeof(BatchCtr), hipHostMallocDefault));
         for (auto& e : c->phase_ev) HIPCHK(c, hipEventCreate(&e));
         std::memset(c->h_bc, 0, sizeof(BatchCtr));
@@ -781,25 +792,44 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
         c->events_used = 0;
         sync_partner(c);
         zero_ring(c);
-        const Frontier f = all_updatable(c, 0);
-        const unsigned int nq = f.size();
+        const Frontier f = frontier_of(c, 0);
+        RoundCtr* start = slot_of(c, -1);
+        launch_compact(c, f, &start->next_count, &start->next_long, 1);
+        read_slots_start(c);
+        const unsigned int nq = c->h_slot[0].next_count + c->h_slot[0].next_long;
         int it = 0;
         float last = 0.f;
         bool converged = nq == 0;
         int64_t edges = 0;
         const int G = choose_group(c, c->n > 0 ? (double)c->entries / (double)std::max<int64_t>(1, nq) : 1.0);
         const auto t_it = Clock::now();
+        float* const buf[2] = {c->F, c->F2};  // sweep t reads buf[t & 1], writes buf[(t + 1) & 1]
         while (!converged && it < max_iter) {
-            const UpdateArgs a{c->F, c->F2, nullptr, 0u, tol, c->ring + (it % kRing), c->ring + ((it + 1) % kRing)};
-            launch_update<false>(c, G, f, a);
-            const RoundCtr r = read_slot(c, it);
-            std::swap(c->F, c->F2);
-            std::memcpy(&last, &r.resid_bits, sizeof(float));
-            edges += (int64_t)(r.edges + r.edges_long);
-            c->log.push_back(round_info(f, r, false, G));
-            ++it;
-            if (last <= tol) converged = true;
+            // a chain of sweeps; each checks on the device whether its predecessor already met the stop rule
+            const int r = std::min<int>(kChain, max_iter - it);
+            for (int i = 0; i < r; ++i) {
+                const int t = it + i;
+                const UpdateArgs a{slot_of(c, t - 1), t == 0 ? 1 : 2, buf[t & 1], buf[(t + 1) & 1], nullptr, 0u, tol,
+                                   slot_of(c, t), slot_of(c, t + 1), (int64_t)nq};
+                launch_update<false>(c, G, f, a);
+            }
+            read_slots(c, it, r);
+            for (int i = 0; i < r; ++i) {
+                const RoundCtr& rc = c->h_slot[i];
+                if (!rc.executed) break;
+                std::memcpy(&last, &rc.resid_bits, sizeof(float));
+                edges += (int64_t)(rc.edges + rc.edges_long);
+                c->log.push_back(round_info(rc, false, G));
+                ++it;
+                if (last <= tol) {
+                    converged = true;
+                    break;
+                }
+            }
         }
+        // the labels of the last executed sweep
+        c->F = buf[it & 1];
+        c->F2 = buf[(it + 1) & 1];
         const float kernel_ms_total = c->time_kernels ? collect_kernel_ms(c) : 0.f;
         if (stats) {
             stats->iterations = it;
@@ -934,76 +964,87 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
             hipLaunchKernelGGL(k_apply_seeds, dim3(grid_for(s * 16)), dim3(kBlock), 0, c->stream, s, d_sv, d_sc, c->C, c->CP,
                                c->seed_class, c->F, c->meta, c->pool, c->flag);
         zero_ring(c);
-        // first frontier from the flags, and the list of all updatable vertices
-        Frontier f = frontier_of(c, 0);
-        launch_compact(c, f, &c->bc->init_count, &c->bc->init_long, 0);
+        // first frontier from the flags (its size goes to the start slot), and the list of all updatable
+        // vertices
+        RoundCtr* start = slot_of(c, -1);
+        launch_compact(c, frontier_of(c, 0), &start->next_count, &start->next_long, 0);
         Frontier universe = frontier_of(c, 2);
         launch_compact(c, universe, &c->bc->upd_short, &c->bc->upd_long, 1);
         read_bc(c);
-        universe.ns = c->h_bc->upd_short;
-        universe.nl = c->h_bc->upd_long;
+        read_slots_start(c);
         c->pool_tail = (int64_t)c->h_bc->pool_tail;
         const int64_t relocated = c->h_bc->relocated;
-        f.ns = c->h_bc->init_count;
-        f.nl = c->h_bc->init_long;
+        universe.ns = c->h_bc->upd_short;
+        universe.nl = c->h_bc->upd_long;
+        unsigned int known = c->h_slot[0].next_count + c->h_slot[0].next_long;  // |V_aff| the host knows of
         HIPCHK(c, hipEventRecord(c->phase_ev[2], c->stream));
 
-        // ---- Step 3: rounds over V_aff ----
-        const int64_t frontier_initial = f.size();
-        int64_t peak = f.size(), rows = 0, edges = 0;
-        int it = 0, cur = 0;
+        // ---- Step 3: rounds over V_aff, queued in chains of kChain rounds per host round trip ----
+        const int64_t frontier_initial = known;
+        int64_t peak = known, rows = 0, edges = 0;
+        int it = 0, cur = 0;  // round `it` reads the frontier of parity `cur`
         float last = 0.f;
         double avg_len = c->n > 0 ? (double)c->entries / (double)c->n : 1.0;
         bool pingpong = false;
-        while (f.size() > 0 && it < c->max_iter) {
-            const unsigned int nq = f.size();
+        while (known > 0 && it < c->max_iter) {
             const int G = choose_group(c, avg_len);
-            RoundCtr* slot = c->ring + (it % kRing);
-            RoundCtr* next_slot = c->ring + ((it + 1) % kRing);
-            // A stretch of ping-pong rounds starts when V_aff covers nearly every updatable vertex; it
-            // costs one copy of F so that the partner buffer agrees on every row outside V_aff.
-            if (!pingpong && (double)nq >= kDenseEnter * (double)universe.size()) {
+            // A stretch of ping-pong rounds starts when V_aff covers nearly every updatable vertex (one copy
+            // of F makes the partner buffer agree on every row outside V_aff) and ends when V_aff has shrunk.
+            // Both kinds of round are correct for any V_aff, so the choice is only made between chains.
+            if (!pingpong && (double)known >= kDenseEnter * (double)universe.size()) {
                 sync_partner(c);
                 pingpong = true;
+            } else if (pingpong && (double)known < kDenseLeave * (double)universe.size()) {
+                pingpong = false;
             }
-            const bool pingpong_round = pingpong;
-            if (pingpong) {
-                // Ping-pong round: new rows go straight into the partner buffer (no staging, no commit,
-                // no marking); the next V_aff is pulled from the two buffers over all updatable vertices.
-                c->round_id = (c->round_id + 1u) & 0x7fffffffu;
-                if (c->round_id == 0u) {  // stamps wrapped: forget the old ones
-                    HIPCHK(c, hipMemsetAsync(c->stamp, 0, (size_t)c->n_cap * sizeof(unsigned int), c->stream));
-                    c->round_id = 1u;
+            const int r = std::min<int>(kChain, c->max_iter - it);
+            float* const buf[2] = {c->F, c->F2};  // ping-pong: round it+i reads buf[i & 1], writes buf[(i + 1) & 1]
+            for (int i = 0; i < r; ++i) {
+                const int t = it + i;
+                RoundCtr* slot = slot_of(c, t);
+                const Frontier f = frontier_of(c, cur);
+                if (pingpong) {
+                    // new rows go straight into the partner buffer; the next V_aff is pulled from the stamps
+                    c->round_id = (c->round_id + 1u) & 0x7fffffffu;
+                    if (c->round_id == 0u) {  // stamps wrapped: forget the old ones
+                        HIPCHK(c, hipMemsetAsync(c->stamp, 0, (size_t)c->n_cap * sizeof(unsigned int), c->stream));
+                        c->round_id = 1u;
+                    }
+                    const UpdateArgs a{slot_of(c, t - 1), 0, buf[i & 1], buf[(i + 1) & 1], c->stamp, c->round_id, c->tol,
+                                       slot, slot_of(c, t + 1), (int64_t)universe.size()};
+                    launch_update<false>(c, G, f, a);
+                    launch_next_frontier(c, universe, buf[(i + 1) & 1], buf[i & 1]);
+                } else {
+                    // rows are staged by frontier position and committed after the kernel; rows that moved mark
+                    // themselves and their neighbours
+                    const UpdateArgs a{slot_of(c, t - 1), 0, c->F, c->F2, nullptr, 0u, c->tol,
+                                       slot, slot_of(c, t + 1), (int64_t)universe.size()};
+                    launch_update<true>(c, G, f, a);
+                    launch_commit(c, f, slot_of(c, t - 1), (int64_t)universe.size());
                 }
-                const UpdateArgs a{c->F, c->F2, c->stamp, c->round_id, c->tol, slot, next_slot};
-                launch_update<false>(c, G, f, a);
-                std::swap(c->F, c->F2);
-                launch_next_frontier(c, universe);
-                if ((double)nq < kDenseLeave * (double)universe.size()) pingpong = false;
-            } else {
-                // Staged round: rows are staged by frontier position, committed after the kernel, and
-                // the rows that moved mark themselves and their neighbours for the next round.
-                const UpdateArgs a{c->F, c->F2, nullptr, 0u, c->tol, slot, next_slot};
-                launch_update<true>(c, G, f, a);
-                launch_commit(c, f);
+                launch_compact(c, frontier_of(c, cur ^ 1), &slot->next_count, &slot->next_long, 0);
+                cur ^= 1;
             }
-            const bool staged = !pingpong_round;
-            Frontier nf = frontier_of(c, cur ^ 1);
-            launch_compact(c, nf, &slot->next_count, &slot->next_long, 0);
-            const RoundCtr r = read_slot(c, it);
-            c->log.push_back(round_info(f, r, staged, G));
-            nf.ns = r.next_count;
-            nf.nl = r.next_long;
-            f = nf;
-            cur ^= 1;
-            std::memcpy(&last, &r.resid_bits, sizeof(float));
-            rows += nq;
-            edges += (int64_t)(r.edges + r.edges_long);
-            avg_len = nq ? (double)(r.edges + r.edges_long) / (double)nq : avg_len;
-            peak = std::max<int64_t>(peak, f.size());
-            ++it;
+            read_slots(c, it, r);
+            int executed = 0;
+            for (int i = 0; i < r; ++i) {
+                const RoundCtr& rc = c->h_slot[i];
+                if (!rc.executed) break;
+                ++executed;
+                const unsigned int nq = rc.rows_short + rc.rows_long;
+                std::memcpy(&last, &rc.resid_bits, sizeof(float));
+                rows += nq;
+                edges += (int64_t)(rc.edges + rc.edges_long);
+                avg_len = nq ? (double)(rc.edges + rc.edges_long) / (double)nq : avg_len;
+                c->log.push_back(round_info(rc, !pingpong, G));
+                known = rc.next_count + rc.next_long;
+                peak = std::max<int64_t>(peak, known);
+            }
+            if (pingpong && (executed & 1)) std::swap(c->F, c->F2);  // the output of the last executed round
+            it += executed;
+            if (executed < r) known = 0;  // a round found V_aff empty
         }
-        const unsigned int nq = f.size();
+        const unsigned int nq = known;
         HIPCHK(c, hipEventRecord(c->phase_ev[3], c->stream));
         HIPCHK(c, hipStreamSynchronize(c->stream));
         const float kernel_ms_total = c->time_kernels ? collect_kernel_ms(c) : 0.f;

@@ -26,13 +26,19 @@ struct __attribute__((aligned(16))) RowMeta {
 };
 
 // Counters one propagation round leaves for the host (one slot of a small ring).
-struct __attribute__((aligned(32))) RoundCtr {
+// Rounds are launched in chains without a host round trip: the kernels of round t read the size of
+// their frontier from the slot of round t-1 and leave their own results in the slot of round t.
+struct __attribute__((aligned(64))) RoundCtr {
     unsigned int next_count;   // short rows of V_aff for the next round (written by compaction)
+    unsigned int next_long;    // long rows of V_aff for the next round
     unsigned int resid_bits;   // max change of this round, float bits (non-negative floats order as uints)
     unsigned int changed;      // rows whose change exceeded tol
-    unsigned int next_long;    // long rows of V_aff for the next round
-    unsigned long long edges;  // CSR entries traversed by the short-row update kernel
-    unsigned long long edges_long;  // CSR entries traversed by the long-row update kernel
+    unsigned long long edges;  // CSR entries traversed in short rows
+    unsigned long long edges_long;  // CSR entries traversed in long rows
+    unsigned int executed;     // 1 if the round updated anything (0: frontier was empty / already converged)
+    unsigned int rows_short;   // the frontier this round worked on
+    unsigned int rows_long;
+    unsigned int pad[5];
 };
 
 // Scalars of the insertion step and error reporting.

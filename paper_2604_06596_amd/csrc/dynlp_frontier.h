@@ -93,10 +93,11 @@ __global__ void __launch_bounds__(kBlock) k_compact(unsigned int n, uint8_t* __r
 // Commit of staged rows (staged rounds) and the next frontier after a ping-pong round
 // =================================================================================================
 // F[vertex at position i] = Fq[i] for all positions: the Jacobi commit of a staged round.
-__global__ void __launch_bounds__(kBlock) k_commit(unsigned int ns, unsigned int nl,
+__global__ void __launch_bounds__(kBlock) k_commit(const RoundCtr* __restrict__ prev,
                                                   const int32_t* __restrict__ front,
                                                   const int32_t* __restrict__ back,
                                                   const float* __restrict__ Fq, float* __restrict__ F, int CP) {
+    const unsigned int ns = prev->next_count, nl = prev->next_long;
     const unsigned int nq = ns + nl;
     if (CP >= 4) {
         const unsigned int vpr = CP / 4;
@@ -417,13 +418,17 @@ __device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, c
     flush_round_counters(rmax, edges, nchanged, ctr, &ctr->edges_long);
 }
 
-// One launch per round: workgroups [0, long_blocks) take the long rows (started first, they are the
-// long poles), the remaining workgroups take the short rows.  Workgroup 0 also clears the counter
-// slot of the next round.
+// One launch per round.  The frontier's size comes from the previous round's counter slot (prev), so
+// that rounds can be queued back to back without the host reading anything.  Workgroups
+// [0, long_blocks) take the long rows (started first: they are the long poles), the rest take the
+// short rows.  Workgroup 0 clears the counter slot of the next round and records what this round
+// worked on.  stop_bits: a static sweep does nothing if the previous sweep already met the stop rule
+// (max change <= tol, as float bits) or did not run; frontier rounds pass 0xffffffff... never stop.
 template <int CP, int G, bool STAGED>
-__global__ void __launch_bounds__(kBlock) k_row_update(const int32_t* __restrict__ front, unsigned int ns,
-                                                      const int32_t* __restrict__ back, unsigned int nl,
-                                                      unsigned int long_blocks, const RowMeta* __restrict__ meta,
+__global__ void __launch_bounds__(kBlock) k_row_update(const RoundCtr* __restrict__ prev, int static_stop,
+                                                      unsigned int stop_bits, const int32_t* __restrict__ front,
+                                                      const int32_t* __restrict__ back,
+                                                      const RowMeta* __restrict__ meta,
                                                       const Edge* __restrict__ pool,
                                                       const float* __restrict__ F_in, float* __restrict__ F_out,
                                                       uint8_t* __restrict__ flag, unsigned int* __restrict__ stamp,
@@ -437,7 +442,33 @@ __global__ void __launch_bounds__(kBlock) k_row_update(const int32_t* __restrict
         ctr_zero->changed = 0;
         ctr_zero->edges = 0;
         ctr_zero->edges_long = 0;
+        ctr_zero->executed = 0;
+        ctr_zero->rows_short = 0;
+        ctr_zero->rows_long = 0;
     }
+    const unsigned int ns = prev->next_count, nl = prev->next_long;
+    if (ns + nl == 0) return;
+    if (static_stop) {
+        if (static_stop == 2 && (!prev->executed || prev->resid_bits <= stop_bits)) {
+            // keep the frontier for whoever reads this slot next
+            if (blockIdx.x == 0 && threadIdx.x == 0) {
+                ctr->next_count = ns;
+                ctr->next_long = nl;
+            }
+            return;
+        }
+        if (blockIdx.x == 0 && threadIdx.x == 0) {  // a static sweep's frontier never changes
+            ctr->next_count = ns;
+            ctr->next_long = nl;
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        ctr->executed = 1;
+        ctr->rows_short = ns;
+        ctr->rows_long = nl;
+    }
+    const unsigned int quarter = gridDim.x / 4;
+    const unsigned int long_blocks = nl < quarter ? nl : quarter;
     if (blockIdx.x < long_blocks)
         row_update_long<CP, STAGED>(blockIdx.x, long_blocks, back, nl, ns, meta, pool, F_in, F_out, flag, stamp,
                                     round_id, tol, ctr);
