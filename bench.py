@@ -137,6 +137,8 @@ def main():
     ap.add_argument("--tol", type=float, default=None, help="threshold delta (default: the workload's)")
     ap.add_argument("--group-lanes", type=int, default=0)
     ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of CPU oracle work (0 = skip)")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="do not bracket the row-update launches with HIP events (roofline fields become 0)")
     ap.add_argument("--host-inputs", action="store_true",
                     help="hand the library host arrays (PCIe-inclusive timing; not the headline number)")
     args = ap.parse_args()
@@ -171,7 +173,7 @@ def main():
     tot_e = sum(b.num_edges for b in batches)
     d = P.DynLP(base["n"], dv(base["row_ptr"], torch.int64), dv(base["col"], torch.int32), dv(base["w"], torch.float32),
                 base["C"], dv(base["seed_vertex"], torch.int32), dv(base["seed_class"], torch.int32),
-                device_ptrs=not args.host_inputs, reserve_vertices=tot_v + 1024, reserve_edges=2 * tot_e + 1024, time_kernels=True,
+                device_ptrs=not args.host_inputs, reserve_vertices=tot_v + 1024, reserve_edges=2 * tot_e + 1024, time_kernels=not args.no_kernel_timing,
                 group_lanes=args.group_lanes)
     st, s0 = d.static_solve(tol, cfg["max_iter"])
     cold = dict(status=st, sweeps=s0.iterations, ms=s0.ms_total, ms_update_kernel=s0.ms_update_kernel,

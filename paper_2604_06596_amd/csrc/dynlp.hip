@@ -83,8 +83,9 @@ struct dynlp_ctx {
                                                       // updatable vertices (see dynlp_frontier.h)
     int32_t* add_cnt = nullptr;
     float* deg = nullptr;
-    unsigned int* stamp = nullptr;  // per-vertex round stamps of ping-pong rounds (see k_next_frontier)
-    unsigned int round_id = 0;      // id of the last ping-pong round; 0 is never used as a stamp
+    unsigned int* moved[2] = {nullptr, nullptr};  // 1 bit per vertex: "moved by > tol" of ping-pong rounds,
+    int64_t moved_words = 0;                      // two parities (see k_pull_frontier)
+    unsigned int pp_round = 0;                    // ping-pong rounds so far; parity selects the bitmap
 
     int32_t* touched = nullptr;
     int64_t* reloc_off = nullptr;
@@ -209,8 +210,9 @@ void alloc_vertex_arrays(dynlp_ctx* c, int64_t new_cap) {
     int32_t* q2 = dev_alloc_n<int32_t>(c, new_cap);
     int32_t* add = dev_alloc_n<int32_t>(c, new_cap);
     float* deg = dev_alloc_n<float>(c, new_cap);
-    unsigned int* stamp = dev_alloc_n<unsigned int>(c, new_cap);
-    HIPCHK(c, hipMemsetAsync(stamp, 0, (size_t)new_cap * sizeof(unsigned int), c->stream));
+    const int64_t moved_words = (new_cap + 31) / 32 + 64;
+    unsigned int* mv0 = dev_alloc_n<unsigned int>(c, moved_words);
+    unsigned int* mv1 = dev_alloc_n<unsigned int>(c, moved_words);
     HIPCHK(c, hipMemsetAsync(flag, 0, (size_t)flag_cap, c->stream));
     HIPCHK(c, hipMemsetAsync(add, 0, (size_t)new_cap * sizeof(int32_t), c->stream));
     if (old_n > 0 && c->meta) {
@@ -230,9 +232,11 @@ void alloc_vertex_arrays(dynlp_ctx* c, int64_t new_cap) {
     dev_free(c, c->queue[2]);
     dev_free(c, c->add_cnt);
     dev_free(c, c->deg);
-    dev_free(c, c->stamp);
-    c->stamp = stamp;
-    c->round_id = 0;
+    dev_free(c, c->moved[0]);
+    dev_free(c, c->moved[1]);
+    c->moved[0] = mv0;
+    c->moved[1] = mv1;
+    c->moved_words = moved_words;
     c->meta = meta;
     c->F = F;
     c->F2 = F2;
@@ -334,8 +338,7 @@ struct UpdateArgs {
     int static_stop;       // 0: frontier round; 1: static sweep; 2: static sweep that checks prev's stop rule
     const float* F_in;
     float* F_out;
-    unsigned int* stamp;  // per-vertex round stamps (ping-pong rounds), NULL otherwise
-    unsigned int round_id;
+    unsigned int* moved;  // "moved by > tol" bitmap of this round (ping-pong rounds), NULL otherwise
     float tol;
     RoundCtr* ctr;
     RoundCtr* ctr_zero;
@@ -350,7 +353,7 @@ void launch_update_inst(dynlp_ctx* c, const Frontier& f, const UpdateArgs& a) {
     unsigned int stop_bits;
     std::memcpy(&stop_bits, &a.tol, sizeof stop_bits);
     hipLaunchKernelGGL((k_row_update<CP, G, STAGED>), dim3(blocks), dim3(kBlock), 0, c->stream, a.prev, a.static_stop,
-                       stop_bits, f.front, f.back, c->meta, c->pool, a.F_in, a.F_out, c->flag, a.stamp, a.round_id, a.tol,
+                       stop_bits, f.front, f.back, c->meta, c->pool, a.F_in, a.F_out, c->flag, a.moved, a.tol,
                        a.ctr, a.ctr_zero);
 }
 
@@ -449,14 +452,21 @@ void launch_commit(dynlp_ctx* c, const Frontier& f, const RoundCtr* prev, int64_
     HIPCHK(c, hipGetLastError());
 }
 
-// Pull the next V_aff out of the round stamps; F_new holds the rows just written, F_old the
-// round-start rows; `universe` lists every updatable vertex.
-void launch_next_frontier(dynlp_ctx* c, const Frontier& universe, const float* F_new, float* F_old) {
-    const unsigned int blocks = (unsigned int)std::max<int64_t>(
-        1, std::min<int64_t>(ceil_div(universe.size(), kBlock / 16), (int64_t)c->num_cu * 16));
-    hipLaunchKernelGGL(k_next_frontier, dim3(blocks), dim3(kBlock), 0, c->stream, universe.ns, universe.nl,
-                       universe.front, universe.back, c->stamp, c->round_id, F_new, F_old, c->CP, c->meta, c->pool,
-                       c->flag);
+// Pull the next V_aff out of the round's "moved" bitmap straight into the frontier `out` (its counts go to
+// *count_short / *count_long, zero beforehand); F_new holds the rows just written, F_old the round-start
+// rows; `universe` lists every updatable vertex.
+void launch_pull_frontier(dynlp_ctx* c, const Frontier& universe, const unsigned int* moved, unsigned int* moved_next,
+                          const float* F_new, float* F_old, const Frontier& out, unsigned int* count_short,
+                          unsigned int* count_long) {
+    const int64_t cap = (int64_t)c->num_cu * 8;
+    const unsigned int long_blocks =
+        (unsigned int)std::min<int64_t>(ceil_div(universe.nl, (kBlock / kWave) * kPullSub), cap / 2);
+    const unsigned int short_blocks =
+        (unsigned int)std::max<int64_t>(1, std::min<int64_t>(ceil_div(universe.ns, kBlock * kPullSub), cap));
+    hipLaunchKernelGGL(k_pull_frontier, dim3(long_blocks + short_blocks), dim3(kBlock), 0, c->stream, universe.ns,
+                       universe.nl, long_blocks, universe.front, universe.back, moved, moved_next, (unsigned int)c->moved_words,
+                       F_new, F_old, c->CP,
+                       c->meta, c->pool, out.front, out.back, count_short, count_long);
     HIPCHK(c, hipGetLastError());
 }
 
@@ -545,7 +555,7 @@ void destroy_ctx(dynlp_ctx* c) {
     if (!c) return;
     (void)hipSetDevice(c->device);
     if (c->stream || c->meta) (void)hipStreamSynchronize(c->stream);
-    void* ptrs[] = {c->meta, c->pool, c->F, c->F2, c->seed_class, c->flag, c->queue[0], c->queue[1], c->queue[2], c->stamp, c->add_cnt,
+    void* ptrs[] = {c->meta, c->pool, c->F, c->F2, c->seed_class, c->flag, c->queue[0], c->queue[1], c->queue[2], c->moved[0], c->moved[1], c->add_cnt,
                     c->deg, c->touched, c->reloc_off, c->b_eu, c->b_ev, c->b_ew, c->b_sv, c->b_sc};
     for (void* p : ptrs) dev_free(c, p);
     if (c->ring) (void)hipFree(c->ring);
@@ -809,7 +819,7 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
             const int r = std::min<int>(kChain, max_iter - it);
             for (int i = 0; i < r; ++i) {
                 const int t = it + i;
-                const UpdateArgs a{slot_of(c, t - 1), t == 0 ? 1 : 2, buf[t & 1], buf[(t + 1) & 1], nullptr, 0u, tol,
+                const UpdateArgs a{slot_of(c, t - 1), t == 0 ? 1 : 2, buf[t & 1], buf[(t + 1) & 1], nullptr, tol,
                                    slot_of(c, t), slot_of(c, t + 1), (int64_t)nq};
                 launch_update<false>(c, G, f, a);
             }
@@ -993,6 +1003,8 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
             // Both kinds of round are correct for any V_aff, so the choice is only made between chains.
             if (!pingpong && (double)known >= kDenseEnter * (double)universe.size()) {
                 sync_partner(c);
+                for (unsigned int* mv : c->moved)
+                    HIPCHK(c, hipMemsetAsync(mv, 0, (size_t)c->moved_words * sizeof(unsigned int), c->stream));
                 pingpong = true;
             } else if (pingpong && (double)known < kDenseLeave * (double)universe.size()) {
                 pingpong = false;
@@ -1004,25 +1016,25 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
                 RoundCtr* slot = slot_of(c, t);
                 const Frontier f = frontier_of(c, cur);
                 if (pingpong) {
-                    // new rows go straight into the partner buffer; the next V_aff is pulled from the stamps
-                    c->round_id = (c->round_id + 1u) & 0x7fffffffu;
-                    if (c->round_id == 0u) {  // stamps wrapped: forget the old ones
-                        HIPCHK(c, hipMemsetAsync(c->stamp, 0, (size_t)c->n_cap * sizeof(unsigned int), c->stream));
-                        c->round_id = 1u;
-                    }
-                    const UpdateArgs a{slot_of(c, t - 1), 0, buf[i & 1], buf[(i + 1) & 1], c->stamp, c->round_id, c->tol,
+                    // new rows go straight into the partner buffer; the next V_aff is pulled from the bitmap
+                    // of rows that moved
+                    unsigned int* mv = c->moved[c->pp_round & 1u];
+                    unsigned int* mv_next = c->moved[(c->pp_round + 1u) & 1u];
+                    ++c->pp_round;
+                    const UpdateArgs a{slot_of(c, t - 1), 0, buf[i & 1], buf[(i + 1) & 1], mv, c->tol,
                                        slot, slot_of(c, t + 1), (int64_t)universe.size()};
                     launch_update<false>(c, G, f, a);
-                    launch_next_frontier(c, universe, buf[(i + 1) & 1], buf[i & 1]);
+                    launch_pull_frontier(c, universe, mv, mv_next, buf[(i + 1) & 1], buf[i & 1], frontier_of(c, cur ^ 1),
+                                         &slot->next_count, &slot->next_long);
                 } else {
                     // rows are staged by frontier position and committed after the kernel; rows that moved mark
                     // themselves and their neighbours
-                    const UpdateArgs a{slot_of(c, t - 1), 0, c->F, c->F2, nullptr, 0u, c->tol,
+                    const UpdateArgs a{slot_of(c, t - 1), 0, c->F, c->F2, nullptr, c->tol,
                                        slot, slot_of(c, t + 1), (int64_t)universe.size()};
                     launch_update<true>(c, G, f, a);
                     launch_commit(c, f, slot_of(c, t - 1), (int64_t)universe.size());
+                    launch_compact(c, frontier_of(c, cur ^ 1), &slot->next_count, &slot->next_long, 0);
                 }
-                launch_compact(c, frontier_of(c, cur ^ 1), &slot->next_count, &slot->next_long, 0);
                 cur ^= 1;
             }
             read_slots(c, it, r);

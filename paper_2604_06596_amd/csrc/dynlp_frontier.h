@@ -124,51 +124,166 @@ __device__ inline void mark(uint8_t* __restrict__ flag, int32_t v) {
     if (!flag[v]) flag[v] = 1;
 }
 
-// Next V_aff after a ping-pong round, computed by *pulling* instead of marking.  The update kernels
-// of a ping-pong round leave a stamp per updated row: stamp[u] = round id if the row moved by more
-// than tol, round id | kStampStill if it was updated but did not move.  Alg. 2 Step 3 puts u into the
-// next V_aff iff u moved or one of its neighbours moved; this kernel evaluates exactly that for every
-// updatable vertex u (the universe list): one stamp read, and only when u itself did not move a scan
-// of N(u)'s stamps, 16 neighbours at a time, that stops at the first chunk with a hit.  A row that was
-// updated in this round and now leaves V_aff gets its new value copied into F_old, so that the two
-// label buffers keep agreeing on every row outside V_aff (the invariant ping-pong rounds rely on).
-// 16 lanes per vertex.
-constexpr unsigned int kStampStill = 0x80000000u;
+// Next V_aff after a ping-pong round, computed by *pulling* instead of marking, and written straight
+// into the next frontier (no flag bytes, no separate compaction).  The update kernels of a ping-pong
+// round set one bit per row that moved by more than tol (moved[], 1 bit per vertex: 125 KB per million
+// vertices, so the neighbour look-ups below stay in cache).  Alg. 2 Step 3 puts u into the next V_aff
+// iff u moved or one of its neighbours moved; this kernel evaluates exactly that for every updatable
+// vertex u (the universe list, short rows first, long rows from the back): one bit read, and only
+// when u itself did not move a scan of N(u)'s bits that stops at the first hit.  A row that does not
+// make it into the next V_aff gets its current value copied into F_old if the two buffers differ
+// (it was updated in this round), so that they keep agreeing on every row outside V_aff (the
+// invariant ping-pong rounds rely on).  The kernel also clears the bitmap of the next round.
+// Workgroups [0, long_blocks): long rows, one wave per row, 64 neighbours per step.  The others:
+// short rows, one lane per row.  A workgroup handles chunks of consecutive universe positions and
+// reserves the output range of a whole chunk with ONE atomic (atomics on one address run at only
+// ~10^8 per second device-wide, so they are kept to a few hundred per launch); kept ids are written
+// in universe order inside the chunk's range.
+__device__ inline bool moved_bit(const unsigned int* __restrict__ moved, int32_t v) {
+    return (moved[(unsigned int)v >> 5] >> ((unsigned int)v & 31u)) & 1u;
+}
 
-__global__ void __launch_bounds__(kBlock) k_next_frontier(unsigned int ns, unsigned int nl,
-                                                         const int32_t* __restrict__ front,
-                                                         const int32_t* __restrict__ back,
-                                                         const unsigned int* __restrict__ stamp,
-                                                         unsigned int round_id, const float* __restrict__ F_new,
-                                                         float* __restrict__ F_old, int CP,
-                                                         const RowMeta* __restrict__ meta,
-                                                         const Edge* __restrict__ pool, uint8_t* __restrict__ flag) {
-    constexpr int G = 16;
-    const unsigned int nq = ns + nl;
-    const int gl = threadIdx.x % G;
-    const int group_in_wave = (threadIdx.x % kWave) / G;
-    for (unsigned int pos = blockIdx.x * (kBlock / G) + threadIdx.x / G; pos < nq; pos += gridDim.x * (kBlock / G)) {
-        const int32_t u = frontier_vertex(front, back, ns, pos);
-        const unsigned int su = stamp[u];
-        bool keep = su == round_id;
-        if (!keep) {
-            const RowMeta m = meta[u];
-            const Edge* __restrict__ row = pool + m.off;
-            for (int base = 0; base < m.len; base += G) {  // uniform across the group
-                const int j = base + gl;
-                const bool hit = j < m.len && stamp[row[j].col] == round_id;
-                const unsigned long long b = __ballot(hit);
-                if ((b >> (group_in_wave * G)) & 0xffffull) {
-                    keep = true;
-                    break;
+constexpr int kPullSub = 16;  // sub-steps per workgroup chunk (one queue atomic per chunk)
+
+__global__ void __launch_bounds__(kBlock) k_pull_frontier(unsigned int ns, unsigned int nl, unsigned int long_blocks,
+                                                         const int32_t* __restrict__ ufront,
+                                                         const int32_t* __restrict__ uback,
+                                                         const unsigned int* __restrict__ moved,
+                                                         unsigned int* __restrict__ moved_next, unsigned int words,
+                                                         const float* __restrict__ F_new, float* __restrict__ F_old,
+                                                         int CP, const RowMeta* __restrict__ meta,
+                                                         const Edge* __restrict__ pool,
+                                                         int32_t* __restrict__ front, int32_t* __restrict__ back,
+                                                         unsigned int* __restrict__ count_short,
+                                                         unsigned int* __restrict__ count_long) {
+    constexpr int NW = kBlock / kWave;
+    __shared__ unsigned int cnt[kPullSub][NW];  // kept items per sub-step and wave, then their offsets
+    __shared__ unsigned int sbase;
+    const int wave = threadIdx.x / kWave;
+    const int lane = lane_id();
+    for (unsigned int w = blockIdx.x * kBlock + threadIdx.x; w < words; w += gridDim.x * kBlock) moved_next[w] = 0u;
+
+    if (blockIdx.x < long_blocks) {
+        // long rows: one wave per row, kPullSub rows per wave and chunk
+        constexpr unsigned int CH = NW * kPullSub;
+        for (unsigned int c0 = blockIdx.x * CH; c0 < nl; c0 += long_blocks * CH) {  // uniform per workgroup
+            unsigned int keepmask = 0;
+            for (int sub = 0; sub < kPullSub; ++sub) {
+                const unsigned int j = c0 + sub * NW + wave;
+                bool keep = false;
+                if (j < nl) {
+                    const int32_t u = uback[-(long long)j];
+                    keep = moved_bit(moved, u);
+                    if (!keep) {
+                        const RowMeta m = meta[u];
+                        const Edge* __restrict__ row = pool + m.off;
+                        for (int base = 0; base < m.len; base += kWave) {  // uniform per wave
+                            const int idx = base + lane;
+                            const bool hit = idx < m.len && moved_bit(moved, row[idx].col);
+                            if (__ballot(hit)) {
+                                keep = true;
+                                break;
+                            }
+                        }
+                        if (!keep) {
+                            for (int k = lane; k < CP; k += kWave) {
+                                const float a = F_new[(size_t)u * CP + k];
+                                if (a != F_old[(size_t)u * CP + k]) F_old[(size_t)u * CP + k] = a;
+                            }
+                        }
+                    }
+                }
+                if (keep) keepmask |= 1u << sub;
+                if (lane == 0) cnt[sub][wave] = keep ? 1u : 0u;
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                unsigned int run = 0;
+                for (int sub = 0; sub < kPullSub; ++sub)
+                    for (int q = 0; q < NW; ++q) {
+                        const unsigned int t = cnt[sub][q];
+                        cnt[sub][q] = run;
+                        run += t;
+                    }
+                sbase = run ? atomicAdd(count_long, run) : 0u;
+            }
+            __syncthreads();
+            if (lane == 0) {
+                for (int sub = 0; sub < kPullSub; ++sub)
+                    if ((keepmask >> sub) & 1u)
+                        back[-(long long)(sbase + cnt[sub][wave])] = uback[-(long long)(c0 + sub * NW + wave)];
+            }
+            __syncthreads();
+        }
+        return;
+    }
+    // short rows: one lane per row, kPullSub * kBlock consecutive universe positions per chunk
+    constexpr unsigned int CH = kBlock * kPullSub;
+    const unsigned int nb = gridDim.x - long_blocks;
+    const unsigned int bid = blockIdx.x - long_blocks;
+    for (unsigned int c0 = bid * CH; c0 < ns; c0 += nb * CH) {  // uniform per workgroup
+        // all ids of the chunk first, then all their bits: two memory round trips instead of 2 * kPullSub
+        int32_t us[kPullSub];
+#pragma unroll
+        for (int sub = 0; sub < kPullSub; ++sub) {
+            const unsigned int pos = c0 + sub * kBlock + threadIdx.x;
+            us[sub] = pos < ns ? ufront[pos] : -1;
+        }
+        unsigned int keepmask = 0;
+#pragma unroll
+        for (int sub = 0; sub < kPullSub; ++sub)
+            if (us[sub] >= 0 && moved_bit(moved, us[sub])) keepmask |= 1u << sub;
+#pragma unroll
+        for (int sub = 0; sub < kPullSub; ++sub) {
+            const int32_t u = us[sub];
+            bool keep = (keepmask >> sub) & 1u;
+            if (u >= 0 && !keep) {
+                const RowMeta m = meta[u];
+                const Edge* __restrict__ row = pool + m.off;
+                // eight independent look-ups per step (the lane waits once per step, not once per entry)
+                for (int j = 0; j < m.len && !keep; j += 8) {
+                    unsigned int hit = 0;
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        const int jj = j + q < m.len ? j + q : m.len - 1;
+                        hit |= moved_bit(moved, row[jj].col) ? 1u : 0u;
+                    }
+                    keep = hit != 0;
+                }
+                if (keep) {
+                    keepmask |= 1u << sub;
+                } else {
+                    for (int k = 0; k < CP; ++k) {
+                        const float a = F_new[(size_t)u * CP + k];
+                        if (a != F_old[(size_t)u * CP + k]) F_old[(size_t)u * CP + k] = a;
+                    }
                 }
             }
+            const unsigned long long b = __ballot(keep);
+            if (lane == 0) cnt[sub][wave] = (unsigned int)__popcll(b);
         }
-        if (keep) {
-            if (gl == 0) flag[u] = 1;
-        } else if (su == (round_id | kStampStill)) {  // updated in this round, leaves V_aff
-            for (int k = gl; k < CP; k += G) F_old[(size_t)u * CP + k] = F_new[(size_t)u * CP + k];
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            unsigned int run = 0;
+            for (int sub = 0; sub < kPullSub; ++sub)
+                for (int q = 0; q < NW; ++q) {
+                    const unsigned int t = cnt[sub][q];
+                    cnt[sub][q] = run;
+                    run += t;
+                }
+            sbase = run ? atomicAdd(count_short, run) : 0u;
         }
+        __syncthreads();
+#pragma unroll
+        for (int sub = 0; sub < kPullSub; ++sub) {
+            const bool keep = (keepmask >> sub) & 1u;
+            const unsigned long long b = __ballot(keep);
+            if (keep) {
+                const unsigned int rank = (unsigned int)__popcll(b & ((1ull << lane) - 1ull));
+                front[sbase + cnt[sub][wave] + rank] = us[sub];
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -270,8 +385,8 @@ __device__ inline void flush_round_counters(float rmax, unsigned long long edges
 
 // Short rows: G lanes per row, grid-strided (body; k_row_update dispatches to it).
 //   STAGED = false (static sweep / ping-pong round): F'_u is written to row u of F_out, the
-//            ping-pong partner of F_in; stamp[u] (if not NULL) records the round id and whether
-//            the row moved by more than tol (see k_next_frontier).
+//            ping-pong partner of F_in; a row that moved by more than tol sets its bit in moved[]
+//            (if not NULL; see k_pull_frontier).
 //   STAGED = true (partial round): F'_u is staged at row pos of F_out so that every row of this
 //            round reads the round-start F (Jacobi); a row that moved by > tol marks itself and
 //            its neighbours in flag[] for the next round.
@@ -280,7 +395,7 @@ __device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, 
                                         unsigned int ns, const RowMeta* __restrict__ meta,
                                         const Edge* __restrict__ pool, const float* __restrict__ F_in,
                                         float* __restrict__ F_out, uint8_t* __restrict__ flag,
-                                        unsigned int* __restrict__ stamp, unsigned int round_id, float tol,
+                                        unsigned int* __restrict__ moved, float tol,
                                         RoundCtr* __restrict__ ctr) {
     constexpr int VEC = RowShape<CP>::VEC;
     constexpr int LPN = RowShape<CP>::LPN;
@@ -323,8 +438,8 @@ __device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, 
                 const int last_base = ((m.len - 1) / G) * G;
                 for (int idx = gl; idx < last_base; idx += G) mark(flag, row[idx].col);
             }
-        } else if (stamp && gl == 0) {
-            stamp[u] = big ? round_id : (round_id | 0x80000000u);
+        } else if (moved && big && gl == 0) {
+            atomicOr(&moved[(unsigned int)u >> 5], 1u << ((unsigned int)u & 31u));
         }
         if (gl == 0) {
             rmax = fmaxf(rmax, r);
@@ -343,7 +458,7 @@ __device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, c
                                        unsigned int nl, unsigned int pos_base, const RowMeta* __restrict__ meta,
                                        const Edge* __restrict__ pool, const float* __restrict__ F_in,
                                        float* __restrict__ F_out, uint8_t* __restrict__ flag,
-                                       unsigned int* __restrict__ stamp, unsigned int round_id, float tol,
+                                       unsigned int* __restrict__ moved, float tol,
                                        RoundCtr* __restrict__ ctr) {
     constexpr int VEC = RowShape<CP>::VEC;
     constexpr int LPN = RowShape<CP>::LPN;
@@ -402,7 +517,7 @@ __device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, c
             if (gl == 0) {
                 const bool big = r > tol;
                 sh_big = big ? 1 : 0;
-                if (!STAGED && stamp) stamp[u] = big ? round_id : (round_id | 0x80000000u);
+                if (!STAGED && moved && big) atomicOr(&moved[(unsigned int)u >> 5], 1u << ((unsigned int)u & 31u));
                 rmax = fmaxf(rmax, r);
                 edges += (unsigned long long)m.len;
                 nchanged += big ? 1u : 0u;
@@ -431,8 +546,8 @@ __global__ void __launch_bounds__(kBlock) k_row_update(const RoundCtr* __restric
                                                       const RowMeta* __restrict__ meta,
                                                       const Edge* __restrict__ pool,
                                                       const float* __restrict__ F_in, float* __restrict__ F_out,
-                                                      uint8_t* __restrict__ flag, unsigned int* __restrict__ stamp,
-                                                      unsigned int round_id, float tol,
+                                                      uint8_t* __restrict__ flag, unsigned int* __restrict__ moved,
+                                                      float tol,
                                                       RoundCtr* __restrict__ ctr,
                                                       RoundCtr* __restrict__ ctr_zero) {
     if (ctr_zero && blockIdx.x == 0 && threadIdx.x == 0) {
@@ -470,11 +585,11 @@ __global__ void __launch_bounds__(kBlock) k_row_update(const RoundCtr* __restric
     const unsigned int quarter = gridDim.x / 4;
     const unsigned int long_blocks = nl < quarter ? nl : quarter;
     if (blockIdx.x < long_blocks)
-        row_update_long<CP, STAGED>(blockIdx.x, long_blocks, back, nl, ns, meta, pool, F_in, F_out, flag, stamp,
-                                    round_id, tol, ctr);
+        row_update_long<CP, STAGED>(blockIdx.x, long_blocks, back, nl, ns, meta, pool, F_in, F_out, flag, moved,
+                                    tol, ctr);
     else
         row_update_short<CP, G, STAGED>(blockIdx.x - long_blocks, gridDim.x - long_blocks, front, ns, meta, pool, F_in,
-                                        F_out, flag, stamp, round_id, tol, ctr);
+                                        F_out, flag, moved, tol, ctr);
 }
 
 }  // namespace dynlp
