@@ -97,6 +97,7 @@ struct dynlp_ctx {
     RoundCtr* ring = nullptr;  // kRing round slots + the start slot
     BatchCtr* bc = nullptr;
     RoundCtr* h_slot = nullptr;  // pinned, kRing slots
+    unsigned int h_slot_start_long = 0;  // long rows among the updatable vertices of the running static solve
     BatchCtr* h_bc = nullptr;    // pinned
 
     float tol = 1e-4f;
@@ -342,18 +343,20 @@ struct UpdateArgs {
     float tol;
     RoundCtr* ctr;
     RoundCtr* ctr_zero;
-    int64_t rows_bound;  // upper bound of the frontier size (sizes the grid)
+    int64_t rows_bound;  // upper bounds of the frontier size and of its long rows (they size the grid)
+    int64_t long_bound;
 };
 
 template <int CP, int G, bool STAGED>
 void launch_update_inst(dynlp_ctx* c, const Frontier& f, const UpdateArgs& a) {
     constexpr int GPB = kBlock / G;
     const int64_t cap = (int64_t)c->num_cu * 8;
-    const unsigned int blocks = (unsigned int)std::max<int64_t>(4, std::min<int64_t>(ceil_div(a.rows_bound, GPB) + 4, cap));
+    const unsigned int short_blocks = (unsigned int)std::max<int64_t>(1, std::min<int64_t>(ceil_div(a.rows_bound, GPB), cap));
+    const unsigned int long_max = (unsigned int)std::min<int64_t>(a.long_bound, cap / 2);
     unsigned int stop_bits;
     std::memcpy(&stop_bits, &a.tol, sizeof stop_bits);
-    hipLaunchKernelGGL((k_row_update<CP, G, STAGED>), dim3(blocks), dim3(kBlock), 0, c->stream, a.prev, a.static_stop,
-                       stop_bits, f.front, f.back, c->meta, c->pool, a.F_in, a.F_out, c->flag, a.moved, a.tol,
+    hipLaunchKernelGGL((k_row_update<CP, G, STAGED>), dim3(short_blocks + long_max), dim3(kBlock), 0, c->stream, a.prev,
+                       a.static_stop, stop_bits, long_max, f.front, f.back, c->meta, c->pool, a.F_in, a.F_out, c->flag, a.moved, a.tol,
                        a.ctr, a.ctr_zero);
 }
 
@@ -807,6 +810,7 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
         launch_compact(c, f, &start->next_count, &start->next_long, 1);
         read_slots_start(c);
         const unsigned int nq = c->h_slot[0].next_count + c->h_slot[0].next_long;
+        c->h_slot_start_long = c->h_slot[0].next_long;
         int it = 0;
         float last = 0.f;
         bool converged = nq == 0;
@@ -820,7 +824,7 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
             for (int i = 0; i < r; ++i) {
                 const int t = it + i;
                 const UpdateArgs a{slot_of(c, t - 1), t == 0 ? 1 : 2, buf[t & 1], buf[(t + 1) & 1], nullptr, tol,
-                                   slot_of(c, t), slot_of(c, t + 1), (int64_t)nq};
+                                   slot_of(c, t), slot_of(c, t + 1), (int64_t)nq, (int64_t)c->h_slot_start_long};
                 launch_update<false>(c, G, f, a);
             }
             read_slots(c, it, r);
@@ -1022,7 +1026,7 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
                     unsigned int* mv_next = c->moved[(c->pp_round + 1u) & 1u];
                     ++c->pp_round;
                     const UpdateArgs a{slot_of(c, t - 1), 0, buf[i & 1], buf[(i + 1) & 1], mv, c->tol,
-                                       slot, slot_of(c, t + 1), (int64_t)universe.size()};
+                                       slot, slot_of(c, t + 1), (int64_t)universe.size(), (int64_t)universe.nl};
                     launch_update<false>(c, G, f, a);
                     launch_pull_frontier(c, universe, mv, mv_next, buf[(i + 1) & 1], buf[i & 1], frontier_of(c, cur ^ 1),
                                          &slot->next_count, &slot->next_long);
@@ -1030,7 +1034,7 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
                     // rows are staged by frontier position and committed after the kernel; rows that moved mark
                     // themselves and their neighbours
                     const UpdateArgs a{slot_of(c, t - 1), 0, c->F, c->F2, nullptr, c->tol,
-                                       slot, slot_of(c, t + 1), (int64_t)universe.size()};
+                                       slot, slot_of(c, t + 1), (int64_t)universe.size(), (int64_t)universe.nl};
                     launch_update<true>(c, G, f, a);
                     launch_commit(c, f, slot_of(c, t - 1), (int64_t)universe.size());
                     launch_compact(c, frontier_of(c, cur ^ 1), &slot->next_count, &slot->next_long, 0);

@@ -535,13 +535,14 @@ __device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, c
 
 // One launch per round.  The frontier's size comes from the previous round's counter slot (prev), so
 // that rounds can be queued back to back without the host reading anything.  Workgroups
-// [0, long_blocks) take the long rows (started first: they are the long poles), the rest take the
-// short rows.  Workgroup 0 clears the counter slot of the next round and records what this round
+// [0, long_blocks) take the long rows (started first: they are the long poles; long_blocks =
+// min(long rows, long_blocks_max)), the rest take the short rows.  Workgroup 0 clears the counter slot of the next round and records what this round
 // worked on.  stop_bits: a static sweep does nothing if the previous sweep already met the stop rule
 // (max change <= tol, as float bits) or did not run; frontier rounds pass 0xffffffff... never stop.
 template <int CP, int G, bool STAGED>
 __global__ void __launch_bounds__(kBlock) k_row_update(const RoundCtr* __restrict__ prev, int static_stop,
-                                                      unsigned int stop_bits, const int32_t* __restrict__ front,
+                                                      unsigned int stop_bits, unsigned int long_blocks_max,
+                                                      const int32_t* __restrict__ front,
                                                       const int32_t* __restrict__ back,
                                                       const RowMeta* __restrict__ meta,
                                                       const Edge* __restrict__ pool,
@@ -582,8 +583,7 @@ __global__ void __launch_bounds__(kBlock) k_row_update(const RoundCtr* __restric
         ctr->rows_short = ns;
         ctr->rows_long = nl;
     }
-    const unsigned int quarter = gridDim.x / 4;
-    const unsigned int long_blocks = nl < quarter ? nl : quarter;
+    const unsigned int long_blocks = nl < long_blocks_max ? nl : long_blocks_max;
     if (blockIdx.x < long_blocks)
         row_update_long<CP, STAGED>(blockIdx.x, long_blocks, back, nl, ns, meta, pool, F_in, F_out, flag, moved,
                                     tol, ctr);
