@@ -232,7 +232,10 @@ def main():
     tpath = os.path.join(ROOT, "profiles", f"row_update_{args.workload}_traffic.json")  # from rocprofv3 --pmc runs
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+            tj = json.load(open(tpath))
+            # the stored figure belongs to one kernel instantiation at full-size launches
+            if tj.get("kernel", "").endswith(dom):
+                traffic = tj.get("hbm_bytes_per_launch")
         except Exception:
             traffic = None
     out = {

@@ -205,3 +205,88 @@ int64_t oracle_step3(int64_t n, const int64_t* row_ptr, const int32_t* col, cons
     free(stage);
     return rounds;
 }
+
+/*
+ * Alg. 2 Step 1, components of the sparsified batch-internal graph G'(V',E'): V' = the k inserted
+ * vertices n_old..n_old+k-1; E' = the batch edges with both endpoints in V' and weight > tau
+ * (each listed edge tested on its own weight).  comp[i] (i = batch-local id) = index of i's
+ * component, components numbered by ascending smallest member.  Breadth-first search over an
+ * adjacency list built by counting.  *kept (may be NULL) = |E'|.  Returns the number of
+ * components.
+ */
+int64_t oracle_components(int64_t n_old, int64_t k, int64_t m, const int32_t* eu, const int32_t* ev,
+                          const double* ew, double tau, int32_t* comp, int64_t* kept) {
+    int64_t* start = (int64_t*)calloc((size_t)k + 2, sizeof(int64_t));
+    int64_t ne = 0;
+    for (int64_t e = 0; e < m; ++e) {
+        int64_t a = eu[e] - n_old, b = ev[e] - n_old;
+        if (a >= 0 && a < k && b >= 0 && b < k && ew[e] > tau) {
+            start[a + 1]++;
+            start[b + 1]++;
+            ne++;
+        }
+    }
+    for (int64_t i = 0; i < k; ++i) start[i + 1] += start[i];
+    int32_t* nbr = (int32_t*)malloc(sizeof(int32_t) * (size_t)(2 * ne + 1));
+    int64_t* fill = (int64_t*)malloc(sizeof(int64_t) * (size_t)(k + 1));
+    memcpy(fill, start, sizeof(int64_t) * (size_t)(k + 1));
+    for (int64_t e = 0; e < m; ++e) {
+        int64_t a = eu[e] - n_old, b = ev[e] - n_old;
+        if (a >= 0 && a < k && b >= 0 && b < k && ew[e] > tau) {
+            nbr[fill[a]++] = (int32_t)b;
+            nbr[fill[b]++] = (int32_t)a;
+        }
+    }
+    int32_t* queue = (int32_t*)malloc(sizeof(int32_t) * (size_t)(k + 1));
+    for (int64_t i = 0; i < k; ++i) comp[i] = -1;
+    int64_t count = 0;
+    for (int64_t s = 0; s < k; ++s) {
+        if (comp[s] >= 0) continue;
+        int64_t head = 0, tail = 0;
+        queue[tail++] = (int32_t)s;
+        comp[s] = (int32_t)count;
+        while (head < tail) {
+            int64_t u = queue[head++];
+            for (int64_t j = start[u]; j < start[u + 1]; ++j) {
+                int32_t v = nbr[j];
+                if (comp[v] < 0) {
+                    comp[v] = (int32_t)count;
+                    queue[tail++] = v;
+                }
+            }
+        }
+        ++count;
+    }
+    if (kept) *kept = ne;
+    free(start);
+    free(nbr);
+    free(fill);
+    free(queue);
+    return count;
+}
+
+/*
+ * Alg. 2 Step 2 on the updated graph (n vertices, CSR already holds the batch):
+ * W[c][j] = sum over members u of component c, over neighbours v of u labelled j, of w(u,v)
+ * (W is num_comp x C, zeroed here); then every unlabelled inserted vertex u gets
+ * F[u][j] = W[comp(u)][j] / sum_j W[comp(u)][j], or 1/C when that sum is 0.
+ */
+void oracle_supernode_init(int64_t n, const int64_t* row_ptr, const int32_t* col, const double* w, int C,
+                           const int32_t* seed_class, int64_t n_old, const int32_t* comp, int64_t num_comp,
+                           double* W, double* F) {
+    memset(W, 0, sizeof(double) * (size_t)num_comp * C);
+    for (int64_t u = n_old; u < n; ++u) {
+        double* Wc = W + (int64_t)comp[u - n_old] * C;
+        for (int64_t j = row_ptr[u]; j < row_ptr[u + 1]; ++j) {
+            int32_t sc = seed_class[col[j]];
+            if (sc >= 0) Wc[sc] += w[j];
+        }
+    }
+    for (int64_t u = n_old; u < n; ++u) {
+        if (seed_class[u] >= 0) continue;
+        const double* Wc = W + (int64_t)comp[u - n_old] * C;
+        double tot = 0.0;
+        for (int c = 0; c < C; ++c) tot += Wc[c];
+        for (int c = 0; c < C; ++c) F[u * C + c] = tot > 0.0 ? Wc[c] / tot : 1.0 / C;
+    }
+}

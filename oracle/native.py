@@ -40,6 +40,10 @@ def lib():
         L.oracle_affected_set.argtypes = [i64, p, p, p, i64, i64, p, p, i64, p, p, p]
         L.oracle_step3.restype = i64
         L.oracle_step3.argtypes = [i64, p, p, p, ct.c_int, p, p, p, i64, f64, i64, ct.c_int, p, p, i64, p, p]
+        L.oracle_components.restype = i64
+        L.oracle_components.argtypes = [i64, i64, i64, p, p, p, f64, p, p]
+        L.oracle_supernode_init.restype = None
+        L.oracle_supernode_init.argtypes = [i64, p, p, p, ct.c_int, p, i64, p, i64, p, p]
         _lib = L
     return _lib
 
@@ -118,3 +122,28 @@ def step3_propagate(row_ptr, col, w, F, seed_class, V_aff, tol, max_iter, decide
     k = min(int(rounds), record)
     return dict(F=F, rounds=int(rounds), frontier_sizes=sizes[:k].copy(), max_changes=changes[:k].copy(),
                 rows_updated=int(totals[0]), edges_traversed=int(totals[1]), remaining=int(rem.value))
+
+
+def components(n_old, k, eu, ev, ew, tau):
+    """Components of the sparsified batch-internal graph (Alg. 2 Step 1).  Returns
+    (comp int32[k], number of components, |E'|)."""
+    eu = np.ascontiguousarray(eu, dtype=np.int32)
+    ev = np.ascontiguousarray(ev, dtype=np.int32)
+    ew = np.ascontiguousarray(ew, dtype=np.float64)
+    comp = np.empty(max(int(k), 1), dtype=np.int32)
+    kept = ct.c_int64(0)
+    cnt = lib().oracle_components(int(n_old), int(k), eu.shape[0], _ptr(eu), _ptr(ev), _ptr(ew), float(tau),
+                                  _ptr(comp), ct.byref(kept))
+    return comp[:int(k)].copy(), int(cnt), int(kept.value)
+
+
+def supernode_init(row_ptr, col, w, F, seed_class, n_old, comp, num_comp):
+    """Alg. 2 Step 2 on the updated CSR.  Returns (F with the inserted unlabelled rows set, W)."""
+    rp, cl, ww = _csr(row_ptr, col, w)
+    F = np.array(F, dtype=np.float64, order="C")
+    sc = np.ascontiguousarray(seed_class, dtype=np.int32)
+    comp = np.ascontiguousarray(comp, dtype=np.int32)
+    W = np.zeros((max(int(num_comp), 1), F.shape[1]), dtype=np.float64)
+    lib().oracle_supernode_init(F.shape[0], _ptr(rp), _ptr(cl), _ptr(ww), F.shape[1], _ptr(sc), int(n_old),
+                                _ptr(comp), int(num_comp), _ptr(W), _ptr(F))
+    return F, W[:int(num_comp)]

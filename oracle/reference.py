@@ -11,7 +11,9 @@ Readings taken where the paper is silent or garbled (each also listed in the des
 * Alg. 2 Step 3 commit: the computed F'_u is stored whether or not it passed the threshold;
 * rows with d(u)=0 never change; parallel edges add their weights;
 * an inserted edge affects both endpoints; a vertex that becomes a seed affects its
-  neighbours and is itself clamped to one-hot and never updated again.
+  neighbours and is itself clamped to one-hot and never updated again;
+* Step 2 for C classes: a supernode's row is its weight share per labelled class, uniform when
+  it has no labelled neighbour; the threshold tau acts on each listed batch edge separately.
 """
 from __future__ import annotations
 
@@ -234,6 +236,105 @@ def step3_update_binary_adjustment(adj, f, seed_class, u):
     w_l1 = sum(wuv for v, wuv in adj[u].items() if seed_class[v] == 1)
     rest = sum((f[v] - f[u]) * wuv / w_all for v, wuv in adj[u].items() if seed_class[v] < 0)
     return f[u] + (0.0 - f[u]) * w_l0 / w_all + (1.0 - f[u]) * w_l1 / w_all + rest
+
+
+# --------------------------------------------------------------------------------------
+# Alg. 2 Step 1 (sparsification + components of G') and Step 2 (label initialisation)
+# --------------------------------------------------------------------------------------
+def mean_edge_weight(w):
+    """The experiments' threshold tau: the average edge weight of the data set.  Every
+    undirected edge appears twice in the directed-entry list, so the mean over entries is the
+    mean over edges."""
+    w = np.asarray(w, dtype=np.float64)
+    return float(w.sum() / w.shape[0]) if w.shape[0] else 0.0
+
+
+def batch_internal_edges(num_old_vertices, num_new_vertices, eu, ev, ew, tau):
+    """E' of Alg. 2 Step 1: the batch's edges whose two endpoints are both inserted vertices
+    (V' = Delta^Ins) and whose weight exceeds tau (strict: an entry with w <= tau is the one
+    the sparsification kernel flags as removed).  Every listed edge is tested on its own
+    weight, parallel edges included.  Returns pairs of batch-local ids 0..k-1."""
+    lo, hi = int(num_old_vertices), int(num_old_vertices) + int(num_new_vertices)
+    out = []
+    for a, b, wab in zip(np.asarray(eu).tolist(), np.asarray(ev).tolist(), np.asarray(ew, dtype=np.float64).tolist()):
+        if lo <= a < hi and lo <= b < hi and wab > tau:
+            out.append((a - lo, b - lo))
+    return out
+
+
+def connected_components(k, edges):
+    """FindConnectedComponents(G'(V',E')): comp[i] = index of i's component, components numbered
+    in the order of their smallest member (so comp is canonical).  Plain breadth-first search."""
+    nbr = [[] for _ in range(k)]
+    for a, b in edges:
+        nbr[a].append(b)
+        nbr[b].append(a)
+    comp = np.full(k, -1, dtype=np.int64)
+    count = 0
+    for s in range(k):
+        if comp[s] >= 0:
+            continue
+        comp[s] = count
+        queue = [s]
+        while queue:
+            nxt = []
+            for u in queue:
+                for v in nbr[u]:
+                    if comp[v] < 0:
+                        comp[v] = count
+                        nxt.append(v)
+            queue = nxt
+        count += 1
+    return comp, count
+
+
+def supernode_weights(adj_after, seed_class_after, num_old_vertices, comp, num_components, C):
+    """Step 2: W_{c_i}^{L_k} = sum_{u in c_i} sum_{v in L_k} w(u,v), the weight between supernode
+    c_i and the supernode of all vertices labelled k (the paper has k in {0,1}; here k < C).
+    The sums run over the updated graph's edges, to old and new labelled vertices alike, and
+    over every member u of c_i."""
+    W = np.zeros((num_components, C), dtype=np.float64)
+    for i, c in enumerate(np.asarray(comp).tolist()):
+        u = num_old_vertices + i
+        for v, wuv in adj_after[u].items():
+            if seed_class_after[v] >= 0:
+                W[c, seed_class_after[v]] += wuv
+    return W
+
+
+def supernode_label(Wrow):
+    """Step 2 initial row of a supernode: class share of its weight to the labelled supernodes,
+    W_k / sum_j W_j.  For two classes column 1 is the paper's
+    0.5 - W^{L0}/(2(W^{L0}+W^{L1})) + W^{L1}/(2(W^{L0}+W^{L1})).  A supernode with no weight to
+    any labelled vertex gets the neutral value (0.5 in the paper, 1/C here)."""
+    Wrow = np.asarray(Wrow, dtype=np.float64)
+    tot = Wrow.sum()
+    if tot <= 0.0:
+        return np.full(Wrow.shape[0], 1.0 / Wrow.shape[0])
+    return Wrow / tot
+
+
+def supernode_label_binary_as_printed(w_l0, w_l1):
+    """The paper's Step-2 expression for the scalar label, term by term."""
+    return 0.5 - w_l0 / (2.0 * (w_l0 + w_l1)) + w_l1 / (2.0 * (w_l0 + w_l1))
+
+
+def step2_initialise(F, adj_after, seed_class_after, num_old_vertices, num_new_vertices, eu, ev, ew, tau):
+    """Steps 1-2 of Alg. 2 for the inserted vertices: components of the sparsified
+    batch-internal graph, then every unlabelled member of a component gets the component's
+    row.  Labelled inserted vertices are members of their component (their edges count in the
+    sums) but keep their one-hot row.  Returns (F with the new rows set, comp, number of
+    components, W)."""
+    F = np.array(F, dtype=np.float64)
+    C = F.shape[1]
+    comp, count = connected_components(num_new_vertices,
+                                       batch_internal_edges(num_old_vertices, num_new_vertices, eu, ev, ew, tau))
+    W = supernode_weights(adj_after, seed_class_after, num_old_vertices, comp, count, C)
+    for i in range(num_new_vertices):
+        u = num_old_vertices + i
+        if seed_class_after[u] < 0:
+            F[u] = supernode_label(W[comp[i]])
+    return F, comp, count, W
 
 
 # --------------------------------------------------------------------------------------

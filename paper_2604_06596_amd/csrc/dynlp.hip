@@ -1114,7 +1114,7 @@ dynlp_status dynlp_get_labels(dynlp_ctx* c, float* soft, int32_t* hard) {
         }
         if (hard) {
             int32_t* dst = c->dev_ptrs ? hard : (d_hard = dev_alloc_n<int32_t>(c, n));
-            hipLaunchKernelGGL(k_argmax, dim3(grid_for(n)), dim3(kBlock), 0, c->stream, n, c->C, c->CP, c->F, dst);
+            hipLaunchKernelGGL(k_argmax, dim3(grid_for(n * (c->CP >= 4 ? c->CP / 4 : 1))), dim3(kBlock), 0, c->stream, n, c->C, c->CP, c->F, dst);
             HIPCHK(c, hipGetLastError());
             if (!c->dev_ptrs)
                 HIPCHK(c, hipMemcpyAsync(hard, dst, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));

@@ -196,19 +196,39 @@ __global__ void __launch_bounds__(kBlock) k_apply_seeds(int64_t s, const int32_t
     for (int j = gl; j < m.len; j += G) flag[pool[m.off + j].col] = 1;
 }
 
-// hard[u] = argmax_c F[u][c], lowest index on ties.
+// hard[u] = argmax_c F[u][c], lowest index on ties.  A row of CP >= 4 floats is read by CP/4 adjacent
+// lanes as one float4 each (a coalesced 16*L-byte segment per row); the lanes' (value, index) pairs
+// are then merged with xor shuffles.  CP < 4 rows are read by one lane.
 __global__ void __launch_bounds__(kBlock) k_argmax(int64_t n, int C, int CP, const float* __restrict__ F,
                                                   int32_t* __restrict__ hard) {
-    const int64_t u = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (u >= n) return;
-    const float* row = F + u * CP;
+    const int L = CP >= 4 ? CP / 4 : 1;  // lanes per row: 1, 2, 4, 8 or 16
+    const int64_t u = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / L;
+    const int sub = threadIdx.x & (L - 1);
+    const bool live = u < n;
+    float bv = -1.0f;  // label values are >= 0
     int best = 0;
-    float bv = row[0];
-    for (int c = 1; c < C; ++c) {
-        const float v = row[c];
-        if (v > bv) { bv = v; best = c; }
+    if (live) {
+        const float* row = F + u * CP;
+        if (CP >= 4) {
+            const float4 q = *reinterpret_cast<const float4*>(row + 4 * sub);
+            const float v[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int c = 4 * sub + k;
+                if (c < C && v[k] > bv) { bv = v[k]; best = c; }
+            }
+        } else {
+            bv = row[0];
+            for (int c = 1; c < C; ++c)
+                if (row[c] > bv) { bv = row[c]; best = c; }
+        }
     }
-    hard[u] = best;
+    for (int d = L >> 1; d > 0; d >>= 1) {
+        const float ov = __shfl_xor(bv, d);
+        const int ob = __shfl_xor(best, d);
+        if (ov > bv || (ov == bv && ob < best)) { bv = ov; best = ob; }
+    }
+    if (live && sub == 0) hard[u] = best;
 }
 
 __global__ void __launch_bounds__(kBlock) k_pack_soft(int64_t n, int C, int CP, const float* __restrict__ F,

@@ -23,6 +23,7 @@ from .graphs import (  # noqa: F401
     chung_lu_vertex_batch,
     small_random,
     small_random_batch,
+    clustered_batch,
     CONFIGS,
     csr_with_batch,
     make_config,

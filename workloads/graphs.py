@@ -458,6 +458,67 @@ def small_random_batch(p: Problem, num_new: int, degree: int, num_new_seeds: int
     return Batch(num_new, lo.astype(np.int32), hi.astype(np.int32), ew, sv, sc)
 
 
+def clustered_batch(p: Problem, num_new: int, mean_cluster: float, intra_degree: int, cross_degree: int,
+                    old_degree: int, num_new_seeds: int) -> Batch:
+    """New vertices that arrive in groups of similar items (the situation the paper's
+    batch-internal sparsified graph is meant for).  The batch is cut into runs of geometric
+    length (mean ``mean_cluster``, so singletons occur); a run shares one class.  Each vertex
+    draws ``intra_degree`` partners inside its run with strong weights U(0.6,1), ``cross_degree``
+    partners anywhere in the batch with weights U(0.05,0.58) (a few above, most below a threshold
+    near the mean weight) and ``old_degree`` partners among the existing vertices, 80% of them
+    of the run's class, with weights U(0.1,1).  Works on any Problem.  Advances ``p``."""
+    st = p.state
+    rng = st["rng"]
+    C, n0 = p.C, p.n
+    nt = n0 + num_new
+    cuts = rng.random(num_new) < 1.0 / max(mean_cluster, 1.0)
+    if num_new:
+        cuts[0] = True
+    run_id = np.cumsum(cuts) - 1
+    num_runs = int(run_id[-1]) + 1 if num_new else 0
+    run_start = np.flatnonzero(cuts)
+    run_len = np.diff(np.concatenate([run_start, [num_new]]))
+    run_cls = rng.integers(0, C, size=num_runs).astype(np.int32)
+    cls_new = run_cls[run_id] if num_new else np.zeros(0, dtype=np.int32)
+    ids = np.arange(n0, nt, dtype=np.int64)
+    # inside the run
+    a1 = np.repeat(ids, intra_degree)
+    r1 = np.repeat(run_id, intra_degree)
+    b1 = n0 + run_start[r1] + (rng.random(a1.shape[0]) * run_len[r1]).astype(np.int64)
+    w1 = rng.uniform(0.6, 1.0, size=a1.shape[0])
+    # anywhere in the batch
+    a2 = np.repeat(ids, cross_degree)
+    b2 = rng.integers(n0, max(nt, n0 + 1), size=a2.shape[0])
+    w2 = rng.uniform(0.05, 0.58, size=a2.shape[0])
+    # to existing vertices
+    a3 = np.repeat(ids, old_degree)
+    c3 = np.repeat(cls_new.astype(np.int64), old_degree)
+    order, start = _members_table(p.true_class[:n0], C)
+    same = rng.random(a3.shape[0]) < 0.8
+    cnt = start[c3 + 1] - start[c3]
+    same &= cnt > 0
+    pick_same = order[np.minimum(start[c3] + (rng.random(a3.shape[0]) * np.maximum(cnt, 1)).astype(np.int64), n0 - 1)]
+    b3 = np.where(same, pick_same, rng.integers(0, n0, size=a3.shape[0]))
+    w3 = rng.uniform(0.1, 1.0, size=a3.shape[0])
+    a = np.concatenate([a1, a2, a3])
+    b = np.concatenate([b1, b2, b3])
+    ww = np.concatenate([w1, w2, w3])
+    keep = a != b
+    a, b, ww = a[keep], b[keep], ww[keep]
+    lo, hi = np.minimum(a, b), np.maximum(a, b)
+    key = lo * np.int64(nt) + hi
+    _, first = np.unique(key, return_index=True)  # first listed weight of a repeated pair wins
+    lo, hi, ww = lo[first], hi[first], ww[first]
+    true_all = np.concatenate([p.true_class, cls_new])
+    sv, sc = _pick_seeds(rng, ids, num_new_seeds, true_all)
+    is_seed = np.concatenate([st["is_seed"], np.zeros(num_new, dtype=bool)])
+    is_seed[sv] = True
+    st["is_seed"] = is_seed
+    p.n = nt
+    p.true_class = true_all
+    return Batch(num_new, lo.astype(np.int32), hi.astype(np.int32), ww.astype(np.float32), sv, sc)
+
+
 # --------------------------------------------------------------------------------------
 # the five named configurations
 # --------------------------------------------------------------------------------------
