@@ -123,8 +123,49 @@ dynlp_status dynlp_static_solve(dynlp_ctx* ctx, float tol, int32_t max_iter, dyn
 dynlp_status dynlp_set_params(dynlp_ctx* ctx, float tol, int32_t max_iter);
 
 /*
+ * Starting rows of the vertices a batch inserts (Alg. 2 Step 1 "sparsification" and Step 2 "label
+ * initialisation").  It changes where Step 3 starts, not the labels it converges to.
+ *   DYNLP_INIT_UNIFORM    every inserted unlabelled row starts at 1/C (the paper's neutral 0.5).
+ *   DYNLP_INIT_SUPERNODE  the batch edges whose two ends are both inserted by this batch and whose
+ *                         weight is > tau form the graph G'; each connected component of G' (over all
+ *                         inserted vertices; a vertex without such an edge is its own component) is
+ *                         a supernode c_i; W[c_i][j] = summed weight of the updated graph's edges
+ *                         from any member of c_i to any vertex labelled j (old or new); every
+ *                         unlabelled member starts at W[c_i][j] / sum_j W[c_i][j], or 1/C when that
+ *                         sum is 0.  For C = 2 column 1 is the paper's
+ *                         0.5 - W^{L0}/(2(W^{L0}+W^{L1})) + W^{L1}/(2(W^{L0}+W^{L1})).
+ * tau (finite, >= 0; ignored for DYNLP_INIT_UNIFORM): the paper's experiments use the mean edge
+ * weight of the data set, which dynlp_mean_edge_weight returns for the graph currently stored.
+ * Each listed batch edge is tested on its own weight.  Default: DYNLP_INIT_UNIFORM.
+ */
+typedef enum dynlp_init_mode { DYNLP_INIT_UNIFORM = 0, DYNLP_INIT_SUPERNODE = 1 } dynlp_init_mode;
+dynlp_status dynlp_set_initialiser(dynlp_ctx* ctx, int32_t mode, float tau);
+
+/* Mean weight over the stored CSR entries (= mean over undirected edges), summed in binary64 in a
+ * fixed order; 0 for an empty graph.  mean is host memory. */
+dynlp_status dynlp_mean_edge_weight(dynlp_ctx* ctx, double* mean);
+
+/* What the supernode initialisation of the last dynlp_apply_batch did (all zero when it did not
+ * run: uniform mode, or a batch without new vertices). */
+typedef struct dynlp_init_info {
+    int64_t vertices;    /* inserted vertices = vertices of G' */
+    int64_t kept_edges;  /* |E'|: batch-internal edges with weight > tau */
+    int64_t components;  /* connected components of G' */
+    int32_t hook_steps;  /* hook/jump iterations of the component search, the final no-change one included */
+    float ms;            /* device time of the whole initialisation (part of dynlp_stats.ms_seed) */
+} dynlp_init_info;
+
+/*
+ * Components found by the last dynlp_apply_batch in DYNLP_INIT_SUPERNODE mode (the set C of Alg. 2):
+ * comp[i] = component of inserted vertex i (i-th new id of that batch), numbered 0..components-1 in
+ * ascending order of each component's smallest member.  comp (cap >= vertices entries; device or
+ * host memory like every array argument) may be NULL to fetch only *info (host memory, may be NULL).
+ */
+dynlp_status dynlp_last_components(dynlp_ctx* ctx, int64_t cap, int32_t* comp, dynlp_init_info* info);
+
+/*
  * DynLP update for one insertion batch (Alg. 2 Steps 1 and 3).
- *   num_new_vertices   they receive ids n .. n+k-1 in order; rows start uniform 1/C
+ *   num_new_vertices   they receive ids n .. n+k-1 in order; rows start as dynlp_set_initialiser chose
  *   eu, ev, ew         num_new_edges undirected edges, each listed once, endpoints in [0, n+k),
  *                      eu != ev, weight finite and > 0; an edge that already exists is legal
  *                      and adds its weight (parallel edge)

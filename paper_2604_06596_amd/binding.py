@@ -41,6 +41,16 @@ class RoundInfo(ct.Structure):
                 ("ms_update", ct.c_float), ("reserved", ct.c_float), ("staged", ct.c_int32), ("group_lanes", ct.c_int32)]
 
 
+class InitInfo(ct.Structure):
+    _fields_ = [("vertices", ct.c_int64), ("kept_edges", ct.c_int64), ("components", ct.c_int64),
+                ("hook_steps", ct.c_int32), ("ms", ct.c_float)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+INIT_UNIFORM, INIT_SUPERNODE = 0, 1
+
 _ALLOC_FN = ct.CFUNCTYPE(ct.c_void_p, ct.c_size_t, ct.c_void_p)
 _DEALLOC_FN = ct.CFUNCTYPE(None, ct.c_void_p, ct.c_void_p)
 
@@ -54,7 +64,8 @@ class Options(ct.Structure):
 
 EXPORTS = ["dynlp_default_options", "dynlp_create", "dynlp_static_solve", "dynlp_set_params", "dynlp_apply_batch",
            "dynlp_get_labels", "dynlp_num_vertices", "dynlp_num_entries", "dynlp_num_classes", "dynlp_export_graph",
-           "dynlp_round_log", "dynlp_last_error", "dynlp_destroy"]
+           "dynlp_round_log", "dynlp_last_error", "dynlp_destroy", "dynlp_set_initialiser",
+           "dynlp_mean_edge_weight", "dynlp_last_components"]
 
 _lib = None
 
@@ -98,6 +109,12 @@ def load_library(path: str | None = None):
     L.dynlp_export_graph.restype = ct.c_int
     L.dynlp_round_log.argtypes = [p, i64, ct.POINTER(RoundInfo)]
     L.dynlp_round_log.restype = i64
+    L.dynlp_set_initialiser.argtypes = [p, i32, f32]
+    L.dynlp_set_initialiser.restype = ct.c_int
+    L.dynlp_mean_edge_weight.argtypes = [p, ct.POINTER(ct.c_double)]
+    L.dynlp_mean_edge_weight.restype = ct.c_int
+    L.dynlp_last_components.argtypes = [p, i64, p, ct.POINTER(InitInfo)]
+    L.dynlp_last_components.restype = ct.c_int
     L.dynlp_last_error.argtypes = [p]
     L.dynlp_last_error.restype = ct.c_char_p
     L.dynlp_destroy.argtypes = [p]
@@ -184,6 +201,26 @@ class DynLP:
 
     def set_params(self, tol, max_iter):
         self._check(self._L.dynlp_set_params(self._h, float(tol), int(max_iter)))
+
+    def set_initialiser(self, mode, tau=0.0):
+        """dynlp_set_initialiser: INIT_UNIFORM or INIT_SUPERNODE with threshold tau."""
+        self._check(self._L.dynlp_set_initialiser(self._h, int(mode), float(tau)))
+
+    def mean_edge_weight(self):
+        """dynlp_mean_edge_weight."""
+        out = ct.c_double(0.0)
+        self._check(self._L.dynlp_mean_edge_weight(self._h, ct.byref(out)))
+        return float(out.value)
+
+    def last_components(self, want_comp=True):
+        """dynlp_last_components.  Returns (comp [vertices] int32 or None, InitInfo)."""
+        info = InitInfo()
+        self._check(self._L.dynlp_last_components(self._h, 0, None, ct.byref(info)))
+        if not want_comp or info.vertices == 0:
+            return None, info
+        comp, cp = self._out((int(info.vertices),), np.int32)
+        self._check(self._L.dynlp_last_components(self._h, int(info.vertices), cp, ct.byref(info)))
+        return comp, info
 
     def apply_batch(self, num_new_vertices, eu, ev, ew, seed_vertex=None, seed_class=None):
         """dynlp_apply_batch.  Returns (status, Stats)."""

@@ -15,6 +15,7 @@
 #include "dynlp.h"
 #include "dynlp_kernels.h"
 #include "dynlp_frontier.h"
+#include "dynlp_components.h"
 
 using namespace dynlp;
 
@@ -99,6 +100,21 @@ struct dynlp_ctx {
     RoundCtr* h_slot = nullptr;  // pinned, kRing slots
     unsigned int h_slot_start_long = 0;  // long rows among the updatable vertices of the running static solve
     BatchCtr* h_bc = nullptr;    // pinned
+
+    // label initialisation of inserted vertices (dynlp_components.h)
+    int init_mode = DYNLP_INIT_UNIFORM;
+    float tau = 0.f;
+    int32_t *cc_par = nullptr, *cc_dense = nullptr, *cc_comp = nullptr;
+    unsigned int* cc_block = nullptr;
+    int64_t cc_vcap = 0;
+    int2* cc_kept = nullptr;
+    int64_t cc_ecap = 0;
+    double* cc_W = nullptr;
+    int64_t cc_wcap = 0;
+    InitCtr* cc_ctr = nullptr;  // device
+    InitCtr* h_cc = nullptr;    // pinned
+    hipEvent_t init_ev[2] = {nullptr, nullptr};
+    dynlp_init_info last_init = {};  // of the last dynlp_apply_batch; vertices == 0: nothing to report
 
     float tol = 1e-4f;
     int32_t max_iter = 100000;
@@ -559,8 +575,13 @@ void destroy_ctx(dynlp_ctx* c) {
     (void)hipSetDevice(c->device);
     if (c->stream || c->meta) (void)hipStreamSynchronize(c->stream);
     void* ptrs[] = {c->meta, c->pool, c->F, c->F2, c->seed_class, c->flag, c->queue[0], c->queue[1], c->queue[2], c->moved[0], c->moved[1], c->add_cnt,
-                    c->deg, c->touched, c->reloc_off, c->b_eu, c->b_ev, c->b_ew, c->b_sv, c->b_sc};
+                    c->deg, c->touched, c->reloc_off, c->b_eu, c->b_ev, c->b_ew, c->b_sv, c->b_sc,
+                    c->cc_par, c->cc_dense, c->cc_comp, c->cc_block, c->cc_kept, c->cc_W};
     for (void* p : ptrs) dev_free(c, p);
+    if (c->cc_ctr) (void)hipFree(c->cc_ctr);
+    if (c->h_cc) (void)hipHostFree(c->h_cc);
+    for (hipEvent_t e : c->init_ev)
+        if (e) (void)hipEventDestroy(e);
     if (c->ring) (void)hipFree(c->ring);
     if (c->bc) (void)hipFree(c->bc);
     if (c->h_slot) (void)hipHostFree(c->h_slot);
@@ -569,6 +590,99 @@ void destroy_ctx(dynlp_ctx* c) {
     for (hipEvent_t e : c->phase_ev)
         if (e) (void)hipEventDestroy(e);
     delete c;
+}
+
+// ---- Alg. 2 Step 1 (components of the sparsified batch-internal graph) + Step 2 (supernode rows) ----
+void ensure_init_scratch(dynlp_ctx* c, int64_t k, int64_t m) {
+    if (!c->cc_ctr) {
+        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->cc_ctr), sizeof(InitCtr)));
+        HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_cc), sizeof(InitCtr), hipHostMallocDefault));
+        for (hipEvent_t& e : c->init_ev) HIPCHK(c, hipEventCreate(&e));
+    }
+    if (k > c->cc_vcap) {
+        dev_free(c, c->cc_par);
+        dev_free(c, c->cc_dense);
+        dev_free(c, c->cc_comp);
+        dev_free(c, c->cc_block);
+        c->cc_par = c->cc_dense = c->cc_comp = nullptr;
+        c->cc_block = nullptr;
+        c->cc_vcap = 0;
+        const int64_t cap = k + k / 2;
+        c->cc_par = dev_alloc_n<int32_t>(c, cap);
+        c->cc_dense = dev_alloc_n<int32_t>(c, cap);
+        c->cc_comp = dev_alloc_n<int32_t>(c, cap);
+        c->cc_block = dev_alloc_n<unsigned int>(c, ceil_div(cap, kBlock) + 1);
+        c->cc_vcap = cap;
+    }
+    if (m > c->cc_ecap) {
+        dev_free(c, c->cc_kept);
+        c->cc_kept = nullptr;
+        c->cc_ecap = 0;
+        const int64_t cap = m + m / 2;
+        c->cc_kept = dev_alloc_n<int2>(c, cap);
+        c->cc_ecap = cap;
+    }
+}
+
+void read_init_ctr(dynlp_ctx* c) {
+    HIPCHK(c, hipMemcpyAsync(c->h_cc, c->cc_ctr, sizeof(InitCtr), hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+}
+
+// Runs after the batch's edges are in the CSR and its seeds are clamped; rewrites only the rows of
+// the k inserted, unlabelled vertices n0 .. n0+k-1.
+void run_supernode_init(dynlp_ctx* c, int64_t n0, int64_t k, int64_t m, const int32_t* d_eu, const int32_t* d_ev,
+                        const float* d_ew) {
+    ensure_init_scratch(c, k, m);
+    HIPCHK(c, hipEventRecord(c->init_ev[0], c->stream));
+    HIPCHK(c, hipMemsetAsync(c->cc_ctr, 0, sizeof(InitCtr), c->stream));
+    hipLaunchKernelGGL(k_cc_reset, dim3(grid_for(k)), dim3(kBlock), 0, c->stream, k, c->cc_par);
+    if (m > 0)
+        hipLaunchKernelGGL(k_cc_filter, dim3(grid_for(m)), dim3(kBlock), 0, c->stream, m, n0, k, d_eu, d_ev, d_ew, c->tau,
+                           c->cc_kept, c->cc_ctr);
+    const unsigned int hook_grid = (unsigned int)std::min<int64_t>(grid_for(std::max<int64_t>(m, 1)), (int64_t)c->num_cu * 8);
+    int hook_steps = 0;
+    for (;;) {
+        for (int i = 0; i < kInitChain; ++i) {
+            hipLaunchKernelGGL(k_cc_hook, dim3(hook_grid), dim3(kBlock), 0, c->stream, i, c->cc_kept, c->cc_par, c->cc_ctr);
+            hipLaunchKernelGGL(k_cc_jump, dim3(grid_for(k)), dim3(kBlock), 0, c->stream, i, k, c->cc_par, c->cc_ctr);
+        }
+        HIPCHK(c, hipGetLastError());
+        read_init_ctr(c);
+        for (int i = 0; i < kInitChain; ++i)
+            if (i == 0 || c->h_cc->changed[i - 1]) ++hook_steps;
+        if (c->h_cc->changed[kInitChain - 1] == 0u) break;  // a hook step found every kept edge inside one tree
+        HIPCHK(c, hipMemsetAsync(c->cc_ctr->changed, 0, sizeof(unsigned int) * kInitChain, c->stream));
+    }
+    const int64_t nb = ceil_div(k, kBlock);
+    hipLaunchKernelGGL(k_cc_count_roots, dim3((unsigned int)nb), dim3(kBlock), 0, c->stream, k, c->cc_par, c->cc_block);
+    hipLaunchKernelGGL(k_cc_scan_blocks, dim3(1), dim3(kBlock), 0, c->stream, nb, c->cc_block, c->cc_ctr);
+    hipLaunchKernelGGL(k_cc_number_roots, dim3((unsigned int)nb), dim3(kBlock), 0, c->stream, k, c->cc_par, c->cc_block,
+                       c->cc_dense);
+    hipLaunchKernelGGL(k_cc_label, dim3(grid_for(k)), dim3(kBlock), 0, c->stream, k, c->cc_par, c->cc_dense, c->cc_comp);
+    HIPCHK(c, hipGetLastError());
+    read_init_ctr(c);
+    const int64_t comps = c->h_cc->components;
+    if (comps * c->C > c->cc_wcap) {
+        dev_free(c, c->cc_W);
+        c->cc_W = nullptr;
+        c->cc_wcap = 0;
+        const int64_t cap = comps * c->C + comps * c->C / 2;
+        c->cc_W = dev_alloc_n<double>(c, cap);
+        c->cc_wcap = cap;
+    }
+    hipLaunchKernelGGL(k_fill_f64, dim3(grid_for(comps * c->C)), dim3(kBlock), 0, c->stream, comps * c->C, c->cc_W, 0.0);
+    hipLaunchKernelGGL(k_supernode_weights, dim3(grid_for(k * 16)), dim3(kBlock), 0, c->stream, n0, k, c->C, c->meta,
+                       c->pool, c->seed_class, c->cc_comp, c->cc_W);
+    hipLaunchKernelGGL(k_supernode_rows, dim3(grid_for(k * c->CP)), dim3(kBlock), 0, c->stream, n0, k, c->C, c->CP,
+                       c->seed_class, c->cc_comp, c->cc_W, c->F);
+    HIPCHK(c, hipGetLastError());
+    HIPCHK(c, hipEventRecord(c->init_ev[1], c->stream));
+    c->last_init.vertices = k;
+    c->last_init.kept_edges = c->h_cc->kept;
+    c->last_init.components = comps;
+    c->last_init.hook_steps = hook_steps;
+    c->last_init.ms = 0.f;  // filled in after the call's final synchronisation
 }
 
 // Prefix offsets of per-row values already stored (caps in meta / lens in an array) need the
@@ -789,6 +903,81 @@ dynlp_status dynlp_set_params(dynlp_ctx* ctx, float tol, int32_t max_iter) {
     return DYNLP_OK;
 }
 
+dynlp_status dynlp_set_initialiser(dynlp_ctx* ctx, int32_t mode, float tau) {
+    if (!ctx) return DYNLP_ERR_INVALID_ARG;
+    if (mode != DYNLP_INIT_UNIFORM && mode != DYNLP_INIT_SUPERNODE) {
+        ctx->err = "mode must be DYNLP_INIT_UNIFORM or DYNLP_INIT_SUPERNODE";
+        return DYNLP_ERR_INVALID_ARG;
+    }
+    if (mode == DYNLP_INIT_SUPERNODE && (!std::isfinite(tau) || tau < 0.f)) {
+        ctx->err = "tau must be finite and >= 0";
+        return DYNLP_ERR_INVALID_ARG;
+    }
+    ctx->init_mode = mode;
+    ctx->tau = tau;
+    return DYNLP_OK;
+}
+
+dynlp_status dynlp_mean_edge_weight(dynlp_ctx* c, double* mean) {
+    if (!c) return DYNLP_ERR_INVALID_ARG;
+    if (!mean) {
+        c->err = "mean is NULL";
+        return DYNLP_ERR_INVALID_ARG;
+    }
+    if (c->poisoned) {
+        c->err = "context is unusable after an earlier device or memory error";
+        return DYNLP_ERR_STATE;
+    }
+    *mean = 0.0;
+    if (c->entries == 0) return DYNLP_OK;
+    double* d_part = nullptr;
+    try {
+        HIPCHK(c, hipSetDevice(c->device));
+        const unsigned int blocks = (unsigned int)std::min<int64_t>(grid_for(c->n * 16), (int64_t)c->num_cu * 4);
+        d_part = dev_alloc_n<double>(c, blocks);
+        std::vector<double> part(blocks);
+        hipLaunchKernelGGL(k_weight_partial, dim3(blocks), dim3(kBlock), 0, c->stream, c->n, c->meta, c->pool, d_part);
+        HIPCHK(c, hipGetLastError());
+        HIPCHK(c, hipMemcpyAsync(part.data(), d_part, sizeof(double) * blocks, hipMemcpyDeviceToHost, c->stream));
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        dev_free(c, d_part);
+        d_part = nullptr;
+        double tot = 0.0;
+        for (double v : part) tot += v;
+        *mean = tot / (double)c->entries;
+        return DYNLP_OK;
+    } catch (const Fail& f) {
+        return f.st;
+    } catch (const std::bad_alloc&) {
+        dev_free(c, d_part);
+        c->err = "host allocation failed";
+        return DYNLP_ERR_OOM;
+    }
+}
+
+dynlp_status dynlp_last_components(dynlp_ctx* c, int64_t cap, int32_t* comp, dynlp_init_info* info) {
+    if (!c) return DYNLP_ERR_INVALID_ARG;
+    if (info) *info = c->last_init;
+    if (!comp || c->last_init.vertices == 0) return DYNLP_OK;
+    if (cap < c->last_init.vertices) {
+        c->err = "comp holds fewer entries than the last batch inserted vertices";
+        return DYNLP_ERR_INVALID_ARG;
+    }
+    if (c->poisoned) {
+        c->err = "context is unusable after an earlier device or memory error";
+        return DYNLP_ERR_STATE;
+    }
+    try {
+        HIPCHK(c, hipSetDevice(c->device));
+        HIPCHK(c, hipMemcpyAsync(comp, c->cc_comp, sizeof(int32_t) * (size_t)c->last_init.vertices,
+                                 c->dev_ptrs ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost, c->stream));
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        return DYNLP_OK;
+    } catch (const Fail& f) {
+        return f.st;
+    }
+}
+
 dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp_stats* stats) {
     if (!c) return DYNLP_ERR_INVALID_ARG;
     fill_stats_zero(stats);
@@ -977,6 +1166,8 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
         if (s > 0)
             hipLaunchKernelGGL(k_apply_seeds, dim3(grid_for(s * 16)), dim3(kBlock), 0, c->stream, s, d_sv, d_sc, c->C, c->CP,
                                c->seed_class, c->F, c->meta, c->pool, c->flag);
+        c->last_init = dynlp_init_info{};
+        if (c->init_mode == DYNLP_INIT_SUPERNODE && k > 0) run_supernode_init(c, n0, k, m, d_eu, d_ev, d_ew);
         zero_ring(c);
         // first frontier from the flags (its size goes to the start slot), and the list of all updatable
         // vertices
@@ -1064,6 +1255,7 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
         HIPCHK(c, hipEventRecord(c->phase_ev[3], c->stream));
         HIPCHK(c, hipStreamSynchronize(c->stream));
         const float kernel_ms_total = c->time_kernels ? collect_kernel_ms(c) : 0.f;
+        if (c->last_init.vertices > 0) (void)hipEventElapsedTime(&c->last_init.ms, c->init_ev[0], c->init_ev[1]);
         if (stats) {
             stats->iterations = it;
             stats->converged = nq == 0 ? 1 : 0;

@@ -10,6 +10,7 @@ constexpr int kWave = 64;
 constexpr int kBlock = 256;       // threads per workgroup for every kernel here
 constexpr int kRowAlign = 8;      // row capacities are multiples of 8 entries = 64 bytes
 constexpr int kRing = 64;         // per-round counter slots
+constexpr int kInitChain = 4;     // hook/jump steps of the component search queued per host round trip
 
 // One CSR entry of the slack pool: neighbour id and weight side by side, so that a single
 // 8-byte load brings both.

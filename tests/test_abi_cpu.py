@@ -120,6 +120,13 @@ def test_product_does_not_import_the_oracle():
             assert not re.search(r"^\s*(from|import)\s+paper_2604_06596_amd", text, flags=re.M), f
 
 
+def test_init_info_layout_and_null_handles(lib):
+    assert ct.sizeof(B.InitInfo) == 32 and B.InitInfo.hook_steps.offset == 24 and B.InitInfo.ms.offset == 28
+    assert lib.dynlp_set_initialiser(None, 1, 0.5) == -1
+    assert lib.dynlp_mean_edge_weight(None, None) == -1
+    assert lib.dynlp_last_components(None, 0, None, None) == -1
+
+
 def test_round_info_layout_matches_header():
     assert ct.sizeof(B.RoundInfo) == 64  # 60 bytes of fields, padded to the 8-byte alignment
     assert B.RoundInfo.max_delta.offset == 40 and B.RoundInfo.group_lanes.offset == 56
