@@ -32,7 +32,7 @@ def algorithmic_bytes(rows: int, edges: int, C: int) -> int:
     return 8 * edges + 4 * C * (edges + 2 * rows) + 20 * rows
 
 
-def build_workload(name: str, batch_frac: float, num_batches: int):
+def build_workload(name: str, batch_frac: float, num_batches: int, batch_kind: str = "default"):
     import workloads as W
 
     cfg = W.CONFIGS[name]
@@ -40,7 +40,19 @@ def build_workload(name: str, batch_frac: float, num_batches: int):
     base = dict(n=p.n, C=p.C, row_ptr=p.row_ptr, col=p.col, w=p.w, seed_vertex=p.seed_vertex,
                 seed_class=p.seed_class)
     batches = []
-    if cfg["kind"] == "sbm":
+    if batch_kind == "clustered":
+        # new vertices arriving in groups of similar items (many strong batch-internal edges): the case
+        # the component-based label initialisation is for; any base graph
+        k = max(1, int(round(batch_frac * cfg["n"])))
+        deg = int(cfg.get("batch_degree", cfg.get("mean_degree", cfg.get("k", 10))))
+        intra, cross = max(1, deg // 5), max(1, deg // 10)
+        for _ in range(num_batches):
+            batches.append(W.clustered_batch(p, k, 8.0, intra, cross, max(1, deg - intra - cross),
+                                             max(1, int(round(cfg["seed_frac"] * k)))))
+        label = (f"{name}: base graph n={cfg['n']} C={cfg['C']}, clustered batches of {k} new vertices "
+                 f"(runs of mean length 8; {intra} strong partners in the run, {cross} in the batch, "
+                 f"{max(1, deg - intra - cross)} among old vertices)")
+    elif cfg["kind"] == "sbm":
         k = max(1, int(round(batch_frac * cfg["n"])))
         for _ in range(num_batches):
             batches.append(W.sbm_vertex_batch(p, k, cfg["batch_degree"], cfg["seed_frac"]))
@@ -139,6 +151,11 @@ def main():
     ap.add_argument("--cpu-budget", type=float, default=20.0, help="seconds of CPU oracle work (0 = skip)")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not bracket the row-update launches with HIP events (roofline fields become 0)")
+    ap.add_argument("--batch-kind", default="default", choices=["default", "clustered"],
+                    help="default: the workload's own batch recipe; clustered: new vertices in groups of similar items")
+    ap.add_argument("--init", default="uniform", choices=["uniform", "supernode"],
+                    help="starting rows of inserted vertices: 1/C, or Alg. 2 Steps 1-2 (components of the sparsified "
+                         "batch-internal graph, tau = mean edge weight of the base graph)")
     ap.add_argument("--host-inputs", action="store_true",
                     help="hand the library host arrays (PCIe-inclusive timing; not the headline number)")
     args = ap.parse_args()
@@ -157,7 +174,7 @@ def main():
         P.build()
     dev = torch.device("cuda:0")
     t_gen = time.perf_counter()
-    cfg, base, batches, label = build_workload(args.workload, args.batch_frac, args.warmup + args.steps)
+    cfg, base, batches, label = build_workload(args.workload, args.batch_frac, args.warmup + args.steps, args.batch_kind)
     tol = float(args.tol if args.tol is not None else cfg["tol"])
     t_gen = time.perf_counter() - t_gen
 
@@ -179,6 +196,11 @@ def main():
     cold = dict(status=st, sweeps=s0.iterations, ms=s0.ms_total, ms_update_kernel=s0.ms_update_kernel,
                 algorithmic_gbs=algorithmic_bytes(s0.rows_updated, s0.edges_traversed, base["C"]) / 1e6 /
                 max(s0.ms_update_kernel, 1e-9))
+    tau = None
+    if args.init == "supernode":
+        tau = float(np.float32(d.mean_edge_weight()))
+        d.set_initialiser(P.INIT_SUPERNODE, tau)
+    init_info = []
     F_before = None
     per_step = []
     round_profile = []
@@ -196,6 +218,10 @@ def main():
         dt = time.perf_counter() - t0
         if timed:
             per_step.append(dict(ms=dt * 1e3, status=st, edges=batches[i].num_edges, **s.as_dict()))
+            if tau is not None:
+                ii = d.last_components(want_comp=False)[1]
+                init_info.append(dict(components=int(ii.components), kept_edges=int(ii.kept_edges),
+                                      hook_steps=int(ii.hook_steps), ms=round(float(ii.ms), 3)))
             info = d.round_log_full()
             for r in info:  # per kernel instantiation: launches, rows, entries, device ms
                 b = buckets.setdefault((int(r.staged), int(r.group_lanes)), [0, 0, 0, 0.0])
@@ -271,7 +297,8 @@ def main():
                                           for k, v in kstats.items()},
                    "row_update_all_kernels_algorithmic_GBs": round(all_bytes / 1e6 / max(all_ms, 1e-9), 1),
                    "round_profile_first_step": round_profile,
-                   "cold_start": cold, "gen_s": round(t_gen, 1)},
+                   "cold_start": cold, "gen_s": round(t_gen, 1),
+                   "init": {"mode": args.init, "tau": tau, "per_step": init_info}},
     }
     if args.cpu_budget > 0 and per_step:
         out["cpu_baseline"] = cpu_baseline(base, batches[:args.warmup], batches[args.warmup], F_before, tol,

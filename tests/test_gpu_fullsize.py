@@ -172,3 +172,55 @@ def test_cfg2_ten_successive_batches_stay_close_to_exact_labels():
     # residual a stopped iteration leaves and its distance from the exact labels) is several hundred
     # at 1% seeds, against ~100 on the well-mixing SBM / Chung-Lu graphs.  Ten batches at tol = 1e-6.
     assert drift <= 3e-4
+
+
+def test_cfg3_full_size_supernode_initialisation_and_first_rounds():
+    """Alg. 2 Steps 1-2 at full size: a clustered batch of 10% new vertices on the 1M-vertex graph
+    (about 270K kept batch-internal edges): component ids bit-exact, Step-2 rows within 1e-6 of the
+    oracle's, and the first rounds from that start match the oracle's Step-3 loop."""
+    cfg = W.CONFIGS["cfg3"]
+    p = W.make_config("cfg3", SCALE)
+    n0, C = p.n, p.C
+    base = (p.row_ptr, p.col, p.w, p.seed_vertex.copy(), p.seed_class.copy())
+    k = max(1, int(0.1 * p.n))
+    b = W.clustered_batch(p, k, 8.0, 4, 2, 14, max(1, k // 100))
+    rounds = 3
+    d = P.DynLP(n0, _dv(base[0], torch.int64), _dv(base[1], torch.int32), _dv(base[2], torch.float32), C,
+                _dv(base[3], torch.int32), _dv(base[4], torch.int32), device_ptrs=True)
+    try:
+        st, _ = d.static_solve(cfg["tol"], cfg["max_iter"])
+        assert st == 0
+        soft0 = d.get_labels(soft=True, hard=False)[0].cpu().numpy()
+        tau = np.float32(d.mean_edge_weight())
+        assert abs(float(tau) - R.mean_edge_weight(base[2])) < 1e-6
+        d.set_initialiser(P.INIT_SUPERNODE, tau)
+        args = (b.num_new_vertices, _dv(b.eu, torch.int32), _dv(b.ev, torch.int32), _dv(b.ew, torch.float32),
+                _dv(b.seed_vertex, torch.int32), _dv(b.seed_class, torch.int32))
+        d.set_params(cfg["tol"], rounds)
+        st, s = d.apply_batch(*args)
+        soft = d.get_labels(soft=True, hard=False)[0].cpu().numpy()
+        sizes, deltas = d.round_log()
+        comp, info = d.last_components()
+        comp = comp.cpu().numpy()
+    finally:
+        d.destroy()
+    ocomp, count, kept = ON.components(n0, k, b.eu, b.ev, b.ew, float(tau))
+    print(f"supernode init: {info.vertices} vertices, {info.kept_edges} kept edges, {info.components} components, "
+          f"{info.hook_steps} hook steps, {info.ms:.3f} ms")
+    assert info.kept_edges == kept and info.components == count
+    assert np.array_equal(comp, ocomp)
+    rp, col, w = W.csr_with_batch(n0, base[0], base[1], base[2], b)
+    sc = np.full(n0 + k, -1, dtype=np.int32)
+    sc[base[3]] = base[4]
+    sc[b.seed_vertex] = b.seed_class
+    F = np.concatenate([soft0.astype(np.float64), np.full((k, C), 1.0 / C)])
+    F[b.seed_vertex] = 0
+    F[b.seed_vertex, b.seed_class] = 1
+    F_init, _ = ON.supernode_init(rp, col, w.astype(np.float64), F, sc, n0, ocomp, count)
+    F_start = F_init.copy()
+    F_start[n0:] = F_init[n0:].astype(np.float32).astype(np.float64)  # the rows as the library stores them
+    A0 = ON.affected_set(rp, col, sc, n0, b.eu, b.ev, b.seed_vertex)
+    o2 = ON.step3_propagate(rp, col, w.astype(np.float64), F_start, sc, A0, cfg["tol"], rounds)
+    assert sizes.tolist() == o2["frontier_sizes"].tolist()
+    assert np.max(np.abs(soft - o2["F"])) <= 5e-6
+    assert np.abs(F_init[n0:] - 1.0 / C).max() > 0.5  # the initialisation really moved rows away from 1/C
