@@ -156,6 +156,9 @@ def main():
     ap.add_argument("--init", default="uniform", choices=["uniform", "supernode"],
                     help="starting rows of inserted vertices: 1/C, or Alg. 2 Steps 1-2 (components of the sparsified "
                          "batch-internal graph, tau = mean edge weight of the base graph)")
+    ap.add_argument("--update-mode", default="in-place", choices=["synchronous", "in-place"],
+                    help="synchronous: every row of a round reads the round-start labels; in-place: rows are "
+                         "replaced at once (Alg. 2's parallel loop taken literally)")
     ap.add_argument("--host-inputs", action="store_true",
                     help="hand the library host arrays (PCIe-inclusive timing; not the headline number)")
     args = ap.parse_args()
@@ -192,6 +195,8 @@ def main():
                 base["C"], dv(base["seed_vertex"], torch.int32), dv(base["seed_class"], torch.int32),
                 device_ptrs=not args.host_inputs, reserve_vertices=tot_v + 1024, reserve_edges=2 * tot_e + 1024, time_kernels=not args.no_kernel_timing,
                 group_lanes=args.group_lanes)
+    if args.update_mode == "in-place":
+        d.set_update_mode(P.UPDATE_IN_PLACE)
     st, s0 = d.static_solve(tol, cfg["max_iter"])
     cold = dict(status=st, sweeps=s0.iterations, ms=s0.ms_total, ms_update_kernel=s0.ms_update_kernel,
                 algorithmic_gbs=algorithmic_bytes(s0.rows_updated, s0.edges_traversed, base["C"]) / 1e6 /
@@ -277,7 +282,7 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic" + (" (host-resident inputs: PCIe-inclusive)" if args.host_inputs else ""),
-        "config": {"workload": label, "tol": tol, "edges_per_batch": edges_inserted // max(1, len(per_step)),
+        "config": {"workload": label, "tol": tol, "update_mode": args.update_mode, "edges_per_batch": edges_inserted // max(1, len(per_step)),
                    "vertices_after": d.num_vertices, "directed_entries_after": d.num_entries},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
@@ -298,7 +303,8 @@ def main():
                    "row_update_all_kernels_algorithmic_GBs": round(all_bytes / 1e6 / max(all_ms, 1e-9), 1),
                    "round_profile_first_step": round_profile,
                    "cold_start": cold, "gen_s": round(t_gen, 1),
-                   "init": {"mode": args.init, "tau": tau, "per_step": init_info}},
+                   "init": {"mode": args.init, "tau": tau, "per_step": init_info},
+                   "update_mode": args.update_mode},
     }
     if args.cpu_budget > 0 and per_step:
         out["cpu_baseline"] = cpu_baseline(base, batches[:args.warmup], batches[args.warmup], F_before, tol,

@@ -123,6 +123,21 @@ dynlp_status dynlp_static_solve(dynlp_ctx* ctx, float tol, int32_t max_iter, dyn
 dynlp_status dynlp_set_params(dynlp_ctx* ctx, float tol, int32_t max_iter);
 
 /*
+ * How the rows of one propagation round see each other (Eq. (1) is written with iteration indices,
+ * Alg. 2 Step 3 updates F_u inside a parallel loop over V_aff).
+ *   DYNLP_UPDATE_SYNCHRONOUS  (default) every row of a round is computed from the labels the round
+ *       started with (Jacobi); for a given edge order results are reproducible round by round.
+ *   DYNLP_UPDATE_IN_PLACE     a new row replaces the old one at once and later rows of the same round
+ *       may already read it, as in the parallel loop of Alg. 2 executed literally.  Same fixed point
+ *       and same stop rule (a row leaves V_aff when it moves by <= tol), about 1.5x fewer rounds, no
+ *       second label buffer traffic; which mix of old and new neighbour rows a row reads depends on
+ *       scheduling, so two runs agree only within the convergence tolerance, not bit for bit.
+ * Applies to dynlp_static_solve and dynlp_apply_batch calls that follow.
+ */
+typedef enum dynlp_update_mode { DYNLP_UPDATE_SYNCHRONOUS = 0, DYNLP_UPDATE_IN_PLACE = 1 } dynlp_update_mode;
+dynlp_status dynlp_set_update_mode(dynlp_ctx* ctx, int32_t mode);
+
+/*
  * Starting rows of the vertices a batch inserts (Alg. 2 Step 1 "sparsification" and Step 2 "label
  * initialisation").  It changes where Step 3 starts, not the labels it converges to.
  *   DYNLP_INIT_UNIFORM    every inserted unlabelled row starts at 1/C (the paper's neutral 0.5).
@@ -216,8 +231,10 @@ typedef struct dynlp_round_info {
     float max_delta;       /* max_u max_c |F'_u - F_u| */
     float ms_update;       /* device time of the round's row-update launch (0 unless time_kernels) */
     float reserved;
-    int32_t staged;        /* 1: rows staged and committed after the kernel; 0: written straight into
-                              the second label buffer (static sweeps, ping-pong rounds) */
+    int32_t staged;        /* 1: the round marked the next V_aff in per-vertex flags from inside the update
+                              kernel (synchronous mode: rows staged by position and committed after the
+                              kernel); 0: rows written by vertex and the next V_aff pulled from a bitmap of
+                              moved rows (static sweeps, rounds over nearly all vertices) */
     int32_t group_lanes;   /* lanes per row the short-row kernel ran with */
 } dynlp_round_info;
 

@@ -6,5 +6,6 @@
 loading fails loudly if the library has not been built.
 """
 from .build import build, library_path  # noqa: F401
-from .binding import (DynLP, DynLPError, Stats, InitInfo, INIT_UNIFORM, INIT_SUPERNODE, load_library,  # noqa: F401
+from .binding import (DynLP, DynLPError, Stats, InitInfo, INIT_UNIFORM, INIT_SUPERNODE, UPDATE_SYNCHRONOUS, UPDATE_IN_PLACE,
+                      load_library,  # noqa: F401
                       STATUS)

@@ -50,6 +50,7 @@ class InitInfo(ct.Structure):
 
 
 INIT_UNIFORM, INIT_SUPERNODE = 0, 1
+UPDATE_SYNCHRONOUS, UPDATE_IN_PLACE = 0, 1
 
 _ALLOC_FN = ct.CFUNCTYPE(ct.c_void_p, ct.c_size_t, ct.c_void_p)
 _DEALLOC_FN = ct.CFUNCTYPE(None, ct.c_void_p, ct.c_void_p)
@@ -65,7 +66,7 @@ class Options(ct.Structure):
 EXPORTS = ["dynlp_default_options", "dynlp_create", "dynlp_static_solve", "dynlp_set_params", "dynlp_apply_batch",
            "dynlp_get_labels", "dynlp_num_vertices", "dynlp_num_entries", "dynlp_num_classes", "dynlp_export_graph",
            "dynlp_round_log", "dynlp_last_error", "dynlp_destroy", "dynlp_set_initialiser",
-           "dynlp_mean_edge_weight", "dynlp_last_components"]
+           "dynlp_mean_edge_weight", "dynlp_last_components", "dynlp_set_update_mode"]
 
 _lib = None
 
@@ -109,6 +110,8 @@ def load_library(path: str | None = None):
     L.dynlp_export_graph.restype = ct.c_int
     L.dynlp_round_log.argtypes = [p, i64, ct.POINTER(RoundInfo)]
     L.dynlp_round_log.restype = i64
+    L.dynlp_set_update_mode.argtypes = [p, i32]
+    L.dynlp_set_update_mode.restype = ct.c_int
     L.dynlp_set_initialiser.argtypes = [p, i32, f32]
     L.dynlp_set_initialiser.restype = ct.c_int
     L.dynlp_mean_edge_weight.argtypes = [p, ct.POINTER(ct.c_double)]
@@ -201,6 +204,10 @@ class DynLP:
 
     def set_params(self, tol, max_iter):
         self._check(self._L.dynlp_set_params(self._h, float(tol), int(max_iter)))
+
+    def set_update_mode(self, mode):
+        """dynlp_set_update_mode: UPDATE_SYNCHRONOUS or UPDATE_IN_PLACE."""
+        self._check(self._L.dynlp_set_update_mode(self._h, int(mode)))
 
     def set_initialiser(self, mode, tau=0.0):
         """dynlp_set_initialiser: INIT_UNIFORM or INIT_SUPERNODE with threshold tau."""

@@ -101,6 +101,7 @@ struct dynlp_ctx {
     unsigned int h_slot_start_long = 0;  // long rows among the updatable vertices of the running static solve
     BatchCtr* h_bc = nullptr;    // pinned
 
+    int update_mode = DYNLP_UPDATE_SYNCHRONOUS;
     // label initialisation of inserted vertices (dynlp_components.h)
     int init_mode = DYNLP_INIT_UNIFORM;
     float tau = 0.f;
@@ -361,6 +362,7 @@ struct UpdateArgs {
     RoundCtr* ctr_zero;
     int64_t rows_bound;  // upper bounds of the frontier size and of its long rows (they size the grid)
     int64_t long_bound;
+    int by_vertex = 0;  // flag-marking rounds only: write row u of F_out instead of staging by position
 };
 
 template <int CP, int G, bool STAGED>
@@ -372,7 +374,7 @@ void launch_update_inst(dynlp_ctx* c, const Frontier& f, const UpdateArgs& a) {
     unsigned int stop_bits;
     std::memcpy(&stop_bits, &a.tol, sizeof stop_bits);
     hipLaunchKernelGGL((k_row_update<CP, G, STAGED>), dim3(short_blocks + long_max), dim3(kBlock), 0, c->stream, a.prev,
-                       a.static_stop, stop_bits, long_max, f.front, f.back, c->meta, c->pool, a.F_in, a.F_out, c->flag, a.moved, a.tol,
+                       a.static_stop, stop_bits, long_max, f.front, f.back, c->meta, c->pool, a.F_in, a.F_out, a.by_vertex, c->flag, a.moved, a.tol,
                        a.ctr, a.ctr_zero);
 }
 
@@ -903,6 +905,16 @@ dynlp_status dynlp_set_params(dynlp_ctx* ctx, float tol, int32_t max_iter) {
     return DYNLP_OK;
 }
 
+dynlp_status dynlp_set_update_mode(dynlp_ctx* ctx, int32_t mode) {
+    if (!ctx) return DYNLP_ERR_INVALID_ARG;
+    if (mode != DYNLP_UPDATE_SYNCHRONOUS && mode != DYNLP_UPDATE_IN_PLACE) {
+        ctx->err = "mode must be DYNLP_UPDATE_SYNCHRONOUS or DYNLP_UPDATE_IN_PLACE";
+        return DYNLP_ERR_INVALID_ARG;
+    }
+    ctx->update_mode = mode;
+    return DYNLP_OK;
+}
+
 dynlp_status dynlp_set_initialiser(dynlp_ctx* ctx, int32_t mode, float tau) {
     if (!ctx) return DYNLP_ERR_INVALID_ARG;
     if (mode != DYNLP_INIT_UNIFORM && mode != DYNLP_INIT_SUPERNODE) {
@@ -992,7 +1004,8 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
         HIPCHK(c, hipSetDevice(c->device));
         c->log.clear();
         c->events_used = 0;
-        sync_partner(c);
+        const bool in_place = c->update_mode == DYNLP_UPDATE_IN_PLACE;
+        if (!in_place) sync_partner(c);
         zero_ring(c);
         const Frontier f = frontier_of(c, 0);
         RoundCtr* start = slot_of(c, -1);
@@ -1006,7 +1019,8 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
         int64_t edges = 0;
         const int G = choose_group(c, c->n > 0 ? (double)c->entries / (double)std::max<int64_t>(1, nq) : 1.0);
         const auto t_it = Clock::now();
-        float* const buf[2] = {c->F, c->F2};  // sweep t reads buf[t & 1], writes buf[(t + 1) & 1]
+        // synchronous: sweep t reads buf[t & 1], writes buf[(t + 1) & 1]; in place: every sweep reads and writes F
+        float* const buf[2] = {c->F, in_place ? c->F : c->F2};
         while (!converged && it < max_iter) {
             // a chain of sweeps; each checks on the device whether its predecessor already met the stop rule
             const int r = std::min<int>(kChain, max_iter - it);
@@ -1031,8 +1045,10 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
             }
         }
         // the labels of the last executed sweep
-        c->F = buf[it & 1];
-        c->F2 = buf[(it + 1) & 1];
+        if (!in_place) {
+            c->F = buf[it & 1];
+            c->F2 = buf[(it + 1) & 1];
+        }
         const float kernel_ms_total = c->time_kernels ? collect_kernel_ms(c) : 0.f;
         if (stats) {
             stats->iterations = it;
@@ -1191,13 +1207,14 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
         float last = 0.f;
         double avg_len = c->n > 0 ? (double)c->entries / (double)c->n : 1.0;
         bool pingpong = false;
+        const bool in_place = c->update_mode == DYNLP_UPDATE_IN_PLACE;
         while (known > 0 && it < c->max_iter) {
             const int G = choose_group(c, avg_len);
             // A stretch of ping-pong rounds starts when V_aff covers nearly every updatable vertex (one copy
             // of F makes the partner buffer agree on every row outside V_aff) and ends when V_aff has shrunk.
             // Both kinds of round are correct for any V_aff, so the choice is only made between chains.
             if (!pingpong && (double)known >= kDenseEnter * (double)universe.size()) {
-                sync_partner(c);
+                if (!in_place) sync_partner(c);
                 for (unsigned int* mv : c->moved)
                     HIPCHK(c, hipMemsetAsync(mv, 0, (size_t)c->moved_words * sizeof(unsigned int), c->stream));
                 pingpong = true;
@@ -1205,7 +1222,8 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
                 pingpong = false;
             }
             const int r = std::min<int>(kChain, c->max_iter - it);
-            float* const buf[2] = {c->F, c->F2};  // ping-pong: round it+i reads buf[i & 1], writes buf[(i + 1) & 1]
+            // ping-pong: round it+i reads buf[i & 1], writes buf[(i + 1) & 1]; in place: always F
+            float* const buf[2] = {c->F, in_place ? c->F : c->F2};
             for (int i = 0; i < r; ++i) {
                 const int t = it + i;
                 RoundCtr* slot = slot_of(c, t);
@@ -1219,15 +1237,17 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
                     const UpdateArgs a{slot_of(c, t - 1), 0, buf[i & 1], buf[(i + 1) & 1], mv, c->tol,
                                        slot, slot_of(c, t + 1), (int64_t)universe.size(), (int64_t)universe.nl};
                     launch_update<false>(c, G, f, a);
-                    launch_pull_frontier(c, universe, mv, mv_next, buf[(i + 1) & 1], buf[i & 1], frontier_of(c, cur ^ 1),
-                                         &slot->next_count, &slot->next_long);
+                    launch_pull_frontier(c, universe, mv, mv_next, buf[(i + 1) & 1], in_place ? nullptr : buf[i & 1],
+                                         frontier_of(c, cur ^ 1), &slot->next_count, &slot->next_long);
                 } else {
                     // rows are staged by frontier position and committed after the kernel; rows that moved mark
                     // themselves and their neighbours
-                    const UpdateArgs a{slot_of(c, t - 1), 0, c->F, c->F2, nullptr, c->tol,
-                                       slot, slot_of(c, t + 1), (int64_t)universe.size(), (int64_t)universe.nl};
+                    // (in-place mode: written straight into F, nothing to commit)
+                    const UpdateArgs a{slot_of(c, t - 1), 0, c->F, in_place ? c->F : c->F2, nullptr, c->tol,
+                                       slot, slot_of(c, t + 1), (int64_t)universe.size(), (int64_t)universe.nl,
+                                       in_place ? 1 : 0};
                     launch_update<true>(c, G, f, a);
-                    launch_commit(c, f, slot_of(c, t - 1), (int64_t)universe.size());
+                    if (!in_place) launch_commit(c, f, slot_of(c, t - 1), (int64_t)universe.size());
                     launch_compact(c, frontier_of(c, cur ^ 1), &slot->next_count, &slot->next_long, 0);
                 }
                 cur ^= 1;
@@ -1247,7 +1267,7 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
                 known = rc.next_count + rc.next_long;
                 peak = std::max<int64_t>(peak, known);
             }
-            if (pingpong && (executed & 1)) std::swap(c->F, c->F2);  // the output of the last executed round
+            if (pingpong && !in_place && (executed & 1)) std::swap(c->F, c->F2);  // the output of the last executed round
             it += executed;
             if (executed < r) known = 0;  // a round found V_aff empty
         }

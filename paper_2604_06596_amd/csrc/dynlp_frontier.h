@@ -185,7 +185,7 @@ __global__ void __launch_bounds__(kBlock) k_pull_frontier(unsigned int ns, unsig
                                 break;
                             }
                         }
-                        if (!keep) {
+                        if (!keep && F_old) {
                             for (int k = lane; k < CP; k += kWave) {
                                 const float a = F_new[(size_t)u * CP + k];
                                 if (a != F_old[(size_t)u * CP + k]) F_old[(size_t)u * CP + k] = a;
@@ -252,7 +252,7 @@ __global__ void __launch_bounds__(kBlock) k_pull_frontier(unsigned int ns, unsig
                 }
                 if (keep) {
                     keepmask |= 1u << sub;
-                } else {
+                } else if (F_old) {
                     for (int k = 0; k < CP; ++k) {
                         const float a = F_new[(size_t)u * CP + k];
                         if (a != F_old[(size_t)u * CP + k]) F_old[(size_t)u * CP + k] = a;
@@ -307,7 +307,7 @@ struct RowShape {
 // last chunk this group loaded (or the stand-in if it loaded none).
 template <int CP, int G>
 __device__ inline void accumulate_row(const Edge* __restrict__ row, int len, int first_chunk, int chunk_step,
-                                      int32_t u, const float* __restrict__ F_in, int gl,
+                                      int32_t u, const float* F_in, int gl,
                                       Vec<RowShape<CP>::VEC>& acc, float& s, Edge& e) {
     constexpr int VEC = RowShape<CP>::VEC;
     constexpr int LPN = RowShape<CP>::LPN;
@@ -389,12 +389,17 @@ __device__ inline void flush_round_counters(float rmax, unsigned long long edges
 //            (if not NULL; see k_pull_frontier).
 //   STAGED = true (partial round): F'_u is staged at row pos of F_out so that every row of this
 //            round reads the round-start F (Jacobi); a row that moved by > tol marks itself and
-//            its neighbours in flag[] for the next round.
+//            its neighbours in flag[] for the next round.  With by_vertex != 0 the row is written
+//            to row u of F_out instead (in-place rounds, F_out == F_in: nothing to commit).
+// F_in and F_out may be the same array (in-place mode): a row then reads whatever its neighbours
+// hold at that moment.  Reads and writes are whole 16-byte segments, columns are independent linear
+// systems, and the update is a contraction per column, so mixed old/new reads only change the path
+// to the fixed point, not the fixed point.
 template <int CP, int G, bool STAGED>
 __device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, const int32_t* __restrict__ front,
                                         unsigned int ns, const RowMeta* __restrict__ meta,
-                                        const Edge* __restrict__ pool, const float* __restrict__ F_in,
-                                        float* __restrict__ F_out, uint8_t* __restrict__ flag,
+                                        const Edge* __restrict__ pool, const float* F_in,
+                                        float* F_out, int by_vertex, uint8_t* __restrict__ flag,
                                         unsigned int* __restrict__ moved, float tol,
                                         RoundCtr* __restrict__ ctr) {
     constexpr int VEC = RowShape<CP>::VEC;
@@ -429,7 +434,7 @@ __device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, 
         }
 #pragma unroll
         for (int d = 1; d < LPN; d <<= 1) r = fmaxf(r, __shfl_xor(r, d, G));
-        if (slot == 0) store_vec<VEC>(F_out + (size_t)(STAGED ? g : (unsigned int)u) * CP + chunk * VEC, fn);
+        if (slot == 0) store_vec<VEC>(F_out + (size_t)(STAGED && !by_vertex ? g : (unsigned int)u) * CP + chunk * VEC, fn);
         const bool big = r > tol;
         if (STAGED) {
             if (big) {  // V_aff <- V_aff U {u} U N(u); the last chunk of the row is still in registers
@@ -456,8 +461,8 @@ __device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, 
 template <int CP, bool STAGED>
 __device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, const int32_t* __restrict__ back,
                                        unsigned int nl, unsigned int pos_base, const RowMeta* __restrict__ meta,
-                                       const Edge* __restrict__ pool, const float* __restrict__ F_in,
-                                       float* __restrict__ F_out, uint8_t* __restrict__ flag,
+                                       const Edge* __restrict__ pool, const float* F_in,
+                                       float* F_out, int by_vertex, uint8_t* __restrict__ flag,
                                        unsigned int* __restrict__ moved, float tol,
                                        RoundCtr* __restrict__ ctr) {
     constexpr int VEC = RowShape<CP>::VEC;
@@ -513,7 +518,7 @@ __device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, c
             }
 #pragma unroll
             for (int d = 1; d < LPN; d <<= 1) r = fmaxf(r, __shfl_xor(r, d, G));
-            store_vec<VEC>(F_out + (size_t)(STAGED ? pos_base + j : (unsigned int)u) * CP + chunk * VEC, fn);
+            store_vec<VEC>(F_out + (size_t)(STAGED && !by_vertex ? pos_base + j : (unsigned int)u) * CP + chunk * VEC, fn);
             if (gl == 0) {
                 const bool big = r > tol;
                 sh_big = big ? 1 : 0;
@@ -546,7 +551,7 @@ __global__ void __launch_bounds__(kBlock) k_row_update(const RoundCtr* __restric
                                                       const int32_t* __restrict__ back,
                                                       const RowMeta* __restrict__ meta,
                                                       const Edge* __restrict__ pool,
-                                                      const float* __restrict__ F_in, float* __restrict__ F_out,
+                                                      const float* F_in, float* F_out, int by_vertex,
                                                       uint8_t* __restrict__ flag, unsigned int* __restrict__ moved,
                                                       float tol,
                                                       RoundCtr* __restrict__ ctr,
@@ -585,11 +590,11 @@ __global__ void __launch_bounds__(kBlock) k_row_update(const RoundCtr* __restric
     }
     const unsigned int long_blocks = nl < long_blocks_max ? nl : long_blocks_max;
     if (blockIdx.x < long_blocks)
-        row_update_long<CP, STAGED>(blockIdx.x, long_blocks, back, nl, ns, meta, pool, F_in, F_out, flag, moved,
+        row_update_long<CP, STAGED>(blockIdx.x, long_blocks, back, nl, ns, meta, pool, F_in, F_out, by_vertex, flag, moved,
                                     tol, ctr);
     else
         row_update_short<CP, G, STAGED>(blockIdx.x - long_blocks, gridDim.x - long_blocks, front, ns, meta, pool, F_in,
-                                        F_out, flag, moved, tol, ctr);
+                                        F_out, by_vertex, flag, moved, tol, ctr);
 }
 
 }  // namespace dynlp

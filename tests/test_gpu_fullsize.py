@@ -31,7 +31,11 @@ def _dv(a, dt):
     return torch.from_numpy(np.ascontiguousarray(a)).to(dt).cuda()
 
 
-def _run(name, make_batch, tol):
+MODES = [P.UPDATE_SYNCHRONOUS, P.UPDATE_IN_PLACE]
+MODE_IDS = ["synchronous", "in_place"]
+
+
+def _run(name, make_batch, tol, mode=P.UPDATE_SYNCHRONOUS):
     p = W.make_config(name, SCALE)
     n0, C = p.n, p.C
     base = (p.row_ptr, p.col, p.w, p.seed_vertex.copy(), p.seed_class.copy())
@@ -40,6 +44,7 @@ def _run(name, make_batch, tol):
                 _dv(base[3], torch.int32), _dv(base[4], torch.int32), device_ptrs=True,
                 reserve_vertices=b.num_new_vertices + 1024, reserve_edges=2 * b.num_edges + 1024)
     try:
+        d.set_update_mode(mode)
         st, s0 = d.static_solve(tol, W.CONFIGS[name]["max_iter"])
         assert st == 0
         soft0 = d.get_labels(soft=True, hard=False)[0].cpu().numpy()
@@ -117,26 +122,30 @@ def test_cfg3_full_size_first_rounds_match_the_oracle():
     assert s.edges_traversed == o2["edges_traversed"]
 
 
-def test_cfg3_full_size_batch_properties():
+@pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
+def test_cfg3_full_size_batch_properties(mode):
     cfg = W.CONFIGS["cfg3"]
     _run("cfg3", lambda p: W.sbm_vertex_batch(p, max(1, int(0.01 * p.n)), cfg["batch_degree"], cfg["seed_frac"]),
-         cfg["tol"])
+         cfg["tol"], mode)
 
 
-def test_cfg5_full_size_edge_stream_properties():
+@pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
+def test_cfg5_full_size_edge_stream_properties(mode):
     cfg = W.CONFIGS["cfg5"]
     _run("cfg5", lambda p: W.sbm_edge_batch(p, int(cfg["edges_per_batch"] * SCALE) or 1, cfg["intra_frac"],
                                             int(cfg["revealed_per_batch"] * SCALE) or 1),
-         cfg["tol"])
+         cfg["tol"], mode)
 
 
-def test_cfg4_full_size_batch_properties():
+@pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
+def test_cfg4_full_size_batch_properties(mode):
     cfg = W.CONFIGS["cfg4"]
     _run("cfg4", lambda p: W.chung_lu_vertex_batch(p, max(1, int(0.01 * p.n)), cfg["seed_frac"]),
-         cfg["tol"])
+         cfg["tol"], mode)
 
 
-def test_cfg2_ten_successive_batches_stay_close_to_exact_labels():
+@pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
+def test_cfg2_ten_successive_batches_stay_close_to_exact_labels(mode):
     """The medium kNN configuration end to end: ten batches, then the exact labels of the final graph."""
     p = W.make_config("cfg2", min(1.0, SCALE))
     n0, C = p.n, p.C
@@ -146,6 +155,7 @@ def test_cfg2_ten_successive_batches_stay_close_to_exact_labels():
     d = P.DynLP(n0, _dv(rp, torch.int64), _dv(col, torch.int32), _dv(w, torch.float32), C,
                 _dv(p.seed_vertex, torch.int32), _dv(p.seed_class, torch.int32), device_ptrs=True)
     try:
+        d.set_update_mode(mode)
         st, _ = d.static_solve(1e-6, 20000)
         assert st == 0
         n = n0

@@ -1,0 +1,132 @@
+"""GPU parity of the in-place update mode (rows of a round may already read rows the same round
+wrote, as in the parallel loop of Alg. 2).  Which neighbour values a row sees depends on
+scheduling, so there is no round-by-round comparison; what is fixed is
+* the graph, the affected set after Step 1 and the first frontier size (same code as the
+  synchronous mode; bit-exact),
+* the converged labels: within 1e-4 of the exact harmonic labels (oracle O1) at tol = 1e-6, the same
+  bar as the synchronous mode, and within max(2e-5, 2*tol*n/|seeds|) of the oracle's Step-3 loop,
+* hard labels wherever the exact top-2 margin is clear; seeds one-hot; rows are distributions,
+* a round count in the same window as the synchronous mode's (the gain in rounds only shows on
+  graphs much larger than what is resident on the chip at once; the full-size tests print it).
+"""
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import native as ON
+from oracle import reference as R
+import paper_2604_06596_amd as P
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-6
+O1_ATOL = 1e-4
+
+
+def _make(p, **kw):
+    d = P.DynLP(p.n, p.row_ptr, p.col, p.w, p.C, p.seed_vertex, p.seed_class, **kw)
+    d.set_update_mode(P.UPDATE_IN_PLACE)
+    return d
+
+
+def _o2_atol(g, tol):
+    return max(2e-5, 2.0 * tol * g.n / max(1, int((g.seed_class >= 0).sum())))
+
+
+def _check_labels(soft, hard, g, rp, col, w):
+    exact, _, _ = ON.itlp_solve(rp, col, w, g.seed_class, g.C, tol=1e-12, max_iter=5_000_000)
+    reach = R.seed_reachable(rp, col, g.seed_class)
+    err = float(np.max(np.abs(soft - exact)[reach]))
+    assert err <= O1_ATOL
+    clear = reach & (R.top2_margin(exact) > 2 * O1_ATOL)
+    assert np.array_equal(hard[clear], R.hard_labels(exact)[clear])
+    s_idx = np.flatnonzero(g.seed_class >= 0)
+    assert np.array_equal(soft[s_idx], R.initial_labels(g.seed_class, g.C)[s_idx].astype(np.float32))
+    assert soft.min() >= 0 and np.max(np.abs(soft.sum(1) - 1)) < 1e-5
+    return err
+
+
+@pytest.mark.parametrize("kind,C", [("cfg1", 4), ("random", 2), ("random", 10), ("random", 50), ("sbm", 10), ("hub", 3)])
+def test_static_solve_in_place_reaches_the_exact_labels(kind, C):
+    if kind == "cfg1":
+        p = W.make_config("cfg1")
+    elif kind == "random":
+        p = W.small_random(6000, C, 8.0, 300, 40 + C)
+    elif kind == "sbm":
+        p = W.sbm(30000, C, 20.0, 8.0, 0.01, 778)
+    else:
+        p = W.chung_lu(20000, C, 12.0, 2.1, 3000, 0.8, 0.02, 99)
+    g = R.Graph(p.n, p.row_ptr, p.col, p.w, p.C, p.seed_vertex, p.seed_class)
+    rp, col, w = g.csr()
+    with _make(p) as d:
+        st, s = d.static_solve(TOL, 20000)
+        assert st == 0 and s.converged == 1 and s.final_max_delta <= TOL
+        soft, hard = d.get_labels()
+        d.set_update_mode(P.UPDATE_SYNCHRONOUS)
+        st2, s2 = d.static_solve(TOL, 20000)  # already converged: the synchronous stop rule is met after a short tail
+        assert st2 == 0 and s2.iterations <= max(5, s.iterations // 5)
+    _, it_jacobi, _ = ON.itlp_solve(rp, col, w, g.seed_class, g.C, tol=TOL, max_iter=100000)
+    err = _check_labels(soft, hard, g, rp, col, w)
+    print(f"{kind} C={C}: in-place sweeps {s.iterations}, synchronous (oracle) {it_jacobi}, err vs exact {err:.2e}")
+    # graphs this small are resident on the chip all at once, so the sweeps behave like Jacobi sweeps
+    assert s.iterations <= 1.1 * it_jacobi + 5
+
+
+def _batches(kind, C):
+    if kind == "random":
+        p, p0 = W.small_random(5000, C, 9.0, 250, 950 + C), W.small_random(5000, C, 9.0, 250, 950 + C)
+        bs = [W.small_random_batch(p, 250, 7, 5, num_extra_edges=60, num_revealed=3),
+              W.small_random_batch(p, 40, 5, 1, num_extra_edges=30)]
+    elif kind == "sbm":
+        p, p0 = W.sbm(30000, C, 20.0, 8.0, 0.01, 779), W.sbm(30000, C, 20.0, 8.0, 0.01, 779)
+        bs = [W.sbm_vertex_batch(p, 300, 20, 0.01), W.sbm_edge_batch(p, 500, 0.5, 10)]
+    elif kind == "hub":
+        p, p0 = (W.chung_lu(20000, C, 12.0, 2.1, 3000, 0.8, 0.02, 98) for _ in range(2))
+        bs = [W.chung_lu_vertex_batch(p, 200, 0.02)]
+    else:
+        p, p0 = W.make_config("cfg1"), W.make_config("cfg1")
+        bs = [W.knn_mixture_batch(p, 100, 5)]
+    return p0, bs
+
+
+@pytest.mark.parametrize("kind,C", [("cfg1", 4), ("random", 2), ("random", 10), ("random", 50), ("sbm", 10), ("hub", 3)])
+def test_batch_updates_in_place_match_the_oracle_at_convergence(kind, C):
+    p0, batches = _batches(kind, C)
+    g = R.Graph(p0.n, p0.row_ptr, p0.col, p0.w, p0.C, p0.seed_vertex, p0.seed_class)
+    with _make(p0) as d:
+        assert d.static_solve(TOL, 20000)[0] == 0
+        soft, _ = d.get_labels()
+        for b in batches:
+            F_before = soft.astype(np.float64)
+            n_old = g.n
+            st, s = d.apply_batch(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+            assert st == 0 and s.converged == 1
+            soft, hard = d.get_labels()
+            sizes, deltas = d.round_log()
+            g.insert(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+            rp, col, w = g.csr()
+            A0 = ON.affected_set(rp, col, g.seed_class, n_old, b.eu, b.ev, b.seed_vertex)
+            assert s.frontier_initial == len(A0) == sizes[0]
+            F = np.concatenate([F_before, np.full((b.num_new_vertices, g.C), 1.0 / g.C)])
+            F[b.seed_vertex] = np.eye(g.C)[b.seed_class]
+            o2 = ON.step3_propagate(rp, col, w, F, g.seed_class, A0, TOL, 20000)
+            err = _check_labels(soft, hard, g, rp, col, w)
+            e2 = float(np.max(np.abs(soft - o2["F"])))
+            print(f"{kind} C={C}: rounds {s.iterations} (synchronous oracle {o2['rounds']}), err vs exact {err:.2e}, "
+                  f"vs oracle Step 3 {e2:.2e}")
+            assert e2 <= _o2_atol(g, TOL)
+            # once the per-round change of the slowest mode sits near tol, which rows stay in V_aff is decided
+            # by rounding-level differences, so the tail length is only checked for sanity
+            assert 0.3 * o2["rounds"] - 5 <= s.iterations <= 3 * o2["rounds"] + 10
+            assert s.rows_updated == int(sizes.sum()) and len(sizes) == s.iterations
+            erp, ecol, ew_, _, esc = d.export_graph()
+            assert erp.tolist() == rp.tolist() and esc.tolist() == g.seed_class.tolist()
+
+
+def test_mode_switch_is_validated_and_max_iter_still_cuts():
+    p = W.small_random(3000, 3, 6.0, 60, 5)
+    with _make(p) as d:
+        with pytest.raises(P.DynLPError):
+            d.set_update_mode(2)
+        st, s = d.static_solve(1e-7, 3)
+        assert st == 1 and s.iterations == 3 and s.converged == 0
