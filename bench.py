@@ -186,6 +186,14 @@ def main():
             return np.ascontiguousarray(a)
         return torch.from_numpy(np.ascontiguousarray(a)).to(dt).to(dev)
 
+    # One plain device-to-device copy of known size (256 MiB), outside the timed region: under
+    # rocprofv3 --pmc it is the yardstick that turns FETCH_SIZE / WRITE_SIZE readings into bytes.
+    cal_src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
     d_batches = [dict(k=b.num_new_vertices, eu=dv(b.eu, torch.int32), ev=dv(b.ev, torch.int32),
                       ew=dv(b.ew, torch.float32), sv=dv(b.seed_vertex, torch.int32), sc=dv(b.seed_class, torch.int32))
                  for b in batches]
