@@ -89,8 +89,11 @@ def itlp_solve(row_ptr, col, w, seed_class, C, tol=1e-10, max_iter=1_000_000, F0
     return F, int(it), float(last.value)
 
 
-def affected_set(row_ptr, col, seed_class, n_old, eu, ev, new_seed_vertex):
-    """V_aff of an insertion batch on the already-updated CSR; ascending int32 ids."""
+def affected_set(row_ptr, col, seed_class, n_old, eu, ev, new_seed_vertex, deleted_neighbours=None):
+    """V_aff of a batch on the already-updated CSR; ascending int32 ids.  ``deleted_neighbours``:
+    the vertices that were adjacent to a deleted vertex before the batch (Alg. 2 adds N(u) for
+    every deleted u); they join the set under the same rule as everyone else (unlabelled and not
+    isolated in the updated graph)."""
     rp = np.ascontiguousarray(row_ptr, dtype=np.int64)
     cl = np.ascontiguousarray(col, dtype=np.int32)
     sc = np.ascontiguousarray(seed_class, dtype=np.int32)
@@ -102,7 +105,12 @@ def affected_set(row_ptr, col, seed_class, n_old, eu, ev, new_seed_vertex):
     out = np.empty(max(n, 1), dtype=np.int32)
     cnt = lib().oracle_affected_set(n, _ptr(rp), _ptr(cl), _ptr(sc), int(n_old), eu.shape[0], _ptr(eu), _ptr(ev),
                                     sv.shape[0], _ptr(sv), _ptr(flag), _ptr(out))
-    return out[:cnt].copy()
+    A = out[:cnt].copy()
+    if deleted_neighbours is not None and len(deleted_neighbours):
+        extra = np.unique(np.asarray(deleted_neighbours, dtype=np.int64))
+        ok = (sc[extra] < 0) & (np.diff(rp)[extra] > 0)
+        A = np.union1d(A, extra[ok].astype(np.int32)).astype(np.int32)
+    return A
 
 
 def step3_propagate(row_ptr, col, w, F, seed_class, V_aff, tol, max_iter, decide_fp32=True, record=4096):

@@ -12,6 +12,8 @@ Readings taken where the paper is silent or garbled (each also listed in the des
 * rows with d(u)=0 never change; parallel edges add their weights;
 * an inserted edge affects both endpoints; a vertex that becomes a seed affects its
   neighbours and is itself clamped to one-hot and never updated again;
+* a deleted vertex keeps its id as an isolated, unlabelled vertex with the neutral row 1/C; a
+  neighbour that loses its last edge keeps the label it had;
 * Step 2 for C classes: a supernode's row is its weight share per labelled class, uniform when
   it has no labelled neighbour; the threshold tau acts on each listed batch edge separately.
 """
@@ -51,6 +53,16 @@ class Graph:
         self.w = np.concatenate([self.w, ew, ew])
         self.seed_class = np.concatenate([self.seed_class, np.full(int(num_new_vertices), -1, dtype=np.int64)])
         self.seed_class[np.asarray(seed_vertex, dtype=np.int64)] = np.asarray(seed_class, dtype=np.int64)
+
+    def delete(self, vertices):
+        """Alg. 2 Step 1 for Delta^Del: every edge incident to a deleted vertex disappears.  Ids are
+        not renumbered: a deleted vertex stays behind as an isolated, unlabelled vertex (it is
+        never updated again and can be given edges by a later batch)."""
+        dead = np.zeros(self.n, dtype=bool)
+        dead[np.asarray(vertices, dtype=np.int64)] = True
+        keep = ~(dead[self.src] | dead[self.dst])
+        self.src, self.dst, self.w = self.src[keep], self.dst[keep], self.w[keep]
+        self.seed_class[dead] = -1
 
     def csr(self):
         """(row_ptr int64, col int64, w float64), rows in insertion order."""
@@ -165,12 +177,17 @@ def recompute_from_scratch(graph: Graph, tol=1e-10, max_iter=1_000_000):
 # --------------------------------------------------------------------------------------
 # Alg. 2: affected set and Step 3 (frontier-restricted propagation)
 # --------------------------------------------------------------------------------------
-def affected_set(adj_after, seed_class_after, num_old_vertices, num_new_vertices, eu, ev, new_seed_vertex):
-    """V_aff after Step 1 for an insertion batch: each inserted vertex and its neighbours
-    (Alg. 2: V_aff <- V_aff U {u} U N(u)); for edges between existing vertices, both
-    endpoints; for a vertex that became a seed, its neighbours.  Seeds and isolated vertices
-    are never in the set (they are never updated).  ``adj_after`` is the updated graph."""
+def affected_set(adj_after, seed_class_after, num_old_vertices, num_new_vertices, eu, ev, new_seed_vertex,
+                 deleted=(), adj_before=None):
+    """V_aff after Step 1: for each deleted vertex its neighbours in the graph before the batch
+    (Alg. 2: V_aff <- V_aff U N(u) for u in Delta^Del; needs ``adj_before``); each inserted
+    vertex and its neighbours (V_aff <- V_aff U {u} U N(u)); for edges between existing
+    vertices, both endpoints; for a vertex that became a seed, its neighbours.  Seeds and
+    isolated vertices are never in the set (they are never updated).  ``adj_after`` is the
+    updated graph."""
     A = set()
+    for u in np.asarray(deleted, dtype=np.int64).tolist():
+        A.update(adj_before[u].keys())
     for u in range(num_old_vertices, num_old_vertices + num_new_vertices):
         A.add(u)
         A.update(adj_after[u].keys())
