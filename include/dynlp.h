@@ -201,6 +201,26 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* ctx, int64_t num_new_vertices, int64_t
                                const int32_t* seed_vertex, const int32_t* seed_class, dynlp_stats* stats);
 
 /*
+ * DynLP update for one batch with deletions and insertions (Alg. 2 Steps 1 and 3 in full; Delta_t =
+ * {Delta^Ins, Delta^Del}).  dynlp_apply_batch is this call with num_deleted = 0; the insertion
+ * arguments, Step 3, the statuses and the stats are the same.
+ *   deleted_vertex   num_deleted ids of existing vertices (in [0, n) as of before the call; an id
+ *                    listed twice is deleted once)
+ * Deletions are applied first: every neighbour of a deleted vertex joins V_aff (V_aff <- V_aff U
+ * N(u)); all edges of the deleted vertex are removed from both sides (the order of the remaining
+ * entries of a row is kept).  Ids are never renumbered: the deleted vertex stays behind as an
+ * isolated, unlabelled vertex whose row is 1/C (a deleted seed stops being a seed); it is never
+ * updated, and the insertion part of this or a later batch may give it edges again.  A vertex that
+ * loses its last edge keeps the label it has.  The pool space of removed entries is not reclaimed.
+ * Seed arguments are validated against the state before the call.
+ * DYNLP_ERR_INVALID_ARG (context unchanged) additionally on: deleted vertex out of range.
+ */
+dynlp_status dynlp_apply_update(dynlp_ctx* ctx, int64_t num_deleted, const int32_t* deleted_vertex,
+                                int64_t num_new_vertices, int64_t num_new_edges, const int32_t* eu,
+                                const int32_t* ev, const float* ew, int64_t num_new_seeds,
+                                const int32_t* seed_vertex, const int32_t* seed_class, dynlp_stats* stats);
+
+/*
  * Current labels.  soft: n*C floats row-major (no padding), or NULL.  hard: n int32 =
  * argmax_c F[u][c] with the lowest class index winning ties (for C=2 the paper's 0.5 cut-off), or
  * NULL.  Seed rows are exactly one-hot.

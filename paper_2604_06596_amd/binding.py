@@ -66,7 +66,7 @@ class Options(ct.Structure):
 EXPORTS = ["dynlp_default_options", "dynlp_create", "dynlp_static_solve", "dynlp_set_params", "dynlp_apply_batch",
            "dynlp_get_labels", "dynlp_num_vertices", "dynlp_num_entries", "dynlp_num_classes", "dynlp_export_graph",
            "dynlp_round_log", "dynlp_last_error", "dynlp_destroy", "dynlp_set_initialiser",
-           "dynlp_mean_edge_weight", "dynlp_last_components", "dynlp_set_update_mode"]
+           "dynlp_mean_edge_weight", "dynlp_last_components", "dynlp_set_update_mode", "dynlp_apply_update"]
 
 _lib = None
 
@@ -99,6 +99,8 @@ def load_library(path: str | None = None):
     L.dynlp_set_params.restype = ct.c_int
     L.dynlp_apply_batch.argtypes = [p, i64, i64, p, p, p, i64, p, p, ct.POINTER(Stats)]
     L.dynlp_apply_batch.restype = ct.c_int
+    L.dynlp_apply_update.argtypes = [p, i64, p, i64, i64, p, p, p, i64, p, p, ct.POINTER(Stats)]
+    L.dynlp_apply_update.restype = ct.c_int
     L.dynlp_get_labels.argtypes = [p, p, p]
     L.dynlp_get_labels.restype = ct.c_int
     for name in ("dynlp_num_vertices", "dynlp_num_entries"):
@@ -237,6 +239,20 @@ class DynLP:
         st = self._L.dynlp_apply_batch(self._h, int(num_new_vertices), m, self._in(eu, np.int32),
                                        self._in(ev, np.int32), self._in(ew, np.float32), ns,
                                        self._in(seed_vertex, np.int32), self._in(seed_class, np.int32), ct.byref(s))
+        self._keep.clear()
+        self._check(st, ok=(0, 1))
+        return st, s
+
+    def apply_update(self, deleted_vertex, num_new_vertices=0, eu=None, ev=None, ew=None, seed_vertex=None,
+                     seed_class=None):
+        """dynlp_apply_update (deletions, then insertions).  Returns (status, Stats)."""
+        s = Stats()
+        nd = 0 if deleted_vertex is None else int(len(deleted_vertex))
+        m = 0 if eu is None else int(len(eu))
+        ns = 0 if seed_vertex is None else int(len(seed_vertex))
+        st = self._L.dynlp_apply_update(self._h, nd, self._in(deleted_vertex, np.int32), int(num_new_vertices), m,
+                                        self._in(eu, np.int32), self._in(ev, np.int32), self._in(ew, np.float32), ns,
+                                        self._in(seed_vertex, np.int32), self._in(seed_class, np.int32), ct.byref(s))
         self._keep.clear()
         self._check(st, ok=(0, 1))
         return st, s

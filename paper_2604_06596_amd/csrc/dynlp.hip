@@ -47,6 +47,7 @@ const char* validation_message(int code) {
         case kErrSeedConflict: return "one vertex listed with two different classes (seed %lld)";
         case kErrEndpoint: return "edge endpoint out of range (edge %lld)";
         case kErrRelabel: return "vertex is already a seed of another class (seed %lld)";
+        case kErrDeleted: return "deleted vertex out of range (item %lld)";
         default: return "validation error %lld";
     }
 }
@@ -1075,6 +1076,12 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
 
 dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t* eu, const int32_t* ev,
                                const float* ew, int64_t s, const int32_t* sv, const int32_t* sc, dynlp_stats* stats) {
+    return dynlp_apply_update(c, 0, nullptr, k, m, eu, ev, ew, s, sv, sc, stats);
+}
+
+dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, int64_t k, int64_t m, const int32_t* eu,
+                                const int32_t* ev, const float* ew, int64_t s, const int32_t* sv, const int32_t* sc,
+                                dynlp_stats* stats) {
     if (!c) return DYNLP_ERR_INVALID_ARG;
     fill_stats_zero(stats);
     if (c->poisoned) {
@@ -1085,7 +1092,8 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
         c->err = msg;
         return DYNLP_ERR_INVALID_ARG;
     };
-    if (k < 0 || m < 0 || s < 0) return bad("counts must be >= 0");
+    if (k < 0 || m < 0 || s < 0 || nd < 0) return bad("counts must be >= 0");
+    if (nd > 0 && !del) return bad("deleted_vertex is NULL");
     if (m > 0 && (!eu || !ev || !ew)) return bad("edge arrays are NULL");
     if (s > 0 && (!sv || !sc)) return bad("seed arrays are NULL");
     const int64_t n0 = c->n, n1 = c->n + k;
@@ -1095,6 +1103,8 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
         std::string e;
         if (!host_check_edges(e, m, n1, eu, ev, ew)) return bad(e);
         if (!host_check_seeds(e, s, n1, c->C, sv, sc)) return bad(e);
+        for (int64_t i = 0; i < nd; ++i)
+            if (del[i] < 0 || del[i] >= n0) return bad(format_validation(kErrDeleted, i));
     }
     const auto t0 = Clock::now();
     bool mutated = false;
@@ -1124,6 +1134,50 @@ dynlp_status dynlp_apply_batch(dynlp_ctx* c, int64_t k, int64_t m, const int32_t
             d_sc = c->b_sc;
         }
         HIPCHK(c, hipEventRecord(c->phase_ev[0], c->stream));
+
+        // ---- deletions come first (Alg. 2 Step 1): the whole batch is validated before anything changes ----
+        if (nd > 0) {
+            DevIn<int32_t> d_del(c, del, nd);
+            if (c->n_cap > c->touched_cap) {  // any vertex may lose an entry
+                dev_free(c, c->touched);
+                dev_free(c, c->reloc_off);
+                c->touched = nullptr;
+                c->reloc_off = nullptr;
+                c->touched_cap = 0;
+                c->touched = dev_alloc_n<int32_t>(c, c->n_cap);
+                c->reloc_off = dev_alloc_n<int64_t>(c, c->n_cap);
+                c->touched_cap = c->n_cap;
+            }
+            std::memset(c->h_bc, 0, sizeof(BatchCtr));
+            c->h_bc->pool_tail = (unsigned long long)c->pool_tail;
+            HIPCHK(c, hipMemcpyAsync(c->bc, c->h_bc, sizeof(BatchCtr), hipMemcpyHostToDevice, c->stream));
+            hipLaunchKernelGGL(k_validate_deleted, dim3(grid_for(nd)), dim3(kBlock), 0, c->stream, nd, n0, d_del.ptr, c->bc);
+            if (m > 0)
+                hipLaunchKernelGGL(k_validate_edges, dim3(grid_for(m)), dim3(kBlock), 0, c->stream, m, n1, d_eu, d_ev, d_ew,
+                                   c->bc);
+            if (s > 0) {
+                hipLaunchKernelGGL(k_validate_seeds, dim3(grid_for(s)), dim3(kBlock), 0, c->stream, s, n1, n0, c->C, d_sv,
+                                   d_sc, c->seed_class, c->add_cnt, c->bc);
+                hipLaunchKernelGGL(k_clear_seed_tmp, dim3(grid_for(s)), dim3(kBlock), 0, c->stream, s, n1, d_sv, c->add_cnt);
+            }
+            HIPCHK(c, hipGetLastError());
+            read_bc(c);
+            if (c->h_bc->err_code) return bad(format_validation(c->h_bc->err_code, c->h_bc->err_index));
+            mutated = true;
+            hipLaunchKernelGGL(k_mark_deleted, dim3(grid_for(nd)), dim3(kBlock), 0, c->stream, nd, d_del.ptr, c->seed_class,
+                               kDeletedMark);
+            hipLaunchKernelGGL(k_delete_rows, dim3(grid_for(nd * 16)), dim3(kBlock), 0, c->stream, nd, d_del.ptr, c->C, c->CP,
+                               c->meta, c->pool, c->seed_class, c->flag, c->add_cnt, c->touched, c->deg, c->F, c->bc);
+            HIPCHK(c, hipGetLastError());
+            read_bc(c);
+            const unsigned int nt_del = c->h_bc->touched;
+            if (nt_del)
+                hipLaunchKernelGGL(k_drop_deleted_entries, dim3(grid_for((int64_t)nt_del * 16)), dim3(kBlock), 0, c->stream,
+                                   nt_del, c->touched, c->meta, c->pool, c->seed_class, c->add_cnt, c->deg);
+            hipLaunchKernelGGL(k_mark_deleted, dim3(grid_for(nd)), dim3(kBlock), 0, c->stream, nd, d_del.ptr, c->seed_class, -1);
+            HIPCHK(c, hipGetLastError());
+            c->entries -= (int64_t)c->h_bc->removed;
+        }
 
         // ---- validate, count entries per row, plan relocations: one read-back for all three ----
         std::memset(c->h_bc, 0, sizeof(BatchCtr));

@@ -56,6 +56,7 @@ struct __attribute__((aligned(64))) BatchCtr {
     unsigned long long scan_total;   // grand total of the last block-sum scan
     unsigned int upd_short;          // updatable vertices (unlabelled, >= 1 edge): short rows
     unsigned int upd_long;           //                                              long rows
+    unsigned long long removed;      // CSR entries removed by the deletion step
 };
 
 enum ValidationError : int {
@@ -69,6 +70,7 @@ enum ValidationError : int {
     kErrSeedConflict = 7,
     kErrEndpoint = 8,
     kErrRelabel = 9,
+    kErrDeleted = 10,
 };
 
 __device__ inline void report_error(BatchCtr* bc, int code, long long index) {

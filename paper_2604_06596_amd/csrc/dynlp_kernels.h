@@ -384,6 +384,119 @@ __global__ void __launch_bounds__(kBlock) k_clear_counts(unsigned int nt, const 
 }
 
 // =================================================================================================
+// Vertex deletion (Alg. 2 Step 1 for Delta^Del): V_aff <- V_aff U N(u), then u and its edges go
+// =================================================================================================
+constexpr int32_t kDeletedMark = -2;  // seed_class value of a vertex while its batch deletes it
+
+__global__ void __launch_bounds__(kBlock) k_validate_deleted(int64_t nd, int64_t n, const int32_t* __restrict__ del,
+                                                            BatchCtr* bc) {
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= nd) return;
+    const int32_t u = del[i];
+    if (u < 0 || u >= n) report_error(bc, kErrDeleted, i);
+}
+
+__global__ void __launch_bounds__(kBlock) k_mark_deleted(int64_t nd, const int32_t* __restrict__ del,
+                                                        int32_t* __restrict__ seed_class, int32_t value) {
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i < nd) seed_class[del[i]] = value;
+}
+
+// One 16-lane group per listed vertex.  The group that swaps the row length to 0 owns the row (a
+// vertex listed twice is handled once): every surviving neighbour v is put into V_aff (flag) and, on
+// first touch, into the list of rows that must drop their entries towards deleted vertices.  The
+// deleted row keeps its place and capacity in the pool (a later batch may give the id edges again);
+// its label row becomes the neutral 1/C.
+__global__ void __launch_bounds__(kBlock) k_delete_rows(int64_t nd, const int32_t* __restrict__ del, int C, int CP,
+                                                       RowMeta* meta, const Edge* __restrict__ pool,
+                                                       const int32_t* __restrict__ seed_class,
+                                                       uint8_t* __restrict__ flag, int32_t* __restrict__ add_cnt,
+                                                       int32_t* __restrict__ touched, float* __restrict__ deg,
+                                                       float* __restrict__ F, BatchCtr* bc) {
+    constexpr int G = 16;
+    const int64_t i = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / G;
+    const int gl = threadIdx.x % G;
+    int len = 0;
+    int32_t u = 0;
+    int64_t off = 0;
+    if (i < nd) {
+        u = del[i];
+        if (gl == 0) len = atomicExch(&meta[u].len, 0);
+        len = __shfl(len, 0, G);
+        off = meta[u].off;
+    }
+    // all 64 lanes of the wave walk together (wave_reserve needs every lane)
+    int maxlen = len;
+#pragma unroll
+    for (int d = G; d < kWave; d <<= 1) maxlen = max(maxlen, __shfl_xor(maxlen, d, kWave));
+    unsigned long long removed = 0;
+    for (int base = 0; base < maxlen; base += G) {
+        const int j = base + gl;
+        bool first = false;
+        int32_t v = -1;
+        if (j < len) {
+            v = pool[off + j].col;
+            removed += 1;
+            if (seed_class[v] != kDeletedMark) {
+                flag[v] = 1;
+                removed += 1;  // the entry v -> u goes as well
+                first = atomicAdd(&add_cnt[v], 1) == 0;
+            }
+        }
+        const unsigned int slot = wave_reserve(&bc->touched, first);
+        if (first) touched[slot] = v;
+    }
+    removed = wave_sum(removed);
+    if (lane_id() == 0 && removed) atomicAdd(&bc->removed, removed);
+    if (i < nd) {  // also for a vertex that had no edges, or is listed twice: the same values again
+        if (gl == 0) deg[u] = 0.f;
+        for (int c = gl; c < CP; c += G) F[(size_t)u * CP + c] = c < C ? 1.0f / (float)C : 0.f;
+    }
+}
+
+// Touched rows: drop the entries that point at deleted vertices, keeping the order of the others,
+// then recompute d(v) from the stored row (same summation order as k_finish_rows) and clear the
+// counting scratch.  16 lanes per row; a chunk is loaded completely before any of it is written
+// back, and the write position never passes the read position.
+__global__ void __launch_bounds__(kBlock) k_drop_deleted_entries(unsigned int nt, const int32_t* __restrict__ touched,
+                                                                RowMeta* __restrict__ meta, Edge* __restrict__ pool,
+                                                                const int32_t* __restrict__ seed_class,
+                                                                int32_t* __restrict__ add_cnt,
+                                                                float* __restrict__ deg) {
+    constexpr int G = 16;
+    const unsigned int t = (blockIdx.x * kBlock + threadIdx.x) / G;
+    const int gl = threadIdx.x % G;
+    const int gshift = (lane_id() / G) * G;
+    if (t >= nt) return;
+    const int32_t v = touched[t];
+    const RowMeta m = meta[v];
+    int out = 0;
+    for (int base = 0; base < m.len; base += G) {
+        const int j = base + gl;
+        Edge e;
+        e.col = 0;
+        e.w = 0.f;
+        bool keep = false;
+        if (j < m.len) {
+            e = pool[m.off + j];
+            keep = seed_class[e.col] != kDeletedMark;
+        }
+        const unsigned int mask = (unsigned int)((__ballot(keep) >> gshift) & 0xffffull);
+        if (keep) pool[m.off + out + __popc(mask & ((1u << gl) - 1u))] = e;
+        out += __popc(mask);
+    }
+    float s = 0.f;
+    for (int j = gl; j < out; j += G) s += pool[m.off + j].w;
+#pragma unroll
+    for (int d = G / 2; d > 0; d >>= 1) s += __shfl_xor(s, d, G);
+    if (gl == 0) {
+        meta[v].len = out;
+        deg[v] = s;
+        add_cnt[v] = 0;
+    }
+}
+
+// =================================================================================================
 // Export (inspection / tests)
 // =================================================================================================
 __global__ void __launch_bounds__(kBlock) k_row_lens(int64_t n, const RowMeta* __restrict__ meta,

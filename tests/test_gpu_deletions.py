@@ -1,0 +1,249 @@
+"""GPU parity of vertex deletions (Alg. 2 Step 1 for Delta^Del, then Step 3) against the CPU oracle,
+through dynlp_apply_update.  Bars as for insertion batches: graph bit-exact (row order included:
+the compaction is stable), first V_aff equal, first rounds within 5e-6 of the oracle's synchronous
+Step-3 loop with equal frontiers, converged labels within 1e-4 of the exact labels."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import native as ON
+from oracle import reference as R
+import paper_2604_06596_amd as P
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-6
+O1_ATOL = 1e-4
+ROUNDS_ATOL = 5e-6
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "deletion_cases.json")
+
+
+def _make(p, **kw):
+    return P.DynLP(p.n, p.row_ptr, p.col, p.w, p.C, p.seed_vertex, p.seed_class, **kw)
+
+
+def _graph_rows(rp, col, w):
+    return [list(zip(col[rp[u]:rp[u + 1]].tolist(), np.asarray(w[rp[u]:rp[u + 1]], dtype=np.float32).tolist()))
+            for u in range(len(rp) - 1)]
+
+
+def _check_graph(d, g, ordered=True):
+    rp, col, w, deg, sc = d.export_graph()
+    orp, ocol, ow = g.csr()
+    assert rp.tolist() == orp.tolist()
+    a, b = _graph_rows(rp, col, w), _graph_rows(orp, ocol, ow)
+    if not ordered:  # rows that received entries from a batch: order of that batch's entries is unspecified
+        a, b = [sorted(r) for r in a], [sorted(r) for r in b]
+    assert a == b
+    assert sc.tolist() == g.seed_class.tolist()
+    assert d.num_entries == int(orp[-1])
+    d64 = np.bincount(g.src, weights=g.w, minlength=g.n)
+    np.testing.assert_allclose(deg, d64, rtol=1e-5, atol=0)
+
+
+def _exact(g):
+    rp, col, w = g.csr()
+    exact, _, _ = ON.itlp_solve(rp, col, w, g.seed_class, g.C, tol=1e-12, max_iter=5_000_000)
+    return exact, R.seed_reachable(rp, col, g.seed_class)
+
+
+@pytest.mark.parametrize("case", json.load(open(GOLDEN))["cases"], ids=lambda c: c["name"])
+def test_hand_worked_deletions_on_the_gpu(case):
+    e = np.array(case["edges"], dtype=np.float64).reshape(-1, 3)
+    rp, col, w = W.edges_to_csr(case["n"], e[:, 0].astype(np.int64), e[:, 1].astype(np.int64), e[:, 2])
+    sv = np.array([s[0] for s in case["seeds"]], dtype=np.int32)
+    sc = np.array([s[1] for s in case["seeds"]], dtype=np.int32)
+    g = R.Graph(case["n"], rp, col, w, case["C"], sv, sc)
+    with P.DynLP(case["n"], rp, col, w.astype(np.float32), case["C"], sv, sc) as d:
+        assert d.static_solve(1e-7, 100000)[0] == 0
+        st, s = d.apply_update(np.array(case["delete"], dtype=np.int32))
+        assert st == 0 and s.frontier_initial == len(case["affected"])
+        soft, hard = d.get_labels()
+        g.delete(case["delete"])
+        _check_graph(d, g)
+    for u, row in case["expect"].items():
+        np.testing.assert_allclose(soft[int(u)], row, atol=2e-5)
+    for u in case["delete"]:
+        np.testing.assert_array_equal(soft[u], np.full(case["C"], np.float32(1.0) / np.float32(case["C"])))
+
+
+def _random_problem(kind, C, seed):
+    if kind == "random":
+        return W.small_random(5000, C, 9.0, 250, seed)
+    if kind == "sbm":
+        return W.sbm(30000, C, 20.0, 8.0, 0.01, seed)
+    return W.chung_lu(20000, C, 12.0, 2.1, 3000, 0.8, 0.02, seed)
+
+
+def _pick_deleted(p, rng, count):
+    deg = np.diff(p.row_ptr)
+    dead = rng.choice(p.n, size=count, replace=False)
+    dead[0] = p.seed_vertex[0]          # a seed
+    dead[1] = int(np.argmax(deg))       # the largest row
+    return np.unique(dead).astype(np.int32)
+
+
+@pytest.mark.parametrize("kind,C", [("random", 2), ("random", 10), ("random", 50), ("sbm", 10), ("hub", 3)])
+@pytest.mark.parametrize("R_", [1, 3, 25])
+def test_first_rounds_after_deletions_match_the_oracle(kind, C, R_):
+    p = _random_problem(kind, C, 2100 + C)
+    g = R.Graph(p.n, p.row_ptr, p.col, p.w, p.C, p.seed_vertex, p.seed_class)
+    dead = _pick_deleted(p, np.random.default_rng(C), 60)
+    with _make(p) as d:
+        assert d.static_solve(TOL, 20000)[0] == 0
+        soft0, _ = d.get_labels()
+        d.set_params(TOL, R_)
+        st, s = d.apply_update(dead)
+        soft, _ = d.get_labels()
+        sizes, deltas = d.round_log()
+        rp0, col0, _ = g.csr()
+        dn = np.concatenate([col0[rp0[u]:rp0[u + 1]] for u in dead])
+        g.delete(dead)
+        _check_graph(d, g)
+    rp, col, w = g.csr()
+    A0 = ON.affected_set(rp, col, g.seed_class, g.n, [], [], [], deleted_neighbours=dn)
+    F0 = soft0.astype(np.float64)
+    F0[dead] = 1.0 / C
+    o2 = ON.step3_propagate(rp, col, w, F0, g.seed_class, A0, TOL, R_)
+    assert s.frontier_initial == len(A0)
+    assert s.iterations == o2["rounds"] == R_
+    assert sizes.tolist() == o2["frontier_sizes"].tolist()
+    assert np.max(np.abs(soft - o2["F"])) <= ROUNDS_ATOL
+    np.testing.assert_allclose(deltas, o2["max_changes"], atol=1e-6)
+    assert s.edges_traversed == o2["edges_traversed"]
+
+
+@pytest.mark.parametrize("mode", [P.UPDATE_SYNCHRONOUS, P.UPDATE_IN_PLACE], ids=["synchronous", "in_place"])
+@pytest.mark.parametrize("kind,C", [("random", 4), ("sbm", 10), ("hub", 3)])
+def test_mixed_batches_converge_to_the_exact_labels(kind, C, mode):
+    """The paper's batch mix (mostly new unlabelled vertices, a few new labelled ones, some deletions),
+    two batches in a row; the second re-attaches an id the first one deleted."""
+    p = _random_problem(kind, C, 2200 + C)
+    p0 = _random_problem(kind, C, 2200 + C)
+    g = R.Graph(p0.n, p0.row_ptr, p0.col, p0.w, p0.C, p0.seed_vertex, p0.seed_class)
+    rng = np.random.default_rng(7 + C)
+    with _make(p0) as d:
+        d.set_update_mode(mode)
+        assert d.static_solve(TOL, 20000)[0] == 0
+        revived = None
+        for step in range(2):
+            n_old = g.n
+            dead = _pick_deleted(p0, rng, 40) if step == 0 else rng.choice(n_old, size=25, replace=False).astype(np.int32)
+            if kind == "random":
+                b = W.small_random_batch(p, 200, 6, 4, num_extra_edges=30)
+            elif kind == "sbm":
+                b = W.sbm_vertex_batch(p, 300, 20, 0.01)
+            else:
+                b = W.chung_lu_vertex_batch(p, 200, 0.02)
+            if step == 0:
+                revived = int(dead[2])
+            else:  # one new edge goes to a vertex deleted by the previous batch
+                b.eu = np.concatenate([b.eu, [revived]]).astype(np.int32)
+                b.ev = np.concatenate([b.ev, [n_old]]).astype(np.int32)
+                b.ew = np.concatenate([b.ew, [0.8]]).astype(np.float32)
+            rp0, col0, _ = g.csr()
+            dn = np.concatenate([col0[rp0[u]:rp0[u + 1]] for u in dead])
+            st, s = d.apply_update(dead, b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+            assert st == 0 and s.converged == 1
+            g.delete(dead)
+            g.insert(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+            _check_graph(d, g, ordered=False)
+            rp, col, w = g.csr()
+            A0 = ON.affected_set(rp, col, g.seed_class, n_old, b.eu, b.ev, b.seed_vertex, deleted_neighbours=dn)
+            assert s.frontier_initial == len(A0)
+            soft, hard = d.get_labels()
+            exact, reach = _exact(g)
+            err = float(np.max(np.abs(soft - exact)[reach]))
+            print(f"{kind} C={C} step {step}: {len(dead)} deleted, rounds {s.iterations}, err vs exact {err:.2e}")
+            # a locally stopped run sits up to about tol * n / |seeds| from the exact labels (1e-4 at 1% seeds)
+            atol = max(O1_ATOL, 2.0 * TOL * g.n / max(1, int((g.seed_class >= 0).sum())))
+            assert err <= atol
+            clear = reach & (R.top2_margin(exact) > 2 * atol)
+            assert np.array_equal(hard[clear], R.hard_labels(exact)[clear])
+            s_idx = np.flatnonzero(g.seed_class >= 0)
+            assert np.array_equal(soft[s_idx], R.initial_labels(g.seed_class, g.C)[s_idx].astype(np.float32))
+        assert revived is not None and np.diff(rp)[revived] >= 1
+
+
+def test_degenerate_deletions():
+    p = W.small_random(800, 3, 5.0, 40, 31, connected=False)
+    g = R.Graph(p.n, p.row_ptr, p.col, p.w, p.C, p.seed_vertex, p.seed_class)
+    deg = np.diff(p.row_ptr)
+    with _make(p) as d:
+        assert d.static_solve(TOL, 20000)[0] == 0
+        soft0, _ = d.get_labels()
+        # nothing to delete
+        st, s = d.apply_update(np.zeros(0, dtype=np.int32))
+        assert st == 0 and s.iterations == 0 and s.frontier_initial == 0
+        # an id listed three times, and an isolated vertex if there is one
+        u = int(np.argmax(deg))
+        lone = np.flatnonzero(deg == 0)
+        dead = np.array([u, u, u] + ([int(lone[0])] if len(lone) else []), dtype=np.int32)
+        assert d.apply_update(dead)[0] == 0
+        g.delete(dead)
+        _check_graph(d, g)
+        # all neighbours of one vertex: it becomes isolated and keeps its label
+        rp, col, w = g.csr()
+        v = int(np.flatnonzero((np.diff(rp) >= 2) & (g.seed_class < 0))[0])
+        nb = np.unique(col[rp[v]:rp[v + 1]]).astype(np.int32)
+        before, _ = d.get_labels()
+        assert d.apply_update(nb)[0] == 0
+        g.delete(nb)
+        _check_graph(d, g)
+        after, _ = d.get_labels()
+        assert np.array_equal(after[v], before[v])
+        # deleting an already deleted vertex changes nothing
+        rows_before = d.export_graph()
+        st, s = d.apply_update(nb[:1])
+        assert st == 0 and s.frontier_initial == 0
+        assert all(np.array_equal(a, b) for a, b in zip(rows_before, d.export_graph()))
+        exact, reach = _exact(g)
+        soft, _ = d.get_labels()
+        assert np.max(np.abs(soft - exact)[reach]) <= O1_ATOL
+
+
+def test_rejected_update_leaves_the_context_unchanged():
+    p = W.small_random(500, 3, 5.0, 30, 8)
+    with _make(p) as d:
+        assert d.static_solve(TOL, 20000)[0] == 0
+        snap = d.export_graph()
+        labels = d.get_labels()[0]
+        for bad in ([500], [-1], [3, 9999]):
+            with pytest.raises(P.DynLPError) as ei:
+                d.apply_update(np.array(bad, dtype=np.int32))
+            assert ei.value.status == -1 and "deleted vertex" in ei.value.message
+        # a valid deletion list with an invalid insertion part is rejected as a whole
+        with pytest.raises(P.DynLPError):
+            d.apply_update(np.array([1, 2], dtype=np.int32), 1, np.array([500], dtype=np.int32),
+                           np.array([777], dtype=np.int32), np.array([1.0], dtype=np.float32))
+        assert all(np.array_equal(a, b) for a, b in zip(snap, d.export_graph()))
+        assert np.array_equal(labels, d.get_labels()[0])
+        assert d.num_vertices == 500
+
+
+def test_device_pointer_mode_deletions():
+    import torch
+
+    p = W.small_random(3000, 5, 8.0, 100, 77)
+    g = R.Graph(p.n, p.row_ptr, p.col, p.w, p.C, p.seed_vertex, p.seed_class)
+    dev = torch.device("cuda:0")
+    t = lambda a, dt: torch.as_tensor(np.ascontiguousarray(a), dtype=dt, device=dev)
+    dead = _pick_deleted(p, np.random.default_rng(3), 50)
+    d = P.DynLP(p.n, t(p.row_ptr, torch.int64), t(p.col, torch.int32), t(p.w, torch.float32), p.C,
+                t(p.seed_vertex, torch.int32), t(p.seed_class, torch.int32), device_ptrs=True)
+    with d:
+        assert d.static_solve(TOL, 20000)[0] == 0
+        with pytest.raises(P.DynLPError):
+            d.apply_update(t([p.n], torch.int32))
+        st, s = d.apply_update(t(dead, torch.int32))
+        assert st == 0
+        soft = d.get_labels()[0].cpu().numpy()
+        rp, col, w, deg, sc = (x.cpu().numpy() for x in d.export_graph())
+    g.delete(dead)
+    orp, ocol, ow = g.csr()
+    assert rp.tolist() == orp.tolist() and col.tolist() == ocol.tolist()
+    exact, reach = _exact(g)
+    assert np.max(np.abs(soft - exact)[reach]) <= O1_ATOL
