@@ -156,6 +156,9 @@ def main():
     ap.add_argument("--init", default="uniform", choices=["uniform", "supernode"],
                     help="starting rows of inserted vertices: 1/C, or Alg. 2 Steps 1-2 (components of the sparsified "
                          "batch-internal graph, tau = mean edge weight of the base graph)")
+    ap.add_argument("--delete-frac", type=float, default=0.0,
+                    help="also delete this fraction of a batch's vertex count from the existing vertices in every batch "
+                         "(the paper's experiments use 9 deletions per 91 insertions: 0.099)")
     ap.add_argument("--update-mode", default="in-place", choices=["synchronous", "in-place"],
                     help="synchronous: every row of a round reads the round-start labels; in-place: rows are "
                          "replaced at once (Alg. 2's parallel loop taken literally)")
@@ -194,6 +197,10 @@ def main():
     torch.cuda.synchronize()
     del cal_src, cal_dst
 
+    del_rng = np.random.default_rng(20260406 + 77)
+    dels = [del_rng.choice(base["n"], size=int(round(args.delete_frac * b.num_new_vertices)), replace=False).astype(np.int32)
+            for b in batches]
+    d_dels = [dv(x, torch.int32) for x in dels]
     d_batches = [dict(k=b.num_new_vertices, eu=dv(b.eu, torch.int32), ev=dv(b.ev, torch.int32),
                       ew=dv(b.ew, torch.float32), sv=dv(b.seed_vertex, torch.int32), sc=dv(b.seed_class, torch.int32))
                  for b in batches]
@@ -225,7 +232,10 @@ def main():
             F_before = F_before if args.host_inputs else F_before.cpu().numpy()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        st, s = d.apply_batch(b["k"], b["eu"], b["ev"], b["ew"], b["sv"], b["sc"])
+        if len(dels[i]):
+            st, s = d.apply_update(d_dels[i], b["k"], b["eu"], b["ev"], b["ew"], b["sv"], b["sc"])
+        else:
+            st, s = d.apply_batch(b["k"], b["eu"], b["ev"], b["ew"], b["sv"], b["sc"])
         _, hard = d.get_labels(soft=False, hard=True)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
@@ -312,7 +322,8 @@ def main():
                    "round_profile_first_step": round_profile,
                    "cold_start": cold, "gen_s": round(t_gen, 1),
                    "init": {"mode": args.init, "tau": tau, "per_step": init_info},
-                   "update_mode": args.update_mode},
+                   "update_mode": args.update_mode,
+                   "deleted_per_step": [int(len(x)) for x in dels[args.warmup:]]},
     }
     if args.cpu_budget > 0 and per_step:
         out["cpu_baseline"] = cpu_baseline(base, batches[:args.warmup], batches[args.warmup], F_before, tol,
