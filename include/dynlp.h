@@ -86,6 +86,11 @@ typedef struct dynlp_options {
     void* (*alloc)(size_t bytes, void* user);
     void (*dealloc)(void* ptr, void* user);
     void* alloc_user;
+    int32_t binary_scalar;   /* 1 (needs num_classes == 2): keep one float per vertex, the paper's scalar
+                                label F_u in [0,1] = weight of class 1 (seeds 0 or 1, neutral start 0.5,
+                                hard label by the 0.5 cut-off); dynlp_get_labels still returns n x 2 rows
+                                (1 - F_u, F_u).  0: n x C rows */
+    int32_t reserved;
 } dynlp_options;
 
 /* Fill *opt with the defaults (device 0, default stream, host pointers). */

@@ -72,6 +72,7 @@ struct dynlp_ctx {
     int num_cu = 256;
 
     int C = 0, CP = 0;
+    int Cs = 0, coff = 0;  // stored columns and the class of stored column 0 (binary scalar layout: 1, 1)
     int64_t n = 0, n_cap = 0, flag_cap = 0;
     int64_t entries = 0;  // directed CSR entries stored
     RowMeta* meta = nullptr;
@@ -677,7 +678,7 @@ void run_supernode_init(dynlp_ctx* c, int64_t n0, int64_t k, int64_t m, const in
     hipLaunchKernelGGL(k_fill_f64, dim3(grid_for(comps * c->C)), dim3(kBlock), 0, c->stream, comps * c->C, c->cc_W, 0.0);
     hipLaunchKernelGGL(k_supernode_weights, dim3(grid_for(k * 16)), dim3(kBlock), 0, c->stream, n0, k, c->C, c->meta,
                        c->pool, c->seed_class, c->cc_comp, c->cc_W);
-    hipLaunchKernelGGL(k_supernode_rows, dim3(grid_for(k * c->CP)), dim3(kBlock), 0, c->stream, n0, k, c->C, c->CP,
+    hipLaunchKernelGGL(k_supernode_rows, dim3(grid_for(k * c->CP)), dim3(kBlock), 0, c->stream, n0, k, c->C, c->Cs, c->coff, c->CP,
                        c->seed_class, c->cc_comp, c->cc_W, c->F);
     HIPCHK(c, hipGetLastError());
     HIPCHK(c, hipEventRecord(c->init_ev[1], c->stream));
@@ -740,7 +741,9 @@ dynlp_status dynlp_create(dynlp_ctx** out, int64_t n, const int64_t* row_ptr, co
     if (o.slack_factor > 8.0f) return bad("slack_factor must be <= 8");
     if (o.reserve_vertices < 0 || o.reserve_edges < 0) return bad("reserve counts must be >= 0");
     if ((o.alloc == nullptr) != (o.dealloc == nullptr)) return bad("alloc and dealloc must be given together");
-    const int CP = padded_classes(num_classes);
+    if (o.binary_scalar != 0 && num_classes != 2) return bad("binary_scalar needs num_classes == 2");
+    const int Cs = o.binary_scalar != 0 ? 1 : num_classes;  // stored columns
+    const int CP = padded_classes(Cs);
     if (o.group_lanes != 0) {
         const int g = o.group_lanes;
         if (!(g == 4 || g == 8 || g == 16 || g == 32 || g == 64) || g < lanes_per_neighbour(CP))
@@ -782,6 +785,8 @@ dynlp_status dynlp_create(dynlp_ctx** out, int64_t n, const int64_t* row_ptr, co
         c->dealloc_fn = o.dealloc;
         c->alloc_user = o.alloc_user;
         c->C = num_classes;
+        c->Cs = Cs;
+        c->coff = num_classes - Cs;  // 1 in the binary scalar layout (column 0 holds class 1), else 0
         c->CP = CP;
         HIPCHK(c, hipSetDevice(c->device));
         hipDeviceProp_t prop;
@@ -873,7 +878,7 @@ dynlp_status dynlp_create(dynlp_ctx** out, int64_t n, const int64_t* row_ptr, co
                                d_sv.ptr, d_sc.ptr, c->seed_class);
         if (n > 0) {
             hipLaunchKernelGGL(k_init_labels, dim3(grid_for(n * c->CP)), dim3(kBlock), 0, c->stream, (int64_t)0, n, c->C,
-                               c->CP, c->seed_class, c->F);
+                               c->Cs, c->coff, c->CP, c->seed_class, c->F);
             hipLaunchKernelGGL(k_row_degree, dim3(grid_for(n * 16)), dim3(kBlock), 0, c->stream, n, c->meta, c->pool,
                                c->deg);
         }
@@ -1166,7 +1171,7 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
             mutated = true;
             hipLaunchKernelGGL(k_mark_deleted, dim3(grid_for(nd)), dim3(kBlock), 0, c->stream, nd, d_del.ptr, c->seed_class,
                                kDeletedMark);
-            hipLaunchKernelGGL(k_delete_rows, dim3(grid_for(nd * 16)), dim3(kBlock), 0, c->stream, nd, d_del.ptr, c->C, c->CP,
+            hipLaunchKernelGGL(k_delete_rows, dim3(grid_for(nd * 16)), dim3(kBlock), 0, c->stream, nd, d_del.ptr, c->C, c->Cs, c->CP,
                                c->meta, c->pool, c->seed_class, c->flag, c->add_cnt, c->touched, c->deg, c->F, c->bc);
             HIPCHK(c, hipGetLastError());
             read_bc(c);
@@ -1216,8 +1221,8 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
         // ---- from here on the graph changes ----
         mutated = true;
         if (k > 0)
-            hipLaunchKernelGGL(k_init_labels, dim3(grid_for(k * c->CP)), dim3(kBlock), 0, c->stream, n0, n1, c->C, c->CP,
-                               c->seed_class, c->F);
+            hipLaunchKernelGGL(k_init_labels, dim3(grid_for(k * c->CP)), dim3(kBlock), 0, c->stream, n0, n1, c->C, c->Cs, c->coff,
+                               c->CP, c->seed_class, c->F);
         if (nt) {
             hipLaunchKernelGGL(k_plan_reserve, dim3(grid_for(nt)), dim3(kBlock), 0, c->stream, nt, c->touched, c->meta,
                                c->add_cnt, c->slack, c->reloc_off, c->bc);
@@ -1234,7 +1239,7 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
         HIPCHK(c, hipEventRecord(c->phase_ev[1], c->stream));
         // ---- seeds: clamp one-hot, their neighbours join V_aff; first compaction ----
         if (s > 0)
-            hipLaunchKernelGGL(k_apply_seeds, dim3(grid_for(s * 16)), dim3(kBlock), 0, c->stream, s, d_sv, d_sc, c->C, c->CP,
+            hipLaunchKernelGGL(k_apply_seeds, dim3(grid_for(s * 16)), dim3(kBlock), 0, c->stream, s, d_sv, d_sc, c->Cs, c->coff, c->CP,
                                c->seed_class, c->F, c->meta, c->pool, c->flag);
         c->last_init = dynlp_init_info{};
         if (c->init_mode == DYNLP_INIT_SUPERNODE && k > 0) run_supernode_init(c, n0, k, m, d_eu, d_ev, d_ew);
@@ -1373,14 +1378,20 @@ dynlp_status dynlp_get_labels(dynlp_ctx* c, float* soft, int32_t* hard) {
         HIPCHK(c, hipSetDevice(c->device));
         if (soft) {
             float* dst = c->dev_ptrs ? soft : (d_soft = dev_alloc_n<float>(c, n * c->C));
-            hipLaunchKernelGGL(k_pack_soft, dim3(grid_for(n * c->C)), dim3(kBlock), 0, c->stream, n, c->C, c->CP, c->F, dst);
+            if (c->coff)
+                hipLaunchKernelGGL(k_scalar_soft, dim3(grid_for(2 * n)), dim3(kBlock), 0, c->stream, n, c->F, dst);
+            else
+                hipLaunchKernelGGL(k_pack_soft, dim3(grid_for(n * c->C)), dim3(kBlock), 0, c->stream, n, c->C, c->CP, c->F, dst);
             HIPCHK(c, hipGetLastError());
             if (!c->dev_ptrs)
                 HIPCHK(c, hipMemcpyAsync(soft, dst, (size_t)n * c->C * sizeof(float), hipMemcpyDeviceToHost, c->stream));
         }
         if (hard) {
             int32_t* dst = c->dev_ptrs ? hard : (d_hard = dev_alloc_n<int32_t>(c, n));
-            hipLaunchKernelGGL(k_argmax, dim3(grid_for(n * (c->CP >= 4 ? c->CP / 4 : 1))), dim3(kBlock), 0, c->stream, n, c->C, c->CP, c->F, dst);
+            if (c->coff)
+                hipLaunchKernelGGL(k_scalar_hard, dim3(grid_for(n)), dim3(kBlock), 0, c->stream, n, c->F, dst);
+            else
+                hipLaunchKernelGGL(k_argmax, dim3(grid_for(n * (c->CP >= 4 ? c->CP / 4 : 1))), dim3(kBlock), 0, c->stream, n, c->C, c->CP, c->F, dst);
             HIPCHK(c, hipGetLastError());
             if (!c->dev_ptrs)
                 HIPCHK(c, hipMemcpyAsync(hard, dst, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));

@@ -184,7 +184,7 @@ __global__ void __launch_bounds__(kBlock) k_supernode_weights(int64_t n0, int64_
 // Step 2, rows: F_u[j] = W[comp(u)][j] / sum_j W[comp(u)][j] for every unlabelled inserted vertex,
 // 1/C when the supernode has no labelled neighbour; padding columns stay 0.  One lane per stored
 // column; every lane adds the C sums in class order.
-__global__ void __launch_bounds__(kBlock) k_supernode_rows(int64_t n0, int64_t k, int C, int CP,
+__global__ void __launch_bounds__(kBlock) k_supernode_rows(int64_t n0, int64_t k, int C, int Cs, int coff, int CP,
                                                           const int32_t* __restrict__ seed_class,
                                                           const int32_t* __restrict__ comp,
                                                           const double* __restrict__ W, float* __restrict__ F) {
@@ -198,7 +198,7 @@ __global__ void __launch_bounds__(kBlock) k_supernode_rows(int64_t n0, int64_t k
     double tot = 0.0;
     for (int c = 0; c < C; ++c) tot += Wc[c];
     float out = 0.f;
-    if (j < C) out = tot > 0.0 ? (float)(Wc[j] / tot) : 1.0f / (float)C;
+    if (j < Cs) out = tot > 0.0 ? (float)(Wc[j + coff] / tot) : 1.0f / (float)C;  // stored column j = class j + coff
     F[u * CP + j] = out;
 }
 

@@ -115,7 +115,9 @@ __global__ void __launch_bounds__(kBlock) k_row_degree(int64_t n, const RowMeta*
 // Labels: initialisation, seed clamping, argmax, packing
 // =================================================================================================
 // Rows [u0, u1): seed rows one-hot, others uniform 1/C, padding columns 0.
-__global__ void __launch_bounds__(kBlock) k_init_labels(int64_t u0, int64_t u1, int C, int CP,
+// Stored column c holds class c + coff: coff = 0 and Cs = C normally; the binary scalar layout
+// (C = 2) stores only class 1 (Cs = 1, coff = 1), class 0 being 1 - F_u.
+__global__ void __launch_bounds__(kBlock) k_init_labels(int64_t u0, int64_t u1, int C, int Cs, int coff, int CP,
                                                        const int32_t* __restrict__ seed_class,
                                                        float* __restrict__ F) {
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -124,7 +126,7 @@ __global__ void __launch_bounds__(kBlock) k_init_labels(int64_t u0, int64_t u1, 
     if (u >= u1) return;
     const int sc = seed_class[u];
     float v = 0.f;
-    if (c < C) v = sc < 0 ? 1.0f / (float)C : (c == sc ? 1.0f : 0.0f);
+    if (c < Cs) v = sc < 0 ? 1.0f / (float)C : (c + coff == sc ? 1.0f : 0.0f);
     F[u * CP + c] = v;
 }
 
@@ -181,7 +183,7 @@ __global__ void __launch_bounds__(kBlock) k_set_seed_class(int64_t s, const int3
 // New seeds of a batch: clamp the row one-hot (the row is never updated again) and put the
 // neighbours into V_aff.  16 lanes per seed.
 __global__ void __launch_bounds__(kBlock) k_apply_seeds(int64_t s, const int32_t* __restrict__ sv,
-                                                       const int32_t* __restrict__ sc, int C, int CP,
+                                                       const int32_t* __restrict__ sc, int Cs, int coff, int CP,
                                                        int32_t* __restrict__ seed_class, float* __restrict__ F,
                                                        const RowMeta* __restrict__ meta,
                                                        const Edge* __restrict__ pool, uint8_t* __restrict__ flag) {
@@ -191,7 +193,7 @@ __global__ void __launch_bounds__(kBlock) k_apply_seeds(int64_t s, const int32_t
     if (i >= s) return;
     const int32_t v = sv[i], c = sc[i];
     if (gl == 0) seed_class[v] = c;
-    for (int k = gl; k < CP; k += G) F[(int64_t)v * CP + k] = (k == c) ? 1.0f : 0.0f;
+    for (int k = gl; k < CP; k += G) F[(int64_t)v * CP + k] = (k < Cs && k + coff == c) ? 1.0f : 0.0f;
     const RowMeta m = meta[v];
     for (int j = gl; j < m.len; j += G) flag[pool[m.off + j].col] = 1;
 }
@@ -236,6 +238,22 @@ __global__ void __launch_bounds__(kBlock) k_pack_soft(int64_t n, int C, int CP, 
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= n * C) return;
     soft[i] = F[(i / C) * CP + (i % C)];
+}
+
+// Binary scalar layout: hard label = the paper's 0.5 cut-off (class 1 iff F_u > 0.5, i.e. iff class 1
+// beats class 0; a tie goes to class 0 like the argmax), soft row = (1 - F_u, F_u).
+__global__ void __launch_bounds__(kBlock) k_scalar_hard(int64_t n, const float* __restrict__ F,
+                                                       int32_t* __restrict__ hard) {
+    const int64_t u = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (u < n) hard[u] = F[u] > 0.5f ? 1 : 0;
+}
+
+__global__ void __launch_bounds__(kBlock) k_scalar_soft(int64_t n, const float* __restrict__ F,
+                                                       float* __restrict__ soft) {
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= 2 * n) return;
+    const float f = F[i >> 1];
+    soft[i] = (i & 1) ? f : 1.0f - f;
 }
 
 // =================================================================================================
@@ -407,7 +425,7 @@ __global__ void __launch_bounds__(kBlock) k_mark_deleted(int64_t nd, const int32
 // first touch, into the list of rows that must drop their entries towards deleted vertices.  The
 // deleted row keeps its place and capacity in the pool (a later batch may give the id edges again);
 // its label row becomes the neutral 1/C.
-__global__ void __launch_bounds__(kBlock) k_delete_rows(int64_t nd, const int32_t* __restrict__ del, int C, int CP,
+__global__ void __launch_bounds__(kBlock) k_delete_rows(int64_t nd, const int32_t* __restrict__ del, int C, int Cs, int CP,
                                                        RowMeta* meta, const Edge* __restrict__ pool,
                                                        const int32_t* __restrict__ seed_class,
                                                        uint8_t* __restrict__ flag, int32_t* __restrict__ add_cnt,
@@ -450,7 +468,7 @@ __global__ void __launch_bounds__(kBlock) k_delete_rows(int64_t nd, const int32_
     if (lane_id() == 0 && removed) atomicAdd(&bc->removed, removed);
     if (i < nd) {  // also for a vertex that had no edges, or is listed twice: the same values again
         if (gl == 0) deg[u] = 0.f;
-        for (int c = gl; c < CP; c += G) F[(size_t)u * CP + c] = c < C ? 1.0f / (float)C : 0.f;
+        for (int c = gl; c < CP; c += G) F[(size_t)u * CP + c] = c < Cs ? 1.0f / (float)C : 0.f;
     }
 }
 

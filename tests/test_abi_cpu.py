@@ -40,7 +40,7 @@ def test_stats_and_options_layout_match_header():
     assert B.Stats.rows_updated.offset == 16
     assert B.Stats.ms_update_kernel.offset == 64
     assert B.Options.stream.offset == 8 and B.Options.slack_factor.offset == 20
-    assert B.Options.alloc.offset == 48 and ct.sizeof(B.Options) == 72
+    assert B.Options.alloc.offset == 48 and B.Options.binary_scalar.offset == 72 and ct.sizeof(B.Options) == 80
 
 
 def _tiny():
@@ -66,14 +66,16 @@ def _tiny():
     (lambda a: a.update(sc=np.array([2], dtype=np.int32)), "seed class"),
     (lambda a: a.update(sv=np.array([0, 0], dtype=np.int32), sc=np.array([0, 1], dtype=np.int32)), "two different"),
     (lambda a: a.update(group_lanes=5), "group_lanes"),
+    (lambda a: a.update(C=3, binary_scalar=True), "binary_scalar"),
 ])
 def test_create_rejects_bad_arguments_without_a_gpu(lib, mutate, needle):
     rp, col, w = _tiny()
     a = dict(n=3, rp=rp, col=col, w=w, C=2, sv=np.array([0], dtype=np.int32), sc=np.array([1], dtype=np.int32),
-             group_lanes=0)
+             group_lanes=0, binary_scalar=False)
     mutate(a)
     with pytest.raises(B.DynLPError) as ei:
-        P.DynLP(a["n"], a["rp"], a["col"], a["w"], a["C"], a["sv"], a["sc"], group_lanes=a["group_lanes"])
+        P.DynLP(a["n"], a["rp"], a["col"], a["w"], a["C"], a["sv"], a["sc"], group_lanes=a["group_lanes"],
+                binary_scalar=a["binary_scalar"])
     assert ei.value.status == -1
     assert needle in ei.value.message
 
