@@ -32,11 +32,11 @@ def algorithmic_bytes(rows: int, edges: int, C: int) -> int:
     return 8 * edges + 4 * C * (edges + 2 * rows) + 20 * rows
 
 
-def build_workload(name: str, batch_frac: float, num_batches: int, batch_kind: str = "default"):
+def build_workload(name: str, batch_frac: float, num_batches: int, batch_kind: str = "default", scale: float = 1.0):
     import workloads as W
 
     cfg = W.CONFIGS[name]
-    p = W.make_config(name)
+    p = W.make_config(name, scale)
     base = dict(n=p.n, C=p.C, row_ptr=p.row_ptr, col=p.col, w=p.w, seed_vertex=p.seed_vertex,
                 seed_class=p.seed_class)
     batches = []
@@ -71,6 +71,11 @@ def build_workload(name: str, batch_frac: float, num_batches: int, batch_kind: s
         for _ in range(num_batches):
             batches.append(W.chung_lu_vertex_batch(p, k, cfg["seed_frac"]))
         label = f"{name}: Chung-Lu n={cfg['n']} C={cfg['C']} mean degree {cfg['mean_degree']:g}, batches of {k} new vertices"
+    elif cfg["kind"] == "er-single-batch":
+        b = p.state["single_batch"]
+        batches = [b] * num_batches  # every step starts from a fresh context holding only the labelled vertices
+        label = (f"{name}: Erdos-Renyi n={cfg['n']} mean degree {cfg['mean_degree']:g}, binary labels, "
+                 f"{p.n} labelled vertices, all {b.num_new_vertices} unlabelled vertices in one batch")
     else:
         raise KeyError(name)
     return cfg, base, batches, label
@@ -144,7 +149,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "cfg6"])
     ap.add_argument("--batch-frac", type=float, default=0.01, help="new vertices per batch as a fraction of n")
     ap.add_argument("--tol", type=float, default=None, help="threshold delta (default: the workload's)")
     ap.add_argument("--group-lanes", type=int, default=0)
@@ -156,6 +161,9 @@ def main():
     ap.add_argument("--init", default="uniform", choices=["uniform", "supernode"],
                     help="starting rows of inserted vertices: 1/C, or Alg. 2 Steps 1-2 (components of the sparsified "
                          "batch-internal graph, tau = mean edge weight of the base graph)")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload's vertex count (same law)")
+    ap.add_argument("--binary-scalar", type=int, default=-1,
+                    help="1: one float per vertex (needs C = 2); 0: n x C rows; default: 1 for cfg6, else 0")
     ap.add_argument("--delete-frac", type=float, default=0.0,
                     help="also delete this fraction of a batch's vertex count from the existing vertices in every batch "
                          "(the paper's experiments use 9 deletions per 91 insertions: 0.099)")
@@ -180,7 +188,7 @@ def main():
         P.build()
     dev = torch.device("cuda:0")
     t_gen = time.perf_counter()
-    cfg, base, batches, label = build_workload(args.workload, args.batch_frac, args.warmup + args.steps, args.batch_kind)
+    cfg, base, batches, label = build_workload(args.workload, args.batch_frac, args.warmup + args.steps, args.batch_kind, args.scale)
     tol = float(args.tol if args.tol is not None else cfg["tol"])
     t_gen = time.perf_counter() - t_gen
 
@@ -201,25 +209,42 @@ def main():
     dels = [del_rng.choice(base["n"], size=int(round(args.delete_frac * b.num_new_vertices)), replace=False).astype(np.int32)
             for b in batches]
     d_dels = [dv(x, torch.int32) for x in dels]
-    d_batches = [dict(k=b.num_new_vertices, eu=dv(b.eu, torch.int32), ev=dv(b.ev, torch.int32),
-                      ew=dv(b.ew, torch.float32), sv=dv(b.seed_vertex, torch.int32), sc=dv(b.seed_class, torch.int32))
-                 for b in batches]
-    tot_v = sum(b.num_new_vertices for b in batches)
-    tot_e = sum(b.num_edges for b in batches)
-    d = P.DynLP(base["n"], dv(base["row_ptr"], torch.int64), dv(base["col"], torch.int32), dv(base["w"], torch.float32),
-                base["C"], dv(base["seed_vertex"], torch.int32), dv(base["seed_class"], torch.int32),
-                device_ptrs=not args.host_inputs, reserve_vertices=tot_v + 1024, reserve_edges=2 * tot_e + 1024, time_kernels=not args.no_kernel_timing,
-                group_lanes=args.group_lanes)
-    if args.update_mode == "in-place":
-        d.set_update_mode(P.UPDATE_IN_PLACE)
-    st, s0 = d.static_solve(tol, cfg["max_iter"])
+    fresh = cfg["kind"] == "er-single-batch"  # every step: a new context, then the one big batch
+    scalar = bool(args.binary_scalar) if args.binary_scalar >= 0 else fresh
+    Cs = 1 if scalar else base["C"]  # stored label columns
+    dev_batch = {}
+
+    def to_dev(b):
+        if id(b) not in dev_batch:
+            dev_batch[id(b)] = dict(k=b.num_new_vertices, eu=dv(b.eu, torch.int32), ev=dv(b.ev, torch.int32),
+                                    ew=dv(b.ew, torch.float32), sv=dv(b.seed_vertex, torch.int32),
+                                    sc=dv(b.seed_class, torch.int32))
+        return dev_batch[id(b)]
+
+    d_batches = [to_dev(b) for b in batches]
+    tot_v = sum(b.num_new_vertices for b in (batches[:1] if fresh else batches))
+    tot_e = sum(b.num_edges for b in (batches[:1] if fresh else batches))
+    d_base = [dv(base["row_ptr"], torch.int64), dv(base["col"], torch.int32), dv(base["w"], torch.float32),
+              dv(base["seed_vertex"], torch.int32), dv(base["seed_class"], torch.int32)]
+
+    def new_context():
+        ctx = P.DynLP(base["n"], d_base[0], d_base[1], d_base[2], base["C"], d_base[3], d_base[4],
+                      device_ptrs=not args.host_inputs, reserve_vertices=tot_v + 1024, reserve_edges=2 * tot_e + 1024,
+                      time_kernels=not args.no_kernel_timing, group_lanes=args.group_lanes, binary_scalar=scalar)
+        if args.update_mode == "in-place":
+            ctx.set_update_mode(P.UPDATE_IN_PLACE)
+        st_, s_ = ctx.static_solve(tol, cfg["max_iter"])
+        t_ = None
+        if args.init == "supernode":
+            # the base graph of cfg6 holds labelled vertices only; its mean weight is the data set's law
+            t_ = float(np.float32(ctx.mean_edge_weight()))
+            ctx.set_initialiser(P.INIT_SUPERNODE, t_)
+        return ctx, st_, s_, t_
+
+    d, st, s0, tau = new_context()
     cold = dict(status=st, sweeps=s0.iterations, ms=s0.ms_total, ms_update_kernel=s0.ms_update_kernel,
-                algorithmic_gbs=algorithmic_bytes(s0.rows_updated, s0.edges_traversed, base["C"]) / 1e6 /
+                algorithmic_gbs=algorithmic_bytes(s0.rows_updated, s0.edges_traversed, Cs) / 1e6 /
                 max(s0.ms_update_kernel, 1e-9))
-    tau = None
-    if args.init == "supernode":
-        tau = float(np.float32(d.mean_edge_weight()))
-        d.set_initialiser(P.INIT_SUPERNODE, tau)
     init_info = []
     F_before = None
     per_step = []
@@ -227,9 +252,12 @@ def main():
     buckets = {}
     for i, b in enumerate(d_batches):
         timed = i >= args.warmup
-        if i == args.warmup and args.cpu_budget > 0:
+        if i == args.warmup and args.cpu_budget > 0 and not fresh:
             F_before = d.get_labels(soft=True, hard=False)[0]
             F_before = F_before if args.host_inputs else F_before.cpu().numpy()
+        if fresh and i > 0:
+            d.destroy()
+            d, _, _, tau = new_context()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         if len(dels[i]):
@@ -262,11 +290,11 @@ def main():
     rows = sum(x["rows_updated"] for x in per_step)
     trav = sum(x["edges_traversed"] for x in per_step)
     # The roofline entry is for the kernel that takes the most device time in the timed region.
-    CP = next(c for c in (1, 2, 4, 8, 16, 32, 64) if c >= base["C"])
+    CP = next(c for c in (1, 2, 4, 8, 16, 32, 64) if c >= Cs)
     kstats = {}
     for (staged, glanes), (cnt, rws, ent, ms) in buckets.items():
         name = f"k_row_update<{CP}, {glanes}, {'true' if staged else 'false'}>"
-        ab = algorithmic_bytes(rws, ent, base["C"])
+        ab = algorithmic_bytes(rws, ent, Cs)
         kstats[name] = dict(launches=cnt, rows=rws, entries=ent, device_ms=round(ms, 3),
                             avg_launch_us=round(ms * 1e3 / max(1, cnt), 1),
                             algorithmic_GBs=round(ab / 1e6 / max(ms, 1e-9), 1), algorithmic_bytes=ab)
@@ -300,7 +328,7 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic" + (" (host-resident inputs: PCIe-inclusive)" if args.host_inputs else ""),
-        "config": {"workload": label, "tol": tol, "update_mode": args.update_mode, "edges_per_batch": edges_inserted // max(1, len(per_step)),
+        "config": {"workload": label, "tol": tol, "update_mode": args.update_mode, "binary_scalar": scalar, "edges_per_batch": edges_inserted // max(1, len(per_step)),
                    "vertices_after": d.num_vertices, "directed_entries_after": d.num_entries},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
@@ -325,7 +353,7 @@ def main():
                    "update_mode": args.update_mode,
                    "deleted_per_step": [int(len(x)) for x in dels[args.warmup:]]},
     }
-    if args.cpu_budget > 0 and per_step:
+    if args.cpu_budget > 0 and per_step and not fresh:
         out["cpu_baseline"] = cpu_baseline(base, batches[:args.warmup], batches[args.warmup], F_before, tol,
                                            per_step[0]["edges_traversed"], args.cpu_budget)
     else:

@@ -24,6 +24,7 @@ from .graphs import (  # noqa: F401
     small_random,
     small_random_batch,
     clustered_batch,
+    erdos_renyi_single_batch,
     CONFIGS,
     csr_with_batch,
     make_config,

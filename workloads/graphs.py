@@ -519,6 +519,28 @@ def clustered_batch(p: Problem, num_new: int, mean_cluster: float, intra_degree:
     return Batch(num_new, lo.astype(np.int32), hi.astype(np.int32), ww.astype(np.float32), sv, sc)
 
 
+def erdos_renyi_single_batch(n: int, mean_degree: float, seed_frac: float, seed: int):
+    """The paper's "all unlabelled vertices in one batch" experiment on an Erdos-Renyi graph
+    (n vertices, n * mean_degree / 2 uniformly drawn pairs, duplicates and loops dropped, weights
+    ~ U(0.1, 1), two classes drawn at random).  The first round(seed_frac * n) ids are the labelled
+    vertices; they and the edges among them form the base graph, every other vertex and edge is
+    the batch.  Returns (Problem of the base graph, Batch)."""
+    rng = np.random.default_rng(seed)
+    m = int(round(n * mean_degree / 2.0))
+    lo, hi = _dedupe_undirected(n, rng.integers(0, n, size=m), rng.integers(0, n, size=m))
+    ew = rng.uniform(0.1, 1.0, size=lo.shape[0]).astype(np.float32)
+    cls = rng.integers(0, 2, size=n).astype(np.int32)
+    ns = max(1, int(round(seed_frac * n)))
+    old = hi < ns  # lo < hi, so both ends are labelled vertices
+    row_ptr, col, w = edges_to_csr(ns, lo[old], hi[old], ew[old])
+    sv = np.arange(ns, dtype=np.int32)
+    st = dict(kind="er", rng=rng, is_seed=np.ones(ns, dtype=bool))
+    p = Problem(ns, 2, row_ptr, col, w, sv, cls[:ns].copy(), cls[:ns].copy(), st)
+    b = Batch(n - ns, lo[~old].astype(np.int32), hi[~old].astype(np.int32), ew[~old],
+              np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.int32))
+    return p, b
+
+
 # --------------------------------------------------------------------------------------
 # the five named configurations
 # --------------------------------------------------------------------------------------
@@ -535,6 +557,9 @@ CONFIGS = {
     "cfg5": dict(kind="sbm-edge-stream", n=1_000_000, C=10, mean_degree=20.0, in_out_ratio=8.0,
                  seed_frac=0.01, tol=1e-6, max_iter=20000, num_batches=100, edges_per_batch=100_000,
                  intra_frac=0.5, revealed_per_batch=1_000),
+    # the paper's own setting: binary labels, Erdos-Renyi graph, every unlabelled vertex in one batch
+    "cfg6": dict(kind="er-single-batch", n=50_000_000, C=2, mean_degree=5.0, seed_frac=0.01, tol=1e-6,
+                 max_iter=100000),
 }
 
 
@@ -552,6 +577,10 @@ def make_config(name: str, scale: float = 1.0) -> Problem:
         d_max = max(8, int(round(cfg["d_max"] * min(1.0, scale * 4)))) if scale < 1 else cfg["d_max"]
         return chung_lu(n, cfg["C"], cfg["mean_degree"], cfg["exponent"], d_max, cfg["intra_frac"],
                         cfg["seed_frac"], seed)
+    if cfg["kind"] == "er-single-batch":  # base graph = the labelled vertices; the batch holds the rest
+        p, b = erdos_renyi_single_batch(n, cfg["mean_degree"], cfg["seed_frac"], seed)
+        p.state["single_batch"] = b
+        return p
     raise KeyError(name)
 
 
