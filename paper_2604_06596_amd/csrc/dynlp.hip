@@ -642,7 +642,7 @@ void run_supernode_init(dynlp_ctx* c, int64_t n0, int64_t k, int64_t m, const in
     HIPCHK(c, hipMemsetAsync(c->cc_ctr, 0, sizeof(InitCtr), c->stream));
     hipLaunchKernelGGL(k_cc_reset, dim3(grid_for(k)), dim3(kBlock), 0, c->stream, k, c->cc_par);
     if (m > 0)
-        hipLaunchKernelGGL(k_cc_filter, dim3(grid_for(m)), dim3(kBlock), 0, c->stream, m, n0, k, d_eu, d_ev, d_ew, c->tau,
+        hipLaunchKernelGGL(k_cc_filter, dim3(grid_for(ceil_div(m, kAppendItems))), dim3(kBlock), 0, c->stream, m, n0, k, d_eu, d_ev, d_ew, c->tau,
                            c->cc_kept, c->cc_ctr);
     const unsigned int hook_grid = (unsigned int)std::min<int64_t>(grid_for(std::max<int64_t>(m, 1)), (int64_t)c->num_cu * 8);
     int hook_steps = 0;
@@ -1200,7 +1200,7 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
             hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(k)), dim3(kBlock), 0, c->stream, n0, n1, c->seed_class, -1);
         }
         if (m > 0)
-            hipLaunchKernelGGL(k_count_halfedges, dim3(grid_for(2 * m)), dim3(kBlock), 0, c->stream, m, n1, d_eu, d_ev,
+            hipLaunchKernelGGL(k_count_halfedges, dim3(grid_for(ceil_div(2 * m, kAppendItems))), dim3(kBlock), 0, c->stream, m, n1, d_eu, d_ev,
                                c->add_cnt, c->touched, c->bc);
         HIPCHK(c, hipGetLastError());
         read_bc(c);

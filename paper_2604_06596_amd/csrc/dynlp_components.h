@@ -56,21 +56,31 @@ __global__ void __launch_bounds__(kBlock) k_cc_reset(int64_t k, int32_t* __restr
 }
 
 // E': batch edges with both ends inserted in this batch and weight > tau, as pairs of batch-local
-// ids, appended in arbitrary order (one counter atomic per wave).
+// ids, appended in arbitrary order (a workgroup takes kAppendItems * kBlock edges and reserves its
+// output range with one counter atomic).
 __global__ void __launch_bounds__(kBlock) k_cc_filter(int64_t m, int64_t n0, int64_t k, const int32_t* __restrict__ eu,
                                                      const int32_t* __restrict__ ev, const float* __restrict__ ew,
                                                      float tau, int2* __restrict__ kept, InitCtr* ctr) {
-    const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    bool keep = false;
-    int a = 0, b = 0;
-    if (e < m) {
-        const int64_t la = (int64_t)eu[e] - n0, lb = (int64_t)ev[e] - n0;
-        keep = la >= 0 && la < k && lb >= 0 && lb < k && ew[e] > tau;
-        a = (int)la;
-        b = (int)lb;
+    __shared__ unsigned int smem[kBlock / kWave + 1];
+    const int64_t base = (int64_t)blockIdx.x * kBlock * kAppendItems;
+    int2 pairs[kAppendItems];
+    unsigned int keepmask = 0;
+#pragma unroll
+    for (int q = 0; q < kAppendItems; ++q) {
+        const int64_t e = base + (int64_t)q * kBlock + threadIdx.x;
+        pairs[q] = make_int2(0, 0);
+        if (e < m) {
+            const int64_t la = (int64_t)eu[e] - n0, lb = (int64_t)ev[e] - n0;
+            if (la >= 0 && la < k && lb >= 0 && lb < k && ew[e] > tau) {
+                keepmask |= 1u << q;
+                pairs[q] = make_int2((int)la, (int)lb);
+            }
+        }
     }
-    const unsigned int slot = wave_reserve(&ctr->kept, keep);
-    if (keep) kept[slot] = make_int2(a, b);
+    unsigned int slot = block_reserve(&ctr->kept, (unsigned int)__popc(keepmask), smem);
+#pragma unroll
+    for (int q = 0; q < kAppendItems; ++q)
+        if ((keepmask >> q) & 1u) kept[slot++] = pairs[q];
 }
 
 // Hook step `iter` of a chain.  Skipped when the previous hook step of the chain changed nothing.

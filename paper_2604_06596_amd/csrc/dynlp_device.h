@@ -10,6 +10,7 @@ constexpr int kWave = 64;
 constexpr int kBlock = 256;       // threads per workgroup for every kernel here
 constexpr int kRowAlign = 8;      // row capacities are multiples of 8 entries = 64 bytes
 constexpr int kRing = 64;         // per-round counter slots
+constexpr int kAppendItems = 8;   // items per thread in kernels that append to a list (one counter atomic per 2,048 items)
 constexpr int kInitChain = 4;     // hook/jump steps of the component search queued per host round trip
 
 // One CSR entry of the slack pool: neighbour id and weight side by side, so that a single
@@ -140,6 +141,20 @@ __device__ inline unsigned int wave_reserve(unsigned int* counter, bool pred) {
     if (pred && lane == leader) base = atomicAdd(counter, (unsigned int)__popcll(mask));
     base = __shfl(base, leader < 0 ? 0 : leader, kWave);
     return base + (unsigned int)__popcll(mask & ((1ull << lane) - 1ull));
+}
+
+// Append-slot reservation with one atomic per workgroup: every thread asks for `count` consecutive
+// slots (0 allowed) and gets the index of its first one.  smem must hold kBlock / kWave + 1 elements.
+// Contains barriers: call from all threads of the workgroup.
+__device__ inline unsigned int block_reserve(unsigned int* counter, unsigned int count, unsigned int* smem) {
+    __shared__ unsigned int base;
+    unsigned int total;
+    const unsigned int ex = block_exclusive_scan<unsigned int>(count, smem, &total);
+    if (threadIdx.x == 0) base = total ? atomicAdd(counter, total) : 0u;
+    __syncthreads();
+    const unsigned int r = base + ex;
+    __syncthreads();
+    return r;
 }
 
 // ---- small vectors of floats for row chunks ---------------------------------------------------

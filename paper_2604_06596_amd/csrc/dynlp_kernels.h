@@ -273,27 +273,39 @@ __global__ void __launch_bounds__(kBlock) k_validate_edges(int64_t m, int64_t n_
 
 // Half-edge i < m has source eu[i]; half-edge m + i has source ev[i].  Count the entries each row
 // will receive and list every row that receives any ("touched" rows).  Out-of-range sources are
-// skipped (the validation kernel reports them).
+// skipped (the validation kernel reports them).  A workgroup takes kAppendItems * kBlock half-edges
+// and appends its first-touched rows with one counter atomic.
 __global__ void __launch_bounds__(kBlock) k_count_halfedges(int64_t m, int64_t n_total, const int32_t* __restrict__ eu,
                                                            const int32_t* __restrict__ ev,
                                                            int32_t* __restrict__ add_cnt,
                                                            int32_t* __restrict__ touched, BatchCtr* bc) {
-    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    bool first = false;
-    int32_t src = -1;
-    if (i < 2 * m) {
-        src = i < m ? eu[i] : ev[i - m];
-        if (src >= 0 && src < n_total) first = atomicAdd(&add_cnt[src], 1) == 0;
+    __shared__ unsigned int smem[kBlock / kWave + 1];
+    const int64_t base = (int64_t)blockIdx.x * kBlock * kAppendItems;
+    int32_t srcs[kAppendItems];
+    unsigned int firstmask = 0;
+#pragma unroll
+    for (int k = 0; k < kAppendItems; ++k) {
+        const int64_t i = base + (int64_t)k * kBlock + threadIdx.x;
+        int32_t src = -1;
+        if (i < 2 * m) {
+            src = i < m ? eu[i] : ev[i - m];
+            if (src >= 0 && src < n_total && atomicAdd(&add_cnt[src], 1) == 0) firstmask |= 1u << k;
+        }
+        srcs[k] = src;
     }
-    const unsigned int slot = wave_reserve(&bc->touched, first);
-    if (first) touched[slot] = src;
+    unsigned int slot = block_reserve(&bc->touched, (unsigned int)__popc(firstmask), smem);
+#pragma unroll
+    for (int k = 0; k < kAppendItems; ++k)
+        if ((firstmask >> k) & 1u) touched[slot++] = srcs[k];
 }
 
-// Rows whose slack cannot take the new entries: total capacity they need at the pool tail.
+// Rows whose slack cannot take the new entries: total capacity they need at the pool tail (one
+// counter atomic per workgroup: atomics on one address run at about 1e8 per second).
 __global__ void __launch_bounds__(kBlock) k_plan_sum(unsigned int nt, const int32_t* __restrict__ touched,
                                                     const RowMeta* __restrict__ meta,
                                                     const int32_t* __restrict__ add_cnt, float slack,
                                                     BatchCtr* bc) {
+    __shared__ unsigned long long part[kBlock / kWave];
     const unsigned int t = blockIdx.x * kBlock + threadIdx.x;
     unsigned long long need_cap = 0;
     if (t < nt) {
@@ -303,15 +315,23 @@ __global__ void __launch_bounds__(kBlock) k_plan_sum(unsigned int nt, const int3
         if (need > m.cap) need_cap = (unsigned long long)row_capacity(need, slack);
     }
     need_cap = wave_sum(need_cap);
-    if (lane_id() == 0 && need_cap) atomicAdd(&bc->reloc_need, need_cap);
+    if (lane_id() == 0) part[threadIdx.x / kWave] = need_cap;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long tot = 0;
+        for (int i = 0; i < kBlock / kWave; ++i) tot += part[i];
+        if (tot) atomicAdd(&bc->reloc_need, tot);
+    }
 }
 
-// Reserve tail space for every overflowing touched row (one atomic per wave); reloc_off[t] is the
-// new offset or -1.
+// Reserve tail space for every overflowing touched row (one tail atomic per workgroup); reloc_off[t]
+// is the new offset or -1.
 __global__ void __launch_bounds__(kBlock) k_plan_reserve(unsigned int nt, const int32_t* __restrict__ touched,
                                                         const RowMeta* __restrict__ meta,
                                                         const int32_t* __restrict__ add_cnt, float slack,
                                                         int64_t* __restrict__ reloc_off, BatchCtr* bc) {
+    __shared__ unsigned long long smem[kBlock / kWave + 1];
+    __shared__ unsigned long long sbase;
     const unsigned int t = blockIdx.x * kBlock + threadIdx.x;
     unsigned long long cap = 0;
     if (t < nt) {
@@ -320,14 +340,15 @@ __global__ void __launch_bounds__(kBlock) k_plan_reserve(unsigned int nt, const 
         const int64_t need = (int64_t)m.len + add_cnt[u];
         if (need > m.cap) cap = (unsigned long long)row_capacity(need, slack);
     }
-    const unsigned long long inc = wave_inclusive_scan(cap);
-    const unsigned long long total = __shfl(inc, kWave - 1, kWave);
-    unsigned long long base = 0;
-    if (lane_id() == kWave - 1 && total) base = atomicAdd(&bc->pool_tail, total);
-    base = __shfl(base, kWave - 1, kWave);
-    const unsigned long long nrel = __popcll(__ballot(cap != 0));
-    if (lane_id() == 0 && nrel) atomicAdd(&bc->relocated, (unsigned int)nrel);
-    if (t < nt) reloc_off[t] = cap ? (int64_t)(base + inc - cap) : -1;
+    unsigned long long total;
+    const unsigned long long ex = block_exclusive_scan<unsigned long long>(cap, smem, &total);
+    const int nrel = __syncthreads_count(cap != 0);
+    if (threadIdx.x == 0) {
+        sbase = total ? atomicAdd(&bc->pool_tail, total) : 0ull;
+        if (nrel) atomicAdd(&bc->relocated, (unsigned int)nrel);
+    }
+    __syncthreads();
+    if (t < nt) reloc_off[t] = cap ? (int64_t)(sbase + ex) : -1;
 }
 
 // Move the valid entries of every relocated row to its new place (16 lanes per row).

@@ -118,19 +118,19 @@ def test_supernode_initialisation_and_convergence_in_the_scalar_layout(mode):
             d.set_initialiser(P.INIT_SUPERNODE, tau)
             d.set_params(TOL, max_iter)
             st, s = d.apply_batch(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
-            out[max_iter] = (st, d.get_labels(), d.last_components())
+            out[max_iter] = (st, d.get_labels(), d.last_components(), soft0)
     n_old = g.n
     g.insert(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
     rp, col, w = g.csr()
     ocomp, count, kept = ON.components(n_old, b.num_new_vertices, b.eu, b.ev, b.ew, float(tau))
+    st0, (init_rows, _), (comp, info), soft0 = out[0]  # the labels that context held before the batch
     F = np.concatenate([soft0.astype(np.float64), np.full((b.num_new_vertices, 2), 0.5)])
     F[b.seed_vertex] = np.eye(2)[b.seed_class]
     F_init, _ = ON.supernode_init(rp, col, w, F, g.seed_class, n_old, ocomp, count)
-    st0, (init_rows, _), (comp, info) = out[0]
     assert np.array_equal(comp, ocomp) and info.components == count
     assert np.max(np.abs(init_rows - F_init)) <= 1e-6
     assert np.abs(F_init[n_old:, 1] - 0.5).max() > 0.4  # the initialisation moved rows
-    st1, (soft, hard), _ = out[20000]
+    st1, (soft, hard), _, _ = out[20000]
     assert st1 == 0
     exact, _, _ = ON.itlp_solve(rp, col, w, g.seed_class, 2, tol=1e-12, max_iter=5_000_000)
     reach = R.seed_reachable(rp, col, g.seed_class)
