@@ -511,6 +511,20 @@ void zero_ring(dynlp_ctx* c) {
 // Slot of round t; round -1 is the start slot that holds the size of the first frontier.
 RoundCtr* slot_of(dynlp_ctx* c, int t) { return t < 0 ? c->ring + kRing : c->ring + (t % kRing); }
 
+// Fold a copied slot's partial records into its header fields.
+void fold_slot(RoundCtr& r) {
+    r.resid_bits = 0;
+    r.changed = 0;
+    r.edges = 0;
+    r.edges_long = 0;
+    for (const RoundPart& p : r.part) {
+        r.resid_bits = std::max(r.resid_bits, p.resid_bits);
+        r.changed += p.changed;
+        r.edges += p.edges;
+        r.edges_long += p.edges_long;
+    }
+}
+
 // Copy the slots of rounds [t0, t0 + count) to the host (count <= kRing) and wait for them.
 void read_slots(dynlp_ctx* c, int t0, int count) {
     for (int i = 0; i < count;) {
@@ -520,6 +534,7 @@ void read_slots(dynlp_ctx* c, int t0, int count) {
         i += run;
     }
     HIPCHK(c, hipStreamSynchronize(c->stream));
+    for (int i = 0; i < count; ++i) fold_slot(c->h_slot[i]);
 }
 
 // Rounds queued per host round trip.

@@ -30,17 +30,34 @@ struct __attribute__((aligned(16))) RowMeta {
 // Counters one propagation round leaves for the host (one slot of a small ring).
 // Rounds are launched in chains without a host round trip: the kernels of round t read the size of
 // their frontier from the slot of round t-1 and leave their own results in the slot of round t.
+//
+// What every workgroup of the row update contributes (max change, rows moved, entries traversed) goes
+// to one of kCtrLanes partial records, each in a cache line of its own: atomics on one address (or one
+// line) run at about 1e8 per second, so 2,048 workgroups hitting one record would cost more than a
+// whole sweep over a 100K-vertex graph.  The host folds the partial records into the header fields
+// after copying a slot; on the device only the static stop rule needs the maximum over them.
+constexpr int kCtrLanes = 32;
+
+struct __attribute__((aligned(64))) RoundPart {
+    unsigned int resid_bits;        // max change, float bits (non-negative floats order as uints)
+    unsigned int changed;           // rows whose change exceeded tol
+    unsigned long long edges;       // CSR entries traversed in short rows
+    unsigned long long edges_long;  // CSR entries traversed in long rows
+    unsigned int pad[10];
+};
+
 struct __attribute__((aligned(64))) RoundCtr {
     unsigned int next_count;   // short rows of V_aff for the next round (written by compaction)
     unsigned int next_long;    // long rows of V_aff for the next round
-    unsigned int resid_bits;   // max change of this round, float bits (non-negative floats order as uints)
-    unsigned int changed;      // rows whose change exceeded tol
-    unsigned long long edges;  // CSR entries traversed in short rows
-    unsigned long long edges_long;  // CSR entries traversed in long rows
+    unsigned int resid_bits;   // header copies of the folded partial records (filled on the host)
+    unsigned int changed;
+    unsigned long long edges;
+    unsigned long long edges_long;
     unsigned int executed;     // 1 if the round updated anything (0: frontier was empty / already converged)
     unsigned int rows_short;   // the frontier this round worked on
     unsigned int rows_long;
     unsigned int pad[5];
+    RoundPart part[kCtrLanes];
 };
 
 // Scalars of the insertion step and error reporting.

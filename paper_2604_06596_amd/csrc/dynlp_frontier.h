@@ -356,9 +356,9 @@ __device__ inline void accumulate_row(const Edge* __restrict__ row, int len, int
     }
 }
 
-// Per-workgroup totals -> one set of atomics on the round's counters.
+// Per-workgroup totals -> one set of atomics on one of the round's partial records.
 __device__ inline void flush_round_counters(float rmax, unsigned long long edges, unsigned int changed,
-                                            RoundCtr* __restrict__ ctr, unsigned long long* edges_field) {
+                                            RoundCtr* __restrict__ ctr, bool long_rows) {
     __shared__ float sm_r[kBlock / kWave];
     __shared__ unsigned long long sm_e[kBlock / kWave];
     __shared__ unsigned int sm_c[kBlock / kWave];
@@ -377,9 +377,10 @@ __device__ inline void flush_round_counters(float rmax, unsigned long long edges
             edges += sm_e[i];
             changed += sm_c[i];
         }
-        atomicMax(&ctr->resid_bits, __float_as_uint(rmax));
-        if (edges) atomicAdd(edges_field, edges);
-        if (changed) atomicAdd(&ctr->changed, changed);
+        RoundPart* p = &ctr->part[blockIdx.x & (kCtrLanes - 1)];
+        if (rmax > 0.f) atomicMax(&p->resid_bits, __float_as_uint(rmax));
+        if (edges) atomicAdd(long_rows ? &p->edges_long : &p->edges, edges);
+        if (changed) atomicAdd(&p->changed, changed);
     }
 }
 
@@ -452,7 +453,7 @@ __device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, 
             nchanged += big ? 1u : 0u;
         }
     }
-    flush_round_counters(rmax, edges, nchanged, ctr, &ctr->edges);
+    flush_round_counters(rmax, edges, nchanged, ctr, false);
 }
 
 // Long rows: one workgroup per row (body; k_row_update dispatches to it).  Its kBlock/G groups take the row's chunks round-robin; their
@@ -535,7 +536,7 @@ __device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, c
         }
         __syncthreads();
     }
-    flush_round_counters(rmax, edges, nchanged, ctr, &ctr->edges_long);
+    flush_round_counters(rmax, edges, nchanged, ctr, true);
 }
 
 // One launch per round.  The frontier's size comes from the previous round's counter slot (prev), so
@@ -556,21 +557,36 @@ __global__ void __launch_bounds__(kBlock) k_row_update(const RoundCtr* __restric
                                                       float tol,
                                                       RoundCtr* __restrict__ ctr,
                                                       RoundCtr* __restrict__ ctr_zero) {
-    if (ctr_zero && blockIdx.x == 0 && threadIdx.x == 0) {
-        ctr_zero->next_count = 0;
-        ctr_zero->next_long = 0;
-        ctr_zero->resid_bits = 0;
-        ctr_zero->changed = 0;
-        ctr_zero->edges = 0;
-        ctr_zero->edges_long = 0;
-        ctr_zero->executed = 0;
-        ctr_zero->rows_short = 0;
-        ctr_zero->rows_long = 0;
+    if (ctr_zero && blockIdx.x == 0) {
+        if (threadIdx.x == 0) {
+            ctr_zero->next_count = 0;
+            ctr_zero->next_long = 0;
+            ctr_zero->executed = 0;
+            ctr_zero->rows_short = 0;
+            ctr_zero->rows_long = 0;
+        }
+        if (threadIdx.x < kCtrLanes) {
+            RoundPart* p = &ctr_zero->part[threadIdx.x];
+            p->resid_bits = 0;
+            p->changed = 0;
+            p->edges = 0;
+            p->edges_long = 0;
+        }
     }
     const unsigned int ns = prev->next_count, nl = prev->next_long;
     if (ns + nl == 0) return;
     if (static_stop) {
-        if (static_stop == 2 && (!prev->executed || prev->resid_bits <= stop_bits)) {
+        unsigned int prev_resid = 0xffffffffu;
+        if (static_stop == 2) {  // max change of the previous sweep: maximum over its partial records
+            const int lane = lane_id();
+            prev_resid = lane < kCtrLanes ? prev->part[lane].resid_bits : 0u;
+#pragma unroll
+            for (int d = kWave / 2; d > 0; d >>= 1) {
+                const unsigned int o = __shfl_xor(prev_resid, d, kWave);
+                prev_resid = o > prev_resid ? o : prev_resid;
+            }
+        }
+        if (static_stop == 2 && (!prev->executed || prev_resid <= stop_bits)) {
             // keep the frontier for whoever reads this slot next
             if (blockIdx.x == 0 && threadIdx.x == 0) {
                 ctr->next_count = ns;
