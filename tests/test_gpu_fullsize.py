@@ -6,8 +6,8 @@ defaults): properties that hold at any size, evaluated by the CPU oracle over th
   one oracle sweep (float64) over the GPU output moves no row by more than the bound of a locally
   stopped run.  A row leaves V_aff once it moves by <= tol; afterwards its neighbours may each keep
   moving by just under tol per round while the slowest mode (decay rate ~ 1 - seed fraction) dies out,
-  so the residual left behind is bounded by about tol / seed fraction, not by tol.  The tests allow half
-  of that (measured: about a quarter).
+  so the residual left behind is bounded by about tol / seed fraction, not by tol (measured: a quarter to
+  two thirds of that bound, depending on the graph and the run).
 * The first rounds of a full-size batch match the oracle's Step-3 loop frontier by frontier.
 * Seeds exactly one-hot, rows are distributions, hard labels are the argmax of the soft labels.
 """
@@ -72,13 +72,13 @@ def _run(name, make_batch, tol, mode=P.UPDATE_SYNCHRONOUS):
     Fn, res = ON.itlp_sweep(rp, col, w.astype(np.float64), F, sc)
     print(f"{name}: batch {s.iterations} rounds, |V_aff|0 = {s.frontier_initial}, peak {s.frontier_peak}, "
           f"oracle residual of the GPU labels {res:.2e}")
-    assert res <= 0.5 * tol * sc.shape[0] / seeds_count(sc)
+    assert res <= tol * sc.shape[0] / seeds_count(sc)
     seeds = np.flatnonzero(sc >= 0)
     assert np.array_equal(soft[seeds], R.initial_labels(sc, C)[seeds].astype(np.float32))
     assert soft.min() >= 0 and np.max(np.abs(soft.sum(1, dtype=np.float64) - 1)) < 2e-5
     assert np.array_equal(hard, np.argmax(soft, axis=1).astype(np.int32))
     # hard labels against the oracle's one-sweep refinement wherever the decision is not marginal
-    clear = R.top2_margin(Fn) > tol * sc.shape[0] / seeds_count(sc)  # twice the residual bound
+    clear = R.top2_margin(Fn) > 2 * tol * sc.shape[0] / seeds_count(sc)  # twice the residual bound
     assert np.array_equal(hard[clear], R.hard_labels(Fn)[clear])
 
 
@@ -280,9 +280,7 @@ def test_cfg3_full_size_mixed_batch_with_deletions(mode):
     Fn, res = ON.itlp_sweep(rp, col, w, soft.astype(np.float64), sc)
     print(f"cfg3 mixed batch: {nd} deleted, {b.num_new_vertices} inserted, {s.iterations} rounds, |V_aff|0 = "
           f"{s.frontier_initial}, oracle residual of the GPU labels {res:.2e}")
-    # the bound of a locally stopped run itself (tol / seed fraction); the insertion-only tests stay within half
-    # of it, a batch that also removes 900 vertices' edges has been measured at 0.6 of it
-    assert res <= tol * sc.shape[0] / seeds_count(sc)
+    assert res <= tol * sc.shape[0] / seeds_count(sc)  # measured at 0.6 of the bound
     gone = dead[np.diff(rp)[dead] == 0]  # the batch's own insertions re-attach some deleted ids
     assert 0 < gone.shape[0] <= nd
     assert np.array_equal(soft[gone], np.full((gone.shape[0], C), np.float32(1.0) / np.float32(C)))
@@ -327,8 +325,7 @@ def test_cfg6_binary_scalar_single_batch_properties(init):
     Fn, res = ON.itlp_sweep(rp, col, w.astype(np.float64), soft.astype(np.float64), sc)
     print(f"cfg6/10 ({init}): {s.iterations} rounds, |V_aff|0 = {s.frontier_initial}, oracle residual of the GPU "
           f"labels {res:.2e}")
-    # the model's bound (tol / seed fraction); on this sparse graph (many rows of degree 1-2, long chains
-    # of sub-threshold moves) the residual has been measured at 0.64 of it
+    # on this sparse graph (many rows of degree 1-2, long chains of sub-threshold moves) measured at 0.64 of the bound
     assert res <= tol * n1 / seeds_count(sc)
     assert np.array_equal(soft[:, 0], np.float32(1.0) - soft[:, 1])
     assert np.array_equal(hard, (soft[:, 1] > 0.5).astype(np.int32))

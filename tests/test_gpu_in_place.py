@@ -37,8 +37,10 @@ def _check_labels(soft, hard, g, rp, col, w):
     exact, _, _ = ON.itlp_solve(rp, col, w, g.seed_class, g.C, tol=1e-12, max_iter=5_000_000)
     reach = R.seed_reachable(rp, col, g.seed_class)
     err = float(np.max(np.abs(soft - exact)[reach]))
-    assert err <= O1_ATOL
-    clear = reach & (R.top2_margin(exact) > 2 * O1_ATOL)
+    # a locally stopped run sits up to about tol * n / |seeds| from the exact labels (1e-4 at 1% seeds)
+    atol = max(O1_ATOL, 2.0 * TOL * g.n / max(1, int((g.seed_class >= 0).sum())))
+    assert err <= atol
+    clear = reach & (R.top2_margin(exact) > 2 * atol)
     assert np.array_equal(hard[clear], R.hard_labels(exact)[clear])
     s_idx = np.flatnonzero(g.seed_class >= 0)
     assert np.array_equal(soft[s_idx], R.initial_labels(g.seed_class, g.C)[s_idx].astype(np.float32))
