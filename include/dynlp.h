@@ -118,8 +118,8 @@ dynlp_status dynlp_create(dynlp_ctx** out, int64_t n, const int64_t* row_ptr, co
                           const int32_t* seed_class, const dynlp_options* opt);
 
 /*
- * Static ItLP (Eq. (1)): Jacobi sweeps over all unlabelled rows with d(u) > 0, starting from the
- * current F, until max_u max_c |F^(k+1) - F^(k)| <= tol or max_iter sweeps.  Also stores tol and
+ * Static ItLP (Eq. (1)): sweeps (Jacobi, or in place: see dynlp_set_update_mode) over all unlabelled rows
+ * with d(u) > 0, starting from the current F, until max_u max_c |F^(k+1) - F^(k)| <= tol or max_iter sweeps.  Also stores tol and
  * max_iter for later dynlp_apply_batch calls.  tol >= 0, max_iter >= 0.  stats may be NULL.
  */
 dynlp_status dynlp_static_solve(dynlp_ctx* ctx, float tol, int32_t max_iter, dynlp_stats* stats);
@@ -191,7 +191,8 @@ dynlp_status dynlp_last_components(dynlp_ctx* ctx, int64_t cap, int32_t* comp, d
  *                      and adds its weight (parallel edge)
  *   seed_vertex/class  num_new_seeds vertices (old or new) that are labelled from now on
  * Step 1: both directions of every edge are appended to their rows (rows whose slack is
- * exhausted move to the pool tail with fresh slack); degrees are updated; new seeds are clamped
+ * exhausted move to the pool tail with fresh slack; the appended entries of a row are then put in
+ * ascending (neighbour id, weight bits) order, so the stored graph does not depend on timing); degrees are updated; new seeds are clamped
  * one-hot; V_aff = inserted vertices, endpoints of inserted edges and neighbours of new seeds,
  * without seeds and isolated vertices.  Step 3: rounds of F'_u = sum_v w(u,v) F_v / d(u) for
  * u in V_aff from the round-start F; every F'_u is stored; u with max_c |F'_u - F_u| > tol
@@ -239,8 +240,9 @@ int32_t dynlp_num_classes(const dynlp_ctx* ctx);
 
 /*
  * Copy the graph out as a compact CSR (inspection and tests): row_ptr n+1 offsets, col/w
- * dynlp_num_entries() entries in stored order (within a row: creation order, then insertion
- * order, which for edges of one batch is unspecified); degree: n floats d(u) as maintained by the
+ * dynlp_num_entries() entries in stored order (within a row: the entries given to dynlp_create in
+ * their order, then batch by batch the entries that batch added, each batch's in ascending order
+ * of (neighbour id, weight bit pattern); deletions keep the order of what remains); degree: n floats d(u) as maintained by the
  * insertion step, or NULL; seed_class: n int32, -1 for unlabelled, or NULL.
  */
 dynlp_status dynlp_export_graph(dynlp_ctx* ctx, int64_t* row_ptr, int32_t* col, float* w, float* degree,

@@ -1245,6 +1245,13 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
                                c->meta, c->add_cnt, c->slack, c->reloc_off, c->pool);
             hipLaunchKernelGGL(k_write_halfedges, dim3(grid_for(2 * m)), dim3(kBlock), 0, c->stream, m, d_eu, d_ev, d_ew,
                                c->meta, c->pool);
+            // the batch's entries of every row in a fixed order (the relocation offsets are no longer needed:
+            // their array holds the list of rows with long appended segments)
+            int32_t* long_list = reinterpret_cast<int32_t*>(c->reloc_off);
+            hipLaunchKernelGGL(k_sort_segments, dim3(grid_for((int64_t)nt * 16)), dim3(kBlock), 0, c->stream, nt, c->touched,
+                               c->meta, c->pool, c->add_cnt, long_list, c->bc);
+            hipLaunchKernelGGL(k_sort_long_segments, dim3(std::min<unsigned int>(nt, 512u)), dim3(kBlock), 0, c->stream,
+                               long_list, c->meta, c->pool, c->add_cnt, c->bc);
             hipLaunchKernelGGL(k_finish_rows, dim3(grid_for((int64_t)nt * 16)), dim3(kBlock), 0, c->stream, nt, c->touched,
                                c->meta, c->pool, c->add_cnt, c->deg, c->flag);
             HIPCHK(c, hipGetLastError());

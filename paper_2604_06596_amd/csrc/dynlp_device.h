@@ -10,6 +10,7 @@ constexpr int kWave = 64;
 constexpr int kBlock = 256;       // threads per workgroup for every kernel here
 constexpr int kRowAlign = 8;      // row capacities are multiples of 8 entries = 64 bytes
 constexpr int kRing = 64;         // per-round counter slots
+constexpr int kSortRegs = 8;      // appended entries per lane the in-register segment sort can hold (16 lanes per row)
 constexpr int kAppendItems = 8;   // items per thread in kernels that append to a list (one counter atomic per 2,048 items)
 constexpr int kInitChain = 4;     // hook/jump steps of the component search queued per host round trip
 
@@ -75,6 +76,8 @@ struct __attribute__((aligned(64))) BatchCtr {
     unsigned int upd_short;          // updatable vertices (unlabelled, >= 1 edge): short rows
     unsigned int upd_long;           //                                              long rows
     unsigned long long removed;      // CSR entries removed by the deletion step
+    unsigned int sort_long;          // touched rows whose appended segment is sorted by a whole workgroup
+    unsigned int sort_pad;
 };
 
 enum ValidationError : int {

@@ -392,6 +392,106 @@ __global__ void __launch_bounds__(kBlock) k_write_halfedges(int64_t m, const int
     pool[meta[src].off + slot] = e;
 }
 
+// The entries one batch appends to a row land in the order their atomics happened to take.  Sorting
+// the appended segment by (neighbour id, weight bits) makes the stored row, and with it every sum
+// over the row, a function of the batch alone.  16 lanes per touched row; segments of up to
+// 16 * kSortRegs entries are rank-sorted in registers (every key is broadcast to the group once),
+// longer ones are queued for k_sort_long_segments.
+__device__ inline unsigned long long edge_key(const Edge& e) {
+    return ((unsigned long long)(unsigned int)e.col << 32) | (unsigned long long)__float_as_uint(e.w);
+}
+
+__device__ inline Edge key_edge(unsigned long long k) {
+    Edge e;
+    e.col = (int32_t)(unsigned int)(k >> 32);
+    e.w = __uint_as_float((unsigned int)(k & 0xffffffffull));
+    return e;
+}
+
+__global__ void __launch_bounds__(kBlock) k_sort_segments(unsigned int nt, const int32_t* __restrict__ touched,
+                                                         const RowMeta* __restrict__ meta, Edge* __restrict__ pool,
+                                                         const int32_t* __restrict__ add_cnt,
+                                                         int32_t* __restrict__ long_list, BatchCtr* bc) {
+    constexpr int G = 16;
+    const unsigned int t = (blockIdx.x * kBlock + threadIdx.x) / G;
+    const int gl = threadIdx.x % G;
+    if (t >= nt) return;
+    const int32_t u = touched[t];
+    const int a = add_cnt[u];
+    if (a <= 1) return;
+    const RowMeta m = meta[u];
+    Edge* seg = pool + m.off + (m.len - a);
+    if (a > G * kSortRegs) {
+        if (gl == 0) long_list[atomicAdd(&bc->sort_long, 1u)] = u;
+        return;
+    }
+    const int slots = (a + G - 1) / G;  // uniform in the group
+    unsigned long long key[kSortRegs];
+#pragma unroll
+    for (int r = 0; r < kSortRegs; ++r) {
+        const int j = r * G + gl;
+        key[r] = (r < slots && j < a) ? edge_key(seg[j]) : ~0ull;
+    }
+    int rank[kSortRegs];
+#pragma unroll
+    for (int r = 0; r < kSortRegs; ++r) rank[r] = 0;
+#pragma unroll
+    for (int r2 = 0; r2 < kSortRegs; ++r2) {
+        if (r2 < slots) {
+            for (int l = 0; l < G; ++l) {
+                const unsigned int hi = __shfl((unsigned int)(key[r2] >> 32), l, G);
+                const unsigned int lo = __shfl((unsigned int)(key[r2] & 0xffffffffull), l, G);
+                const unsigned long long other = ((unsigned long long)hi << 32) | lo;
+                const int oj = r2 * G + l;
+#pragma unroll
+                for (int r = 0; r < kSortRegs; ++r) {
+                    const int j = r * G + gl;
+                    rank[r] += (other < key[r] || (other == key[r] && oj < j)) ? 1 : 0;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kSortRegs; ++r) {
+        const int j = r * G + gl;
+        if (r < slots && j < a) seg[rank[r]] = key_edge(key[r]);
+    }
+}
+
+// Long appended segments: one workgroup per row sorts the segment in place with a bitonic network
+// whose compare-exchanges all point the same way (the first step of every merge pairs i with its
+// mirror image inside the block), so positions past the end act as +infinity without being stored.
+__global__ void __launch_bounds__(kBlock) k_sort_long_segments(const int32_t* __restrict__ long_list,
+                                                              const RowMeta* __restrict__ meta, Edge* pool,
+                                                              const int32_t* __restrict__ add_cnt,
+                                                              const BatchCtr* bc) {
+    const unsigned int count = bc->sort_long;
+    for (unsigned int q = blockIdx.x; q < count; q += gridDim.x) {  // uniform per workgroup
+        const int32_t u = long_list[q];
+        const int a = add_cnt[u];
+        const RowMeta m = meta[u];
+        Edge* seg = pool + m.off + (m.len - a);
+        unsigned int P = 1;
+        while (P < (unsigned int)a) P <<= 1;
+        for (unsigned int k = 2; k <= P; k <<= 1) {
+            for (unsigned int j = k >> 1; j > 0; j >>= 1) {
+                const unsigned int mask = (j == (k >> 1)) ? (k - 1) : j;
+                for (unsigned int i = threadIdx.x; i < (unsigned int)a; i += kBlock) {
+                    const unsigned int l = i ^ mask;
+                    if (l > i && l < (unsigned int)a) {
+                        const Edge x = seg[i], y = seg[l];
+                        if (edge_key(y) < edge_key(x)) {
+                            seg[i] = y;
+                            seg[l] = x;
+                        }
+                    }
+                }
+                __syncthreads();
+            }
+        }
+    }
+}
+
 // Touched rows: recompute d(u) from the stored row, clear the counting scratch, and put the row
 // into V_aff (both endpoints of every inserted edge are affected).
 __global__ void __launch_bounds__(kBlock) k_finish_rows(unsigned int nt, const int32_t* __restrict__ touched,
