@@ -167,6 +167,30 @@ def itlp_solve(row_ptr, col, w, seed_class, C, tol=1e-10, max_iter=1_000_000, F0
     return F, it, change
 
 
+def itlp_solve_in_place(row_ptr, col, w, seed_class, C, tol=1e-10, max_iter=1_000_000, F0=None, order=None):
+    """Eq. (1) applied row after row on one array: a row's new value is visible to the rows that
+    come later in the same sweep (what Alg. 2's loop over V_aff does when it runs on a single
+    label array).  ``order``: the sequence in which the unlabelled rows are visited (default: by
+    id).  Same stop rule as itlp_solve (largest change of a sweep <= tol).  Returns
+    (F, sweeps, last_change)."""
+    seed_class = np.asarray(seed_class)
+    F = initial_labels(seed_class, C) if F0 is None else np.array(F0, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    rows = [u for u in (range(seed_class.shape[0]) if order is None else order)
+            if seed_class[u] < 0 and row_ptr[u + 1] > row_ptr[u]]
+    change = 0.0
+    for sweep in range(1, max_iter + 1):
+        change = 0.0
+        for u in rows:
+            a, b = row_ptr[u], row_ptr[u + 1]
+            new = (w[a:b, None] * F[col[a:b]]).sum(axis=0) / w[a:b].sum()
+            change = max(change, float(np.max(np.abs(new - F[u]))))
+            F[u] = new
+        if change <= tol:
+            return F, sweep, change
+    return F, max_iter, change
+
+
 def recompute_from_scratch(graph: Graph, tol=1e-10, max_iter=1_000_000):
     """Alg. 1 Step 2 with ItLP in place of the dense inverse: labels of the *current* graph
     from the uniform start."""

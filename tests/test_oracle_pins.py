@@ -223,3 +223,20 @@ def test_hard_labels_lowest_index_on_ties():
     F3 = np.array([[0.3, 0.35, 0.35]])
     assert R.hard_labels(F3).tolist() == [1]
     assert abs(R.top2_margin(F3)[0]) < 1e-16
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_in_place_sweeps_share_the_fixed_point_and_need_fewer_sweeps(seed):
+    """Updating rows on one array (any visiting order) converges to the same harmonic labels as the
+    Jacobi form of Eq. (1): the basis of the library's in-place update mode."""
+    p = W.small_random(300, 3, 4.0, 15, seed)
+    g = R.Graph(p.n, p.row_ptr, p.col, p.w, p.C, p.seed_vertex, p.seed_class)
+    rp, col, w = g.csr()
+    exact = R.harmonic_closed_form(rp, col, w, g.seed_class, p.C)
+    Fj, sweeps_j, _ = R.itlp_solve(rp, col, w, g.seed_class, p.C, tol=1e-11)
+    order = np.random.default_rng(seed).permutation(p.n).tolist()
+    for o in (None, order, order[::-1]):
+        Fg, sweeps_g, _ = R.itlp_solve_in_place(rp, col, w, g.seed_class, p.C, tol=1e-11, order=o)
+        assert np.abs(Fg - exact).max() < 1e-8
+        assert sweeps_g < sweeps_j
+    assert np.abs(Fj - exact).max() < 1e-8
