@@ -248,6 +248,18 @@ int32_t dynlp_num_classes(const dynlp_ctx* ctx);
 dynlp_status dynlp_export_graph(dynlp_ctx* ctx, int64_t* row_ptr, int32_t* col, float* w, float* degree,
                                 int32_t* seed_class);
 
+/*
+ * Storage of the mutable CSR.  Rows that outgrow their slack move to the end of the entry pool and
+ * deleted entries are only dropped from their rows, so the pool's used part grows with every batch
+ * even when the graph does not.  dynlp_storage_info reports the used part and the capacity (in
+ * entries of 8 bytes; either pointer may be NULL; host memory).  dynlp_compact_storage lays all rows
+ * out again in id order, each with fresh slack, in a new pool of the size that needs (plus a quarter
+ * for growth) and releases the old one; graph, labels and every later result are unchanged.  It needs
+ * room for both pools at once.
+ */
+dynlp_status dynlp_storage_info(const dynlp_ctx* ctx, int64_t* pool_used, int64_t* pool_capacity);
+dynlp_status dynlp_compact_storage(dynlp_ctx* ctx);
+
 /* One propagation round of the last dynlp_static_solve / dynlp_apply_batch. */
 typedef struct dynlp_round_info {
     int64_t rows_short;    /* |V_aff| of the round, split by how the row was updated: rows of at most 512 */

@@ -67,7 +67,8 @@ class Options(ct.Structure):
 EXPORTS = ["dynlp_default_options", "dynlp_create", "dynlp_static_solve", "dynlp_set_params", "dynlp_apply_batch",
            "dynlp_get_labels", "dynlp_num_vertices", "dynlp_num_entries", "dynlp_num_classes", "dynlp_export_graph",
            "dynlp_round_log", "dynlp_last_error", "dynlp_destroy", "dynlp_set_initialiser",
-           "dynlp_mean_edge_weight", "dynlp_last_components", "dynlp_set_update_mode", "dynlp_apply_update"]
+           "dynlp_mean_edge_weight", "dynlp_last_components", "dynlp_set_update_mode", "dynlp_apply_update", "dynlp_storage_info",
+           "dynlp_compact_storage"]
 
 _lib = None
 
@@ -113,6 +114,10 @@ def load_library(path: str | None = None):
     L.dynlp_export_graph.restype = ct.c_int
     L.dynlp_round_log.argtypes = [p, i64, ct.POINTER(RoundInfo)]
     L.dynlp_round_log.restype = i64
+    L.dynlp_storage_info.argtypes = [p, ct.POINTER(i64), ct.POINTER(i64)]
+    L.dynlp_storage_info.restype = ct.c_int
+    L.dynlp_compact_storage.argtypes = [p]
+    L.dynlp_compact_storage.restype = ct.c_int
     L.dynlp_set_update_mode.argtypes = [p, i32]
     L.dynlp_set_update_mode.restype = ct.c_int
     L.dynlp_set_initialiser.argtypes = [p, i32, f32]
@@ -208,6 +213,16 @@ class DynLP:
 
     def set_params(self, tol, max_iter):
         self._check(self._L.dynlp_set_params(self._h, float(tol), int(max_iter)))
+
+    def storage_info(self):
+        """dynlp_storage_info.  Returns (pool entries in use, pool capacity)."""
+        used, cap = ct.c_int64(0), ct.c_int64(0)
+        self._check(self._L.dynlp_storage_info(self._h, ct.byref(used), ct.byref(cap)))
+        return int(used.value), int(cap.value)
+
+    def compact_storage(self):
+        """dynlp_compact_storage."""
+        self._check(self._L.dynlp_compact_storage(self._h))
 
     def set_update_mode(self, mode):
         """dynlp_set_update_mode: UPDATE_SYNCHRONOUS or UPDATE_IN_PLACE."""

@@ -926,6 +926,55 @@ dynlp_status dynlp_set_params(dynlp_ctx* ctx, float tol, int32_t max_iter) {
     return DYNLP_OK;
 }
 
+dynlp_status dynlp_storage_info(const dynlp_ctx* c, int64_t* pool_used, int64_t* pool_capacity) {
+    if (!c) return DYNLP_ERR_INVALID_ARG;
+    if (pool_used) *pool_used = c->pool_tail;
+    if (pool_capacity) *pool_capacity = c->pool_cap;
+    return DYNLP_OK;
+}
+
+dynlp_status dynlp_compact_storage(dynlp_ctx* c) {
+    if (!c) return DYNLP_ERR_INVALID_ARG;
+    if (c->poisoned) {
+        c->err = "context is unusable after an earlier device or memory error";
+        return DYNLP_ERR_STATE;
+    }
+    if (c->n == 0) return DYNLP_OK;
+    RowMeta* meta_new = nullptr;
+    int64_t* block_sums = nullptr;
+    Edge* pool_new = nullptr;
+    try {
+        HIPCHK(c, hipSetDevice(c->device));
+        const int64_t n = c->n;
+        const int64_t nb = grid_for(n);
+        meta_new = dev_alloc_n<RowMeta>(c, c->n_cap);
+        block_sums = dev_alloc_n<int64_t>(c, nb);
+        hipLaunchKernelGGL(k_recap_rows, dim3(nb), dim3(kBlock), 0, c->stream, n, c->meta, c->slack, meta_new, block_sums);
+        HIPCHK(c, hipGetLastError());
+        const int64_t tail = scan_block_sums(c, nb, block_sums);
+        hipLaunchKernelGGL(k_row_offsets, dim3(nb), dim3(kBlock), 0, c->stream, n, meta_new, block_sums);
+        const int64_t cap = round_up(tail + tail / 4 + (1 << 16), kRowAlign);
+        pool_new = dev_alloc_n<Edge>(c, cap);
+        hipLaunchKernelGGL(k_copy_rows, dim3(grid_for(n * 16)), dim3(kBlock), 0, c->stream, n, c->meta, meta_new, c->pool,
+                           pool_new);
+        HIPCHK(c, hipGetLastError());
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        dev_free(c, c->meta);
+        dev_free(c, c->pool);
+        dev_free(c, block_sums);
+        c->meta = meta_new;
+        c->pool = pool_new;
+        c->pool_cap = cap;
+        c->pool_tail = tail;
+        return DYNLP_OK;
+    } catch (const Fail& f) {
+        return f.st;
+    } catch (const std::bad_alloc&) {
+        c->err = "host allocation failed";
+        return DYNLP_ERR_OOM;
+    }
+}
+
 dynlp_status dynlp_set_update_mode(dynlp_ctx* ctx, int32_t mode) {
     if (!ctx) return DYNLP_ERR_INVALID_ARG;
     if (mode != DYNLP_UPDATE_SYNCHRONOUS && mode != DYNLP_UPDATE_IN_PLACE) {

@@ -636,6 +636,38 @@ __global__ void __launch_bounds__(kBlock) k_drop_deleted_entries(unsigned int nt
 }
 
 // =================================================================================================
+// Storage compaction: rows laid out again in id order with fresh slack (reclaims what relocations
+// and deletions left behind)
+// =================================================================================================
+__global__ void __launch_bounds__(kBlock) k_recap_rows(int64_t n, const RowMeta* __restrict__ meta_old, float slack,
+                                                      RowMeta* __restrict__ meta_new,
+                                                      int64_t* __restrict__ block_sums) {
+    __shared__ int64_t sm[kBlock / kWave + 1];
+    const int64_t u = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    int64_t cap = 0;
+    if (u < n) {
+        const int32_t len = meta_old[u].len;
+        cap = row_capacity(len, slack);
+        meta_new[u].len = len;
+        meta_new[u].cap = (int32_t)cap;
+    }
+    int64_t total;
+    block_exclusive_scan<int64_t>(cap, sm, &total);
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
+}
+
+__global__ void __launch_bounds__(kBlock) k_copy_rows(int64_t n, const RowMeta* __restrict__ meta_old,
+                                                     const RowMeta* __restrict__ meta_new,
+                                                     const Edge* __restrict__ pool_old, Edge* __restrict__ pool_new) {
+    constexpr int G = 16;
+    const int64_t u = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / G;
+    const int gl = threadIdx.x % G;
+    if (u >= n) return;
+    const RowMeta a = meta_old[u], b = meta_new[u];
+    for (int j = gl; j < a.len; j += G) pool_new[b.off + j] = pool_old[a.off + j];
+}
+
+// =================================================================================================
 // Export (inspection / tests)
 // =================================================================================================
 __global__ void __launch_bounds__(kBlock) k_row_lens(int64_t n, const RowMeta* __restrict__ meta,
