@@ -334,7 +334,11 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": dom, "launches": launches,
                      "avg_launch_us": k_ms * 1e3 / max(1, launches),
-                     "algorithmic_bytes_per_launch": alg_bytes / max(1, launches)},
+                     "algorithmic_bytes_per_launch": alg_bytes / max(1, launches),
+                     # what the counters say the same launch moves on the HBM side, as a rate (context: `frac`
+                     # above is the algorithmic one)
+                     "traffic_GBs": (traffic / (k_ms * 1e6 / max(1, launches))) if traffic else None,
+                     "traffic_frac": (traffic / (k_ms * 1e6 / max(1, launches)) / HBM_PEAK_GBS) if traffic else None},
         "detail": {"rounds_per_step": [x["iterations"] for x in per_step],
                    "frontier_initial": [x["frontier_initial"] for x in per_step],
                    "frontier_peak": [x["frontier_peak"] for x in per_step],
