@@ -81,7 +81,7 @@ def build_workload(name: str, batch_frac: float, num_batches: int, batch_kind: s
     return cfg, base, batches, label
 
 
-def cpu_baseline(base, batches_applied, batch, F_before, tol, gpu_edges_traversed, budget_s):
+def cpu_baseline(base, batches_applied, batch, F_before, tol, gpu_edges_traversed, budget_s, F_cold=None, F_after=None):
     """Oracle Step 3 on the host cores for the first rounds of ``batch`` (bounded by budget_s),
     scaled to the metric's unit with the total work the GPU needed for the same batch."""
     from oracle import native as ON
@@ -96,6 +96,9 @@ def cpu_baseline(base, batches_applied, batch, F_before, tol, gpu_edges_traverse
         w64 = base["w"].astype(np.float64)
         F = F_before[:base["n"]].astype(np.float64)
         entries_per_sweep = int(np.diff(base["row_ptr"])[sc < 0].sum())
+        residual = None
+        if F_cold is not None:  # how far one exact sweep moves the labels the GPU's cold start ended with
+            _, residual = ON.itlp_sweep(base["row_ptr"], base["col"], w64, F_cold.astype(np.float64), sc)
         t0 = time.perf_counter()
         F, _ = ON.itlp_sweep(base["row_ptr"], base["col"], w64, F, sc)
         probe = time.perf_counter() - t0
@@ -112,7 +115,9 @@ def cpu_baseline(base, batches_applied, batch, F_before, tol, gpu_edges_traverse
                            f"sweeps = {edges} CSR entries in {t_used:.2f} s = {edges_per_s / 1e6:.1f} M entries/s; "
                            f"whole-batch latency extrapolated to the {gpu_edges_traversed} entries the full update "
                            f"traverses = {est_latency:.1f} s",
-                    traversed_entries_per_s=edges_per_s)
+                    traversed_entries_per_s=edges_per_s,
+                    oracle_residual=dict(state="GPU labels after the cold start, one float64 sweep over the base graph",
+                                         max_change=residual))
 
     g = R.Graph(base["n"], base["row_ptr"], base["col"], base["w"], base["C"], base["seed_vertex"], base["seed_class"])
     for b in batches_applied:
@@ -141,7 +146,10 @@ def cpu_baseline(base, batches_applied, batch, F_before, tol, gpu_edges_traverse
                        f"{edges} CSR entries traversed in {t_used:.2f} s = {edges_per_s / 1e6:.1f} M entries/s; "
                        f"whole-batch latency extrapolated to the {gpu_edges_traversed} entries the full update traverses "
                        f"= {est_latency:.1f} s",
-                traversed_entries_per_s=edges_per_s)
+                traversed_entries_per_s=edges_per_s,
+                oracle_residual=dict(state="GPU labels after the first timed batch, one float64 sweep over the updated graph",
+                                     max_change=(ON.itlp_sweep(rp, col, w, F_after.astype(np.float64), g.seed_class)[1]
+                                                 if F_after is not None else None)))
 
 
 def main():
@@ -247,6 +255,12 @@ def main():
                 max(s0.ms_update_kernel, 1e-9))
     init_info = []
     F_before = None
+    F_after = None
+    big = base["col"].shape[0] > 100_000_000
+    F_cold = None
+    if args.cpu_budget > 0 and not fresh and big:
+        F_cold = d.get_labels(soft=True, hard=False)[0]
+        F_cold = F_cold if args.host_inputs else F_cold.cpu().numpy()
     per_step = []
     round_profile = []
     buckets = {}
@@ -280,6 +294,9 @@ def main():
                 b[1] += int(r.rows_short + r.rows_long)
                 b[2] += int(r.entries_short + r.entries_long)
                 b[3] += float(r.ms_update)
+            if len(per_step) == 1 and args.cpu_budget > 0 and not fresh and not big and args.delete_frac == 0:
+                F_after = d.get_labels(soft=True, hard=False)[0]
+                F_after = F_after if args.host_inputs else F_after.cpu().numpy()
             if len(per_step) == 1:  # how the row-update kernels behave as V_aff grows and shrinks
                 pick = sorted(set(np.linspace(0, len(info) - 1, num=min(16, len(info))).astype(int).tolist()))
                 round_profile = [dict(round=int(j), frontier=int(info[j].rows_short + info[j].rows_long),
@@ -359,7 +376,7 @@ def main():
     }
     if args.cpu_budget > 0 and per_step and not fresh:
         out["cpu_baseline"] = cpu_baseline(base, batches[:args.warmup], batches[args.warmup], F_before, tol,
-                                           per_step[0]["edges_traversed"], args.cpu_budget)
+                                           per_step[0]["edges_traversed"], args.cpu_budget, F_cold=F_cold, F_after=F_after)
     else:
         out["cpu_baseline"] = None
     d.destroy()
