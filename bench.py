@@ -250,6 +250,8 @@ def main():
         return ctx, st_, s_, t_
 
     d, st, s0, tau = new_context()
+    # what plain streaming kernels sustain on this machine: 1 GiB copy (read + write) and 1 GiB read-only pass
+    copy_gbs, read_gbs = d.stream_bandwidth(1 << 30, 10)
     cold = dict(status=st, sweeps=s0.iterations, ms=s0.ms_total, ms_update_kernel=s0.ms_update_kernel,
                 algorithmic_gbs=algorithmic_bytes(s0.rows_updated, s0.edges_traversed, Cs) / 1e6 /
                 max(s0.ms_update_kernel, 1e-9))
@@ -354,6 +356,7 @@ def main():
                      "algorithmic_bytes_per_launch": alg_bytes / max(1, launches),
                      # what the counters say the same launch moves on the HBM side, as a rate (context: `frac`
                      # above is the algorithmic one)
+                     "stream_copy_GBs": copy_gbs, "stream_read_GBs": read_gbs, "frac_of_stream_read": achieved / read_gbs,
                      "traffic_GBs": (traffic / (k_ms * 1e6 / max(1, launches))) if traffic else None,
                      "traffic_frac": (traffic / (k_ms * 1e6 / max(1, launches)) / HBM_PEAK_GBS) if traffic else None},
         "detail": {"rounds_per_step": [x["iterations"] for x in per_step],

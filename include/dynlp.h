@@ -260,6 +260,16 @@ dynlp_status dynlp_export_graph(dynlp_ctx* ctx, int64_t* row_ptr, int32_t* col, 
 dynlp_status dynlp_storage_info(const dynlp_ctx* ctx, int64_t* pool_used, int64_t* pool_capacity);
 dynlp_status dynlp_compact_storage(dynlp_ctx* ctx);
 
+/*
+ * Yardsticks for bandwidth figures, measured on the context's stream with two temporary device
+ * buffers of `bytes` bytes (rounded down to 16): `repetitions` launches of a plain float4 streaming
+ * copy -> *copy_gb_per_s = (bytes read + bytes written) / time; then of a read-only pass that sums
+ * what it reads -> *read_gb_per_s = bytes read / time.  Both outputs are host memory, either may be
+ * NULL.
+ */
+dynlp_status dynlp_stream_bandwidth(dynlp_ctx* ctx, int64_t bytes, int32_t repetitions, double* copy_gb_per_s,
+                                    double* read_gb_per_s);
+
 /* One propagation round of the last dynlp_static_solve / dynlp_apply_batch. */
 typedef struct dynlp_round_info {
     int64_t rows_short;    /* |V_aff| of the round, split by how the row was updated: rows of at most 512 */

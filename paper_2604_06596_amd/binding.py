@@ -68,7 +68,7 @@ EXPORTS = ["dynlp_default_options", "dynlp_create", "dynlp_static_solve", "dynlp
            "dynlp_get_labels", "dynlp_num_vertices", "dynlp_num_entries", "dynlp_num_classes", "dynlp_export_graph",
            "dynlp_round_log", "dynlp_last_error", "dynlp_destroy", "dynlp_set_initialiser",
            "dynlp_mean_edge_weight", "dynlp_last_components", "dynlp_set_update_mode", "dynlp_apply_update", "dynlp_storage_info",
-           "dynlp_compact_storage"]
+           "dynlp_compact_storage", "dynlp_stream_bandwidth"]
 
 _lib = None
 
@@ -116,6 +116,8 @@ def load_library(path: str | None = None):
     L.dynlp_round_log.restype = i64
     L.dynlp_storage_info.argtypes = [p, ct.POINTER(i64), ct.POINTER(i64)]
     L.dynlp_storage_info.restype = ct.c_int
+    L.dynlp_stream_bandwidth.argtypes = [p, i64, i32, ct.POINTER(ct.c_double), ct.POINTER(ct.c_double)]
+    L.dynlp_stream_bandwidth.restype = ct.c_int
     L.dynlp_compact_storage.argtypes = [p]
     L.dynlp_compact_storage.restype = ct.c_int
     L.dynlp_set_update_mode.argtypes = [p, i32]
@@ -219,6 +221,12 @@ class DynLP:
         used, cap = ct.c_int64(0), ct.c_int64(0)
         self._check(self._L.dynlp_storage_info(self._h, ct.byref(used), ct.byref(cap)))
         return int(used.value), int(cap.value)
+
+    def stream_bandwidth(self, nbytes=1 << 30, repetitions=10):
+        """dynlp_stream_bandwidth: (GB/s of a plain copy, read + written; GB/s of a read-only pass)."""
+        cp, rd = ct.c_double(0.0), ct.c_double(0.0)
+        self._check(self._L.dynlp_stream_bandwidth(self._h, int(nbytes), int(repetitions), ct.byref(cp), ct.byref(rd)))
+        return float(cp.value), float(rd.value)
 
     def compact_storage(self):
         """dynlp_compact_storage."""

@@ -926,6 +926,49 @@ dynlp_status dynlp_set_params(dynlp_ctx* ctx, float tol, int32_t max_iter) {
     return DYNLP_OK;
 }
 
+dynlp_status dynlp_stream_bandwidth(dynlp_ctx* c, int64_t bytes, int32_t repetitions, double* copy_gb_per_s,
+                                    double* read_gb_per_s) {
+    if (!c) return DYNLP_ERR_INVALID_ARG;
+    if (bytes < 16 || repetitions < 1) {
+        c->err = "bytes < 16 or repetitions < 1";
+        return DYNLP_ERR_INVALID_ARG;
+    }
+    float4 *src = nullptr, *dst = nullptr;
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    try {
+        HIPCHK(c, hipSetDevice(c->device));
+        const int64_t n16 = bytes / 16;
+        const unsigned int blocks = (unsigned int)std::min<int64_t>(grid_for(n16), (int64_t)c->num_cu * 16);
+        src = static_cast<float4*>(dev_alloc(c, (size_t)n16 * 16));
+        dst = static_cast<float4*>(dev_alloc(c, std::max<size_t>((size_t)n16 * 16, (size_t)blocks * kBlock * sizeof(float))));
+        HIPCHK(c, hipMemsetAsync(src, 0, (size_t)n16 * 16, c->stream));
+        for (hipEvent_t& e : ev) HIPCHK(c, hipEventCreate(&e));
+        hipLaunchKernelGGL(k_stream_copy, dim3(blocks), dim3(kBlock), 0, c->stream, n16, src, dst);  // warm-up
+        HIPCHK(c, hipEventRecord(ev[0], c->stream));
+        for (int r = 0; r < repetitions; ++r)
+            hipLaunchKernelGGL(k_stream_copy, dim3(blocks), dim3(kBlock), 0, c->stream, n16, src, dst);
+        HIPCHK(c, hipEventRecord(ev[1], c->stream));
+        for (int r = 0; r < repetitions; ++r)
+            hipLaunchKernelGGL(k_stream_read, dim3(blocks), dim3(kBlock), 0, c->stream, n16, src,
+                               reinterpret_cast<float*>(dst));
+        HIPCHK(c, hipEventRecord(ev[2], c->stream));
+        HIPCHK(c, hipGetLastError());
+        HIPCHK(c, hipEventSynchronize(ev[2]));
+        float ms_copy = 0.f, ms_read = 0.f;
+        HIPCHK(c, hipEventElapsedTime(&ms_copy, ev[0], ev[1]));
+        HIPCHK(c, hipEventElapsedTime(&ms_read, ev[1], ev[2]));
+        const double moved = (double)n16 * 16.0 * repetitions;
+        if (copy_gb_per_s) *copy_gb_per_s = 2.0 * moved / ((double)ms_copy * 1e6);  // bytes read + bytes written
+        if (read_gb_per_s) *read_gb_per_s = moved / ((double)ms_read * 1e6);
+        for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+        dev_free(c, src);
+        dev_free(c, dst);
+        return DYNLP_OK;
+    } catch (const Fail& f) {
+        return f.st;
+    }
+}
+
 dynlp_status dynlp_storage_info(const dynlp_ctx* c, int64_t* pool_used, int64_t* pool_capacity) {
     if (!c) return DYNLP_ERR_INVALID_ARG;
     if (pool_used) *pool_used = c->pool_tail;

@@ -668,6 +668,28 @@ __global__ void __launch_bounds__(kBlock) k_copy_rows(int64_t n, const RowMeta* 
 }
 
 // =================================================================================================
+// Yardstick: a plain streaming copy (what this chip sustains when every byte is used once)
+// =================================================================================================
+__global__ void __launch_bounds__(kBlock) k_stream_copy(int64_t n16, const float4* __restrict__ src,
+                                                       float4* __restrict__ dst) {
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+// Read-only counterpart (the row update reads about 40 times what it writes): every thread sums what
+// it reads and stores one float, so that the loads cannot be dropped.
+__global__ void __launch_bounds__(kBlock) k_stream_read(int64_t n16, const float4* __restrict__ src,
+                                                       float* __restrict__ sink) {
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    float acc = 0.f;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n16; i += stride) {
+        const float4 v = src[i];
+        acc += (v.x + v.y) + (v.z + v.w);
+    }
+    sink[(int64_t)blockIdx.x * kBlock + threadIdx.x] = acc;
+}
+
+// =================================================================================================
 // Export (inspection / tests)
 // =================================================================================================
 __global__ void __launch_bounds__(kBlock) k_row_lens(int64_t n, const RowMeta* __restrict__ meta,

@@ -335,3 +335,49 @@ def test_cfg6_binary_scalar_single_batch_properties(init):
     assert np.all(soft[lone[sc[lone] < 0]] == 0.5)  # isolated unlabelled vertices keep the neutral value
     clear = R.top2_margin(Fn) > 2 * tol * n1 / seeds_count(sc)
     assert np.array_equal(hard[clear], R.hard_labels(Fn)[clear])
+
+
+def test_cfg5_stream_of_fifty_batches_tracks_the_exact_labels():
+    """The edge-stream configuration over many batches (a tenth of its size so that the exact labels can be
+    recomputed on the host): edge-only batches plus newly labelled old vertices, in-place mode, drift from the
+    exact labels of the current graph and rows relocated recorded along the way."""
+    cfg = W.CONFIGS["cfg5"]
+    scale = 0.1 * min(1.0, SCALE)
+    p = W.make_config("cfg5", scale)
+    n, C, tol = p.n, p.C, cfg["tol"]
+    rp, col, w = p.row_ptr, p.col, p.w
+    sc = np.full(n, -1, dtype=np.int32)
+    sc[p.seed_vertex] = p.seed_class
+    m_batch, revealed = max(1, int(cfg["edges_per_batch"] * scale)), max(1, int(cfg["revealed_per_batch"] * scale))
+    d = P.DynLP(n, _dv(rp, torch.int64), _dv(col, torch.int32), _dv(w, torch.float32), C,
+                _dv(p.seed_vertex, torch.int32), _dv(p.seed_class, torch.int32), device_ptrs=True)
+    relocated, rounds, inserted = 0, [], 0
+    try:
+        d.set_update_mode(P.UPDATE_IN_PLACE)
+        assert d.static_solve(tol, cfg["max_iter"])[0] == 0
+        entries0 = d.num_entries
+        for i in range(1, 51):
+            b = W.sbm_edge_batch(p, m_batch, cfg["intra_frac"], revealed)
+            st, s = d.apply_batch(0, _dv(b.eu, torch.int32), _dv(b.ev, torch.int32), _dv(b.ew, torch.float32),
+                                  _dv(b.seed_vertex, torch.int32), _dv(b.seed_class, torch.int32))
+            assert st == 0
+            relocated += s.rows_relocated
+            inserted += b.num_edges
+            rounds.append(s.iterations)
+            rp, col, w = W.csr_with_batch(n, rp, col, w, b)
+            sc[b.seed_vertex] = b.seed_class
+            if i % 25 == 0:
+                soft, hard = d.get_labels()
+                soft, hard = soft.cpu().numpy(), hard.cpu().numpy()
+                exact, sweeps, _ = ON.itlp_solve(rp, col, w.astype(np.float64), sc, C, tol=1e-10, max_iter=200000,
+                                                 F0=soft.astype(np.float64))
+                reach = R.seed_reachable(rp, col, sc)
+                drift = float(np.max(np.abs(soft - exact)[reach]))
+                clear = reach & (R.top2_margin(exact) > 4e-4)
+                wrong = int((hard[clear] != R.hard_labels(exact)[clear]).sum())
+                print(f"cfg5/10 after {i} batches: drift {drift:.2e}, hard-label disagreements {wrong}, rows relocated so far "
+                      f"{relocated}, rounds per batch {min(rounds)}-{max(rounds)}, seeds {int((sc >= 0).sum())}")
+                assert drift <= 2.0 * tol * n / seeds_count(sc) + 1e-4 and wrong == 0
+        assert d.num_entries == entries0 + 2 * inserted and relocated > 0
+    finally:
+        d.destroy()
