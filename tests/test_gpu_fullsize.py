@@ -381,3 +381,46 @@ def test_cfg5_stream_of_fifty_batches_tracks_the_exact_labels():
         assert d.num_entries == entries0 + 2 * inserted and relocated > 0
     finally:
         d.destroy()
+
+
+def test_cfg4_scaled_copy_full_parity_with_exact_labels():
+    """A 100,000-vertex copy of the power-law configuration (same degree law, C = 50, hubs included), small
+    enough for the oracle to compute the exact labels: cold start and one batch, in-place mode."""
+    cfg = W.CONFIGS["cfg4"]
+    tol = cfg["tol"]
+    p = W.make_config("cfg4", 0.01 * min(1.0, SCALE))
+    n0, C = p.n, p.C
+    base = (p.row_ptr, p.col, p.w, p.seed_vertex.copy(), p.seed_class.copy())
+    b = W.chung_lu_vertex_batch(p, max(1, n0 // 100), cfg["seed_frac"])
+    d = P.DynLP(n0, _dv(base[0], torch.int64), _dv(base[1], torch.int32), _dv(base[2], torch.float32), C,
+                _dv(base[3], torch.int32), _dv(base[4], torch.int32), device_ptrs=True)
+    try:
+        d.set_update_mode(P.UPDATE_IN_PLACE)
+        assert d.static_solve(tol, cfg["max_iter"])[0] == 0
+        soft0 = d.get_labels(soft=True, hard=False)[0].cpu().numpy()
+        st, s = d.apply_batch(b.num_new_vertices, _dv(b.eu, torch.int32), _dv(b.ev, torch.int32), _dv(b.ew, torch.float32),
+                              _dv(b.seed_vertex, torch.int32), _dv(b.seed_class, torch.int32))
+        assert st == 0
+        soft, hard = d.get_labels()
+        soft, hard = soft.cpu().numpy(), hard.cpu().numpy()
+    finally:
+        d.destroy()
+    sc0 = np.full(n0, -1, dtype=np.int32)
+    sc0[base[3]] = base[4]
+    bound = 2.0 * tol * n0 / seeds_count(sc0)  # 0.5% seeds: 4e-4
+    exact0, sweeps0, _ = ON.itlp_solve(base[0], base[1], base[2].astype(np.float64), sc0, C, tol=1e-10, max_iter=200000,
+                                       F0=soft0.astype(np.float64))
+    reach0 = R.seed_reachable(base[0], base[1], sc0)
+    e0 = float(np.max(np.abs(soft0 - exact0)[reach0]))
+    rp, col, w = W.csr_with_batch(n0, base[0], base[1], base[2], b)
+    sc = np.concatenate([sc0, np.full(b.num_new_vertices, -1, dtype=np.int32)])
+    sc[b.seed_vertex] = b.seed_class
+    exact, sweeps, _ = ON.itlp_solve(rp, col, w.astype(np.float64), sc, C, tol=1e-10, max_iter=200000,
+                                     F0=soft.astype(np.float64))
+    reach = R.seed_reachable(rp, col, sc)
+    e1 = float(np.max(np.abs(soft - exact)[reach]))
+    print(f"cfg4/100: max row length {int(np.diff(rp).max())}, cold start err {e0:.2e}, after the batch {e1:.2e} "
+          f"(bound {bound:.1e}), {s.iterations} rounds")
+    assert e0 <= bound and e1 <= bound
+    clear = reach & (R.top2_margin(exact) > 2 * bound)
+    assert np.array_equal(hard[clear], R.hard_labels(exact)[clear])
