@@ -143,7 +143,7 @@ __device__ inline bool moved_bit(const unsigned int* __restrict__ moved, int32_t
     return (moved[(unsigned int)v >> 5] >> ((unsigned int)v & 31u)) & 1u;
 }
 
-constexpr int kPullSub = 16;  // sub-steps per workgroup chunk (one queue atomic per chunk)
+constexpr int kPullSub = 4;  // sub-steps per workgroup chunk (one queue atomic per chunk)
 
 __global__ void __launch_bounds__(kBlock) k_pull_frontier(unsigned int ns, unsigned int nl, unsigned int long_blocks,
                                                          const int32_t* __restrict__ ufront,
