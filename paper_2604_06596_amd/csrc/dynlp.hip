@@ -370,7 +370,7 @@ struct UpdateArgs {
 template <int CP, int G, bool STAGED>
 void launch_update_inst(dynlp_ctx* c, const Frontier& f, const UpdateArgs& a) {
     constexpr int GPB = kBlock / G;
-    const int64_t cap = (int64_t)c->num_cu * 8;
+    const int64_t cap = (int64_t)c->num_cu * 32;
     const unsigned int short_blocks = (unsigned int)std::max<int64_t>(1, std::min<int64_t>(ceil_div(a.rows_bound, GPB), cap));
     const unsigned int long_max = (unsigned int)std::min<int64_t>(a.long_bound, cap / 2);
     unsigned int stop_bits;
