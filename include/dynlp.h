@@ -272,7 +272,7 @@ dynlp_status dynlp_stream_bandwidth(dynlp_ctx* ctx, int64_t bytes, int32_t repet
 
 /* One propagation round of the last dynlp_static_solve / dynlp_apply_batch. */
 typedef struct dynlp_round_info {
-    int64_t rows_short;    /* |V_aff| of the round, split by how the row was updated: rows of at most 512 */
+    int64_t rows_short;    /* |V_aff| of the round, split by how the row was updated: rows of at most 128 */
     int64_t rows_long;     /* entries (a few lanes per row) and longer rows (a workgroup per row)        */
     int64_t entries_short; /* CSR entries those rows hold */
     int64_t entries_long;

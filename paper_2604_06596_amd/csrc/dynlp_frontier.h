@@ -8,7 +8,7 @@ namespace dynlp {
 
 constexpr int kFlagsPerThread = 16;
 constexpr int kFlagsPerBlock = kBlock * kFlagsPerThread;  // 4096
-constexpr int kLongRow = 512;  // rows longer than this get a whole workgroup
+constexpr int kLongRow = 128;  // rows longer than this get a whole workgroup
 
 #ifndef DYNLP_UN_CAP
 #define DYNLP_UN_CAP 8
