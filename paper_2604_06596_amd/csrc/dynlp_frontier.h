@@ -143,8 +143,11 @@ __device__ inline bool moved_bit(const unsigned int* __restrict__ moved, int32_t
     return (moved[(unsigned int)v >> 5] >> ((unsigned int)v & 31u)) & 1u;
 }
 
-constexpr int kPullSub = 4;  // sub-steps per workgroup chunk (one queue atomic per chunk)
-
+// kPullSub = sub-steps per workgroup chunk (one queue atomic per chunk of kPullSub * kBlock positions).
+// Small chunks mean more workgroups (the kernel is latency-bound on small and on low-degree graphs),
+// large chunks mean fewer atomics on the one queue counter (which run at about 1e8 per second and show
+// once every row also scans tens of neighbours): the host picks 4 or 16.
+template <int kPullSub>
 __global__ void __launch_bounds__(kBlock) k_pull_frontier(unsigned int ns, unsigned int nl, unsigned int long_blocks,
                                                          const int32_t* __restrict__ ufront,
                                                          const int32_t* __restrict__ uback,
