@@ -325,15 +325,13 @@ def main():
     all_ms = sum(v["device_ms"] for v in kstats.values())
     all_bytes = sum(v["algorithmic_bytes"] for v in kstats.values())
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"row_update_{args.workload}_traffic.json")  # from rocprofv3 --pmc runs
+    tpath = os.path.join(ROOT, "profiles", f"row_update_{args.workload}_hbm_traffic.md")  # from rocprofv3 --pmc runs
     if os.path.exists(tpath):
-        try:
-            tj = json.load(open(tpath))
-            # the stored figure belongs to one kernel instantiation at full-size launches
-            if tj.get("kernel", "").endswith(dom):
-                traffic = tj.get("hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
+        import re
+        hit = re.search(r"hbm_bytes_per_launch = (\d+) for kernel `([^`]+)`", open(tpath).read())
+        # the stored figure belongs to one kernel instantiation at full-size launches
+        if hit and hit.group(2).endswith(dom):
+            traffic = float(hit.group(1))
     out = {
         "metric": "dynlp_batch_update_inserted_edges_per_s",
         "value": edges_inserted / total_s,
