@@ -1,6 +1,6 @@
 """GPU parity: libdynlp (through the C ABI) against the CPU oracle on the same seeded inputs.
 
-Tolerances (derivation in DESIGN.md, "Numerical tolerances"):
+Tolerances (float32 kernels against a float64 oracle; both stop locally at the threshold tol):
 * one sweep / one round, float32 vs float64:                         max-abs <= 1e-6
 * converged labels vs exact harmonic labels (O1) at tol = 1e-6:      max-abs <= 1e-4
 * the first R rounds of a batch update vs the oracle's Step-3 loop:  max-abs <= 5e-6, same frontiers
