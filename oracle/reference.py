@@ -5,7 +5,7 @@ Notation follows the paper: graph G=(V,E) with symmetric weights w(u,v)>0, label
 the paper's binary scalar F_u is column 1 of the C=2 case), degree d(u)=sum_v w(u,v),
 affected set / frontier V_aff, threshold delta (``tol``).
 
-Readings taken where the paper is silent or garbled (each also listed in the design notes):
+Readings taken where the paper is silent or garbled:
 * multi-class: Eq. (1) applied to every column of F with one-hot seed rows;
 * Alg. 2 Step 3 threshold: absolute change, max over classes, strict ``>``;
 * Alg. 2 Step 3 commit: the computed F'_u is stored whether or not it passed the threshold;
