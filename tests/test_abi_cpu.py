@@ -132,3 +132,26 @@ def test_init_info_layout_and_null_handles(lib):
 def test_round_info_layout_matches_header():
     assert ct.sizeof(B.RoundInfo) == 64  # 60 bytes of fields, padded to the 8-byte alignment
     assert B.RoundInfo.max_delta.offset == 40 and B.RoundInfo.group_lanes.offset == 56
+
+
+def test_device_pointer_mode_refuses_host_arrays_before_calling_the_library():
+    rp, col, w = _tiny()
+    with pytest.raises(TypeError):
+        P.DynLP(3, rp, col, w, 2, np.array([0], dtype=np.int32), np.array([1], dtype=np.int32), device_ptrs=True)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_new_entry_points_reject_null_handles(lib):
+    assert lib.dynlp_apply_update(None, 0, None, 0, 0, None, None, None, 0, None, None, None) == -1
+    assert lib.dynlp_set_update_mode(None, 0) == -1
+    assert lib.dynlp_storage_info(None, None, None) == -1
+    assert lib.dynlp_compact_storage(None) == -1
+    assert lib.dynlp_stream_bandwidth(None, 1 << 20, 1, None, None) == -1
