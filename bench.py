@@ -312,7 +312,8 @@ def main():
     CP = next(c for c in (1, 2, 4, 8, 16, 32, 64) if c >= Cs)
     kstats = {}
     for (staged, glanes), (cnt, rws, ent, ms) in buckets.items():
-        name = f"k_row_update<{CP}, {glanes}, {'true' if staged else 'false'}>"
+        name = (f"k_row_update_pull<{CP}, {glanes}>" if staged == 2 else
+                f"k_row_update<{CP}, {glanes}, {'true' if staged else 'false'}>")
         ab = algorithmic_bytes(rws, ent, Cs)
         kstats[name] = dict(launches=cnt, rows=rws, entries=ent, device_ms=round(ms, 3),
                             avg_launch_us=round(ms * 1e3 / max(1, cnt), 1),

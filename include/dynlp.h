@@ -283,7 +283,9 @@ typedef struct dynlp_round_info {
     int32_t staged;        /* 1: the round marked the next V_aff in per-vertex flags from inside the update
                               kernel (synchronous mode: rows staged by position and committed after the
                               kernel); 0: rows written by vertex and the next V_aff pulled from a bitmap of
-                              moved rows (static sweeps, rounds over nearly all vertices) */
+                              moved rows (static sweeps, rounds over nearly all vertices); 2: as 0, but the
+                              round ran over all updatable vertices and decided per row, from the previous
+                              round's bitmap, whether the row is in V_aff (no frontier list in between) */
     int32_t group_lanes;   /* lanes per row the short-row kernel ran with */
 } dynlp_round_info;
 

@@ -86,9 +86,8 @@ struct dynlp_ctx {
                                                       // updatable vertices (see dynlp_frontier.h)
     int32_t* add_cnt = nullptr;
     float* deg = nullptr;
-    unsigned int* moved[2] = {nullptr, nullptr};  // 1 bit per vertex: "moved by > tol" of ping-pong rounds,
-    int64_t moved_words = 0;                      // two parities (see k_pull_frontier)
-    unsigned int pp_round = 0;                    // ping-pong rounds so far; parity selects the bitmap
+    unsigned int* moved[3] = {nullptr, nullptr, nullptr};  // 1 bit per vertex: "moved by > tol" of ping-pong rounds;
+    int64_t moved_words = 0;                                // round t of a stretch reads t-1's, sets t's, clears t+1's
 
     int32_t* touched = nullptr;
     int64_t* reloc_off = nullptr;
@@ -233,6 +232,7 @@ void alloc_vertex_arrays(dynlp_ctx* c, int64_t new_cap) {
     const int64_t moved_words = (new_cap + 31) / 32 + 64;
     unsigned int* mv0 = dev_alloc_n<unsigned int>(c, moved_words);
     unsigned int* mv1 = dev_alloc_n<unsigned int>(c, moved_words);
+    unsigned int* mv2 = dev_alloc_n<unsigned int>(c, moved_words);
     HIPCHK(c, hipMemsetAsync(flag, 0, (size_t)flag_cap, c->stream));
     HIPCHK(c, hipMemsetAsync(add, 0, (size_t)new_cap * sizeof(int32_t), c->stream));
     if (old_n > 0 && c->meta) {
@@ -254,8 +254,10 @@ void alloc_vertex_arrays(dynlp_ctx* c, int64_t new_cap) {
     dev_free(c, c->deg);
     dev_free(c, c->moved[0]);
     dev_free(c, c->moved[1]);
+    dev_free(c, c->moved[2]);
     c->moved[0] = mv0;
     c->moved[1] = mv1;
+    c->moved[2] = mv2;
     c->moved_words = moved_words;
     c->meta = meta;
     c->F = F;
@@ -430,6 +432,79 @@ void launch_update(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& a) 
     if (c->time_kernels) HIPCHK(c, hipEventRecord(e1, c->stream));
 }
 
+// A ping-pong round that evaluates V_aff membership itself (k_row_update_pull): `universe` lists every
+// updatable vertex, moved_prev / moved_cur / moved_clear are the bitmaps of the previous, this and the next round.
+struct PullRoundArgs {
+    const RoundCtr* prev;
+    const float* F_in;
+    float* F_out;
+    const unsigned int* moved_prev;
+    unsigned int* moved_cur;
+    unsigned int* moved_clear;
+    float tol;
+    RoundCtr* ctr;
+    RoundCtr* ctr_zero;
+};
+
+template <int CP, int G>
+void launch_update_pull_inst(dynlp_ctx* c, const Frontier& universe, const PullRoundArgs& a) {
+    constexpr int GPB = kBlock / G;
+    const int64_t cap = (int64_t)c->num_cu * 32;
+    const unsigned int short_blocks =
+        (unsigned int)std::max<int64_t>(1, std::min<int64_t>(ceil_div((int64_t)universe.ns, GPB), cap));
+    const unsigned int long_max = (unsigned int)std::min<int64_t>((int64_t)universe.nl, cap / 2);
+    hipLaunchKernelGGL((k_row_update_pull<CP, G>), dim3(short_blocks + long_max), dim3(kBlock), 0, c->stream, a.prev, long_max,
+                       universe.front, universe.back, universe.ns, universe.nl, c->meta, c->pool, a.F_in, a.F_out,
+                       a.moved_prev, a.moved_cur, a.moved_clear, (unsigned int)c->moved_words, a.tol, a.ctr, a.ctr_zero);
+}
+
+template <int CP>
+void launch_update_pull_cp(dynlp_ctx* c, int G, const Frontier& universe, const PullRoundArgs& a) {
+    constexpr int LPN = CP >= 4 ? CP / 4 : 1;
+#define DYNLP_CASE(GV)                                              \
+    case GV:                                                        \
+        if constexpr (GV >= LPN) {                                  \
+            launch_update_pull_inst<CP, GV>(c, universe, a);        \
+            return;                                                 \
+        }                                                           \
+        break;
+    switch (G) {
+        DYNLP_CASE(4)
+        DYNLP_CASE(8)
+        DYNLP_CASE(16)
+        DYNLP_CASE(32)
+        DYNLP_CASE(64)
+        default: break;
+    }
+#undef DYNLP_CASE
+    launch_update_pull_inst<CP, 64>(c, universe, a);
+}
+
+void launch_update_pull(dynlp_ctx* c, int G, const Frontier& universe, const PullRoundArgs& a) {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (c->time_kernels) {
+        while (c->events.size() < c->events_used + 2) {
+            hipEvent_t e;
+            HIPCHK(c, hipEventCreate(&e));
+            c->events.push_back(e);
+        }
+        e0 = c->events[c->events_used++];
+        e1 = c->events[c->events_used++];
+        HIPCHK(c, hipEventRecord(e0, c->stream));
+    }
+    switch (c->CP) {
+        case 1: launch_update_pull_cp<1>(c, G, universe, a); break;
+        case 2: launch_update_pull_cp<2>(c, G, universe, a); break;
+        case 4: launch_update_pull_cp<4>(c, G, universe, a); break;
+        case 8: launch_update_pull_cp<8>(c, G, universe, a); break;
+        case 16: launch_update_pull_cp<16>(c, G, universe, a); break;
+        case 32: launch_update_pull_cp<32>(c, G, universe, a); break;
+        default: launch_update_pull_cp<64>(c, G, universe, a); break;
+    }
+    HIPCHK(c, hipGetLastError());
+    if (c->time_kernels) HIPCHK(c, hipEventRecord(e1, c->stream));
+}
+
 // Resolve the per-round events into the round log; returns the summed device time of all
 // row-update launches.
 float collect_kernel_ms(dynlp_ctx* c) {
@@ -444,7 +519,7 @@ float collect_kernel_ms(dynlp_ctx* c) {
     return total;
 }
 
-dynlp_round_info round_info(const RoundCtr& r, bool staged, int G) {
+dynlp_round_info round_info(const RoundCtr& r, int kind, int G) {
     dynlp_round_info ri;
     std::memset(&ri, 0, sizeof ri);
     ri.rows_short = r.rows_short;
@@ -453,7 +528,7 @@ dynlp_round_info round_info(const RoundCtr& r, bool staged, int G) {
     ri.entries_long = (int64_t)r.edges_long;
     std::memcpy(&ri.max_delta, &r.resid_bits, sizeof(float));
     ri.rows_moved = r.changed;
-    ri.staged = staged ? 1 : 0;
+    ri.staged = kind;
     ri.group_lanes = G;
     return ri;
 }
@@ -505,6 +580,18 @@ void launch_pull_frontier(dynlp_ctx* c, const Frontier& universe, double avg_len
         launch_pull_frontier_inst<4>(c, universe, moved, moved_next, F_new, F_old, out, count_short, count_long);
 }
 
+// Whether a ping-pong stretch should run rounds that evaluate V_aff themselves (k_row_update_pull) rather than
+// pairs of row update and pull.  The fused round saves the pull's pass over the graph but puts the membership test
+// (one more dependent look-up for rows that did not move themselves) in front of every row's gathers.
+bool fused_rounds_pay(const dynlp_ctx* c, double avg_len) {
+    // Measured on MI355X, batches of 1% new vertices, whole batch, fused against separate: 1M vertices of mean
+    // degree 20 with 10 / 32 / 64 classes 68 / 78 / 112 ms against 80 / 89 / 138 ms; 2M vertices of mean degree 38
+    // with 10 / 20 classes 611 / 766 ms against 660 / 827 ms; 50M vertices of degree 5, one column, 1.54 s against
+    // 1.89 s; but 10M vertices of mean degree 38 with 50 classes 14.9 ms per round against 14.3 + 0.2 ms.  The
+    // rule below separates the two groups by the bytes a row's update reads.
+    return avg_len * (double)(c->CP * 4 + 8) < 8192.0;
+}
+
 // Ping-pong stretches begin when V_aff holds at least kDenseEnter of the updatable vertices and end
 // when it falls below kDenseLeave (the pull over all updatable vertices stops paying off).
 constexpr double kDenseEnter = 0.90, kDenseLeave = 0.75;
@@ -530,6 +617,8 @@ void fold_slot(RoundCtr& r) {
     r.edges = 0;
     r.edges_long = 0;
     for (const RoundPart& p : r.part) {
+        r.rows_short += p.rows_short;  // only rounds that find their own V_aff count rows here
+        r.rows_long += p.rows_long;
         r.resid_bits = std::max(r.resid_bits, p.resid_bits);
         r.changed += p.changed;
         r.edges += p.edges;
@@ -605,7 +694,7 @@ void destroy_ctx(dynlp_ctx* c) {
     if (!c) return;
     (void)hipSetDevice(c->device);
     if (c->stream || c->meta) (void)hipStreamSynchronize(c->stream);
-    void* ptrs[] = {c->meta, c->pool, c->F, c->F2, c->seed_class, c->flag, c->queue[0], c->queue[1], c->queue[2], c->moved[0], c->moved[1], c->add_cnt,
+    void* ptrs[] = {c->meta, c->pool, c->F, c->F2, c->seed_class, c->flag, c->queue[0], c->queue[1], c->queue[2], c->moved[0], c->moved[1], c->moved[2], c->add_cnt,
                     c->deg, c->touched, c->reloc_off, c->b_eu, c->b_ev, c->b_ew, c->b_sv, c->b_sc,
                     c->cc_par, c->cc_dense, c->cc_comp, c->cc_block, c->cc_kept, c->cc_W};
     for (void* p : ptrs) dev_free(c, p);
@@ -1161,7 +1250,7 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
                 if (!rc.executed) break;
                 std::memcpy(&last, &rc.resid_bits, sizeof(float));
                 edges += (int64_t)(rc.edges + rc.edges_long);
-                c->log.push_back(round_info(rc, false, G));
+                c->log.push_back(round_info(rc, 0, G));
                 ++it;
                 if (last <= tol) {
                     converged = true;
@@ -1392,19 +1481,33 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
         float last = 0.f;
         double avg_len = c->n > 0 ? (double)c->entries / (double)c->n : 1.0;
         bool pingpong = false;
+        int stretch_start = 0;  // first round of the running ping-pong stretch
+        bool fused = false;     // the stretch's rounds evaluate V_aff themselves (no frontier list, no pull)
         const bool in_place = c->update_mode == DYNLP_UPDATE_IN_PLACE;
         while (known > 0 && it < c->max_iter) {
             const int G = choose_group(c, avg_len);
             // A stretch of ping-pong rounds starts when V_aff covers nearly every updatable vertex (one copy
             // of F makes the partner buffer agree on every row outside V_aff) and ends when V_aff has shrunk.
             // Both kinds of round are correct for any V_aff, so the choice is only made between chains.
+            // Inside a stretch no frontier list exists: its first round works on the list it was handed, the
+            // later ones evaluate V_aff = {u : u or a neighbour moved in the previous round} per row, from
+            // the bitmap of moved rows.  Leaving a stretch pulls the list out of the last bitmap once.
             if (!pingpong && (double)known >= kDenseEnter * (double)universe.size()) {
                 if (!in_place) sync_partner(c);
                 for (unsigned int* mv : c->moved)
                     HIPCHK(c, hipMemsetAsync(mv, 0, (size_t)c->moved_words * sizeof(unsigned int), c->stream));
                 pingpong = true;
+                stretch_start = it;
+                fused = fused_rounds_pay(c, avg_len);
             } else if (pingpong && (double)known < kDenseLeave * (double)universe.size()) {
                 pingpong = false;
+                if (fused) {
+                    // rows of the last round are in F (the buffers were swapped to make it so)
+                    const int last = it - 1 - stretch_start;
+                    RoundCtr* slot = slot_of(c, it - 1);
+                    launch_pull_frontier(c, universe, avg_len, c->moved[last % 3], c->moved[(last + 1) % 3], c->F,
+                                         in_place ? nullptr : c->F2, frontier_of(c, cur), &slot->next_count, &slot->next_long);
+                }
             }
             const int r = std::min<int>(kChain, c->max_iter - it);
             // ping-pong: round it+i reads buf[i & 1], writes buf[(i + 1) & 1]; in place: always F
@@ -1414,16 +1517,27 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
                 RoundCtr* slot = slot_of(c, t);
                 const Frontier f = frontier_of(c, cur);
                 if (pingpong) {
-                    // new rows go straight into the partner buffer; the next V_aff is pulled from the bitmap
-                    // of rows that moved
-                    unsigned int* mv = c->moved[c->pp_round & 1u];
-                    unsigned int* mv_next = c->moved[(c->pp_round + 1u) & 1u];
-                    ++c->pp_round;
-                    const UpdateArgs a{slot_of(c, t - 1), 0, buf[i & 1], buf[(i + 1) & 1], mv, c->tol,
-                                       slot, slot_of(c, t + 1), (int64_t)universe.size(), (int64_t)universe.nl};
-                    launch_update<false>(c, G, f, a);
-                    launch_pull_frontier(c, universe, avg_len, mv, mv_next, buf[(i + 1) & 1], in_place ? nullptr : buf[i & 1],
-                                         frontier_of(c, cur ^ 1), &slot->next_count, &slot->next_long);
+                    const int q = t - stretch_start;  // round of the stretch
+                    if (!fused) {
+                        // new rows go straight into the partner buffer; the next V_aff is pulled from the bitmap
+                        // of rows that moved
+                        unsigned int* mv = c->moved[q & 1];
+                        const UpdateArgs a{slot_of(c, t - 1), 0, buf[i & 1], buf[(i + 1) & 1], mv, c->tol,
+                                           slot, slot_of(c, t + 1), (int64_t)universe.size(), (int64_t)universe.nl};
+                        launch_update<false>(c, G, f, a);
+                        launch_pull_frontier(c, universe, avg_len, mv, c->moved[(q + 1) & 1], buf[(i + 1) & 1],
+                                             in_place ? nullptr : buf[i & 1], frontier_of(c, cur ^ 1), &slot->next_count,
+                                             &slot->next_long);
+                        cur ^= 1;
+                    } else if (q == 0) {
+                        const UpdateArgs a{slot_of(c, t - 1), 0, buf[i & 1], buf[(i + 1) & 1], c->moved[0], c->tol,
+                                           slot, slot_of(c, t + 1), (int64_t)universe.size(), (int64_t)universe.nl};
+                        launch_update<false>(c, G, f, a);
+                    } else {
+                        const PullRoundArgs a{slot_of(c, t - 1), buf[i & 1], buf[(i + 1) & 1], c->moved[(q - 1) % 3],
+                                              c->moved[q % 3], c->moved[(q + 1) % 3], c->tol, slot, slot_of(c, t + 1)};
+                        launch_update_pull(c, G, universe, a);
+                    }
                 } else {
                     // rows are staged by frontier position and committed after the kernel; rows that moved mark
                     // themselves and their neighbours
@@ -1434,8 +1548,8 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
                     launch_update<true>(c, G, f, a);
                     if (!in_place) launch_commit(c, f, slot_of(c, t - 1), (int64_t)universe.size());
                     launch_compact(c, frontier_of(c, cur ^ 1), &slot->next_count, &slot->next_long, 0);
+                    cur ^= 1;
                 }
-                cur ^= 1;
             }
             read_slots(c, it, r);
             int executed = 0;
@@ -1448,8 +1562,11 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
                 rows += nq;
                 edges += (int64_t)(rc.edges + rc.edges_long);
                 avg_len = nq ? (double)(rc.edges + rc.edges_long) / (double)nq : avg_len;
-                c->log.push_back(round_info(rc, !pingpong, G));
-                known = rc.next_count + rc.next_long;
+                // the first round of a fused stretch still works on a frontier list
+                c->log.push_back(round_info(rc, !pingpong ? 1 : (fused && it + i > stretch_start ? 2 : 0), G));
+                // inside a stretch the next V_aff is not counted: this round's size stands in for it while
+                // rows still move
+                known = pingpong && fused ? (rc.changed ? std::max(nq, 1u) : 0u) : rc.next_count + rc.next_long;
                 peak = std::max<int64_t>(peak, known);
             }
             if (pingpong && !in_place && (executed & 1)) std::swap(c->F, c->F2);  // the output of the last executed round

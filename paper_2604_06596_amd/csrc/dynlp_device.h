@@ -44,7 +44,9 @@ struct __attribute__((aligned(64))) RoundPart {
     unsigned int changed;           // rows whose change exceeded tol
     unsigned long long edges;       // CSR entries traversed in short rows
     unsigned long long edges_long;  // CSR entries traversed in long rows
-    unsigned int pad[10];
+    unsigned int rows_short;        // rows updated, where the round itself decides which rows are in V_aff
+    unsigned int rows_long;         // (k_row_update_pull); 0 otherwise
+    unsigned int pad[8];
 };
 
 struct __attribute__((aligned(64))) RoundCtr {

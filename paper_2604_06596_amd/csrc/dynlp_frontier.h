@@ -361,17 +361,20 @@ __device__ inline void accumulate_row(const Edge* __restrict__ row, int len, int
 
 // Per-workgroup totals -> one set of atomics on one of the round's partial records.
 __device__ inline void flush_round_counters(float rmax, unsigned long long edges, unsigned int changed,
-                                            RoundCtr* __restrict__ ctr, bool long_rows) {
+                                            RoundCtr* __restrict__ ctr, bool long_rows, unsigned int rows = 0) {
     __shared__ float sm_r[kBlock / kWave];
     __shared__ unsigned long long sm_e[kBlock / kWave];
     __shared__ unsigned int sm_c[kBlock / kWave];
+    __shared__ unsigned int sm_n[kBlock / kWave];
     rmax = wave_max(rmax);
     edges = wave_sum(edges);
     changed = wave_sum(changed);
+    rows = wave_sum(rows);
     if (lane_id() == 0) {
         sm_r[threadIdx.x / kWave] = rmax;
         sm_e[threadIdx.x / kWave] = edges;
         sm_c[threadIdx.x / kWave] = changed;
+        sm_n[threadIdx.x / kWave] = rows;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -379,11 +382,13 @@ __device__ inline void flush_round_counters(float rmax, unsigned long long edges
             rmax = fmaxf(rmax, sm_r[i]);
             edges += sm_e[i];
             changed += sm_c[i];
+            rows += sm_n[i];
         }
         RoundPart* p = &ctr->part[blockIdx.x & (kCtrLanes - 1)];
         if (rmax > 0.f) atomicMax(&p->resid_bits, __float_as_uint(rmax));
         if (edges) atomicAdd(long_rows ? &p->edges_long : &p->edges, edges);
         if (changed) atomicAdd(&p->changed, changed);
+        if (rows) atomicAdd(long_rows ? &p->rows_long : &p->rows_short, rows);
     }
 }
 
@@ -399,13 +404,18 @@ __device__ inline void flush_round_counters(float rmax, unsigned long long edges
 // hold at that moment.  Reads and writes are whole 16-byte segments, columns are independent linear
 // systems, and the update is a contraction per column, so mixed old/new reads only change the path
 // to the fixed point, not the fixed point.
-template <int CP, int G, bool STAGED>
+//   PULL (with STAGED = false): front lists every updatable vertex and the round itself decides which of them
+//            are in V_aff: u is updated iff u or one of its neighbours moved by more than tol in the previous
+//            round (bitmap moved_prev) - Alg. 2 Step 3's V_aff, evaluated where the row is read anyway.  A row
+//            outside V_aff is copied to F_out when that is another buffer, so the two keep agreeing there.
+template <int CP, int G, bool STAGED, bool PULL = false>
 __device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, const int32_t* __restrict__ front,
                                         unsigned int ns, const RowMeta* __restrict__ meta,
                                         const Edge* __restrict__ pool, const float* F_in,
                                         float* F_out, int by_vertex, uint8_t* __restrict__ flag,
                                         unsigned int* __restrict__ moved, float tol,
-                                        RoundCtr* __restrict__ ctr) {
+                                        RoundCtr* __restrict__ ctr,
+                                        const unsigned int* __restrict__ moved_prev = nullptr) {
     constexpr int VEC = RowShape<CP>::VEC;
     constexpr int LPN = RowShape<CP>::LPN;
     constexpr int GPB = kBlock / G;
@@ -415,11 +425,28 @@ __device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, 
     float rmax = 0.f;
     unsigned long long edges = 0;
     unsigned int nchanged = 0;
+    unsigned int nrows = 0;
 
     for (unsigned int g = bid * GPB + threadIdx.x / G; g < ns; g += nblocks * GPB) {
         const int32_t u = front[g];
         const RowMeta m = meta[u];
         const Edge* __restrict__ row = pool + m.off;
+        if (PULL) {
+            bool in_front = moved_bit(moved_prev, u);
+            for (int base = 0; base < m.len && !in_front; base += G) {  // uniform in the group
+                const int idx = base + gl;
+                const bool hit = idx < m.len && moved_bit(moved_prev, row[idx].col);
+                const unsigned long long b = __ballot(hit);
+                const unsigned long long mine = G == kWave ? b : (b >> ((lane_id() / G) * G)) & ((1ull << (G & 63)) - 1ull);
+                in_front = mine != 0ull;
+            }
+            if (!in_front) {
+                if (F_out != F_in && slot == 0)
+                    store_vec<VEC>(F_out + (size_t)u * CP + chunk * VEC, load_vec<VEC>(F_in + (size_t)u * CP + chunk * VEC));
+                continue;
+            }
+            if (gl == 0) nrows += 1;
+        }
         Vec<VEC> acc;
 #pragma unroll
         for (int k = 0; k < VEC; ++k) acc.v[k] = 0.f;
@@ -456,19 +483,20 @@ __device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, 
             nchanged += big ? 1u : 0u;
         }
     }
-    flush_round_counters(rmax, edges, nchanged, ctr, false);
+    flush_round_counters(rmax, edges, nchanged, ctr, false, nrows);
 }
 
 // Long rows: one workgroup per row (body; k_row_update dispatches to it).  Its kBlock/G groups take the row's chunks round-robin; their
 // partial sums meet in LDS and are added in group order (a fixed order: results do not depend on
 // timing).  Position of long row j is pos_base + j.
-template <int CP, bool STAGED>
+template <int CP, bool STAGED, bool PULL = false>
 __device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, const int32_t* __restrict__ back,
                                        unsigned int nl, unsigned int pos_base, const RowMeta* __restrict__ meta,
                                        const Edge* __restrict__ pool, const float* F_in,
                                        float* F_out, int by_vertex, uint8_t* __restrict__ flag,
                                        unsigned int* __restrict__ moved, float tol,
-                                       RoundCtr* __restrict__ ctr) {
+                                       RoundCtr* __restrict__ ctr,
+                                       const unsigned int* __restrict__ moved_prev = nullptr) {
     constexpr int VEC = RowShape<CP>::VEC;
     constexpr int LPN = RowShape<CP>::LPN;
     constexpr int G = LPN > 16 ? LPN : 16;
@@ -484,10 +512,24 @@ __device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, c
     unsigned long long edges = 0;
     unsigned int nchanged = 0;
 
+    unsigned int nrows = 0;
     for (unsigned int j = bid; j < nl; j += nblocks) {
         const int32_t u = back[-(long long)j];
         const RowMeta m = meta[u];
         const Edge* __restrict__ row = pool + m.off;
+        if (PULL) {  // every decision below is uniform across the workgroup
+            bool in_front = moved_bit(moved_prev, u);
+            for (int base = 0; base < m.len && !in_front; base += kBlock) {
+                const int idx = base + (int)threadIdx.x;
+                in_front = __syncthreads_or(idx < m.len && moved_bit(moved_prev, row[idx].col)) != 0;
+            }
+            if (!in_front) {
+                if (F_out != F_in && gi == 0 && slot == 0)
+                    store_vec<VEC>(F_out + (size_t)u * CP + chunk * VEC, load_vec<VEC>(F_in + (size_t)u * CP + chunk * VEC));
+                continue;
+            }
+            if (threadIdx.x == 0) nrows += 1;
+        }
         Vec<VEC> acc;
 #pragma unroll
         for (int k = 0; k < VEC; ++k) acc.v[k] = 0.f;
@@ -539,7 +581,7 @@ __device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, c
         }
         __syncthreads();
     }
-    flush_round_counters(rmax, edges, nchanged, ctr, true);
+    flush_round_counters(rmax, edges, nchanged, ctr, true, nrows);
 }
 
 // One launch per round.  The frontier's size comes from the previous round's counter slot (prev), so
@@ -574,6 +616,8 @@ __global__ void __launch_bounds__(kBlock) k_row_update(const RoundCtr* __restric
             p->changed = 0;
             p->edges = 0;
             p->edges_long = 0;
+            p->rows_short = 0;
+            p->rows_long = 0;
         }
     }
     const unsigned int ns = prev->next_count, nl = prev->next_long;
@@ -614,6 +658,54 @@ __global__ void __launch_bounds__(kBlock) k_row_update(const RoundCtr* __restric
     else
         row_update_short<CP, G, STAGED>(blockIdx.x - long_blocks, gridDim.x - long_blocks, front, ns, meta, pool, F_in,
                                         F_out, by_vertex, flag, moved, tol, ctr);
+}
+
+// A round over nearly all updatable vertices that finds its own V_aff (no frontier list, no separate pull):
+// (front, back, ns, nl) is the list of all updatable vertices; moved_prev has the bits of the rows that moved
+// in the previous round, moved_cur receives this round's, moved_clear (the bitmap of the round after) is
+// zeroed.  The round does nothing if the previous one did not run or moved no row (V_aff is empty then).
+template <int CP, int G>
+__global__ void __launch_bounds__(kBlock) k_row_update_pull(const RoundCtr* __restrict__ prev, unsigned int long_blocks_max,
+                                                           const int32_t* __restrict__ front,
+                                                           const int32_t* __restrict__ back, unsigned int ns,
+                                                           unsigned int nl, const RowMeta* __restrict__ meta,
+                                                           const Edge* __restrict__ pool, const float* F_in,
+                                                           float* F_out, const unsigned int* __restrict__ moved_prev,
+                                                           unsigned int* __restrict__ moved_cur,
+                                                           unsigned int* __restrict__ moved_clear, unsigned int words,
+                                                           float tol, RoundCtr* __restrict__ ctr,
+                                                           RoundCtr* __restrict__ ctr_zero) {
+    if (ctr_zero && blockIdx.x == 0) {
+        if (threadIdx.x == 0) {
+            ctr_zero->next_count = 0;
+            ctr_zero->next_long = 0;
+            ctr_zero->executed = 0;
+            ctr_zero->rows_short = 0;
+            ctr_zero->rows_long = 0;
+        }
+        if (threadIdx.x < kCtrLanes) {
+            RoundPart* p = &ctr_zero->part[threadIdx.x];
+            p->resid_bits = 0;
+            p->changed = 0;
+            p->edges = 0;
+            p->edges_long = 0;
+            p->rows_short = 0;
+            p->rows_long = 0;
+        }
+    }
+    // rows the previous round moved: the sum over its partial records
+    unsigned int prev_changed = lane_id() < kCtrLanes ? prev->part[lane_id()].changed : 0u;
+    prev_changed = wave_sum(prev_changed);
+    if (!prev->executed || prev_changed == 0u) return;
+    for (unsigned int w = blockIdx.x * kBlock + threadIdx.x; w < words; w += gridDim.x * kBlock) moved_clear[w] = 0u;
+    if (blockIdx.x == 0 && threadIdx.x == 0) ctr->executed = 1;
+    const unsigned int long_blocks = nl < long_blocks_max ? nl : long_blocks_max;
+    if (blockIdx.x < long_blocks)
+        row_update_long<CP, false, true>(blockIdx.x, long_blocks, back, nl, ns, meta, pool, F_in, F_out, 1, nullptr,
+                                         moved_cur, tol, ctr, moved_prev);
+    else
+        row_update_short<CP, G, false, true>(blockIdx.x - long_blocks, gridDim.x - long_blocks, front, ns, meta, pool,
+                                             F_in, F_out, 1, nullptr, moved_cur, tol, ctr, moved_prev);
 }
 
 }  // namespace dynlp

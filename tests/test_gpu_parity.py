@@ -317,6 +317,52 @@ def test_first_rounds_of_a_batch_match_the_oracle_step_by_step(kind, C, R_):
     assert s.edges_traversed == o2["edges_traversed"] and s.rows_updated == o2["rows_updated"]
 
 
+@pytest.mark.parametrize("tol", [TOL, 2e-5])
+@pytest.mark.parametrize("deg,C,kinds", [(9.0, 10, {0, 2}), (40.0, 50, {0})])
+def test_rounds_over_nearly_all_vertices_match_the_oracle_round_by_round(deg, C, kinds, tol):
+    """Once V_aff holds nearly every vertex the library stops keeping a frontier list.  Light rows (few bytes per
+    update): the rounds decide membership per row themselves; heavy rows: row update and pull stay two launches.
+    Either way every round must work on exactly the oracle's V_aff."""
+    R_ = 30 if tol == TOL else 2000
+    p = W.small_random(3000, C, deg, 150, 4100 + C)
+    p0 = W.small_random(3000, C, deg, 150, 4100 + C)
+    b = W.small_random_batch(p, 300, int(deg), 5, num_extra_edges=40, num_revealed=2)
+    g = _oracle_graph(p0)
+    with _make(p0) as d:
+        st, _ = d.static_solve(TOL, 20000)
+        assert st == 0
+        soft0, _ = d.get_labels()
+        d.set_params(tol, R_)
+        st, s = d.apply_batch(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+        soft, _ = d.get_labels()
+        sizes, deltas = d.round_log()
+        how = [int(r.staged) for r in d.round_log_full()]
+    rp, col, w, F_start, A0 = _apply_oracle_batch(g, soft0.astype(np.float64), b)
+    o2 = ON.step3_propagate(rp, col, w, F_start, g.seed_class, A0, tol, R_)
+    print("round kinds", how, "sizes", sizes.tolist())
+    updatable = int(np.count_nonzero((g.seed_class < 0) & (np.diff(rp) > 0)))
+    assert sizes.max() >= 0.9 * updatable, "the case is meant to reach a stretch over nearly all vertices"
+    assert set(how) - {1} == kinds
+    if tol == TOL:
+        assert s.iterations == R_ and st == 1  # cut inside the stretch
+    else:
+        # run to the end: V_aff shrinks while the stretch is still running, and the loop ends inside it
+        assert st == 0
+    assert s.iterations == o2["rounds"]
+    np.testing.assert_allclose(deltas, o2["max_changes"], atol=1e-6)
+    if tol == TOL:
+        assert np.max(np.abs(soft - o2["F"])) <= ROUNDS_ATOL
+        assert sizes.tolist() == o2["frontier_sizes"].tolist()
+        assert s.edges_traversed == o2["edges_traversed"] and s.rows_updated == o2["rows_updated"]
+    else:
+        # while V_aff collapses many rows change by almost exactly the threshold, and the two sides add a row's
+        # terms in different orders: a few rows per round may fall on the other side
+        diff = np.abs(sizes - o2["frontier_sizes"])
+        print("size differences", diff[diff > 0].tolist(), "oracle tail", o2["frontier_sizes"][-4:].tolist())
+        assert np.all(diff <= np.maximum(3, 0.01 * o2["frontier_sizes"]))
+        assert np.max(np.abs(soft - o2["F"])) <= _o2_atol(g, tol)  # a row that freezes a round earlier keeps ~tol
+
+
 def test_cfg1_batch_update_matches_oracle():
     p = W.make_config("cfg1")
     b = W.knn_mixture_batch(p, 100, 5)
