@@ -332,6 +332,9 @@ int choose_group(const dynlp_ctx* c, double avg_len) {
     // fastest or within 2% of it for every padded class count; wider groups only pay off when the
     // typical row fills several 16-entry chunks.
     int g = 16;
+    // rows of a few entries with one to four label columns (50M vertices of degree 5, one column: 6.2 / 6.3 / 6.5 ms
+    // per round over all rows with 4 / 8 / 16 lanes): narrow groups leave fewer lanes idle
+    if (avg_len < 8.0 && c->CP <= 4) g = 4;
     if (avg_len >= 96.0) g = 32;
     if (avg_len >= 384.0) g = 64;
     return std::max(g, lpn);
