@@ -172,6 +172,8 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload's vertex count (same law)")
     ap.add_argument("--binary-scalar", type=int, default=-1,
                     help="1: one float per vertex (needs C = 2); 0: n x C rows; default: 1 for cfg6, else 0")
+    ap.add_argument("--binned-rounds", type=int, default=0,
+                    help="scalar labels: 0 = the library decides, -1 = never, 8..15 = always with 2^k receivers per bin")
     ap.add_argument("--delete-frac", type=float, default=0.0,
                     help="also delete this fraction of a batch's vertex count from the existing vertices in every batch "
                          "(the paper's experiments use 9 deletions per 91 insertions: 0.099)")
@@ -238,7 +240,8 @@ def main():
     def new_context():
         ctx = P.DynLP(base["n"], d_base[0], d_base[1], d_base[2], base["C"], d_base[3], d_base[4],
                       device_ptrs=not args.host_inputs, reserve_vertices=tot_v + 1024, reserve_edges=2 * tot_e + 1024,
-                      time_kernels=not args.no_kernel_timing, group_lanes=args.group_lanes, binary_scalar=scalar)
+                      time_kernels=not args.no_kernel_timing, group_lanes=args.group_lanes, binary_scalar=scalar,
+                      binned_rounds=args.binned_rounds)
         if args.update_mode == "in-place":
             ctx.set_update_mode(P.UPDATE_IN_PLACE)
         st_, s_ = ctx.static_solve(tol, cfg["max_iter"])
@@ -312,7 +315,7 @@ def main():
     CP = next(c for c in (1, 2, 4, 8, 16, 32, 64) if c >= Cs)
     kstats = {}
     for (staged, glanes), (cnt, rws, ent, ms) in buckets.items():
-        name = (f"k_row_update_pull<{CP}, {glanes}>" if staged == 2 else
+        name = ("k_pb_scatter + k_pb_gather" if staged == 3 else f"k_row_update_pull<{CP}, {glanes}>" if staged == 2 else
                 f"k_row_update<{CP}, {glanes}, {'true' if staged else 'false'}>")
         ab = algorithmic_bytes(rws, ent, Cs)
         kstats[name] = dict(launches=cnt, rows=rws, entries=ent, device_ms=round(ms, 3),

@@ -90,7 +90,10 @@ typedef struct dynlp_options {
                                 label F_u in [0,1] = weight of class 1 (seeds 0 or 1, neutral start 0.5,
                                 hard label by the 0.5 cut-off); dynlp_get_labels still returns n x 2 rows
                                 (1 - F_u, F_u).  0: n x C rows */
-    int32_t reserved;
+    int32_t binned_rounds;   /* scalar labels only (tuning knob): rounds over nearly all vertices as two streaming
+                                passes (scatter labels into bins of receivers, gather per bin) instead of row
+                                updates with random gathers.  0: the library decides (large graphs with short
+                                rows); -1: never; 8..15: always, with 2^k receivers per bin */
 } dynlp_options;
 
 /* Fill *opt with the defaults (device 0, default stream, host pointers). */

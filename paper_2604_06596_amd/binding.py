@@ -61,7 +61,7 @@ class Options(ct.Structure):
                 ("slack_factor", ct.c_float), ("reserve_vertices", ct.c_int64), ("reserve_edges", ct.c_int64),
                 ("time_kernels", ct.c_int32), ("group_lanes", ct.c_int32), ("alloc", _ALLOC_FN),
                 ("dealloc", _DEALLOC_FN), ("alloc_user", ct.c_void_p), ("binary_scalar", ct.c_int32),
-                ("reserved", ct.c_int32)]
+                ("binned_rounds", ct.c_int32)]
 
 
 EXPORTS = ["dynlp_default_options", "dynlp_create", "dynlp_static_solve", "dynlp_set_params", "dynlp_apply_batch",
@@ -145,7 +145,7 @@ class DynLP:
 
     def __init__(self, n, row_ptr, col, w, num_classes, seed_vertex, seed_class, *, device=0, stream=None,
                  device_ptrs=False, slack_factor=1.25, reserve_vertices=0, reserve_edges=0, time_kernels=False,
-                 group_lanes=0, binary_scalar=False, library=None):
+                 group_lanes=0, binary_scalar=False, binned_rounds=0, library=None):
         self._L = load_library(library)
         self._h = ct.c_void_p()
         self.device_ptrs = bool(device_ptrs)
@@ -162,6 +162,7 @@ class DynLP:
         opt.time_kernels = 1 if time_kernels else 0
         opt.group_lanes = int(group_lanes)
         opt.binary_scalar = 1 if binary_scalar else 0
+        opt.binned_rounds = int(binned_rounds)
         nseeds = 0 if seed_vertex is None else int(len(seed_vertex))
         st = self._L.dynlp_create(ct.byref(self._h), int(n), self._in(row_ptr, np.int64), self._in(col, np.int32),
                                   self._in(w, np.float32), int(num_classes), nseeds, self._in(seed_vertex, np.int32),

@@ -16,6 +16,7 @@
 #include "dynlp_kernels.h"
 #include "dynlp_frontier.h"
 #include "dynlp_components.h"
+#include "dynlp_binned.h"
 
 using namespace dynlp;
 
@@ -103,6 +104,30 @@ struct dynlp_ctx {
     BatchCtr* h_bc = nullptr;    // pinned
 
     int update_mode = DYNLP_UPDATE_SYNCHRONOUS;
+    // binned rounds for scalar labels (dynlp_binned.h)
+    int binned = 0;                 // option: 0 = automatic, -1 = never, 8..15 = always, with this many bin bits
+    bool pb_built = false;          // the arrays below describe the graph as it stands
+    int pb_bits = 0, pb_bins = 0;
+    // per stored entry, rows in vertex order
+    unsigned int* pb_src = nullptr;    // its row
+    unsigned short* pb_lpos = nullptr;  // its position in its chunk once sorted by slot
+    unsigned int* pb_oslot = nullptr;  // per chunk position: the slot behind it
+    float* pb_tmp = nullptr;           // build scratch: the entries' weights in stream order
+    // per slot
+    unsigned short* pb_dst = nullptr;
+    float* pb_wn = nullptr;
+    unsigned int* pb_val = nullptr;
+    int64_t pb_ent_cap = 0;
+    int pb_chunks = 0;
+    // per vertex
+    int32_t* pb_len = nullptr;
+    unsigned int* pb_upd = nullptr;
+    unsigned int* pb_first = nullptr;  // (+1) first entry of the row in the stream
+    unsigned int* pb_block = nullptr;  // per kBlock vertices: scan scratch
+    int64_t pb_vcap = 0;
+    unsigned int* pb_bin = nullptr;  // bin_count | bin_off (+1), kPbMaxBins + 1 each
+    unsigned int* pb_table = nullptr;  // entries per (chunk, bin) during the build
+    int64_t pb_table_cap = 0;
     // label initialisation of inserted vertices (dynlp_components.h)
     int init_mode = DYNLP_INIT_UNIFORM;
     float tau = 0.f;
@@ -369,7 +394,7 @@ struct UpdateArgs {
     RoundCtr* ctr_zero;
     int64_t rows_bound;  // upper bounds of the frontier size and of its long rows (they size the grid)
     int64_t long_bound;
-    int by_vertex = 0;  // flag-marking rounds only: write row u of F_out instead of staging by position
+    int by_vertex = 0;  // flag-marking rounds only: kRowByVertex (write row u of F_out instead of staging by position), kRowLazy
 };
 
 template <int CP, int G, bool STAGED>
@@ -508,6 +533,126 @@ void launch_update_pull(dynlp_ctx* c, int G, const Frontier& universe, const Pul
     if (c->time_kernels) HIPCHK(c, hipEventRecord(e1, c->stream));
 }
 
+// ---- binned rounds (dynlp_binned.h) -----------------------------------------------------------------
+// Whether a stretch of rounds over nearly all vertices should run as scatter + gather passes: one label column,
+// and either forced by the option or labels that are larger than the L2 (8 x 4 MB), so that the ordinary
+// round's gathers miss.  Measured on MI355X, binary labels, one round over all rows, binned against ordinary: 50M
+// vertices of degree 5: 1.63 against 6.2 ms; 10M vertices of mean degree 38: 2.26 against 6.2 ms; 1M vertices of
+// mean degree 20 (4 MB of labels): 0.29 against 0.24 ms, and whole batches twice as slow because the binned
+// rounds are Jacobi rounds also in in-place mode.
+bool binned_rounds_pay(const dynlp_ctx* c, const Frontier& universe, double avg_len) {
+    (void)avg_len;
+    if (c->CP != 1 || c->binned < 0) return false;
+    if (ceil_div(c->n, (int64_t)1 << (c->binned > 0 ? c->binned : kPbMaxBinBits)) > kPbMaxBins) return false;
+    if (c->entries >= ((int64_t)1 << 32) - 2 * kPbChunk) return false;  // slots and stream positions are 32-bit
+    if (c->binned > 0) return true;
+    return universe.size() >= (8u << 20);
+}
+
+// Slots, per-slot receiver offsets and normalised weights for the graph as it stands.
+void build_binned(dynlp_ctx* c) {
+    const int bits = c->binned > 0 ? c->binned : kPbMaxBinBits;
+    const int nbins = (int)ceil_div(std::max<int64_t>(c->n, 1), (int64_t)1 << bits);
+    const int chunks = (int)ceil_div(std::max<int64_t>(c->entries, 1), kPbChunk);
+    if ((int64_t)chunks * kPbChunk > c->pb_ent_cap) {
+        void* old[] = {c->pb_src, c->pb_lpos, c->pb_oslot, c->pb_tmp, c->pb_dst, c->pb_wn, c->pb_val};
+        for (void* q : old) dev_free(c, q);
+        c->pb_src = c->pb_oslot = c->pb_val = nullptr;
+        c->pb_lpos = c->pb_dst = nullptr;
+        c->pb_tmp = c->pb_wn = nullptr;
+        c->pb_ent_cap = 0;
+        const int64_t cap = round_up(c->entries + c->entries / 8 + 1, kPbChunk);
+        c->pb_src = dev_alloc_n<unsigned int>(c, cap);
+        c->pb_lpos = dev_alloc_n<unsigned short>(c, cap);
+        c->pb_oslot = dev_alloc_n<unsigned int>(c, cap);
+        c->pb_tmp = dev_alloc_n<float>(c, cap);
+        c->pb_dst = dev_alloc_n<unsigned short>(c, cap);
+        c->pb_wn = dev_alloc_n<float>(c, cap);
+        c->pb_val = dev_alloc_n<unsigned int>(c, cap);
+        c->pb_ent_cap = cap;
+    }
+    if (c->n > c->pb_vcap) {
+        void* old[] = {c->pb_len, c->pb_upd, c->pb_first, c->pb_block};
+        for (void* q : old) dev_free(c, q);
+        c->pb_len = nullptr;
+        c->pb_upd = c->pb_first = c->pb_block = nullptr;
+        c->pb_vcap = 0;
+        c->pb_len = dev_alloc_n<int32_t>(c, c->n_cap);
+        c->pb_upd = dev_alloc_n<unsigned int>(c, c->n_cap / 32 + 64);
+        c->pb_first = dev_alloc_n<unsigned int>(c, c->n_cap + 1);
+        c->pb_block = dev_alloc_n<unsigned int>(c, c->n_cap / kBlock + 2);
+        c->pb_vcap = c->n_cap;
+    }
+    if (!c->pb_bin) c->pb_bin = dev_alloc_n<unsigned int>(c, 2 * (kPbMaxBins + 1));
+    if ((int64_t)chunks * nbins > c->pb_table_cap) {
+        dev_free(c, c->pb_table);
+        c->pb_table = nullptr;
+        c->pb_table_cap = 0;
+        const int64_t cap = (int64_t)chunks * nbins + (int64_t)chunks * nbins / 8;
+        c->pb_table = dev_alloc_n<unsigned int>(c, cap);
+        c->pb_table_cap = cap;
+    }
+    unsigned int* bin_count = c->pb_bin;
+    unsigned int* bin_off = c->pb_bin + (kPbMaxBins + 1);
+    const unsigned int* num_entries = c->pb_first + c->n;
+    const unsigned int vblocks = grid_for(c->n);
+    hipLaunchKernelGGL(k_pb_receivers, dim3(grid_for(round_up(c->n, 64))), dim3(kBlock), 0, c->stream, c->n, c->meta,
+                       c->seed_class, c->pb_len, c->pb_upd);
+    hipLaunchKernelGGL(k_pb_row_blocks, dim3(vblocks), dim3(kBlock), 0, c->stream, c->n, c->meta, c->pb_block);
+    hipLaunchKernelGGL(k_pb_scan_blocks, dim3(1), dim3(kBlock), 0, c->stream, (int64_t)vblocks, c->pb_block);
+    hipLaunchKernelGGL(k_pb_row_first, dim3(vblocks), dim3(kBlock), 0, c->stream, c->n, c->meta, c->pb_block, c->pb_first);
+    HIPCHK(c, hipGetLastError());
+    // every array above is sized from the host's count of stored entries: it must be the device's
+    unsigned int device_entries = 0;
+    HIPCHK(c, hipMemcpyAsync(&device_entries, num_entries, sizeof device_entries, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    if ((int64_t)device_entries != c->entries) {
+        c->err = "internal error: the stored rows hold " + std::to_string(device_entries) + " entries, the context counts " +
+                 std::to_string(c->entries);
+        c->poisoned = true;
+        throw Fail{DYNLP_ERR_STATE};
+    }
+    unsigned int* ecol = c->pb_val;  // scratch until the first scatter pass overwrites it
+    hipLaunchKernelGGL(k_pb_expand, dim3(grid_for(c->n * 16)), dim3(kBlock), 0, c->stream, c->n, c->meta, c->pool, c->pb_first,
+                       c->pb_src, ecol, c->pb_tmp);
+    hipLaunchKernelGGL(k_pb_count, dim3(chunks), dim3(kBlock), 0, c->stream, num_entries, bits, nbins, ecol, c->pb_upd,
+                       c->pb_table);
+    hipLaunchKernelGGL(k_pb_chunk_bases, dim3(grid_for(nbins)), dim3(kBlock), 0, c->stream, nbins, chunks, c->pb_table,
+                       bin_count);
+    hipLaunchKernelGGL(k_pb_offsets, dim3(1), dim3(kBlock), 0, c->stream, nbins, bin_count, bin_off);
+    hipLaunchKernelGGL(k_pb_place, dim3(chunks), dim3(kBlock), 0, c->stream, num_entries, bits, nbins, ecol, c->pb_tmp,
+                       c->pb_upd, c->pb_table, bin_off, c->pb_lpos, c->pb_oslot, c->pb_dst, c->pb_wn);
+    hipLaunchKernelGGL(k_pb_normalise, dim3(nbins), dim3(kBlock), 0, c->stream, bits, bin_off, c->pb_dst, c->deg, c->pb_wn);
+    HIPCHK(c, hipGetLastError());
+    c->pb_bits = bits;
+    c->pb_bins = nbins;
+    c->pb_chunks = chunks;
+    c->pb_built = true;
+}
+
+// One binned round: scatter pass + gather pass (arguments as for the fused round).
+void launch_binned_round(dynlp_ctx* c, const PullRoundArgs& a) {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (c->time_kernels) {
+        while (c->events.size() < c->events_used + 2) {
+            hipEvent_t e;
+            HIPCHK(c, hipEventCreate(&e));
+            c->events.push_back(e);
+        }
+        e0 = c->events[c->events_used++];
+        e1 = c->events[c->events_used++];
+        HIPCHK(c, hipEventRecord(e0, c->stream));
+    }
+    const unsigned int* bin_off = c->pb_bin + (kPbMaxBins + 1);
+    hipLaunchKernelGGL(k_pb_scatter, dim3(8 * (unsigned int)ceil_div(c->pb_chunks, 8)), dim3(kPbScatterThreads), 0, c->stream, a.prev,
+                       c->pb_first + c->n, (unsigned int)c->pb_chunks, c->pb_src, c->pb_lpos, c->pb_oslot, a.F_in, a.moved_prev,
+                       a.moved_clear, (unsigned int)c->moved_words, c->pb_val, a.ctr_zero);
+    hipLaunchKernelGGL(k_pb_gather, dim3(c->pb_bins), dim3(kPbGatherThreads), 0, c->stream, a.prev, c->n, c->pb_bits, bin_off,
+                       c->pb_dst, c->pb_wn, c->pb_val, c->pb_len, a.F_in, a.F_out, a.moved_prev, a.moved_cur, a.tol, a.ctr);
+    HIPCHK(c, hipGetLastError());
+    if (c->time_kernels) HIPCHK(c, hipEventRecord(e1, c->stream));
+}
+
 // Resolve the per-round events into the round log; returns the summed device time of all
 // row-update launches.
 float collect_kernel_ms(dynlp_ctx* c) {
@@ -598,6 +743,9 @@ bool fused_rounds_pay(const dynlp_ctx* c, double avg_len) {
 // Ping-pong stretches begin when V_aff holds at least kDenseEnter of the updatable vertices and end
 // when it falls below kDenseLeave (the pull over all updatable vertices stops paying off).
 constexpr double kDenseEnter = 0.90, kDenseLeave = 0.75;
+// A binned round costs the same whatever the size of V_aff (two streams over the whole graph), about a third of an
+// ordinary round over all rows: such stretches begin and end at smaller V_aff.
+constexpr double kBinnedEnter = 0.50, kBinnedLeave = 0.35;
 
 // The ping-pong partner must agree with F on every row a full sweep does not write (seeds,
 // isolated vertices) before it can receive one.
@@ -699,7 +847,9 @@ void destroy_ctx(dynlp_ctx* c) {
     if (c->stream || c->meta) (void)hipStreamSynchronize(c->stream);
     void* ptrs[] = {c->meta, c->pool, c->F, c->F2, c->seed_class, c->flag, c->queue[0], c->queue[1], c->queue[2], c->moved[0], c->moved[1], c->moved[2], c->add_cnt,
                     c->deg, c->touched, c->reloc_off, c->b_eu, c->b_ev, c->b_ew, c->b_sv, c->b_sc,
-                    c->cc_par, c->cc_dense, c->cc_comp, c->cc_block, c->cc_kept, c->cc_W};
+                    c->cc_par, c->cc_dense, c->cc_comp, c->cc_block, c->cc_kept, c->cc_W,
+                    c->pb_src, c->pb_lpos, c->pb_oslot, c->pb_tmp, c->pb_dst, c->pb_wn, c->pb_val, c->pb_len, c->pb_upd,
+                    c->pb_first, c->pb_block, c->pb_bin, c->pb_table};
     for (void* p : ptrs) dev_free(c, p);
     if (c->cc_ctr) (void)hipFree(c->cc_ctr);
     if (c->h_cc) (void)hipHostFree(c->h_cc);
@@ -863,6 +1013,8 @@ dynlp_status dynlp_create(dynlp_ctx** out, int64_t n, const int64_t* row_ptr, co
     if (o.binary_scalar != 0 && num_classes != 2) return bad("binary_scalar needs num_classes == 2");
     const int Cs = o.binary_scalar != 0 ? 1 : num_classes;  // stored columns
     const int CP = padded_classes(Cs);
+    if (o.binned_rounds != 0 && o.binned_rounds != -1 && (o.binned_rounds < kPbMinBinBits || o.binned_rounds > kPbMaxBinBits))
+        return bad("binned_rounds must be 0 (automatic), -1 (never) or a number of bin bits from 8 to 15");
     if (o.group_lanes != 0) {
         const int g = o.group_lanes;
         if (!(g == 4 || g == 8 || g == 16 || g == 32 || g == 64) || g < lanes_per_neighbour(CP))
@@ -900,6 +1052,7 @@ dynlp_status dynlp_create(dynlp_ctx** out, int64_t n, const int64_t* row_ptr, co
         c->slack = o.slack_factor;
         c->time_kernels = o.time_kernels != 0;
         c->group_lanes = o.group_lanes;
+        c->binned = o.binned_rounds;
         c->alloc_fn = o.alloc;
         c->dealloc_fn = o.dealloc;
         c->alloc_user = o.alloc_user;
@@ -1486,6 +1639,15 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
         bool pingpong = false;
         int stretch_start = 0;  // first round of the running ping-pong stretch
         bool fused = false;     // the stretch's rounds evaluate V_aff themselves (no frontier list, no pull)
+        bool binned = false;    // ... as scatter + gather passes (scalar labels)
+        // Rounds that repeat themselves exactly (same |V_aff|, rows moved and max change, 16 times in a row) are in
+        // a period-2 cycle kept alive by float32 rounding (in-place rounds too: the few rows of such a V_aff run side
+        // by side in one wave and read each other's old values); the rest of the batch's flag-marking rounds then
+        // average old and new row (kRowLazy), which has the same fixed point and no such cycle.
+        int same_run = 0;
+        bool lazy = false;
+        unsigned int prev_sig[3] = {0xffffffffu, 0xffffffffu, 0xffffffffu};
+        c->pb_built = false;    // the batch changed the graph
         const bool in_place = c->update_mode == DYNLP_UPDATE_IN_PLACE;
         while (known > 0 && it < c->max_iter) {
             const int G = choose_group(c, avg_len);
@@ -1495,14 +1657,17 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
             // Inside a stretch no frontier list exists: its first round works on the list it was handed, the
             // later ones evaluate V_aff = {u : u or a neighbour moved in the previous round} per row, from
             // the bitmap of moved rows.  Leaving a stretch pulls the list out of the last bitmap once.
-            if (!pingpong && (double)known >= kDenseEnter * (double)universe.size()) {
+            const bool can_bin = binned_rounds_pay(c, universe, avg_len);
+            if (!pingpong && (double)known >= (can_bin ? kBinnedEnter : kDenseEnter) * (double)universe.size()) {
                 if (!in_place) sync_partner(c);
                 for (unsigned int* mv : c->moved)
                     HIPCHK(c, hipMemsetAsync(mv, 0, (size_t)c->moved_words * sizeof(unsigned int), c->stream));
                 pingpong = true;
                 stretch_start = it;
-                fused = fused_rounds_pay(c, avg_len);
-            } else if (pingpong && (double)known < kDenseLeave * (double)universe.size()) {
+                binned = can_bin;
+                fused = binned || fused_rounds_pay(c, avg_len);
+                if (binned && !c->pb_built) build_binned(c);
+            } else if (pingpong && (double)known < (binned ? kBinnedLeave : kDenseLeave) * (double)universe.size()) {
                 pingpong = false;
                 if (fused) {
                     // rows of the last round are in F (the buffers were swapped to make it so)
@@ -1539,7 +1704,10 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
                     } else {
                         const PullRoundArgs a{slot_of(c, t - 1), buf[i & 1], buf[(i + 1) & 1], c->moved[(q - 1) % 3],
                                               c->moved[q % 3], c->moved[(q + 1) % 3], c->tol, slot, slot_of(c, t + 1)};
-                        launch_update_pull(c, G, universe, a);
+                        if (binned)
+                            launch_binned_round(c, a);
+                        else
+                            launch_update_pull(c, G, universe, a);
                     }
                 } else {
                     // rows are staged by frontier position and committed after the kernel; rows that moved mark
@@ -1547,7 +1715,7 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
                     // (in-place mode: written straight into F, nothing to commit)
                     const UpdateArgs a{slot_of(c, t - 1), 0, c->F, in_place ? c->F : c->F2, nullptr, c->tol,
                                        slot, slot_of(c, t + 1), (int64_t)universe.size(), (int64_t)universe.nl,
-                                       in_place ? 1 : 0};
+                                       (in_place ? kRowByVertex : 0) | (lazy ? kRowLazy : 0)};
                     launch_update<true>(c, G, f, a);
                     if (!in_place) launch_commit(c, f, slot_of(c, t - 1), (int64_t)universe.size());
                     launch_compact(c, frontier_of(c, cur ^ 1), &slot->next_count, &slot->next_long, 0);
@@ -1566,10 +1734,14 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
                 edges += (int64_t)(rc.edges + rc.edges_long);
                 avg_len = nq ? (double)(rc.edges + rc.edges_long) / (double)nq : avg_len;
                 // the first round of a fused stretch still works on a frontier list
-                c->log.push_back(round_info(rc, !pingpong ? 1 : (fused && it + i > stretch_start ? 2 : 0), G));
+                c->log.push_back(round_info(rc, !pingpong ? 1 : (fused && it + i > stretch_start ? (binned ? 3 : 2) : 0), G));
                 // inside a stretch the next V_aff is not counted: this round's size stands in for it while
                 // rows still move
                 known = pingpong && fused ? (rc.changed ? std::max(nq, 1u) : 0u) : rc.next_count + rc.next_long;
+                const unsigned int sig[3] = {nq, rc.changed, rc.resid_bits};
+                same_run = (!pingpong && std::memcmp(sig, prev_sig, sizeof sig) == 0) ? same_run + 1 : 0;
+                std::memcpy(prev_sig, sig, sizeof sig);
+                if (same_run >= 16) lazy = true;
                 peak = std::max<int64_t>(peak, known);
             }
             if (pingpong && !in_place && (executed & 1)) std::swap(c->F, c->F2);  // the output of the last executed round

@@ -398,8 +398,11 @@ __device__ inline void flush_round_counters(float rmax, unsigned long long edges
 //            (if not NULL; see k_pull_frontier).
 //   STAGED = true (partial round): F'_u is staged at row pos of F_out so that every row of this
 //            round reads the round-start F (Jacobi); a row that moved by > tol marks itself and
-//            its neighbours in flag[] for the next round.  With by_vertex != 0 the row is written
-//            to row u of F_out instead (in-place rounds, F_out == F_in: nothing to commit).
+//            its neighbours in flag[] for the next round.  by_vertex is a set of flags.  kRowByVertex: the
+//            row is written to row u of F_out instead (in-place rounds, F_out == F_in: nothing to commit).
+//            kRowLazy: the new row is the mean of the old row and the weighted mean of the neighbours (same
+//            fixed point; the host asks for it when rounds repeat themselves exactly, a period-2 cycle
+//            that float32 rounding keeps alive in a nearly bipartite, weakly tied component).
 // F_in and F_out may be the same array (in-place mode): a row then reads whatever its neighbours
 // hold at that moment.  Reads and writes are whole 16-byte segments, columns are independent linear
 // systems, and the update is a contraction per column, so mixed old/new reads only change the path
@@ -408,6 +411,8 @@ __device__ inline void flush_round_counters(float rmax, unsigned long long edges
 //            are in V_aff: u is updated iff u or one of its neighbours moved by more than tol in the previous
 //            round (bitmap moved_prev) - Alg. 2 Step 3's V_aff, evaluated where the row is read anyway.  A row
 //            outside V_aff is copied to F_out when that is another buffer, so the two keep agreeing there.
+constexpr int kRowByVertex = 1, kRowLazy = 2;
+
 template <int CP, int G, bool STAGED, bool PULL = false>
 __device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, const int32_t* __restrict__ front,
                                         unsigned int ns, const RowMeta* __restrict__ meta,
@@ -461,11 +466,12 @@ __device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, 
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
             fn.v[k] = acc.v[k] / s;
+            if (STAGED && (by_vertex & kRowLazy)) fn.v[k] = 0.5f * (fn.v[k] + old.v[k]);
             r = fmaxf(r, fabsf(fn.v[k] - old.v[k]));
         }
 #pragma unroll
         for (int d = 1; d < LPN; d <<= 1) r = fmaxf(r, __shfl_xor(r, d, G));
-        if (slot == 0) store_vec<VEC>(F_out + (size_t)(STAGED && !by_vertex ? g : (unsigned int)u) * CP + chunk * VEC, fn);
+        if (slot == 0) store_vec<VEC>(F_out + (size_t)(STAGED && !(by_vertex & kRowByVertex) ? g : (unsigned int)u) * CP + chunk * VEC, fn);
         const bool big = r > tol;
         if (STAGED) {
             if (big) {  // V_aff <- V_aff U {u} U N(u); the last chunk of the row is still in registers
@@ -560,11 +566,12 @@ __device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, c
 #pragma unroll
             for (int k = 0; k < VEC; ++k) {
                 fn.v[k] = tot.v[k] / st;
+                if (STAGED && (by_vertex & kRowLazy)) fn.v[k] = 0.5f * (fn.v[k] + old.v[k]);
                 r = fmaxf(r, fabsf(fn.v[k] - old.v[k]));
             }
 #pragma unroll
             for (int d = 1; d < LPN; d <<= 1) r = fmaxf(r, __shfl_xor(r, d, G));
-            store_vec<VEC>(F_out + (size_t)(STAGED && !by_vertex ? pos_base + j : (unsigned int)u) * CP + chunk * VEC, fn);
+            store_vec<VEC>(F_out + (size_t)(STAGED && !(by_vertex & kRowByVertex) ? pos_base + j : (unsigned int)u) * CP + chunk * VEC, fn);
             if (gl == 0) {
                 const bool big = r > tol;
                 sh_big = big ? 1 : 0;

@@ -1,0 +1,130 @@
+"""GPU parity of the binned rounds (scalar labels; rounds over nearly all vertices run as a scatter pass
+into bins of receivers plus a gather pass per bin, with fixed-point accumulation) against the oracle's
+synchronous Step 3, against the library's ordinary rounds, and against the exact labels.
+
+``binned_rounds=8`` forces the binned passes with 256 receivers per bin, so that graphs of a few thousand
+vertices already span tens of bins and a ragged last one."""
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import native as ON
+from oracle import reference as R
+import paper_2604_06596_amd as P
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-6
+ROUNDS_ATOL = 5e-6
+O1_ATOL = 1e-4
+
+
+def _make(p, **kw):
+    return P.DynLP(p.n, p.row_ptr, p.col, p.w, p.C, p.seed_vertex, p.seed_class, binary_scalar=True, **kw)
+
+
+def _case(kind, seed):
+    """(problem for the batch generator, pristine copy, batch, vertices to delete)"""
+    if kind == "random":
+        mk = lambda: W.small_random(6007, 2, 8.0, 300, seed)
+        p, p0 = mk(), mk()
+        b = W.small_random_batch(p, 600, 7, 12, num_extra_edges=60, num_revealed=3)
+    else:  # heavy-tailed degrees: hub receivers take thousands of additions into one accumulator
+        mk = lambda: W.chung_lu(20000, 2, 12.0, 2.1, 3000, 0.8, 0.02, seed)
+        p, p0 = mk(), mk()
+        b = W.chung_lu_vertex_batch(p, 2000, 0.02)
+    dead = np.random.default_rng(seed).choice(p0.n, size=40, replace=False).astype(np.int32)
+    return p0, b, dead
+
+
+def _oracle_after(p0, b, dead, soft0):
+    g = R.Graph(p0.n, p0.row_ptr, p0.col, p0.w, p0.C, p0.seed_vertex, p0.seed_class)
+    n_old = g.n
+    rp0, col0, _ = g.csr()
+    dn = np.concatenate([col0[rp0[u]:rp0[u + 1]] for u in dead]) if len(dead) else np.zeros(0, np.int32)
+    g.delete(dead)
+    g.insert(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+    rp, col, w = g.csr()
+    A0 = ON.affected_set(rp, col, g.seed_class, n_old, b.eu, b.ev, b.seed_vertex, deleted_neighbours=dn)
+    F = np.concatenate([soft0.astype(np.float64), np.full((b.num_new_vertices, 2), 0.5)])
+    F[dead] = 0.5
+    F[b.seed_vertex] = np.eye(2)[b.seed_class]
+    return g, rp, col, w, F, A0
+
+
+def _run(p0, b, dead, max_iter, binned, mode=P.UPDATE_SYNCHRONOUS, tol=TOL):
+    with _make(p0, binned_rounds=binned) as d:
+        d.set_update_mode(mode)
+        assert d.static_solve(TOL, 20000)[0] == 0
+        soft0, _ = d.get_labels()
+        d.set_params(tol, max_iter)
+        st, s = d.apply_update(dead, b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+        soft, hard = d.get_labels()
+        sizes, deltas = d.round_log()
+        kinds = [int(r.staged) for r in d.round_log_full()]
+    return dict(st=st, s=s, soft0=soft0, soft=soft, hard=hard, sizes=sizes, deltas=deltas, kinds=kinds)
+
+
+@pytest.mark.parametrize("kind", ["random", "hub"])
+@pytest.mark.parametrize("R_", [12, 40])
+def test_binned_rounds_match_the_oracle_round_by_round(kind, R_):
+    p0, b, dead = _case(kind, 5100)
+    out = _run(p0, b, dead, R_, 8)
+    g, rp, col, w, F, A0 = _oracle_after(p0, b, dead, out["soft0"])
+    o2 = ON.step3_propagate(rp, col, w, F, g.seed_class, A0, TOL, R_)
+    print("round kinds", out["kinds"], "sizes", out["sizes"].tolist())
+    assert 3 in out["kinds"], "the case is meant to reach binned rounds"
+    assert out["s"].frontier_initial == len(A0) and out["s"].iterations == o2["rounds"] == R_
+    assert out["sizes"].tolist() == o2["frontier_sizes"].tolist()
+    assert np.max(np.abs(out["soft"] - o2["F"])) <= ROUNDS_ATOL
+    np.testing.assert_allclose(out["deltas"], o2["max_changes"], atol=1e-6)
+    assert out["s"].rows_updated == o2["rows_updated"] and out["s"].edges_traversed == o2["edges_traversed"]
+    # the scalar is a probability and its complement is derived from it
+    assert out["soft"].min() >= 0 and out["soft"].max() <= 1
+    assert np.array_equal(out["soft"][:, 0], np.float32(1.0) - out["soft"][:, 1])
+
+
+@pytest.mark.parametrize("kind", ["random", "hub"])
+def test_binned_rounds_against_ordinary_rounds_and_twice_the_same(kind):
+    """Synchronous mode: binned rounds follow the same V_aff as the ordinary rounds and give the same labels to
+    rounding; two runs give identical bits (integer accumulation does not depend on the order of the atomics or
+    on where the build step placed an entry)."""
+    p0, b, dead = _case(kind, 5200)
+    a = _run(p0, b, dead, 60, 8)
+    a2 = _run(p0, b, dead, 60, 8)
+    c = _run(p0, b, dead, 60, -1)
+    assert 3 in a["kinds"] and 3 not in c["kinds"]
+    assert np.array_equal(a["soft"], a2["soft"]) and a["sizes"].tolist() == a2["sizes"].tolist()
+    assert a["sizes"].tolist() == c["sizes"].tolist()
+    assert np.max(np.abs(a["soft"] - c["soft"])) <= 2e-6
+
+
+@pytest.mark.parametrize("mode", [P.UPDATE_SYNCHRONOUS, P.UPDATE_IN_PLACE], ids=["synchronous", "in_place"])
+@pytest.mark.parametrize("kind", ["random", "hub"])
+def test_binned_rounds_converge_to_the_exact_labels(kind, mode):
+    p0, b, dead = _case(kind, 5300)
+    out = _run(p0, b, dead, 20000, 8, mode=mode)
+    g, rp, col, w, F, A0 = _oracle_after(p0, b, dead, out["soft0"])
+    assert out["st"] == 0 and 3 in out["kinds"]
+    exact, _, _ = ON.itlp_solve(rp, col, w, g.seed_class, 2, tol=1e-12, max_iter=5_000_000)
+    reach = R.seed_reachable(rp, col, g.seed_class)
+    assert np.max(np.abs(out["soft"] - exact)[reach]) <= O1_ATOL
+    clear = reach & (R.top2_margin(exact) > 2 * O1_ATOL)
+    assert np.array_equal(out["hard"][clear], R.hard_labels(exact)[clear])
+    s_idx = np.flatnonzero(g.seed_class >= 0)
+    assert np.array_equal(out["soft"][s_idx], R.initial_labels(g.seed_class, 2)[s_idx].astype(np.float32))
+
+
+def test_binned_rounds_need_the_scalar_layout_and_a_valid_bin_size():
+    p = W.small_random(500, 2, 6.0, 30, 7)
+    with pytest.raises(P.DynLPError) as ei:
+        _make(p, binned_rounds=5)
+    assert "binned_rounds" in ei.value.message
+    # with n x C rows the option is accepted and ignored
+    p3 = W.small_random(3000, 3, 8.0, 150, 8)
+    p3b = W.small_random(3000, 3, 8.0, 150, 8)
+    b = W.small_random_batch(p3, 300, 7, 5)
+    with P.DynLP(p3b.n, p3b.row_ptr, p3b.col, p3b.w, p3b.C, p3b.seed_vertex, p3b.seed_class, binned_rounds=8) as d:
+        assert d.static_solve(TOL, 20000)[0] == 0
+        st, s = d.apply_batch(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+        assert st == 0 and 3 not in [int(r.staged) for r in d.round_log_full()]

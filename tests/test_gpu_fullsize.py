@@ -290,12 +290,14 @@ def test_cfg3_full_size_mixed_batch_with_deletions(mode):
     assert np.array_equal(hard[clear], R.hard_labels(Fn)[clear])
 
 
+@pytest.mark.parametrize("binned,mode", [(-1, "in_place"), (15, "in_place"), (15, "synchronous")])
 @pytest.mark.parametrize("init", ["uniform", "supernode"])
-def test_cfg6_binary_scalar_single_batch_properties(init):
+def test_cfg6_binary_scalar_single_batch_properties(init, binned, mode):
     """The paper's own setting (binary scalar labels, Erdos-Renyi graph of mean degree 5, every unlabelled
     vertex arriving in one batch) at a tenth of its 50M vertices, in the configuration bench.py times
-    (in-place mode, scalar layout, device pointers): graph bookkeeping, first V_aff, residual property,
-    hard labels by the 0.5 cut-off."""
+    (scalar layout, device pointers): graph bookkeeping, first V_aff, residual property, hard labels by the
+    0.5 cut-off.  At full size the library runs the rounds over nearly all vertices as binned passes with 32,768
+    receivers per bin; here (5M vertices: labels still fit the L2) that is switched on by the option, or off."""
     cfg = W.CONFIGS["cfg6"]
     tol = cfg["tol"]
     p = W.make_config("cfg6", 0.1 * SCALE)
@@ -303,15 +305,17 @@ def test_cfg6_binary_scalar_single_batch_properties(init):
     n0, n1 = p.n, p.n + b.num_new_vertices
     d = P.DynLP(n0, _dv(p.row_ptr, torch.int64), _dv(p.col, torch.int32), _dv(p.w, torch.float32), 2,
                 _dv(p.seed_vertex, torch.int32), _dv(p.seed_class, torch.int32), device_ptrs=True, binary_scalar=True,
-                reserve_vertices=b.num_new_vertices + 1024, reserve_edges=2 * b.num_edges + 1024)
+                reserve_vertices=b.num_new_vertices + 1024, reserve_edges=2 * b.num_edges + 1024, binned_rounds=binned)
     try:
-        d.set_update_mode(P.UPDATE_IN_PLACE)
+        d.set_update_mode(P.UPDATE_IN_PLACE if mode == "in_place" else P.UPDATE_SYNCHRONOUS)
         assert d.static_solve(tol, cfg["max_iter"])[0] == 0
         if init == "supernode":
             d.set_initialiser(P.INIT_SUPERNODE, np.float32(d.mean_edge_weight()))
         st, s = d.apply_batch(b.num_new_vertices, _dv(b.eu, torch.int32), _dv(b.ev, torch.int32), _dv(b.ew, torch.float32),
                               None, None)
         assert st == 0 and s.converged == 1
+        kinds = [int(r.staged) for r in d.round_log_full()]
+        assert (3 in kinds) == (binned > 0)
         soft, hard = d.get_labels()
         soft, hard = soft.cpu().numpy(), hard.cpu().numpy()
         assert d.num_vertices == n1 and d.num_entries == p.col.shape[0] + 2 * b.num_edges
@@ -323,17 +327,19 @@ def test_cfg6_binary_scalar_single_batch_properties(init):
     A0 = ON.affected_set(rp, col, sc, n0, b.eu, b.ev, b.seed_vertex)
     assert s.frontier_initial == A0.shape[0]
     Fn, res = ON.itlp_sweep(rp, col, w.astype(np.float64), soft.astype(np.float64), sc)
-    print(f"cfg6/10 ({init}): {s.iterations} rounds, |V_aff|0 = {s.frontier_initial}, oracle residual of the GPU "
+    print(f"cfg6/10 ({init}, {mode}, binned {binned}: {kinds.count(3)} binned rounds): {s.iterations} rounds, |V_aff|0 = {s.frontier_initial}, oracle residual of the GPU "
           f"labels {res:.2e}")
     # on this sparse graph (many rows of degree 1-2, long chains of sub-threshold moves) measured at 0.64 of the bound
-    assert res <= tol * n1 / seeds_count(sc)
+    # with in-place rows; rounds that read round-start labels only (synchronous mode, binned rounds) stop rows
+    # earlier and leave up to 1.1 of it
+    assert res <= (1.0 if binned < 0 else 1.5) * tol * n1 / seeds_count(sc)
     assert np.array_equal(soft[:, 0], np.float32(1.0) - soft[:, 1])
     assert np.array_equal(hard, (soft[:, 1] > 0.5).astype(np.int32))
     seeds = np.flatnonzero(sc >= 0)
     assert np.array_equal(soft[seeds], R.initial_labels(sc, 2)[seeds].astype(np.float32))
     lone = np.flatnonzero(np.diff(rp) == 0)
     assert np.all(soft[lone[sc[lone] < 0]] == 0.5)  # isolated unlabelled vertices keep the neutral value
-    clear = R.top2_margin(Fn) > 2 * tol * n1 / seeds_count(sc)
+    clear = R.top2_margin(Fn) > 3 * tol * n1 / seeds_count(sc)
     assert np.array_equal(hard[clear], R.hard_labels(Fn)[clear])
 
 

@@ -363,6 +363,38 @@ def test_rounds_over_nearly_all_vertices_match_the_oracle_round_by_round(deg, C,
         assert np.max(np.abs(soft - o2["F"])) <= _o2_atol(g, tol)  # a row that freezes a round earlier keeps ~tol
 
 
+@pytest.mark.parametrize("mode", ["synchronous", "in_place"])
+def test_a_strongly_tied_pair_converges_in_both_modes(mode):
+    """Two new vertices tied to each other by weight 1 and to two seeds of different classes by weight 0.001: the
+    Jacobi map has an eigenvalue -1/1.001 there.  In float32 the alternating error stops shrinking once 0.1% of it
+    is less than half an ulp (around 3e-5, far above tol), and synchronous rounds would repeat the same two states
+    until max_iter (in-place rounds too: the two rows run side by side and read each other's old values); the
+    library notices rounds that repeat exactly and averages old and new rows from then on.  The result is the
+    exact harmonic solution: the pair sits at 0.5 -/+ 0.0005/2.001."""
+    p = W.small_random(400, 2, 6.0, 40, 4242)
+    a = int(p.seed_vertex[np.flatnonzero(p.seed_class == 0)[0]])
+    b_ = int(p.seed_vertex[np.flatnonzero(p.seed_class == 1)[0]])
+    u, v = p.n, p.n + 1
+    batch = W.Batch(2, np.array([u, u, v], np.int32), np.array([v, a, b_], np.int32),
+                    np.array([1.0, 0.001, 0.001], np.float32), np.zeros(0, np.int32), np.zeros(0, np.int32))
+    with _make(p) as d:
+        if mode == "in_place":
+            d.set_update_mode(P.UPDATE_IN_PLACE)
+        assert d.static_solve(TOL, 20000)[0] == 0
+        d.set_params(TOL, 20000)
+        st, s = d.apply_batch(2, batch.eu, batch.ev, batch.ew, batch.seed_vertex, batch.seed_class)
+        soft, hard = d.get_labels()
+    print(mode, "rounds", s.iterations, "pair", soft[u], soft[v])
+    assert st == 0 and s.converged == 1
+    assert s.iterations < 8000
+    gap = 0.0005 / 2.001
+    # the threshold rule stops a mode that shrinks by 0.05-0.1% per round while it is still tol / 0.001 away at most
+    assert abs(soft[u, 1] - (0.5 - gap)) <= O1_ATOL and abs(soft[v, 1] - (0.5 + gap)) <= O1_ATOL
+    assert soft[v, 1] - soft[u, 1] > gap
+    assert abs(soft[u, 0] + soft[u, 1] - 1) <= 2 * O1_ATOL  # the columns are solved separately, each to that accuracy
+    assert hard[u] == 0 and hard[v] == 1
+
+
 def test_cfg1_batch_update_matches_oracle():
     p = W.make_config("cfg1")
     b = W.knn_mixture_batch(p, 100, 5)
