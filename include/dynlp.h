@@ -288,7 +288,9 @@ typedef struct dynlp_round_info {
                               kernel); 0: rows written by vertex and the next V_aff pulled from a bitmap of
                               moved rows (static sweeps, rounds over nearly all vertices); 2: as 0, but the
                               round ran over all updatable vertices and decided per row, from the previous
-                              round's bitmap, whether the row is in V_aff (no frontier list in between) */
+                              round's bitmap, whether the row is in V_aff (no frontier list in between); 3: as 2,
+                              as a binned round (scalar labels: scatter pass + gather pass, see
+                              dynlp_options.binned_rounds) */
     int32_t group_lanes;   /* lanes per row the short-row kernel ran with */
 } dynlp_round_info;
 

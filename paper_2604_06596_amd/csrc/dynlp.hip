@@ -540,8 +540,7 @@ void launch_update_pull(dynlp_ctx* c, int G, const Frontier& universe, const Pul
 // vertices of degree 5: 1.63 against 6.2 ms; 10M vertices of mean degree 38: 2.26 against 6.2 ms; 1M vertices of
 // mean degree 20 (4 MB of labels): 0.29 against 0.24 ms, and whole batches twice as slow because the binned
 // rounds are Jacobi rounds also in in-place mode.
-bool binned_rounds_pay(const dynlp_ctx* c, const Frontier& universe, double avg_len) {
-    (void)avg_len;
+bool binned_rounds_pay(const dynlp_ctx* c, const Frontier& universe) {
     if (c->CP != 1 || c->binned < 0) return false;
     if (ceil_div(c->n, (int64_t)1 << (c->binned > 0 ? c->binned : kPbMaxBinBits)) > kPbMaxBins) return false;
     if (c->entries >= ((int64_t)1 << 32) - 2 * kPbChunk) return false;  // slots and stream positions are 32-bit
@@ -1657,7 +1656,7 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
             // Inside a stretch no frontier list exists: its first round works on the list it was handed, the
             // later ones evaluate V_aff = {u : u or a neighbour moved in the previous round} per row, from
             // the bitmap of moved rows.  Leaving a stretch pulls the list out of the last bitmap once.
-            const bool can_bin = binned_rounds_pay(c, universe, avg_len);
+            const bool can_bin = binned_rounds_pay(c, universe);
             if (!pingpong && (double)known >= (can_bin ? kBinnedEnter : kDenseEnter) * (double)universe.size()) {
                 if (!in_place) sync_partner(c);
                 for (unsigned int* mv : c->moved)

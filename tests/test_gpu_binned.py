@@ -115,6 +115,28 @@ def test_binned_rounds_converge_to_the_exact_labels(kind, mode):
     assert np.array_equal(out["soft"][s_idx], R.initial_labels(g.seed_class, 2)[s_idx].astype(np.float32))
 
 
+@pytest.mark.parametrize("n,deg,new", [(3, 1.0, 1), (50, 3.0, 5), (257, 4.0, 40), (700, 2.2, 300)])
+def test_binned_rounds_on_tiny_and_ragged_graphs(n, deg, new):
+    """One bin or a few, a last bin that is mostly empty, rows of one entry, vertices without edges: the binned
+    rounds must follow the ordinary rounds' V_aff exactly and end at the same labels."""
+    mk = lambda: W.small_random(n, 2, deg, max(2, n // 10), 600 + n, connected=(n != 700))
+    p, p0 = mk(), mk()
+    b = W.small_random_batch(p, new, 2, 1 if new > 1 else 0)
+    none = np.zeros(0, np.int32)
+    a = _run(p0, b, none, 20000, 8)
+    c = _run(p0, b, none, 20000, -1)
+    print("kinds", a["kinds"][:12], "sizes", a["sizes"][:12].tolist())
+    assert a["st"] == 0 and c["st"] == 0
+    assert a["s"].frontier_initial == c["s"].frontier_initial
+    k = min(len(a["sizes"]), len(c["sizes"]), 10)
+    assert a["sizes"][:k].tolist() == c["sizes"][:k].tolist()
+    assert np.max(np.abs(a["soft"] - c["soft"])) <= 2e-5
+    g, rp, col, w, F, A0 = _oracle_after(p0, b, none, a["soft0"])
+    exact, _, _ = ON.itlp_solve(rp, col, w, g.seed_class, 2, tol=1e-12, max_iter=5_000_000)
+    reach = R.seed_reachable(rp, col, g.seed_class)
+    assert np.max(np.abs(a["soft"] - exact)[reach]) <= O1_ATOL
+
+
 def test_binned_rounds_need_the_scalar_layout_and_a_valid_bin_size():
     p = W.small_random(500, 2, 6.0, 30, 7)
     with pytest.raises(P.DynLPError) as ei:
