@@ -1390,13 +1390,19 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
         const auto t_it = Clock::now();
         // synchronous: sweep t reads buf[t & 1], writes buf[(t + 1) & 1]; in place: every sweep reads and writes F
         float* const buf[2] = {c->F, in_place ? c->F : c->F2};
+        // sweeps whose max change repeats exactly 16 times are in a float32 limit cycle (a nearly bipartite, weakly
+        // tied component): the remaining sweeps average old and new rows (same fixed point, no such cycle)
+        int same_run = 0;
+        bool lazy = false;
+        unsigned int prev_bits = 0xffffffffu;
         while (!converged && it < max_iter) {
             // a chain of sweeps; each checks on the device whether its predecessor already met the stop rule
             const int r = std::min<int>(kChain, max_iter - it);
             for (int i = 0; i < r; ++i) {
                 const int t = it + i;
                 const UpdateArgs a{slot_of(c, t - 1), t == 0 ? 1 : 2, buf[t & 1], buf[(t + 1) & 1], nullptr, tol,
-                                   slot_of(c, t), slot_of(c, t + 1), (int64_t)nq, (int64_t)c->h_slot_start_long};
+                                   slot_of(c, t), slot_of(c, t + 1), (int64_t)nq, (int64_t)c->h_slot_start_long,
+                                   lazy ? kRowLazy : 0};
                 launch_update<false>(c, G, f, a);
             }
             read_slots(c, it, r);
@@ -1407,6 +1413,9 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
                 edges += (int64_t)(rc.edges + rc.edges_long);
                 c->log.push_back(round_info(rc, 0, G));
                 ++it;
+                same_run = rc.resid_bits == prev_bits ? same_run + 1 : 0;
+                prev_bits = rc.resid_bits;
+                if (same_run >= 16) lazy = true;
                 if (last <= tol) {
                     converged = true;
                     break;

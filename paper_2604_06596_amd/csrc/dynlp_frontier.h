@@ -466,7 +466,7 @@ __device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, 
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
             fn.v[k] = acc.v[k] / s;
-            if (STAGED && (by_vertex & kRowLazy)) fn.v[k] = 0.5f * (fn.v[k] + old.v[k]);
+            if (by_vertex & kRowLazy) fn.v[k] = 0.5f * (fn.v[k] + old.v[k]);
             r = fmaxf(r, fabsf(fn.v[k] - old.v[k]));
         }
 #pragma unroll
@@ -566,7 +566,7 @@ __device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, c
 #pragma unroll
             for (int k = 0; k < VEC; ++k) {
                 fn.v[k] = tot.v[k] / st;
-                if (STAGED && (by_vertex & kRowLazy)) fn.v[k] = 0.5f * (fn.v[k] + old.v[k]);
+                if (by_vertex & kRowLazy) fn.v[k] = 0.5f * (fn.v[k] + old.v[k]);
                 r = fmaxf(r, fabsf(fn.v[k] - old.v[k]));
             }
 #pragma unroll

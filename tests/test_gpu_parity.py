@@ -395,6 +395,32 @@ def test_a_strongly_tied_pair_converges_in_both_modes(mode):
     assert hard[u] == 0 and hard[v] == 1
 
 
+@pytest.mark.parametrize("mode", ["synchronous", "in_place"])
+def test_static_solve_leaves_a_float32_limit_cycle(mode):
+    """The same strongly tied pair as part of the graph the cold start solves: sweeps whose max change repeats
+    exactly switch to averaged rows, and the solve ends well before max_iter at the harmonic solution."""
+    p = W.small_random(400, 2, 6.0, 40, 4243)
+    a = int(p.seed_vertex[np.flatnonzero(p.seed_class == 0)[0]])
+    b_ = int(p.seed_vertex[np.flatnonzero(p.seed_class == 1)[0]])
+    g = _oracle_graph(p)
+    u, v = p.n, p.n + 1
+    g.insert(2, np.array([u, u, v], np.int32), np.array([v, a, b_], np.int32), np.array([1.0, 0.001, 0.001], np.float32),
+             np.zeros(0, np.int32), np.zeros(0, np.int32))
+    rp, col, w = g.csr()
+    sv = np.flatnonzero(g.seed_class >= 0).astype(np.int32)
+    with P.DynLP(g.n, rp, col, w.astype(np.float32), 2, sv, g.seed_class[sv]) as d:
+        if mode == "in_place":
+            d.set_update_mode(P.UPDATE_IN_PLACE)
+        st, s = d.static_solve(TOL, 50000)
+        soft, hard = d.get_labels()
+    print(mode, "sweeps", s.iterations, "pair", soft[u], soft[v])
+    assert st == 0 and s.iterations < 20000
+    gap = 0.0005 / 2.001
+    assert abs(soft[u, 1] - (0.5 - gap)) <= O1_ATOL and abs(soft[v, 1] - (0.5 + gap)) <= O1_ATOL
+    exact = R.harmonic_closed_form(rp, col, w, g.seed_class, 2)
+    assert np.max(np.abs(soft - exact)) <= 2e-3  # tol / (1 - 0.9995): the threshold rule on a mode that slow
+
+
 def test_cfg1_batch_update_matches_oracle():
     p = W.make_config("cfg1")
     b = W.knn_mixture_batch(p, 100, 5)
