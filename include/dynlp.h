@@ -201,6 +201,11 @@ dynlp_status dynlp_last_components(dynlp_ctx* ctx, int64_t cap, int32_t* comp, d
  * u in V_aff from the round-start F; every F'_u is stored; u with max_c |F'_u - F_u| > tol
  * puts itself and N(u) into the next V_aff; stops when V_aff is empty (DYNLP_OK) or after
  * max_iter rounds (DYNLP_NOT_CONVERGED).
+ * One safeguard beyond the paper: when 16 consecutive rounds repeat exactly (same |V_aff|, same
+ * number of rows moved, same max change) the iteration is in a period-2 cycle that float32
+ * rounding keeps alive (a nearly bipartite, weakly tied component); the batch's remaining rounds on
+ * small V_aff then store the mean of the old row and F'_u, which has the same fixed point.
+ * dynlp_static_solve does the same when the max change of 16 consecutive sweeps is one number.
  * DYNLP_ERR_INVALID_ARG (context unchanged) on: negative counts, NULL array with a positive
  * count, endpoint out of range, self loop, bad weight, seed vertex/class out of range, a vertex
  * given two different classes, relabelling an existing seed with another class.
