@@ -31,7 +31,7 @@
 namespace dynlp {
 
 constexpr int kPbMaxBinBits = 15;                  // receivers per bin: at most 32,768 (128 KB of accumulators)
-constexpr int kPbMinBinBits = 8;                   // at least one workgroup pass (kBlock receivers)
+constexpr int kPbMinBinBits = 8;                   // small bins: for tests on small graphs
 constexpr int kPbMaxBins = 4096;                   // bin histograms live in LDS during the build
 constexpr unsigned int kPbNone = 0xffffffffu;      // slot of an entry whose receiver is never updated
 constexpr int kPbChunk = 16384;                    // entries per chunk: 64 KB of staged values (8K / 16K / 32K entries:

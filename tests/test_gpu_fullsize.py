@@ -343,6 +343,40 @@ def test_cfg6_binary_scalar_single_batch_properties(init, binned, mode):
     assert np.array_equal(hard[clear], R.hard_labels(Fn)[clear])
 
 
+@pytest.mark.skipif(SCALE < 1.0, reason="needs the full 50M-vertex graph")
+def test_cfg6_full_size_binned_rounds_pass_an_ordinary_sweep():
+    """cfg6 at full size (50M vertices, 250M stored entries, synchronous mode): the library must choose binned
+    rounds by itself here, and the labels they end with must be a fixed point for the ordinary row update too:
+    one plain sweep over all rows (dynlp_static_solve with max_iter = 1, the kernel the other tests check against
+    the oracle) may move no row by more than the bound the frontier rule leaves."""
+    cfg = W.CONFIGS["cfg6"]
+    tol = cfg["tol"]
+    p = W.make_config("cfg6", 1.0)
+    b = p.state["single_batch"]
+    n1 = p.n + b.num_new_vertices
+    d = P.DynLP(p.n, _dv(p.row_ptr, torch.int64), _dv(p.col, torch.int32), _dv(p.w, torch.float32), 2,
+                _dv(p.seed_vertex, torch.int32), _dv(p.seed_class, torch.int32), device_ptrs=True, binary_scalar=True,
+                reserve_vertices=b.num_new_vertices + 1024, reserve_edges=2 * b.num_edges + 1024)
+    try:
+        assert d.static_solve(tol, cfg["max_iter"])[0] == 0
+        st, s = d.apply_batch(b.num_new_vertices, _dv(b.eu, torch.int32), _dv(b.ev, torch.int32), _dv(b.ew, torch.float32),
+                              None, None)
+        kinds = [int(r.staged) for r in d.round_log_full()]
+        assert st == 0 and s.converged == 1 and kinds.count(3) > 100
+        assert d.num_vertices == n1 and d.num_entries == p.col.shape[0] + 2 * b.num_edges
+        soft, hard = d.get_labels()
+        st1, s1 = d.static_solve(0.0, 1)  # referee: one ordinary sweep from the labels the batch ended with
+        soft1, _ = d.get_labels()
+        moved = float((soft1[:, 1] - soft[:, 1]).abs().max())
+        print(f"cfg6 full size: {s.iterations} rounds ({kinds.count(3)} binned), {s.ms_total:.0f} ms; an ordinary sweep moves "
+              f"the labels by at most {moved:.2e} (its own max change {s1.final_max_delta:.2e})")
+        assert moved <= 1.5 * tol * n1 / p.seed_vertex.shape[0]
+        assert bool(((soft[:, 1] > 0.5).to(torch.int32) == hard).all())
+        assert float(soft.min()) >= 0.0 and float(soft.max()) <= 1.0
+    finally:
+        d.destroy()
+
+
 def test_cfg5_stream_of_fifty_batches_tracks_the_exact_labels():
     """The edge-stream configuration over many batches (a tenth of its size so that the exact labels can be
     recomputed on the host): edge-only batches plus newly labelled old vertices, in-place mode, drift from the
