@@ -243,7 +243,7 @@ std::string format_validation(int code, long long index) {
 // ---- vertex-indexed arrays --------------------------------------------------------------------
 void alloc_vertex_arrays(dynlp_ctx* c, int64_t new_cap) {
     const int64_t old_n = c->n;
-    const int64_t flag_cap = round_up(new_cap, kFlagsPerBlock) + kFlagsPerBlock;
+    const int64_t flag_cap = round_up(new_cap, 4 * kFlagsPerBlock) + 4 * kFlagsPerBlock;
     RowMeta* meta = dev_alloc_n<RowMeta>(c, new_cap);
     float* F = dev_alloc_n<float>(c, new_cap * c->CP);
     float* F2 = dev_alloc_n<float>(c, new_cap * c->CP);
@@ -684,9 +684,15 @@ dynlp_round_info round_info(const RoundCtr& r, int kind, int G) {
 // *count_short / *count_long, which must be zero beforehand.
 void launch_compact(dynlp_ctx* c, const Frontier& out, unsigned int* count_short, unsigned int* count_long,
                     int all_rows) {
-    const unsigned int blocks = (unsigned int)ceil_div(std::max<int64_t>(c->n, 1), kFlagsPerBlock);
-    hipLaunchKernelGGL(k_compact, dim3(blocks), dim3(kBlock), 0, c->stream, (unsigned int)c->n, c->flag, c->seed_class,
-                       c->meta, all_rows, out.front, out.back, count_short, count_long);
+    if (c->n >= (16 << 20)) {
+        const unsigned int blocks = (unsigned int)ceil_div(std::max<int64_t>(c->n, 1), 4 * kFlagsPerBlock);
+        hipLaunchKernelGGL(k_compact<4>, dim3(blocks), dim3(kBlock), 0, c->stream, (unsigned int)c->n, c->flag, c->seed_class,
+                           c->meta, all_rows, out.front, out.back, count_short, count_long);
+    } else {
+        const unsigned int blocks = (unsigned int)ceil_div(std::max<int64_t>(c->n, 1), kFlagsPerBlock);
+        hipLaunchKernelGGL(k_compact<1>, dim3(blocks), dim3(kBlock), 0, c->stream, (unsigned int)c->n, c->flag, c->seed_class,
+                           c->meta, all_rows, out.front, out.back, count_short, count_long);
+    }
     HIPCHK(c, hipGetLastError());
 }
 
