@@ -92,8 +92,8 @@ typedef struct dynlp_options {
                                 (1 - F_u, F_u).  0: n x C rows */
     int32_t binned_rounds;   /* scalar labels only (tuning knob): rounds over nearly all vertices as two streaming
                                 passes (scatter labels into bins of receivers, gather per bin) instead of row
-                                updates with random gathers.  0: the library decides (large graphs with short
-                                rows); -1: never; 8..15: always, with 2^k receivers per bin */
+                                updates with random gathers.  0: the library decides (graphs of 2M updatable
+                                vertices or more); -1: never; 8..15: always, with 2^k receivers per bin */
 } dynlp_options;
 
 /* Fill *opt with the defaults (device 0, default stream, host pointers). */

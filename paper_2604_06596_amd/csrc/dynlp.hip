@@ -535,17 +535,19 @@ void launch_update_pull(dynlp_ctx* c, int G, const Frontier& universe, const Pul
 
 // ---- binned rounds (dynlp_binned.h) -----------------------------------------------------------------
 // Whether a stretch of rounds over nearly all vertices should run as scatter + gather passes: one label column,
-// and either forced by the option or labels that are larger than the L2 (8 x 4 MB), so that the ordinary
-// round's gathers miss.  Measured on MI355X, binary labels, one round over all rows, binned against ordinary: 50M
-// vertices of degree 5: 1.63 against 6.2 ms; 10M vertices of mean degree 38: 2.26 against 6.2 ms; 1M vertices of
-// mean degree 20 (4 MB of labels): 0.29 against 0.24 ms, and whole batches twice as slow because the binned
-// rounds are Jacobi rounds also in in-place mode.
+// and either forced by the option or labels well beyond one XCD's L2 (4 MB = 1M labels), so that the ordinary
+// round's gathers miss it.  Measured on MI355X, binary labels, one round over all rows, binned against ordinary
+// (and whole batches, in-place mode): 50M vertices of degree 5: 1.64 against 6.2 ms (957 against 1,463 ms); 10M
+// vertices of mean degree 38: 2.26 against 6.2 ms (1,095 against 1,510 ms); 5M of degree 5: 0.18 against 0.64 ms
+// (105 against 164 ms); 2M of degree 5: 0.10 against 0.28 ms (77 against 101 ms); 1M of mean degree 20 (4 MB of
+// labels): 0.29 against 0.24 ms, and whole batches twice as slow because the binned rounds are Jacobi rounds
+// also in in-place mode.
 bool binned_rounds_pay(const dynlp_ctx* c, const Frontier& universe) {
     if (c->CP != 1 || c->binned < 0) return false;
     if (ceil_div(c->n, (int64_t)1 << (c->binned > 0 ? c->binned : kPbMaxBinBits)) > kPbMaxBins) return false;
     if (c->entries >= ((int64_t)1 << 32) - 2 * kPbChunk) return false;  // slots and stream positions are 32-bit
     if (c->binned > 0) return true;
-    return universe.size() >= (8u << 20);
+    return universe.size() >= (2u << 20);
 }
 
 // Slots, per-slot receiver offsets and normalised weights for the graph as it stands.
