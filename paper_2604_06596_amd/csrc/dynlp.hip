@@ -1403,23 +1403,43 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
         int same_run = 0;
         bool lazy = false;
         unsigned int prev_bits = 0xffffffffu;
+        // Scalar labels on a large graph: every sweep after the first as a binned round (dynlp_binned.h) in which
+        // every updatable vertex counts as moved, so that V_aff is all of them; a binned round does nothing once
+        // its predecessor moved no row by more than tol, which is the stop rule of the static solve.
+        Frontier all_rows = f;
+        all_rows.ns = c->h_slot[0].next_count;
+        all_rows.nl = c->h_slot[0].next_long;
+        const bool binned = !converged && binned_rounds_pay(c, all_rows);
+        if (binned) {
+            c->pb_built = false;
+            build_binned(c);
+            HIPCHK(c, hipMemsetAsync(c->moved[0], 0xff, (size_t)c->moved_words * sizeof(unsigned int), c->stream));
+        }
         while (!converged && it < max_iter) {
             // a chain of sweeps; each checks on the device whether its predecessor already met the stop rule
             const int r = std::min<int>(kChain, max_iter - it);
+            const bool chain_binned = binned && !lazy;  // the averaged sweeps of a limit cycle are ordinary ones
             for (int i = 0; i < r; ++i) {
                 const int t = it + i;
+                if (chain_binned && t > 0) {
+                    const PullRoundArgs a{slot_of(c, t - 1), buf[t & 1], buf[(t + 1) & 1], c->moved[0], c->moved[1], c->moved[2],
+                                          tol, slot_of(c, t), slot_of(c, t + 1)};
+                    launch_binned_round(c, a);
+                    continue;
+                }
                 const UpdateArgs a{slot_of(c, t - 1), t == 0 ? 1 : 2, buf[t & 1], buf[(t + 1) & 1], nullptr, tol,
                                    slot_of(c, t), slot_of(c, t + 1), (int64_t)nq, (int64_t)c->h_slot_start_long,
                                    lazy ? kRowLazy : 0};
                 launch_update<false>(c, G, f, a);
             }
             read_slots(c, it, r);
+            if (!c->h_slot[0].executed) break;  // cannot happen while the stop rule is unmet; never spin on it
             for (int i = 0; i < r; ++i) {
                 const RoundCtr& rc = c->h_slot[i];
                 if (!rc.executed) break;
                 std::memcpy(&last, &rc.resid_bits, sizeof(float));
                 edges += (int64_t)(rc.edges + rc.edges_long);
-                c->log.push_back(round_info(rc, 0, G));
+                c->log.push_back(round_info(rc, chain_binned && it > 0 ? 3 : 0, G));
                 ++it;
                 same_run = rc.resid_bits == prev_bits ? same_run + 1 : 0;
                 prev_bits = rc.resid_bits;

@@ -343,6 +343,11 @@ __global__ void __launch_bounds__(kPbGatherThreads) k_pb_gather(const RoundCtr* 
     __shared__ float sm_r[NW];
     __shared__ unsigned long long sm_e[NW];
     __shared__ unsigned int sm_c[NW], sm_n[NW];
+    // a static sweep finds the size of its row list in its predecessor's slot: hand it on (0 in batch rounds)
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        ctr->next_count = prev->next_count;
+        ctr->next_long = prev->next_long;
+    }
     if (!pb_round_runs(prev)) return;
     if (blockIdx.x == 0 && threadIdx.x == 0) ctr->executed = 1;
     const int size = 1 << bin_bits;
