@@ -145,7 +145,9 @@ class DynLP:
 
     def __init__(self, n, row_ptr, col, w, num_classes, seed_vertex, seed_class, *, device=0, stream=None,
                  device_ptrs=False, slack_factor=1.25, reserve_vertices=0, reserve_edges=0, time_kernels=False,
-                 group_lanes=0, binary_scalar=False, binned_rounds=0, library=None):
+                 group_lanes=0, binary_scalar=False, binned_rounds=0, allocator=None, library=None):
+        """``allocator``: optional object with ``alloc(nbytes) -> device address (0 = no memory)`` and
+        ``free(address)``; the library then takes all its device arrays from it (dynlp_options.alloc / dealloc)."""
         self._L = load_library(library)
         self._h = ct.c_void_p()
         self.device_ptrs = bool(device_ptrs)
@@ -163,6 +165,12 @@ class DynLP:
         opt.group_lanes = int(group_lanes)
         opt.binary_scalar = 1 if binary_scalar else 0
         opt.binned_rounds = int(binned_rounds)
+        if allocator is not None:
+            # the callbacks must outlive the context
+            self._alloc_cb = _ALLOC_FN(lambda nbytes, user: int(allocator.alloc(int(nbytes))) or None)
+            self._dealloc_cb = _DEALLOC_FN(lambda ptr, user: allocator.free(int(ptr or 0)))
+            opt.alloc = self._alloc_cb
+            opt.dealloc = self._dealloc_cb
         nseeds = 0 if seed_vertex is None else int(len(seed_vertex))
         st = self._L.dynlp_create(ct.byref(self._h), int(n), self._in(row_ptr, np.int64), self._in(col, np.int32),
                                   self._in(w, np.float32), int(num_classes), nseeds, self._in(seed_vertex, np.int32),

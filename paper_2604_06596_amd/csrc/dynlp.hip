@@ -10,6 +10,7 @@
 #include <new>
 #include <string>
 #include <unordered_map>
+#include <unordered_set>
 #include <vector>
 
 #include "dynlp.h"
@@ -67,6 +68,8 @@ struct dynlp_ctx {
     float slack = 1.25f;
     bool time_kernels = false;
     int group_lanes = 0;
+    std::unordered_set<void*> live;  // every device array handed out by dev_alloc and not yet freed: whatever an error
+                                     // path left behind goes back to the allocator when the context is destroyed
     void* (*alloc_fn)(size_t, void*) = nullptr;
     void (*dealloc_fn)(void*, void*) = nullptr;
     void* alloc_user = nullptr;
@@ -169,7 +172,8 @@ struct Fail {
         }                                                                                              \
     } while (0)
 
-void* dev_alloc(dynlp_ctx* c, size_t bytes) {
+// NULL when the allocator has no memory left (nothing else changes).
+void* dev_try_alloc(dynlp_ctx* c, size_t bytes) {
     if (bytes == 0) bytes = 256;
     void* p = nullptr;
     if (c->alloc_fn) {
@@ -178,6 +182,12 @@ void* dev_alloc(dynlp_ctx* c, size_t bytes) {
         (void)hipGetLastError();
         p = nullptr;
     }
+    if (p) c->live.insert(p);
+    return p;
+}
+
+void* dev_alloc(dynlp_ctx* c, size_t bytes) {
+    void* p = dev_try_alloc(c, bytes);
     if (!p) {
         c->err = "device allocation of " + std::to_string(bytes) + " bytes failed";
         c->poisoned = true;
@@ -188,6 +198,7 @@ void* dev_alloc(dynlp_ctx* c, size_t bytes) {
 
 void dev_free(dynlp_ctx* c, void* p) {
     if (!p) return;
+    c->live.erase(p);
     if (c->dealloc_fn) c->dealloc_fn(p, c->alloc_user);
     else (void)hipFree(p);
 }
@@ -550,11 +561,32 @@ bool binned_rounds_pay(const dynlp_ctx* c, const Frontier& universe) {
     return universe.size() >= (2u << 20);
 }
 
-// Slots, per-slot receiver offsets and normalised weights for the graph as it stands.
-void build_binned(dynlp_ctx* c) {
+// Free every array of the binned rounds.
+void free_binned(dynlp_ctx* c) {
+    void* all[] = {c->pb_src, c->pb_lpos, c->pb_oslot, c->pb_tmp, c->pb_dst, c->pb_wn, c->pb_val,
+                   c->pb_len, c->pb_upd, c->pb_first, c->pb_block, c->pb_bin, c->pb_table};
+    for (void* q : all) dev_free(c, q);
+    c->pb_src = c->pb_oslot = c->pb_val = c->pb_upd = c->pb_first = c->pb_block = c->pb_bin = c->pb_table = nullptr;
+    c->pb_lpos = c->pb_dst = nullptr;
+    c->pb_tmp = c->pb_wn = nullptr;
+    c->pb_len = nullptr;
+    c->pb_ent_cap = c->pb_vcap = c->pb_table_cap = 0;
+    c->pb_built = false;
+}
+
+template <typename T>
+bool try_alloc_n(dynlp_ctx* c, T*& p, int64_t count) {
+    p = static_cast<T*>(dev_try_alloc(c, (size_t)std::max<int64_t>(count, 1) * sizeof(T)));
+    return p != nullptr;
+}
+
+// Slots, per-slot receiver offsets and normalised weights for the graph as it stands.  False (and nothing kept)
+// when the arrays cannot be allocated: the caller then runs ordinary rounds.
+bool build_binned(dynlp_ctx* c) {
     const int bits = c->binned > 0 ? c->binned : kPbMaxBinBits;
     const int nbins = (int)ceil_div(std::max<int64_t>(c->n, 1), (int64_t)1 << bits);
     const int chunks = (int)ceil_div(std::max<int64_t>(c->entries, 1), kPbChunk);
+    bool ok = true;
     if ((int64_t)chunks * kPbChunk > c->pb_ent_cap) {
         void* old[] = {c->pb_src, c->pb_lpos, c->pb_oslot, c->pb_tmp, c->pb_dst, c->pb_wn, c->pb_val};
         for (void* q : old) dev_free(c, q);
@@ -563,35 +595,33 @@ void build_binned(dynlp_ctx* c) {
         c->pb_tmp = c->pb_wn = nullptr;
         c->pb_ent_cap = 0;
         const int64_t cap = round_up(c->entries + c->entries / 8 + 1, kPbChunk);
-        c->pb_src = dev_alloc_n<unsigned int>(c, cap);
-        c->pb_lpos = dev_alloc_n<unsigned short>(c, cap);
-        c->pb_oslot = dev_alloc_n<unsigned int>(c, cap);
-        c->pb_tmp = dev_alloc_n<float>(c, cap);
-        c->pb_dst = dev_alloc_n<unsigned short>(c, cap);
-        c->pb_wn = dev_alloc_n<float>(c, cap);
-        c->pb_val = dev_alloc_n<unsigned int>(c, cap);
-        c->pb_ent_cap = cap;
+        ok = try_alloc_n(c, c->pb_src, cap) && try_alloc_n(c, c->pb_lpos, cap) && try_alloc_n(c, c->pb_oslot, cap) &&
+             try_alloc_n(c, c->pb_tmp, cap) && try_alloc_n(c, c->pb_dst, cap) && try_alloc_n(c, c->pb_wn, cap) &&
+             try_alloc_n(c, c->pb_val, cap);
+        if (ok) c->pb_ent_cap = cap;
     }
-    if (c->n > c->pb_vcap) {
+    if (ok && c->n > c->pb_vcap) {
         void* old[] = {c->pb_len, c->pb_upd, c->pb_first, c->pb_block};
         for (void* q : old) dev_free(c, q);
         c->pb_len = nullptr;
         c->pb_upd = c->pb_first = c->pb_block = nullptr;
         c->pb_vcap = 0;
-        c->pb_len = dev_alloc_n<int32_t>(c, c->n_cap);
-        c->pb_upd = dev_alloc_n<unsigned int>(c, c->n_cap / 32 + 64);
-        c->pb_first = dev_alloc_n<unsigned int>(c, c->n_cap + 1);
-        c->pb_block = dev_alloc_n<unsigned int>(c, c->n_cap / kBlock + 2);
-        c->pb_vcap = c->n_cap;
+        ok = try_alloc_n(c, c->pb_len, c->n_cap) && try_alloc_n(c, c->pb_upd, c->n_cap / 32 + 64) &&
+             try_alloc_n(c, c->pb_first, c->n_cap + 1) && try_alloc_n(c, c->pb_block, c->n_cap / kBlock + 2);
+        if (ok) c->pb_vcap = c->n_cap;
     }
-    if (!c->pb_bin) c->pb_bin = dev_alloc_n<unsigned int>(c, 2 * (kPbMaxBins + 1));
-    if ((int64_t)chunks * nbins > c->pb_table_cap) {
+    if (ok && !c->pb_bin) ok = try_alloc_n(c, c->pb_bin, 2 * (kPbMaxBins + 1));
+    if (ok && (int64_t)chunks * nbins > c->pb_table_cap) {
         dev_free(c, c->pb_table);
         c->pb_table = nullptr;
         c->pb_table_cap = 0;
         const int64_t cap = (int64_t)chunks * nbins + (int64_t)chunks * nbins / 8;
-        c->pb_table = dev_alloc_n<unsigned int>(c, cap);
-        c->pb_table_cap = cap;
+        ok = try_alloc_n(c, c->pb_table, cap);
+        if (ok) c->pb_table_cap = cap;
+    }
+    if (!ok) {
+        free_binned(c);
+        return false;
     }
     unsigned int* bin_count = c->pb_bin;
     unsigned int* bin_off = c->pb_bin + (kPbMaxBins + 1);
@@ -629,6 +659,7 @@ void build_binned(dynlp_ctx* c) {
     c->pb_bins = nbins;
     c->pb_chunks = chunks;
     c->pb_built = true;
+    return true;
 }
 
 // One binned round: scatter pass + gather pass (arguments as for the fused round).
@@ -858,6 +889,8 @@ void destroy_ctx(dynlp_ctx* c) {
                     c->pb_src, c->pb_lpos, c->pb_oslot, c->pb_tmp, c->pb_dst, c->pb_wn, c->pb_val, c->pb_len, c->pb_upd,
                     c->pb_first, c->pb_block, c->pb_bin, c->pb_table};
     for (void* p : ptrs) dev_free(c, p);
+    const std::vector<void*> left(c->live.begin(), c->live.end());  // arrays an interrupted call never got to free
+    for (void* p : left) dev_free(c, p);
     if (c->cc_ctr) (void)hipFree(c->cc_ctr);
     if (c->h_cc) (void)hipHostFree(c->h_cc);
     for (hipEvent_t e : c->init_ev)
@@ -1409,12 +1442,9 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
         Frontier all_rows = f;
         all_rows.ns = c->h_slot[0].next_count;
         all_rows.nl = c->h_slot[0].next_long;
-        const bool binned = !converged && binned_rounds_pay(c, all_rows);
-        if (binned) {
-            c->pb_built = false;
-            build_binned(c);
-            HIPCHK(c, hipMemsetAsync(c->moved[0], 0xff, (size_t)c->moved_words * sizeof(unsigned int), c->stream));
-        }
+        c->pb_built = false;
+        const bool binned = !converged && binned_rounds_pay(c, all_rows) && build_binned(c);
+        if (binned) HIPCHK(c, hipMemsetAsync(c->moved[0], 0xff, (size_t)c->moved_words * sizeof(unsigned int), c->stream));
         while (!converged && it < max_iter) {
             // a chain of sweeps; each checks on the device whether its predecessor already met the stop rule
             const int r = std::min<int>(kChain, max_iter - it);
@@ -1676,6 +1706,7 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
         int stretch_start = 0;  // first round of the running ping-pong stretch
         bool fused = false;     // the stretch's rounds evaluate V_aff themselves (no frontier list, no pull)
         bool binned = false;    // ... as scatter + gather passes (scalar labels)
+        bool bin_failed = false;
         // Rounds that repeat themselves exactly (same |V_aff|, rows moved and max change, 16 times in a row) are in
         // a period-2 cycle kept alive by float32 rounding (in-place rounds too: the few rows of such a V_aff run side
         // by side in one wave and read each other's old values); the rest of the batch's flag-marking rounds then
@@ -1693,7 +1724,12 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
             // Inside a stretch no frontier list exists: its first round works on the list it was handed, the
             // later ones evaluate V_aff = {u : u or a neighbour moved in the previous round} per row, from
             // the bitmap of moved rows.  Leaving a stretch pulls the list out of the last bitmap once.
-            const bool can_bin = binned_rounds_pay(c, universe);
+            bool can_bin = !bin_failed && binned_rounds_pay(c, universe);
+            if (can_bin && !pingpong && !c->pb_built && (double)known >= kBinnedEnter * (double)universe.size() &&
+                !build_binned(c)) {
+                bin_failed = true;  // no memory for the binned arrays: ordinary rounds for this batch
+                can_bin = false;
+            }
             if (!pingpong && (double)known >= (can_bin ? kBinnedEnter : kDenseEnter) * (double)universe.size()) {
                 if (!in_place) sync_partner(c);
                 for (unsigned int* mv : c->moved)
@@ -1702,7 +1738,6 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
                 stretch_start = it;
                 binned = can_bin;
                 fused = binned || fused_rounds_pay(c, avg_len);
-                if (binned && !c->pb_built) build_binned(c);
             } else if (pingpong && (double)known < (binned ? kBinnedLeave : kDenseLeave) * (double)universe.size()) {
                 pingpong = false;
                 if (fused) {
