@@ -395,8 +395,9 @@ def test_a_strongly_tied_pair_converges_in_both_modes(mode):
     assert hard[u] == 0 and hard[v] == 1
 
 
+@pytest.mark.parametrize("layout", [{}, dict(binary_scalar=True, binned_rounds=8)], ids=["rows", "scalar_binned"])
 @pytest.mark.parametrize("mode", ["synchronous", "in_place"])
-def test_static_solve_leaves_a_float32_limit_cycle(mode):
+def test_static_solve_leaves_a_float32_limit_cycle(mode, layout):
     """The same strongly tied pair as part of the graph the cold start solves: sweeps whose max change repeats
     exactly switch to averaged rows, and the solve ends well before max_iter at the harmonic solution."""
     p = W.small_random(400, 2, 6.0, 40, 4243)
@@ -408,10 +409,12 @@ def test_static_solve_leaves_a_float32_limit_cycle(mode):
              np.zeros(0, np.int32), np.zeros(0, np.int32))
     rp, col, w = g.csr()
     sv = np.flatnonzero(g.seed_class >= 0).astype(np.int32)
-    with P.DynLP(g.n, rp, col, w.astype(np.float32), 2, sv, g.seed_class[sv]) as d:
+    with P.DynLP(g.n, rp, col, w.astype(np.float32), 2, sv, g.seed_class[sv], **layout) as d:
         if mode == "in_place":
             d.set_update_mode(P.UPDATE_IN_PLACE)
         st, s = d.static_solve(TOL, 50000)
+        kinds = [int(r.staged) for r in d.round_log_full()]
+        assert (3 in kinds) == bool(layout) and kinds[-1] == 0  # the averaged sweeps at the end are ordinary ones
         soft, hard = d.get_labels()
     print(mode, "sweeps", s.iterations, "pair", soft[u], soft[v])
     assert st == 0 and s.iterations < 20000
