@@ -985,7 +985,7 @@ void run_supernode_init(dynlp_ctx* c, int64_t n0, int64_t k, int64_t m, const in
         c->cc_wcap = cap;
     }
     hipLaunchKernelGGL(k_fill_f64, dim3(grid_for(comps * c->C)), dim3(kBlock), 0, c->stream, comps * c->C, c->cc_W, 0.0);
-    hipLaunchKernelGGL(k_supernode_weights, dim3(grid_for(k * 16)), dim3(kBlock), 0, c->stream, n0, k, c->C, c->meta,
+    hipLaunchKernelGGL(k_supernode_weights, dim3((unsigned int)ceil_div(k, kSwRows)), dim3(kBlock), 0, c->stream, n0, k, c->C, c->meta,
                        c->pool, c->seed_class, c->cc_comp, c->cc_W);
     hipLaunchKernelGGL(k_supernode_rows, dim3(grid_for(k * c->CP)), dim3(kBlock), 0, c->stream, n0, k, c->C, c->Cs, c->coff, c->CP,
                        c->seed_class, c->cc_comp, c->cc_W, c->F);

@@ -69,6 +69,31 @@ def test_components_and_initial_rows_match_the_oracle(C, k, mean_cluster):
         assert 1 < count < k  # multi-vertex components and more than one of them
 
 
+@pytest.mark.parametrize("C,seeds,tau", [(3, 3000, 0.0), (10, 2500, 0.0), (4, 3500, 0.45)])
+def test_supernode_sums_with_many_labelled_neighbours_and_one_giant_supernode(C, seeds, tau):
+    """Most of the graph labelled and a batch whose internal edges connect nearly all of its vertices (tau = 0:
+    one supernode takes almost every contribution): a workgroup's rows then bring far more contributions than its
+    LDS list holds, so both the merged atomics and the overflow path carry weight, all onto a handful of sums."""
+    p, p0 = (W.small_random(5000, C, 9.0, seeds, 1700 + C), W.small_random(5000, C, 9.0, seeds, 1700 + C))
+    g = R.Graph(p0.n, p0.row_ptr, p0.col, p0.w, p0.C, p0.seed_vertex, p0.seed_class)
+    b = W.small_random_batch(p, 4000, 9, 50)
+    with _make(p0) as d:
+        assert d.static_solve(TOL, 20000)[0] == 0
+        soft0, _ = d.get_labels()
+        d.set_initialiser(P.INIT_SUPERNODE, tau)
+        d.set_params(TOL, 0)
+        st, s = d.apply_batch(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+        soft, _ = d.get_labels()
+        comp, info = d.last_components()
+    rp, col, w, F_init, A0, ocomp, count, kept = _oracle_init(g, soft0.astype(np.float64), b, float(tau))
+    sizes = np.bincount(ocomp)
+    labelled = int(np.count_nonzero(g.seed_class[col[rp[p0.n]:]] >= 0))  # contributions of the inserted rows
+    print(f"components {count}, largest {sizes.max()} of {b.num_new_vertices}, labelled neighbour entries {labelled}")
+    assert sizes.max() > 0.5 * b.num_new_vertices and labelled > 4 * 1024
+    assert info.components == count and np.array_equal(comp, ocomp)
+    assert np.max(np.abs(soft - F_init)) <= INIT_ATOL
+
+
 @pytest.mark.parametrize("C", [2, 10])
 @pytest.mark.parametrize("R_", [1, 3, 25])
 def test_rounds_after_the_supernode_initialisation_match_the_oracle(C, R_):
