@@ -99,7 +99,8 @@ __global__ void __launch_bounds__(kBlock) k_cc_hook(int iter, const int2* __rest
         const int pb = __atomic_load_n(&par[ab.y], __ATOMIC_RELAXED);
         if (pa != pb) {
             const int hi = pa > pb ? pa : pb, lo = pa > pb ? pb : pa;
-            atomicMin(&par[hi], lo);
+            // many edges of a large component name the same two roots: only the first of them needs the atomic
+            if (__atomic_load_n(&par[hi], __ATOMIC_RELAXED) > lo) atomicMin(&par[hi], lo);
             any = true;
         }
     }
