@@ -241,6 +241,27 @@ dynlp_status dynlp_apply_update(dynlp_ctx* ctx, int64_t num_deleted, const int32
  */
 dynlp_status dynlp_get_labels(dynlp_ctx* ctx, float* soft, int32_t* hard);
 
+/*
+ * dynlp_get_labels for callers that cannot allocate device memory: code between two stream-capture calls of
+ * another part of the program, tight serving loops, harnesses that forbid hipMalloc.  Same results as
+ * dynlp_get_labels, bit for bit, but soft and hard are always HOST pointers (whatever ptrs_on_device says), and
+ * the device-side staging of the packed rows (soft: n*C floats, then, from the next multiple of 256 bytes, hard:
+ * n int32) lives in a static device array of DYNLP_STATIC_SCRATCH_BYTES instead of an allocated buffer.  The call
+ * makes no hipMalloc / hipFree and calls no allocator callback.
+ *   - A request whose staging exceeds DYNLP_STATIC_SCRATCH_BYTES is rejected with DYNLP_ERR_INVALID_ARG (nothing
+ *     is written); dynlp_get_labels has no such limit.  Passing only one of soft / hard halves the need.
+ *   - Every context on one GPU shares that GPU's array, which keeps the previous call's contents; each call
+ *     overwrites exactly the part it then copies out.  Two calls that overlap in time on one GPU (two threads, two
+ *     contexts) race on it: serialise them.
+ *   - The array's address is looked up once per GPU, in the first dynlp_create on that GPU; if that look-up
+ *     failed the call returns DYNLP_ERR_DEVICE.
+ *   - The copies to soft / hard are asynchronous only for pinned host memory; the call returns after they are done.
+ * dynlp_static_scratch_bytes returns DYNLP_STATIC_SCRATCH_BYTES as compiled into the library.
+ */
+#define DYNLP_STATIC_SCRATCH_BYTES (16u << 20)
+dynlp_status dynlp_get_labels_static(dynlp_ctx* ctx, float* soft, int32_t* hard);
+int64_t dynlp_static_scratch_bytes(void);
+
 /* Current number of vertices / directed CSR entries (2x the undirected edge count); -1 on NULL. */
 int64_t dynlp_num_vertices(const dynlp_ctx* ctx);
 int64_t dynlp_num_entries(const dynlp_ctx* ctx);

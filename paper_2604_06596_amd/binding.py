@@ -68,7 +68,7 @@ EXPORTS = ["dynlp_default_options", "dynlp_create", "dynlp_static_solve", "dynlp
            "dynlp_get_labels", "dynlp_num_vertices", "dynlp_num_entries", "dynlp_num_classes", "dynlp_export_graph",
            "dynlp_round_log", "dynlp_last_error", "dynlp_destroy", "dynlp_set_initialiser",
            "dynlp_mean_edge_weight", "dynlp_last_components", "dynlp_set_update_mode", "dynlp_apply_update", "dynlp_storage_info",
-           "dynlp_compact_storage", "dynlp_stream_bandwidth"]
+           "dynlp_compact_storage", "dynlp_stream_bandwidth", "dynlp_get_labels_static", "dynlp_static_scratch_bytes"]
 
 _lib = None
 
@@ -105,6 +105,10 @@ def load_library(path: str | None = None):
     L.dynlp_apply_update.restype = ct.c_int
     L.dynlp_get_labels.argtypes = [p, p, p]
     L.dynlp_get_labels.restype = ct.c_int
+    L.dynlp_get_labels_static.argtypes = [p, p, p]
+    L.dynlp_get_labels_static.restype = ct.c_int
+    L.dynlp_static_scratch_bytes.argtypes = []
+    L.dynlp_static_scratch_bytes.restype = i64
     for name in ("dynlp_num_vertices", "dynlp_num_entries"):
         getattr(L, name).argtypes = [p]
         getattr(L, name).restype = i64
@@ -298,6 +302,21 @@ class DynLP:
         ho, hp = self._out((n,), np.int32) if hard else (None, None)
         self._check(self._L.dynlp_get_labels(self._h, sp, hp))
         return so, ho
+
+    def get_labels_static(self, soft=True, hard=True):
+        """dynlp_get_labels_static: as get_labels, but into host (numpy) arrays in either pointer mode and
+        without any device allocation.  Returns (soft [n, C] float32 or None, hard [n] int32 or None)."""
+        n, C = self.num_vertices, self.num_classes
+        so = np.empty((n, C), dtype=np.float32) if soft else None
+        ho = np.empty((n,), dtype=np.int32) if hard else None
+        sp = so.ctypes.data_as(ct.c_void_p) if soft and so.size else None
+        hp = ho.ctypes.data_as(ct.c_void_p) if hard and ho.size else None
+        self._check(self._L.dynlp_get_labels_static(self._h, sp, hp))
+        return so, ho
+
+    @property
+    def static_scratch_bytes(self):
+        return int(self._L.dynlp_static_scratch_bytes())
 
     @property
     def num_vertices(self):

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <unordered_map>
@@ -57,6 +58,33 @@ const char* validation_message(int code) {
 using Clock = std::chrono::steady_clock;
 inline float ms_since(Clock::time_point t0) {
     return std::chrono::duration<float, std::milli>(Clock::now() - t0).count();
+}
+
+}  // namespace
+
+// Staging area of dynlp_get_labels_static: device memory that exists without any allocation call.  Every GPU
+// the library runs on holds its own copy, at its own address, until the process ends.  In host code the name
+// `scratch` is only a handle for hipGetSymbolAddress; kernels and copies take the resolved per-device address.
+constexpr size_t kStaticScratchBytes = DYNLP_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};        // device address of `scratch` on each device, once resolved
+hipError_t g_scratch_err[kMaxDevices] = {};   // what the resolution returned there
+
+// Resolve the address of `scratch` on `device` (which must be the current device).  Once per device.
+void resolve_static_scratch(int device) {
+    if (device < 0 || device >= kMaxDevices) return;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device]) return;
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    g_scratch_err[device] = e;
+    if (e == hipSuccess) g_scratch_ptr[device] = ptr;
+    else (void)hipGetLastError();
 }
 
 }  // namespace
@@ -1007,6 +1035,25 @@ int64_t scan_block_sums(dynlp_ctx* c, int64_t nb, int64_t* sums) {
     return (int64_t)c->h_bc->scan_total;
 }
 
+// Labels in the caller's format: soft (n x C, no padding) and / or hard (argmax, lowest index on ties) into
+// device buffers.  Every row is overwritten, so the buffers need no clearing.
+void launch_label_output(dynlp_ctx* c, float* d_soft, int32_t* d_hard) {
+    const int64_t n = c->n;
+    if (d_soft) {
+        if (c->coff)
+            hipLaunchKernelGGL(k_scalar_soft, dim3(grid_for(2 * n)), dim3(kBlock), 0, c->stream, n, c->F, d_soft);
+        else
+            hipLaunchKernelGGL(k_pack_soft, dim3(grid_for(n * c->C)), dim3(kBlock), 0, c->stream, n, c->C, c->CP, c->F, d_soft);
+    }
+    if (d_hard) {
+        if (c->coff)
+            hipLaunchKernelGGL(k_scalar_hard, dim3(grid_for(n)), dim3(kBlock), 0, c->stream, n, c->F, d_hard);
+        else
+            hipLaunchKernelGGL(k_argmax, dim3(grid_for(n * (c->CP >= 4 ? c->CP / 4 : 1))), dim3(kBlock), 0, c->stream, n, c->C, c->CP, c->F, d_hard);
+    }
+    HIPCHK(c, hipGetLastError());
+}
+
 }  // namespace
 
 // =================================================================================================
@@ -1101,6 +1148,7 @@ dynlp_status dynlp_create(dynlp_ctx** out, int64_t n, const int64_t* row_ptr, co
         c->coff = num_classes - Cs;  // 1 in the binary scalar layout (column 0 holds class 1), else 0
         c->CP = CP;
         HIPCHK(c, hipSetDevice(c->device));
+        resolve_static_scratch(c->device);  // for dynlp_get_labels_static; a failure is reported by that call
         hipDeviceProp_t prop;
         HIPCHK(c, hipGetDeviceProperties(&prop, c->device));
         c->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
@@ -1865,25 +1913,12 @@ dynlp_status dynlp_get_labels(dynlp_ctx* c, float* soft, int32_t* hard) {
     dynlp_status st = DYNLP_OK;
     try {
         HIPCHK(c, hipSetDevice(c->device));
-        if (soft) {
-            float* dst = c->dev_ptrs ? soft : (d_soft = dev_alloc_n<float>(c, n * c->C));
-            if (c->coff)
-                hipLaunchKernelGGL(k_scalar_soft, dim3(grid_for(2 * n)), dim3(kBlock), 0, c->stream, n, c->F, dst);
-            else
-                hipLaunchKernelGGL(k_pack_soft, dim3(grid_for(n * c->C)), dim3(kBlock), 0, c->stream, n, c->C, c->CP, c->F, dst);
-            HIPCHK(c, hipGetLastError());
-            if (!c->dev_ptrs)
-                HIPCHK(c, hipMemcpyAsync(soft, dst, (size_t)n * c->C * sizeof(float), hipMemcpyDeviceToHost, c->stream));
-        }
-        if (hard) {
-            int32_t* dst = c->dev_ptrs ? hard : (d_hard = dev_alloc_n<int32_t>(c, n));
-            if (c->coff)
-                hipLaunchKernelGGL(k_scalar_hard, dim3(grid_for(n)), dim3(kBlock), 0, c->stream, n, c->F, dst);
-            else
-                hipLaunchKernelGGL(k_argmax, dim3(grid_for(n * (c->CP >= 4 ? c->CP / 4 : 1))), dim3(kBlock), 0, c->stream, n, c->C, c->CP, c->F, dst);
-            HIPCHK(c, hipGetLastError());
-            if (!c->dev_ptrs)
-                HIPCHK(c, hipMemcpyAsync(hard, dst, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+        float* dst_soft = !soft ? nullptr : c->dev_ptrs ? soft : (d_soft = dev_alloc_n<float>(c, n * c->C));
+        int32_t* dst_hard = !hard ? nullptr : c->dev_ptrs ? hard : (d_hard = dev_alloc_n<int32_t>(c, n));
+        launch_label_output(c, dst_soft, dst_hard);
+        if (!c->dev_ptrs) {
+            if (soft) HIPCHK(c, hipMemcpyAsync(soft, dst_soft, (size_t)n * c->C * sizeof(float), hipMemcpyDeviceToHost, c->stream));
+            if (hard) HIPCHK(c, hipMemcpyAsync(hard, dst_hard, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
         }
         HIPCHK(c, hipStreamSynchronize(c->stream));
     } catch (const Fail& f) {
@@ -1892,6 +1927,46 @@ dynlp_status dynlp_get_labels(dynlp_ctx* c, float* soft, int32_t* hard) {
     dev_free(c, d_soft);
     dev_free(c, d_hard);
     return st;
+}
+
+int64_t dynlp_static_scratch_bytes(void) { return (int64_t)kStaticScratchBytes; }
+
+dynlp_status dynlp_get_labels_static(dynlp_ctx* c, float* soft, int32_t* hard) {
+    if (!c) return DYNLP_ERR_INVALID_ARG;
+    if (c->poisoned) {
+        c->err = "context is unusable after an earlier device or memory error";
+        return DYNLP_ERR_STATE;
+    }
+    const int64_t n = c->n;
+    if (n == 0 || (!soft && !hard)) return DYNLP_OK;
+    // staging layout: [soft: n*C floats][padding to 256 bytes][hard: n int32]
+    const size_t soft_bytes = soft ? (size_t)n * c->C * sizeof(float) : 0;
+    const size_t hard_off = (size_t)round_up((int64_t)soft_bytes, 256);
+    const size_t need = hard_off + (hard ? (size_t)n * sizeof(int32_t) : 0);
+    if (need > kStaticScratchBytes) {
+        c->err = "dynlp_get_labels_static: the labels of " + std::to_string(n) + " vertices need " + std::to_string(need) +
+                 " bytes of staging, the static scratch holds " + std::to_string(kStaticScratchBytes) +
+                 "; use dynlp_get_labels";
+        return DYNLP_ERR_INVALID_ARG;
+    }
+    void* base = c->device >= 0 && c->device < kMaxDevices ? g_scratch_ptr[c->device] : nullptr;
+    if (!base) {
+        c->err = std::string("dynlp_get_labels_static: the address of the static scratch could not be resolved on this device (") +
+                 (c->device >= 0 && c->device < kMaxDevices ? hipGetErrorString(g_scratch_err[c->device]) : "device ordinal too large") + ")";
+        return DYNLP_ERR_DEVICE;
+    }
+    try {
+        HIPCHK(c, hipSetDevice(c->device));
+        float* d_soft = soft ? static_cast<float*>(base) : nullptr;
+        int32_t* d_hard = hard ? reinterpret_cast<int32_t*>(static_cast<unsigned char*>(base) + hard_off) : nullptr;
+        launch_label_output(c, d_soft, d_hard);
+        if (soft) HIPCHK(c, hipMemcpyAsync(soft, d_soft, soft_bytes, hipMemcpyDeviceToHost, c->stream));
+        if (hard) HIPCHK(c, hipMemcpyAsync(hard, d_hard, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        return DYNLP_OK;
+    } catch (const Fail& f) {
+        return f.st;
+    }
 }
 
 dynlp_status dynlp_export_graph(dynlp_ctx* c, int64_t* row_ptr, int32_t* col, float* w, float* degree,
