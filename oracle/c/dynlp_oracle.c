@@ -8,6 +8,8 @@
  *                        (1/d(u)) sum_v w(u,v) F_v, read from F_in, written to F_out; seed rows
  *                        and isolated rows are copied.
  *   oracle_itlp_solve    repeat the sweep until max_u max_c |F_new - F| <= tol (ItLP).
+ *   oracle_neumann_solve x = (I - P_UU)^{-1} b as the limit of x <- b + P_UU x (the series sum_k P_UU^k b of the
+ *                        convergence proof), P = D^{-1} W: error bounds for labels that are not yet converged.
  *   oracle_affected_set  V_aff after Step 1 of Alg. 2 for an insertion batch.
  *   oracle_step3         Step 3 of Alg. 2 in synchronous rounds over V_aff.
  *
@@ -90,6 +92,52 @@ int64_t oracle_itlp_solve(int64_t n, const int64_t* row_ptr, const int32_t* col,
         if (change <= tol) break;
     }
     if (a != F) memcpy(F, a, (size_t)n * C * sizeof(double));
+    if (last_change) *last_change = change;
+    return it;
+}
+
+/*
+ * x = sum_k P_UU^k b, i.e. the solution of (I - P_UU) x = b, by the iteration x <- b + P_UU x over the unlabelled
+ * rows with d(u) > 0 (P_uv = w(u,v)/d(u); x is 0 on labelled and isolated vertices, which is how P_UU drops their
+ * columns).  This is the matrix of the convergence corollary: a label matrix F with residual r = F - (P_UU F + P_UL Y)
+ * differs from the fixed point by exactly (I - P_UU)^{-1} r, so |F - F*| <= (I - P_UU)^{-1} |r| row by row, and
+ * with b = 1 the largest x_u is ||(I - P_UU)^{-1}||_inf (the largest expected number of steps of the random walk
+ * before it meets a labelled vertex).  x is read as the start (zero it for the plain series) and overwritten; tmp is
+ * scratch of n doubles.  Stops when max_u |x_new - x| <= tol or after max_iter sweeps; returns the sweeps done.
+ * Only meaningful where every unlabelled vertex reaches a labelled one (elsewhere the series diverges).
+ */
+int64_t oracle_neumann_solve(int64_t n, const int64_t* row_ptr, const int32_t* col, const double* w,
+                             const int32_t* seed_class, const double* b, double* x, double* tmp, double tol,
+                             int64_t max_iter, double* last_change) {
+    double* cur = x;
+    double* nxt = tmp;
+    int64_t it = 0;
+    double change = INFINITY;
+    while (it < max_iter) {
+        change = 0.0;
+#pragma omp parallel for schedule(dynamic, 1024) reduction(max : change)
+        for (int64_t u = 0; u < n; ++u) {
+            if (seed_class[u] >= 0 || row_ptr[u + 1] == row_ptr[u]) {
+                nxt[u] = 0.0;
+                continue;
+            }
+            double d = 0.0, acc = 0.0;
+            for (int64_t j = row_ptr[u]; j < row_ptr[u + 1]; ++j) {
+                const int32_t v = col[j];
+                d += w[j];
+                if (seed_class[v] < 0 && row_ptr[v + 1] > row_ptr[v]) acc += w[j] * cur[v];
+            }
+            nxt[u] = b[u] + acc / d;
+            const double r = fabs(nxt[u] - cur[u]);
+            if (r > change) change = r;
+        }
+        double* t = cur;
+        cur = nxt;
+        nxt = t;
+        ++it;
+        if (change <= tol) break;
+    }
+    if (cur != x) memcpy(x, cur, (size_t)n * sizeof(double));
     if (last_change) *last_change = change;
     return it;
 }

@@ -36,6 +36,8 @@ def lib():
         L.oracle_itlp_sweep.argtypes = [i64, p, p, p, ct.c_int, p, p, p]
         L.oracle_itlp_solve.restype = i64
         L.oracle_itlp_solve.argtypes = [i64, p, p, p, ct.c_int, p, p, p, f64, i64, p]
+        L.oracle_neumann_solve.restype = i64
+        L.oracle_neumann_solve.argtypes = [i64, p, p, p, p, p, p, p, f64, i64, p]
         L.oracle_affected_set.restype = i64
         L.oracle_affected_set.argtypes = [i64, p, p, p, i64, i64, p, p, i64, p, p, p]
         L.oracle_step3.restype = i64
@@ -87,6 +89,24 @@ def itlp_solve(row_ptr, col, w, seed_class, C, tol=1e-10, max_iter=1_000_000, F0
     it = lib().oracle_itlp_solve(F.shape[0], _ptr(rp), _ptr(cl), _ptr(ww), C, _ptr(sc), _ptr(F), _ptr(tmp),
                                  float(tol), int(max_iter), ct.byref(last))
     return F, int(it), float(last.value)
+
+
+def neumann_solve(row_ptr, col, w, seed_class, b, tol=1e-12, max_iter=10_000_000, x0=None):
+    """x = (I - P_UU)^{-1} b by the iteration x <- b + P_UU x (zero on labelled and isolated vertices, and on
+    vertices that reach no labelled vertex, where the series has no limit: b is taken as 0 there).
+    Returns (x, sweeps, last_change)."""
+    from .reference import seed_reachable
+
+    rp, cl, ww = _csr(row_ptr, col, w)
+    sc = np.ascontiguousarray(seed_class, dtype=np.int32)
+    b = np.array(b, dtype=np.float64, order="C")
+    b[~seed_reachable(rp, cl, sc)] = 0.0
+    x = np.zeros_like(b) if x0 is None else np.array(x0, dtype=np.float64, order="C")
+    tmp = np.empty_like(x)
+    last = ct.c_double(0.0)
+    it = lib().oracle_neumann_solve(sc.shape[0], _ptr(rp), _ptr(cl), _ptr(ww), _ptr(sc), _ptr(b), _ptr(x), _ptr(tmp),
+                                    float(tol), int(max_iter), ct.byref(last))
+    return x, int(it), float(last.value)
 
 
 def affected_set(row_ptr, col, seed_class, n_old, eu, ev, new_seed_vertex, deleted_neighbours=None):

@@ -191,6 +191,103 @@ def itlp_solve_in_place(row_ptr, col, w, seed_class, C, tol=1e-10, max_iter=1_00
     return F, max_iter, change
 
 
+# --------------------------------------------------------------------------------------
+# how far labels with a known residual are from the fixed point (convergence corollary)
+# --------------------------------------------------------------------------------------
+def _updatable(row_ptr, col, seed_class):
+    """Unlabelled vertices with at least one edge that reach a labelled vertex: the rows on which
+    Eq. (1) has a unique fixed point (I - P_UU is invertible there)."""
+    seed_class = np.asarray(seed_class)
+    return (seed_class < 0) & (np.diff(row_ptr) > 0) & seed_reachable(row_ptr, col, seed_class)
+
+
+def neumann_solve_dense(row_ptr, col, w, seed_class, b):
+    """x = (I - P_UU)^{-1} b by a dense solve, P = D^{-1} W restricted to the updatable rows (tiny
+    graphs only); 0 elsewhere.  (I - P_UU)^{-1} = sum_k P_UU^k is the matrix of the paper's
+    convergence proof and of Eq. (2)."""
+    seed_class = np.asarray(seed_class)
+    n = seed_class.shape[0]
+    Wm = np.zeros((n, n), dtype=np.float64)
+    np.add.at(Wm, (np.repeat(np.arange(n), np.diff(row_ptr)), np.asarray(col)), np.asarray(w, dtype=np.float64))
+    U = np.flatnonzero(_updatable(row_ptr, col, seed_class))
+    P = Wm[np.ix_(U, U)] / Wm[U].sum(axis=1, keepdims=True)
+    x = np.zeros(n, dtype=np.float64)
+    x[U] = np.linalg.solve(np.eye(U.size) - P, np.asarray(b, dtype=np.float64)[U])
+    return x
+
+
+def _laplacian_blocks(row_ptr, col, w, seed_class):
+    """(U, index of every vertex inside U or -1, d on U, sparse W_UU, sparse W_UL, ids of L) for the
+    library solves below (scipy.sparse)."""
+    import scipy.sparse as sp
+
+    seed_class = np.asarray(seed_class)
+    n = seed_class.shape[0]
+    w = np.asarray(w, dtype=np.float64)
+    col = np.asarray(col, dtype=np.int64)
+    src = np.repeat(np.arange(n, dtype=np.int64), np.diff(row_ptr))
+    d = np.bincount(src, weights=w, minlength=n)
+    in_U = _updatable(row_ptr, col, seed_class)
+    U = np.flatnonzero(in_U)
+    pos = np.full(n, -1, dtype=np.int64)
+    pos[U] = np.arange(U.size)
+    lab = np.flatnonzero(seed_class >= 0)
+    lpos = np.full(n, -1, dtype=np.int64)
+    lpos[lab] = np.arange(lab.size)
+    uu = in_U[src] & in_U[col]
+    ul = in_U[src] & (seed_class[col] >= 0)
+    W_UU = sp.csr_matrix((w[uu], (pos[src[uu]], pos[col[uu]])), shape=(U.size, U.size))
+    W_UL = sp.csr_matrix((w[ul], (pos[src[ul]], lpos[col[ul]])), shape=(U.size, lab.size))
+    return U, d[U], W_UU, W_UL, lab
+
+
+def _cg(A, rhs, x0, rtol, max_iter):
+    import scipy.sparse as sp
+    import scipy.sparse.linalg as spl
+
+    # Jacobi-preconditioned conjugate gradients on the symmetric positive definite matrix (D - W)_UU
+    Minv = sp.diags(1.0 / A.diagonal())
+    x, info = spl.cg(A, rhs, x0=x0, rtol=rtol, atol=0.0, maxiter=max_iter, M=Minv)
+    if info != 0:
+        raise RuntimeError(f"conjugate gradients did not converge (info = {info})")
+    return x
+
+
+def neumann_solve_cg(row_ptr, col, w, seed_class, b, rtol=1e-13, max_iter=20000):
+    """x = (I - P_UU)^{-1} b for large graphs: the same system written with the symmetric matrix,
+    (D - W)_UU x = D_U b, solved by a library routine (conjugate gradients).  0 outside the
+    updatable rows.  Callers certify the result with one step of x <- b + P_UU x."""
+    import scipy.sparse as sp
+
+    U, dU, W_UU, _, _ = _laplacian_blocks(row_ptr, col, w, seed_class)
+    A = (sp.diags(dU) - W_UU).tocsr()
+    b = np.asarray(b, dtype=np.float64)
+    x = np.zeros(b.shape[0], dtype=np.float64)
+    x[U] = _cg(A, dU * b[U], None, rtol, max_iter)
+    return x
+
+
+def harmonic_solve_cg(row_ptr, col, w, seed_class, C, F_other=None, rtol=1e-13, max_iter=20000):
+    """The fixed point of Eq. (1) for large graphs, column by column, from Eq. (2) written with the
+    symmetric matrix: (D - W)_UU F_U = W_UL Y_L, solved by a library routine (conjugate
+    gradients).  Rows outside the updatable set (labelled, isolated, not connected to any label)
+    are taken from ``F_other`` (default: one-hot / uniform start).  Callers certify the result with
+    one sweep of Eq. (1): a fixed point does not move."""
+    import scipy.sparse as sp
+
+    seed_class = np.asarray(seed_class)
+    U, dU, W_UU, W_UL, lab = _laplacian_blocks(row_ptr, col, w, seed_class)
+    A = (sp.diags(dU) - W_UU).tocsr()
+    F = initial_labels(seed_class, C) if F_other is None else np.array(F_other, dtype=np.float64)
+    Y = np.zeros((lab.size, C), dtype=np.float64)
+    Y[np.arange(lab.size), seed_class[lab]] = 1.0
+    F[lab] = Y
+    rhs = W_UL @ Y
+    for c in range(C):
+        F[U, c] = _cg(A, rhs[:, c], None, rtol, max_iter)
+    return F
+
+
 def recompute_from_scratch(graph: Graph, tol=1e-10, max_iter=1_000_000):
     """Alg. 1 Step 2 with ItLP in place of the dense inverse: labels of the *current* graph
     from the uniform start."""
@@ -233,11 +330,13 @@ def _exceeds(new_row, old_row, tol, decide_fp32):
     return r > tol, r
 
 
-def step3_propagate(adj, F, seed_class, V_aff, tol, max_iter, decide_fp32=True):
+def step3_propagate(adj, F, seed_class, V_aff, tol, max_iter, decide_fp32=True, trace=None):
     """Alg. 2 Step 3 in synchronous rounds.  Each round: every u in V_aff gets
     F'_u = sum_v alpha_{u,v} F_v from the round-start F (the equivalence of the adjustment
     form and the weighted mean is the paper's Theoretical-analysis section); all F'_u are
     committed; u with change > tol stay and bring in N(u); the others leave.
+    ``trace``: a list that receives, per round, (sorted V_aff, sorted rows that moved by more
+    than tol, copy of F after the commit).
     Returns (F, rounds, frontier_sizes, max_change_per_round)."""
     F = np.array(F, dtype=np.float64)
     A = set(V_aff)
@@ -252,15 +351,19 @@ def step3_propagate(adj, F, seed_class, V_aff, tol, max_iter, decide_fp32=True):
                 acc += wuv * F[v]
             new_rows[u] = acc / d
         nxt = set()
+        moved = []
         mx = 0.0
         for u, row in new_rows.items():
             big, r = _exceeds(row, F[u], tol, decide_fp32)
             mx = max(mx, r)
             if big:
+                moved.append(u)
                 nxt.add(u)
                 nxt.update(adj[u].keys())
         for u, row in new_rows.items():
             F[u] = row
+        if trace is not None:
+            trace.append((sorted(A), sorted(moved), F.copy()))
         sizes.append(len(A))
         changes.append(mx)
         A = {u for u in nxt if seed_class[u] < 0 and len(adj[u]) > 0}

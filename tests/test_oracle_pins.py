@@ -240,3 +240,101 @@ def test_in_place_sweeps_share_the_fixed_point_and_need_fewer_sweeps(seed):
         assert np.abs(Fg - exact).max() < 1e-8
         assert sweeps_g < sweeps_j
     assert np.abs(Fj - exact).max() < 1e-8
+
+
+# ---- (I - P_UU)^{-1}: the matrix of the convergence corollary, used for error bounds ------------
+def _path(L):
+    """Unit path 0-1-...-L with the two ends labelled (classes 0 and 1)."""
+    eu = np.arange(L, dtype=np.int64)
+    rp, col, w = W.edges_to_csr(L + 1, eu, eu + 1, np.ones(L))
+    sc = np.full(L + 1, -1, dtype=np.int32)
+    sc[0], sc[L] = 0, 1
+    return rp, col, w.astype(np.float64), sc
+
+
+def test_neumann_solve_on_a_path_gives_the_gamblers_ruin_duration(oracle_native):
+    """b = 1: x_i is the expected number of steps of the simple random walk from i to either end of
+    the path, i (L - i) (gambler's ruin), so ||(I - P_UU)^{-1}||_inf = L^2 / 4 for even L."""
+    L = 12
+    rp, col, w, sc = _path(L)
+    want = np.array([i * (L - i) for i in range(L + 1)], dtype=np.float64)
+    ones = np.ones(L + 1)
+    np.testing.assert_allclose(R.neumann_solve_dense(rp, col, w, sc, ones), want, atol=1e-10)
+    x, sweeps, last = oracle_native.neumann_solve(rp, col, w, sc, ones, tol=1e-13)
+    np.testing.assert_allclose(x, want, atol=1e-9)
+    np.testing.assert_allclose(R.neumann_solve_cg(rp, col, w, sc, ones), want, atol=1e-9)
+    assert x.max() == pytest.approx(L * L / 4)
+
+
+def test_neumann_solve_three_ways_on_random_weighted_graphs(oracle_native):
+    p = W.small_random(300, 3, 3.0, 12, 41, connected=False)  # some vertices reach no label: x = 0 there
+    sc = np.full(p.n, -1, dtype=np.int32)
+    sc[p.seed_vertex] = p.seed_class
+    w = p.w.astype(np.float64)
+    b = np.random.default_rng(5).uniform(0.0, 2.0, size=p.n)
+    dense = R.neumann_solve_dense(p.row_ptr, p.col, w, sc, b)
+    it, sweeps, last = oracle_native.neumann_solve(p.row_ptr, p.col, w, sc, b, tol=1e-14)
+    cg = R.neumann_solve_cg(p.row_ptr, p.col, w, sc, b)
+    assert np.max(np.abs(dense - it)) < 1e-9 and np.max(np.abs(dense - cg)) < 1e-9
+    reach = R.seed_reachable(p.row_ptr, p.col, sc)
+    upd = (sc < 0) & (np.diff(p.row_ptr) > 0) & reach
+    assert np.all(dense[~upd] == 0) and dense[upd].min() > 0 and (~reach).sum() > 0
+    # the series sum_k P^k b term by term (what "Neumann" means), 4,000 terms of it
+    n = p.n
+    Wm = np.zeros((n, n))
+    np.add.at(Wm, (np.repeat(np.arange(n), np.diff(p.row_ptr)), p.col), w)
+    U = np.flatnonzero(upd)
+    P = Wm[np.ix_(U, U)] / Wm[U].sum(1, keepdims=True)
+    term, tot = b[U].copy(), b[U].copy()
+    for _ in range(4000):
+        term = P @ term
+        tot += term
+    assert np.max(np.abs(tot - dense[U])) < 1e-6 * dense.max()
+
+
+def test_labels_off_the_fixed_point_differ_from_it_by_the_propagated_residual(oracle_native):
+    """F - F* = (I - P_UU)^{-1} (F - T(F)) for ANY label matrix F whose labelled rows are right (T = one
+    sweep of Eq. (1)); hence |F - F*| <= (I - P_UU)^{-1} |F - T(F)| row by row and
+    ||F - F*||_inf <= ||(I - P_UU)^{-1}||_inf ||F - T(F)||_inf.  This identity is what the GPU tests use to
+    bound the distance of a locally stopped run from the exact labels."""
+    p = W.small_random(250, 4, 3.5, 10, 43)
+    sc = np.full(p.n, -1, dtype=np.int32)
+    sc[p.seed_vertex] = p.seed_class
+    w = p.w.astype(np.float64)
+    exact = R.harmonic_closed_form(p.row_ptr, p.col, w, sc, p.C)
+    rng = np.random.default_rng(7)
+    F = exact + rng.normal(0.0, 1e-3, size=exact.shape) * (sc < 0)[:, None]
+    TF, res = oracle_native.itlp_sweep(p.row_ptr, p.col, w, F, sc)
+    r = F - TF
+    assert res == pytest.approx(np.max(np.abs(r)))
+    for c in range(p.C):
+        prop = R.neumann_solve_dense(p.row_ptr, p.col, w, sc, r[:, c])
+        np.testing.assert_allclose(prop, (F - exact)[:, c], atol=1e-12)
+    bound = R.neumann_solve_dense(p.row_ptr, p.col, w, sc, np.max(np.abs(r), axis=1))
+    err = np.max(np.abs(F - exact), axis=1)
+    assert np.all(err <= bound + 1e-13)
+    H = R.neumann_solve_dense(p.row_ptr, p.col, w, sc, np.ones(p.n)).max()
+    assert err.max() <= H * res and H > 1.0
+    # the bound is not vacuous: it is within a small factor of the error it bounds
+    assert bound.max() <= 50 * err.max()
+
+
+def test_harmonic_solve_by_conjugate_gradients_is_the_fixed_point_of_eq1(oracle_native):
+    """The library solve of (D - W)_UU F_U = W_UL Y_L used as O1 on graphs too large for thousands of sweeps:
+    equals Eq. (2) by dense solve, equals ItLP run to convergence, and one sweep of Eq. (1) leaves it alone."""
+    p = W.small_random(400, 5, 4.0, 20, 47, connected=False)
+    sc = np.full(p.n, -1, dtype=np.int32)
+    sc[p.seed_vertex] = p.seed_class
+    w = p.w.astype(np.float64)
+    cg = R.harmonic_solve_cg(p.row_ptr, p.col, w, sc, p.C)
+    reach = R.seed_reachable(p.row_ptr, p.col, sc)
+    it, _, _ = oracle_native.itlp_solve(p.row_ptr, p.col, w, sc, p.C, tol=1e-14, max_iter=1_000_000)
+    assert np.max(np.abs(cg - it)[reach]) < 1e-10
+    _, moved = oracle_native.itlp_sweep(p.row_ptr, p.col, w, np.where(reach[:, None], cg, it), sc)
+    assert moved < 1e-12
+    assert np.array_equal(cg[~reach], R.initial_labels(sc, p.C)[~reach])  # left at the start values
+    q = W.small_random(120, 3, 3.0, 8, 49)
+    scq = np.full(q.n, -1, dtype=np.int32)
+    scq[q.seed_vertex] = q.seed_class
+    dense = R.harmonic_closed_form(q.row_ptr, q.col, q.w.astype(np.float64), scq, q.C)
+    np.testing.assert_allclose(R.harmonic_solve_cg(q.row_ptr, q.col, q.w.astype(np.float64), scq, q.C), dense, atol=1e-11)

@@ -125,3 +125,100 @@ def test_step3_respects_max_iter(oracle_native):
     A0 = oracle_native.affected_set(rp, col, g.seed_class, n_old, b.eu, b.ev, b.seed_vertex)
     out = oracle_native.step3_propagate(rp, col, w, F, g.seed_class, A0, 1e-9, 3)
     assert out["rounds"] == 3 and out["remaining"] > 0
+
+
+# ---- hand-worked rounds (tests/golden/step3_rounds.json) ---------------------------------------
+import json
+import os
+from fractions import Fraction
+
+_ROUNDS = os.path.join(os.path.dirname(__file__), "golden", "step3_rounds.json")
+
+
+def _fr(xs):
+    return np.array([float(Fraction(x)) for x in xs], dtype=np.float64)
+
+
+def _rows(f):
+    return np.stack([1.0 - f, f], axis=1)
+
+
+def _golden_setup(case):
+    e = np.array(case["edges"], dtype=np.float64).reshape(-1, 3)
+    rp, col, w = W.edges_to_csr(case["n_old"], e[:, 0].astype(np.int64), e[:, 1].astype(np.int64), e[:, 2])
+    g = R.Graph(case["n_old"], rp, col, w, case["C"], [s[0] for s in case["seeds"]], [s[1] for s in case["seeds"]])
+    # the listed start is the exact labelling of the graph before the batch
+    exact = R.harmonic_closed_form(rp, col, w, g.seed_class, case["C"])
+    np.testing.assert_allclose(exact, _rows(_fr(case["start"])), atol=1e-13)
+    b = case["batch"]
+    be = np.array(b["edges"], dtype=np.float64).reshape(-1, 3)
+    eu, ev, ew = be[:, 0].astype(np.int64), be[:, 1].astype(np.int64), be[:, 2]
+    sv = np.array([s[0] for s in b["seeds"]], dtype=np.int64)
+    sc = np.array([s[1] for s in b["seeds"]], dtype=np.int64)
+    g.insert(b["num_new_vertices"], eu, ev, ew, sv, sc)
+    F = np.concatenate([exact, np.full((b["num_new_vertices"], case["C"]), 1.0 / case["C"])])
+    F[sv] = 0
+    F[sv, sc] = 1
+    return g, F, eu, ev, sv
+
+
+@pytest.mark.parametrize("case", json.load(open(_ROUNDS))["cases"], ids=lambda c: c["name"])
+@pytest.mark.parametrize("decide_fp32", [False, True])
+def test_hand_worked_rounds(case, decide_fp32, oracle_native):
+    """V_aff, the rows that moved and all labels after every round, for both statements of Step 3."""
+    g, F0, eu, ev, sv = _golden_setup(case)
+    delta = float(Fraction(case["delta"]))
+    adj = g.adjacency()
+    rp, col, w = g.csr()
+    A0 = R.affected_set(adj, g.seed_class, case["n_old"], case["batch"]["num_new_vertices"], eu, ev, sv)
+    A0c = oracle_native.affected_set(rp, col, g.seed_class, case["n_old"], eu, ev, sv)
+    assert sorted(A0) == case["affected"] == A0c.tolist()
+    trace = []
+    F, rounds, sizes, changes = R.step3_propagate(adj, F0, g.seed_class, A0, delta, 1000, decide_fp32=decide_fp32,
+                                                  trace=trace)
+    want = case["rounds"]
+    assert rounds == len(want) and sizes == [len(r["V_aff"]) for r in want]
+    for t, (r, (A, moved, Ft)) in enumerate(zip(want, trace)):
+        assert A == r["V_aff"] and moved == r["moved"], f"round {t + 1}"
+        np.testing.assert_allclose(Ft, _rows(_fr(r["f"])), atol=1e-14, err_msg=f"round {t + 1}")
+    # the C loop, stopped after t rounds for every t: same labels, same |V_aff| per round, and the size of the
+    # V_aff that remains is that of the next listed round
+    for t in range(1, len(want) + 1):
+        out = oracle_native.step3_propagate(rp, col, w, F0, g.seed_class, A0c, delta, t, decide_fp32=decide_fp32)
+        assert out["rounds"] == t
+        assert out["frontier_sizes"].tolist() == [len(r["V_aff"]) for r in want[:t]]
+        np.testing.assert_allclose(out["F"], _rows(_fr(want[t - 1]["f"])), atol=1e-14)
+        assert out["remaining"] == (len(want[t]["V_aff"]) if t < len(want) else 0)
+        assert out["rows_updated"] == sum(len(r["V_aff"]) for r in want[:t])
+    out = oracle_native.step3_propagate(rp, col, w, F0, g.seed_class, A0c, delta, 1000, decide_fp32=decide_fp32)
+    assert out["rounds"] == len(want) and out["remaining"] == 0
+
+
+@pytest.mark.parametrize("kw", [dict(num_new=25, degree=4, num_new_seeds=2),
+                                dict(num_new=0, degree=0, num_new_seeds=0, num_extra_edges=40, num_revealed=3),
+                                dict(num_new=10, degree=3, num_new_seeds=1, num_extra_edges=30, num_revealed=2)])
+def test_csr_with_batch_is_the_graph_update_of_the_oracle(kw):
+    """workloads.csr_with_batch builds the updated CSR the full-size GPU tests hand to the oracle; it must be
+    the same graph as the oracle's own update (Alg. 1 Step 1): per row the same multiset of (neighbour, weight),
+    parallel edges kept as separate entries."""
+    p = W.small_random(160, 3, 4.0, 9, 31)
+    n_old = p.n  # the batch generator advances p.n
+    b = W.small_random_batch(p, **kw)
+    # make sure parallel edges occur: repeat some batch edges, and re-insert an edge the base graph already has
+    dup = slice(0, min(5, b.num_edges))
+    u0 = int(np.flatnonzero(np.diff(p.row_ptr) > 0)[0])
+    eu = np.concatenate([b.eu, b.eu[dup], [u0]]).astype(b.eu.dtype)
+    ev = np.concatenate([b.ev, b.ev[dup], [p.col[p.row_ptr[u0]]]]).astype(b.ev.dtype)
+    ew = np.concatenate([b.ew, b.ew[dup] * np.float32(0.5), [np.float32(0.25)]]).astype(b.ew.dtype)
+    b2 = W.Batch(num_new_vertices=b.num_new_vertices, eu=eu, ev=ev, ew=ew, seed_vertex=b.seed_vertex, seed_class=b.seed_class)
+    g = R.Graph(n_old, p.row_ptr, p.col, p.w, p.C, p.seed_vertex, p.seed_class)
+    g.insert(b2.num_new_vertices, b2.eu, b2.ev, b2.ew, b2.seed_vertex, b2.seed_class)
+    rp_o, col_o, w_o = g.csr()
+    rp_w, col_w, w_w = W.csr_with_batch(n_old, p.row_ptr, p.col, p.w, b2)
+    assert rp_w.tolist() == rp_o.tolist() and rp_w[-1] == p.col.shape[0] + 2 * b2.num_edges
+    for u in range(g.n):
+        a = sorted(zip(col_o[rp_o[u]:rp_o[u + 1]].tolist(), np.asarray(w_o[rp_o[u]:rp_o[u + 1]], dtype=np.float64).tolist()))
+        c = sorted(zip(col_w[rp_w[u]:rp_w[u + 1]].tolist(), np.asarray(w_w[rp_w[u]:rp_w[u + 1]], dtype=np.float64).tolist()))
+        assert a == c, u
+    # at least one row really holds a parallel edge
+    assert any(len(set(col_o[rp_o[u]:rp_o[u + 1]].tolist())) < rp_o[u + 1] - rp_o[u] for u in range(g.n))
