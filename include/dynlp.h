@@ -68,6 +68,8 @@ typedef struct dynlp_stats {
     float ms_seed;            /* seed clamping + frontier seeding + first compaction */
     float ms_iterate;         /* the propagation loop */
     float ms_total;           /* whole call, host wall clock */
+    int32_t final_checks;     /* rounds over all updatable rows that dynlp_set_final_check added (0 when it is off) */
+    int32_t reserved;
 } dynlp_stats;
 
 typedef struct dynlp_options {
@@ -144,6 +146,20 @@ dynlp_status dynlp_set_params(dynlp_ctx* ctx, float tol, int32_t max_iter);
  */
 typedef enum dynlp_update_mode { DYNLP_UPDATE_SYNCHRONOUS = 0, DYNLP_UPDATE_IN_PLACE = 1 } dynlp_update_mode;
 dynlp_status dynlp_set_update_mode(dynlp_ctx* ctx, int32_t mode);
+
+/*
+ * A guarantee on top of Alg. 2 Step 3 (off by default; the paper stops when V_aff is empty).  Step 3 stops row by
+ * row: a row leaves V_aff once it moves by <= tol, and afterwards its neighbours may each keep moving by just under
+ * tol per round without bringing it back, so the labels a batch ends with can sit further than tol from satisfying
+ * Eq. (1) (the paper reports the effect as hard-label accuracy below 100% for large batches).  With the check on,
+ * every time V_aff empties dynlp_apply_batch / dynlp_apply_update run one more round with V_aff = all updatable
+ * vertices; if it moves no row by more than tol the call ends, else Step 3 continues from the rows it moved.  The
+ * call then ends in the state a static solve ends in: one sweep of Eq. (1) moves no row by more than tol, hence
+ * every row is within tol * ||(I - P_UU)^{-1}||_inf of the exact harmonic labels (convergence corollary), where the
+ * norm is the largest expected number of random-walk steps to a labelled vertex.  Costs one round over all rows
+ * per check (dynlp_stats.final_checks counts them).
+ */
+dynlp_status dynlp_set_final_check(dynlp_ctx* ctx, int32_t on);
 
 /*
  * Starting rows of the vertices a batch inserts (Alg. 2 Step 1 "sparsification" and Step 2 "label

@@ -10,6 +10,8 @@
  *   oracle_itlp_solve    repeat the sweep until max_u max_c |F_new - F| <= tol (ItLP).
  *   oracle_neumann_solve x = (I - P_UU)^{-1} b as the limit of x <- b + P_UU x (the series sum_k P_UU^k b of the
  *                        convergence proof), P = D^{-1} W: error bounds for labels that are not yet converged.
+ *   oracle_laplacian_cg  the linear system of Eq. (2) in symmetric form, (D - W)_UU X = B, by conjugate gradients
+ *                        (for graphs on which the thousands of sweeps of the two iterations above take too long).
  *   oracle_affected_set  V_aff after Step 1 of Alg. 2 for an insertion batch.
  *   oracle_step3         Step 3 of Alg. 2 in synchronous rounds over V_aff.
  *
@@ -139,6 +141,135 @@ int64_t oracle_neumann_solve(int64_t n, const int64_t* row_ptr, const int32_t* c
     }
     if (cur != x) memcpy(x, cur, (size_t)n * sizeof(double));
     if (last_change) *last_change = change;
+    return it;
+}
+
+/*
+ * Solve (D - W)_UU X = B for k right-hand sides at once (X, B: n x k row-major; rows outside U are ignored in B and
+ * left untouched in X, which holds the start on entry).  in_U[u] != 0 marks the rows of U; the caller passes the
+ * unlabelled vertices that have an edge and are connected to a labelled vertex, on which the matrix is symmetric
+ * positive definite.  With B = W_UL Y_L the solution is the harmonic labelling of Eq. (2); with B = D_U b it is
+ * (I - P_UU)^{-1} b.  Method: the textbook conjugate-gradient iteration with the diagonal as preconditioner, the k
+ * systems advancing in lockstep (each has its own step lengths); a system stops changing once its residual norm
+ * is <= rtol times the norm of its right-hand side.  Returns the iterations done; *worst (may be NULL) = the
+ * largest relative residual norm left.  Callers check the result with one sweep of the defining iteration.
+ */
+static void lap_apply(int64_t n, const int64_t* row_ptr, const int32_t* col, const double* w, const uint8_t* in_U,
+                      int k, const double* P, double* out) {
+#pragma omp parallel for schedule(dynamic, 1024)
+    for (int64_t u = 0; u < n; ++u) {
+        if (!in_U[u]) continue;
+        double d = 0.0;
+        double* o = out + u * k;
+        for (int c = 0; c < k; ++c) o[c] = 0.0;
+        for (int64_t j = row_ptr[u]; j < row_ptr[u + 1]; ++j) {
+            const int32_t v = col[j];
+            d += w[j];
+            if (in_U[v])
+                for (int c = 0; c < k; ++c) o[c] -= w[j] * P[(int64_t)v * k + c];
+        }
+        for (int c = 0; c < k; ++c) o[c] += d * P[u * k + c];
+    }
+}
+
+/* dots[c] = sum over U of a[u][c] * b[u][c] */
+static void col_dots(int64_t n, const uint8_t* in_U, int k, const double* a, const double* b, double* dots) {
+    for (int c = 0; c < k; ++c) dots[c] = 0.0;
+#pragma omp parallel
+    {
+        double loc[64];
+        for (int c = 0; c < k; ++c) loc[c] = 0.0;
+#pragma omp for schedule(static)
+        for (int64_t u = 0; u < n; ++u) {
+            if (!in_U[u]) continue;
+            for (int c = 0; c < k; ++c) loc[c] += a[u * k + c] * b[u * k + c];
+        }
+#pragma omp critical
+        for (int c = 0; c < k; ++c) dots[c] += loc[c];
+    }
+}
+
+int64_t oracle_laplacian_cg(int64_t n, const int64_t* row_ptr, const int32_t* col, const double* w,
+                            const uint8_t* in_U, int k, const double* B, double* X, double rtol, int64_t max_iter,
+                            double* worst) {
+    if (k < 1 || k > 64) return -1;
+    const size_t sz = (size_t)(n > 0 ? n : 1) * k;
+    double* r = (double*)calloc(sz, sizeof(double));
+    double* z = (double*)calloc(sz, sizeof(double));
+    double* p = (double*)calloc(sz, sizeof(double));
+    double* Ap = (double*)calloc(sz, sizeof(double));
+    double* diag = (double*)calloc((size_t)(n > 0 ? n : 1), sizeof(double));
+    double rz[64], rz_new[64], pAp[64], bb[64], rr[64], alpha[64], beta[64];
+    int live[64];
+    for (int64_t u = 0; u < n; ++u)
+        for (int64_t j = row_ptr[u]; j < row_ptr[u + 1]; ++j) diag[u] += w[j];
+    /* r = B - A X on U; z = r / diag; p = z */
+    for (int64_t u = 0; u < n; ++u)
+        if (in_U[u])
+            for (int c = 0; c < k; ++c) p[u * k + c] = X[u * k + c];
+    lap_apply(n, row_ptr, col, w, in_U, k, p, Ap);
+    for (int64_t u = 0; u < n; ++u) {
+        for (int c = 0; c < k; ++c) {
+            const int64_t i = u * k + c;
+            if (in_U[u]) {
+                r[i] = B[i] - Ap[i];
+                z[i] = r[i] / diag[u];
+                p[i] = z[i];
+            } else {
+                r[i] = z[i] = p[i] = 0.0;
+            }
+        }
+    }
+    col_dots(n, in_U, k, B, B, bb);
+    col_dots(n, in_U, k, r, z, rz);
+    col_dots(n, in_U, k, r, r, rr);
+    int64_t it = 0;
+    double left = 0.0;
+    for (;;) {
+        int any = 0;
+        left = 0.0;
+        for (int c = 0; c < k; ++c) {
+            const double rel = bb[c] > 0.0 ? sqrt(rr[c] / bb[c]) : (rr[c] > 0.0 ? INFINITY : 0.0);
+            live[c] = rel > rtol && rz[c] > 0.0;
+            if (live[c]) any = 1;
+            if (rel > left) left = rel;
+        }
+        if (!any || it >= max_iter) break;
+        lap_apply(n, row_ptr, col, w, in_U, k, p, Ap);
+        col_dots(n, in_U, k, p, Ap, pAp);
+        for (int c = 0; c < k; ++c) alpha[c] = live[c] && pAp[c] > 0.0 ? rz[c] / pAp[c] : 0.0;
+#pragma omp parallel for schedule(static)
+        for (int64_t u = 0; u < n; ++u) {
+            if (!in_U[u]) continue;
+            for (int c = 0; c < k; ++c) {
+                const int64_t i = u * k + c;
+                X[i] += alpha[c] * p[i];
+                r[i] -= alpha[c] * Ap[i];
+                z[i] = r[i] / diag[u];
+            }
+        }
+        col_dots(n, in_U, k, r, z, rz_new);
+        col_dots(n, in_U, k, r, r, rr);
+        for (int c = 0; c < k; ++c) {
+            beta[c] = live[c] && rz[c] > 0.0 ? rz_new[c] / rz[c] : 0.0;
+            if (live[c]) rz[c] = rz_new[c];
+        }
+#pragma omp parallel for schedule(static)
+        for (int64_t u = 0; u < n; ++u) {
+            if (!in_U[u]) continue;
+            for (int c = 0; c < k; ++c) {
+                const int64_t i = u * k + c;
+                if (live[c]) p[i] = z[i] + beta[c] * p[i];
+            }
+        }
+        ++it;
+    }
+    if (worst) *worst = left;
+    free(r);
+    free(z);
+    free(p);
+    free(Ap);
+    free(diag);
     return it;
 }
 

@@ -38,6 +38,8 @@ def lib():
         L.oracle_itlp_solve.argtypes = [i64, p, p, p, ct.c_int, p, p, p, f64, i64, p]
         L.oracle_neumann_solve.restype = i64
         L.oracle_neumann_solve.argtypes = [i64, p, p, p, p, p, p, p, f64, i64, p]
+        L.oracle_laplacian_cg.restype = i64
+        L.oracle_laplacian_cg.argtypes = [i64, p, p, p, p, ct.c_int, p, p, f64, i64, p]
         L.oracle_affected_set.restype = i64
         L.oracle_affected_set.argtypes = [i64, p, p, p, i64, i64, p, p, i64, p, p, p]
         L.oracle_step3.restype = i64
@@ -107,6 +109,63 @@ def neumann_solve(row_ptr, col, w, seed_class, b, tol=1e-12, max_iter=10_000_000
     it = lib().oracle_neumann_solve(sc.shape[0], _ptr(rp), _ptr(cl), _ptr(ww), _ptr(sc), _ptr(b), _ptr(x), _ptr(tmp),
                                     float(tol), int(max_iter), ct.byref(last))
     return x, int(it), float(last.value)
+
+
+def _updatable_mask(rp, cl, sc):
+    from .reference import seed_reachable
+
+    return ((sc < 0) & (np.diff(rp) > 0) & seed_reachable(rp, cl, sc)).astype(np.uint8)
+
+
+def _laplacian_cg(rp, cl, ww, in_U, B, X, rtol, max_iter):
+    worst = ct.c_double(0.0)
+    k = B.shape[1]
+    assert X.shape == B.shape and X.shape[0] == in_U.shape[0]
+    out = X
+    for c0 in range(0, k, 64):  # the C routine advances up to 64 systems at once
+        Bc = np.ascontiguousarray(B[:, c0:c0 + 64])
+        Xc = np.ascontiguousarray(X[:, c0:c0 + 64])
+        it = lib().oracle_laplacian_cg(in_U.shape[0], _ptr(rp), _ptr(cl), _ptr(ww), _ptr(in_U), Bc.shape[1], _ptr(Bc),
+                                       _ptr(Xc), float(rtol), int(max_iter), ct.byref(worst))
+        if it < 0 or worst.value > rtol:
+            raise RuntimeError(f"conjugate gradients stopped after {it} iterations at relative residual {worst.value:.2e}")
+        out[:, c0:c0 + 64] = Xc
+    return out
+
+
+def neumann_solve_cg(row_ptr, col, w, seed_class, b, rtol=1e-13, max_iter=100_000):
+    """x = (I - P_UU)^{-1} b from the symmetric form (D - W)_UU x = D_U b by conjugate gradients (0 outside the
+    updatable rows).  For graphs where the series iteration of neumann_solve needs too many sweeps."""
+    rp, cl, ww = _csr(row_ptr, col, w)
+    sc = np.ascontiguousarray(seed_class, dtype=np.int32)
+    n = sc.shape[0]
+    in_U = _updatable_mask(rp, cl, sc)
+    deg = np.bincount(np.repeat(np.arange(n), np.diff(rp)), weights=ww, minlength=n)
+    B = (deg * np.asarray(b, dtype=np.float64) * in_U).reshape(n, 1)
+    X = np.zeros((n, 1), dtype=np.float64)
+    return _laplacian_cg(rp, cl, ww, in_U, B, X, rtol, max_iter)[:, 0]
+
+
+def harmonic_solve_cg(row_ptr, col, w, seed_class, C, rtol=1e-13, max_iter=100_000):
+    """The fixed point of Eq. (1) from Eq. (2) in symmetric form, (D - W)_UU F_U = W_UL Y_L, all C columns by
+    conjugate gradients.  Rows outside the updatable set keep their start values (one-hot / uniform)."""
+    from .reference import initial_labels
+
+    rp, cl, ww = _csr(row_ptr, col, w)
+    sc = np.ascontiguousarray(seed_class, dtype=np.int32)
+    n = sc.shape[0]
+    in_U = _updatable_mask(rp, cl, sc)
+    F = initial_labels(sc, C)
+    # B_u = sum over labelled neighbours v of w(u,v) Y_v
+    src = np.repeat(np.arange(n), np.diff(rp))
+    lab = sc[cl] >= 0
+    B = np.zeros((n, C), dtype=np.float64)
+    np.add.at(B, (src[lab], sc[cl[lab]]), ww[lab])
+    B *= in_U[:, None]
+    X = np.full((n, C), 1.0 / C, dtype=np.float64) * in_U[:, None]
+    X = _laplacian_cg(rp, cl, ww, in_U, B, np.ascontiguousarray(X), rtol, max_iter)
+    F[in_U > 0] = X[in_U > 0]
+    return F
 
 
 def affected_set(row_ptr, col, seed_class, n_old, eu, ev, new_seed_vertex, deleted_neighbours=None):

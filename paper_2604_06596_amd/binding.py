@@ -29,7 +29,8 @@ class Stats(ct.Structure):
                 ("rows_updated", ct.c_int64), ("edges_traversed", ct.c_int64), ("frontier_initial", ct.c_int64),
                 ("frontier_peak", ct.c_int64), ("rows_relocated", ct.c_int64), ("update_launches", ct.c_int64),
                 ("ms_update_kernel", ct.c_float), ("ms_insert", ct.c_float), ("ms_seed", ct.c_float),
-                ("ms_iterate", ct.c_float), ("ms_total", ct.c_float)]
+                ("ms_iterate", ct.c_float), ("ms_total", ct.c_float), ("final_checks", ct.c_int32),
+                ("reserved", ct.c_int32)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}
@@ -68,7 +69,8 @@ EXPORTS = ["dynlp_default_options", "dynlp_create", "dynlp_static_solve", "dynlp
            "dynlp_get_labels", "dynlp_num_vertices", "dynlp_num_entries", "dynlp_num_classes", "dynlp_export_graph",
            "dynlp_round_log", "dynlp_last_error", "dynlp_destroy", "dynlp_set_initialiser",
            "dynlp_mean_edge_weight", "dynlp_last_components", "dynlp_set_update_mode", "dynlp_apply_update", "dynlp_storage_info",
-           "dynlp_compact_storage", "dynlp_stream_bandwidth", "dynlp_get_labels_static", "dynlp_static_scratch_bytes"]
+           "dynlp_compact_storage", "dynlp_stream_bandwidth", "dynlp_get_labels_static", "dynlp_static_scratch_bytes",
+           "dynlp_set_final_check"]
 
 _lib = None
 
@@ -126,6 +128,8 @@ def load_library(path: str | None = None):
     L.dynlp_compact_storage.restype = ct.c_int
     L.dynlp_set_update_mode.argtypes = [p, i32]
     L.dynlp_set_update_mode.restype = ct.c_int
+    L.dynlp_set_final_check.argtypes = [p, i32]
+    L.dynlp_set_final_check.restype = ct.c_int
     L.dynlp_set_initialiser.argtypes = [p, i32, f32]
     L.dynlp_set_initialiser.restype = ct.c_int
     L.dynlp_mean_edge_weight.argtypes = [p, ct.POINTER(ct.c_double)]
@@ -248,6 +252,10 @@ class DynLP:
     def set_update_mode(self, mode):
         """dynlp_set_update_mode: UPDATE_SYNCHRONOUS or UPDATE_IN_PLACE."""
         self._check(self._L.dynlp_set_update_mode(self._h, int(mode)))
+
+    def set_final_check(self, on=True):
+        """dynlp_set_final_check: end every batch with a round over all rows that moves none by more than tol."""
+        self._check(self._L.dynlp_set_final_check(self._h, 1 if on else 0))
 
     def set_initialiser(self, mode, tau=0.0):
         """dynlp_set_initialiser: INIT_UNIFORM or INIT_SUPERNODE with threshold tau."""

@@ -135,6 +135,7 @@ struct dynlp_ctx {
     BatchCtr* h_bc = nullptr;    // pinned
 
     int update_mode = DYNLP_UPDATE_SYNCHRONOUS;
+    bool final_check = false;  // dynlp_set_final_check
     // binned rounds for scalar labels (dynlp_binned.h)
     int binned = 0;                 // option: 0 = automatic, -1 = never, 8..15 = always, with this many bin bits
     bool pb_built = false;          // the arrays below describe the graph as it stands
@@ -225,8 +226,7 @@ void* dev_alloc(dynlp_ctx* c, size_t bytes) {
 }
 
 void dev_free(dynlp_ctx* c, void* p) {
-    if (!p) return;
-    c->live.erase(p);
+    if (!p || c->live.erase(p) == 0) return;  // only what dev_try_alloc handed out and has not been freed yet
     if (c->dealloc_fn) c->dealloc_fn(p, c->alloc_user);
     else (void)hipFree(p);
 }
@@ -235,6 +235,31 @@ template <typename T>
 T* dev_alloc_n(dynlp_ctx* c, int64_t count) {
     return static_cast<T*>(dev_alloc(c, (size_t)std::max<int64_t>(count, 1) * sizeof(T)));
 }
+
+// Temporary device array of a call that does not change the context: when the allocator has no memory the call
+// ends with DYNLP_ERR_OOM and the context stays usable (nothing in it has changed); freed on scope exit.
+struct SoftOom {};
+template <typename T>
+struct Temp {
+    dynlp_ctx* c;
+    T* ptr = nullptr;
+    Temp(dynlp_ctx* ctx, int64_t count) : c(ctx) {
+        ptr = static_cast<T*>(dev_try_alloc(c, (size_t)std::max<int64_t>(count, 1) * sizeof(T)));
+        if (!ptr) {
+            c->err = "device allocation of " + std::to_string((size_t)std::max<int64_t>(count, 1) * sizeof(T)) +
+                     " bytes failed (the context is unchanged)";
+            throw SoftOom{};
+        }
+    }
+    ~Temp() { dev_free(c, ptr); }
+    Temp(const Temp&) = delete;
+    Temp& operator=(const Temp&) = delete;
+    T* release() {
+        T* p = ptr;
+        ptr = nullptr;
+        return p;
+    }
+};
 
 inline unsigned int grid_for(int64_t items) { return (unsigned int)std::max<int64_t>(1, ceil_div(items, kBlock)); }
 
@@ -919,12 +944,12 @@ void destroy_ctx(dynlp_ctx* c) {
     for (void* p : ptrs) dev_free(c, p);
     const std::vector<void*> left(c->live.begin(), c->live.end());  // arrays an interrupted call never got to free
     for (void* p : left) dev_free(c, p);
-    if (c->cc_ctr) (void)hipFree(c->cc_ctr);
+    dev_free(c, c->cc_ctr);
     if (c->h_cc) (void)hipHostFree(c->h_cc);
     for (hipEvent_t e : c->init_ev)
         if (e) (void)hipEventDestroy(e);
-    if (c->ring) (void)hipFree(c->ring);
-    if (c->bc) (void)hipFree(c->bc);
+    dev_free(c, c->ring);
+    dev_free(c, c->bc);
     if (c->h_slot) (void)hipHostFree(c->h_slot);
     if (c->h_bc) (void)hipHostFree(c->h_bc);
     for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
@@ -936,7 +961,7 @@ void destroy_ctx(dynlp_ctx* c) {
 // ---- Alg. 2 Step 1 (components of the sparsified batch-internal graph) + Step 2 (supernode rows) ----
 void ensure_init_scratch(dynlp_ctx* c, int64_t k, int64_t m) {
     if (!c->cc_ctr) {
-        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->cc_ctr), sizeof(InitCtr)));
+        c->cc_ctr = static_cast<InitCtr*>(dev_alloc(c, sizeof(InitCtr)));
         HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_cc), sizeof(InitCtr), hipHostMallocDefault));
         for (hipEvent_t& e : c->init_ev) HIPCHK(c, hipEventCreate(&e));
     }
@@ -1152,8 +1177,8 @@ dynlp_status dynlp_create(dynlp_ctx** out, int64_t n, const int64_t* row_ptr, co
         hipDeviceProp_t prop;
         HIPCHK(c, hipGetDeviceProperties(&prop, c->device));
         c->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->ring), sizeof(RoundCtr) * (kRing + 1)));
-        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->bc), sizeof(BatchCtr)));
+        c->ring = static_cast<RoundCtr*>(dev_alloc(c, sizeof(RoundCtr) * (kRing + 1)));
+        c->bc = static_cast<BatchCtr*>(dev_alloc(c, sizeof(BatchCtr)));
         HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_slot), sizeof(RoundCtr) * kRing, hipHostMallocDefault));
         HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_bc), sizeof(BatchCtr), hipHostMallocDefault));
         for (auto& e : c->phase_ev) HIPCHK(c, hipEventCreate(&e));
@@ -1278,14 +1303,14 @@ dynlp_status dynlp_stream_bandwidth(dynlp_ctx* c, int64_t bytes, int32_t repetit
         c->err = "bytes < 16 or repetitions < 1";
         return DYNLP_ERR_INVALID_ARG;
     }
-    float4 *src = nullptr, *dst = nullptr;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
     try {
         HIPCHK(c, hipSetDevice(c->device));
         const int64_t n16 = bytes / 16;
         const unsigned int blocks = (unsigned int)std::min<int64_t>(grid_for(n16), (int64_t)c->num_cu * 16);
-        src = static_cast<float4*>(dev_alloc(c, (size_t)n16 * 16));
-        dst = static_cast<float4*>(dev_alloc(c, std::max<size_t>((size_t)n16 * 16, (size_t)blocks * kBlock * sizeof(float))));
+        Temp<float4> src_t(c, n16);
+        Temp<float4> dst_t(c, std::max<int64_t>(n16, ceil_div((int64_t)blocks * kBlock * (int64_t)sizeof(float), 16)));
+        float4 *src = src_t.ptr, *dst = dst_t.ptr;
         HIPCHK(c, hipMemsetAsync(src, 0, (size_t)n16 * 16, c->stream));
         for (hipEvent_t& e : ev) HIPCHK(c, hipEventCreate(&e));
         hipLaunchKernelGGL(k_stream_copy, dim3(blocks), dim3(kBlock), 0, c->stream, n16, src, dst);  // warm-up
@@ -1306,10 +1331,12 @@ dynlp_status dynlp_stream_bandwidth(dynlp_ctx* c, int64_t bytes, int32_t repetit
         if (copy_gb_per_s) *copy_gb_per_s = 2.0 * moved / ((double)ms_copy * 1e6);  // bytes read + bytes written
         if (read_gb_per_s) *read_gb_per_s = moved / ((double)ms_read * 1e6);
         for (hipEvent_t e : ev) (void)hipEventDestroy(e);
-        dev_free(c, src);
-        dev_free(c, dst);
         return DYNLP_OK;
+    } catch (const SoftOom&) {
+        return DYNLP_ERR_OOM;
     } catch (const Fail& f) {
+        for (hipEvent_t e : ev)
+            if (e) (void)hipEventDestroy(e);
         return f.st;
     }
 }
@@ -1328,33 +1355,34 @@ dynlp_status dynlp_compact_storage(dynlp_ctx* c) {
         return DYNLP_ERR_STATE;
     }
     if (c->n == 0) return DYNLP_OK;
-    RowMeta* meta_new = nullptr;
-    int64_t* block_sums = nullptr;
-    Edge* pool_new = nullptr;
     try {
         HIPCHK(c, hipSetDevice(c->device));
         const int64_t n = c->n;
         const int64_t nb = grid_for(n);
-        meta_new = dev_alloc_n<RowMeta>(c, c->n_cap);
-        block_sums = dev_alloc_n<int64_t>(c, nb);
-        hipLaunchKernelGGL(k_recap_rows, dim3(nb), dim3(kBlock), 0, c->stream, n, c->meta, c->slack, meta_new, block_sums);
+        // the new layout is built beside the old one; the context switches over only when all of it exists, so
+        // running out of memory here leaves graph and labels as they were
+        Temp<RowMeta> meta_new(c, c->n_cap);
+        Temp<int64_t> block_sums(c, nb);
+        hipLaunchKernelGGL(k_recap_rows, dim3(nb), dim3(kBlock), 0, c->stream, n, c->meta, c->slack, meta_new.ptr, block_sums.ptr);
         HIPCHK(c, hipGetLastError());
-        const int64_t tail = scan_block_sums(c, nb, block_sums);
-        hipLaunchKernelGGL(k_row_offsets, dim3(nb), dim3(kBlock), 0, c->stream, n, meta_new, block_sums);
+        const int64_t tail = scan_block_sums(c, nb, block_sums.ptr);
+        hipLaunchKernelGGL(k_row_offsets, dim3(nb), dim3(kBlock), 0, c->stream, n, meta_new.ptr, block_sums.ptr);
         const int64_t cap = round_up(tail + tail / 4 + (1 << 16), kRowAlign);
-        pool_new = dev_alloc_n<Edge>(c, cap);
-        hipLaunchKernelGGL(k_copy_rows, dim3(grid_for(n * 16)), dim3(kBlock), 0, c->stream, n, c->meta, meta_new, c->pool,
-                           pool_new);
+        Temp<Edge> pool_new(c, cap);
+        hipLaunchKernelGGL(k_copy_rows, dim3(grid_for(n * 16)), dim3(kBlock), 0, c->stream, n, c->meta, meta_new.ptr, c->pool,
+                           pool_new.ptr);
         HIPCHK(c, hipGetLastError());
         HIPCHK(c, hipStreamSynchronize(c->stream));
         dev_free(c, c->meta);
         dev_free(c, c->pool);
-        dev_free(c, block_sums);
-        c->meta = meta_new;
-        c->pool = pool_new;
+        c->meta = meta_new.release();
+        c->pool = pool_new.release();
         c->pool_cap = cap;
         c->pool_tail = tail;
         return DYNLP_OK;
+    } catch (const SoftOom&) {
+        (void)hipStreamSynchronize(c->stream);
+        return DYNLP_ERR_OOM;
     } catch (const Fail& f) {
         return f.st;
     } catch (const std::bad_alloc&) {
@@ -1370,6 +1398,16 @@ dynlp_status dynlp_set_update_mode(dynlp_ctx* ctx, int32_t mode) {
         return DYNLP_ERR_INVALID_ARG;
     }
     ctx->update_mode = mode;
+    return DYNLP_OK;
+}
+
+dynlp_status dynlp_set_final_check(dynlp_ctx* ctx, int32_t on) {
+    if (!ctx) return DYNLP_ERR_INVALID_ARG;
+    if (on != 0 && on != 1) {
+        ctx->err = "on must be 0 or 1";
+        return DYNLP_ERR_INVALID_ARG;
+    }
+    ctx->final_check = on != 0;
     return DYNLP_OK;
 }
 
@@ -1400,26 +1438,24 @@ dynlp_status dynlp_mean_edge_weight(dynlp_ctx* c, double* mean) {
     }
     *mean = 0.0;
     if (c->entries == 0) return DYNLP_OK;
-    double* d_part = nullptr;
     try {
         HIPCHK(c, hipSetDevice(c->device));
         const unsigned int blocks = (unsigned int)std::min<int64_t>(grid_for(c->n * 16), (int64_t)c->num_cu * 4);
-        d_part = dev_alloc_n<double>(c, blocks);
+        Temp<double> d_part(c, blocks);
         std::vector<double> part(blocks);
-        hipLaunchKernelGGL(k_weight_partial, dim3(blocks), dim3(kBlock), 0, c->stream, c->n, c->meta, c->pool, d_part);
+        hipLaunchKernelGGL(k_weight_partial, dim3(blocks), dim3(kBlock), 0, c->stream, c->n, c->meta, c->pool, d_part.ptr);
         HIPCHK(c, hipGetLastError());
-        HIPCHK(c, hipMemcpyAsync(part.data(), d_part, sizeof(double) * blocks, hipMemcpyDeviceToHost, c->stream));
+        HIPCHK(c, hipMemcpyAsync(part.data(), d_part.ptr, sizeof(double) * blocks, hipMemcpyDeviceToHost, c->stream));
         HIPCHK(c, hipStreamSynchronize(c->stream));
-        dev_free(c, d_part);
-        d_part = nullptr;
         double tot = 0.0;
         for (double v : part) tot += v;
         *mean = tot / (double)c->entries;
         return DYNLP_OK;
+    } catch (const SoftOom&) {
+        return DYNLP_ERR_OOM;
     } catch (const Fail& f) {
         return f.st;
     } catch (const std::bad_alloc&) {
-        dev_free(c, d_part);
         c->err = "host allocation failed";
         return DYNLP_ERR_OOM;
     }
@@ -1764,6 +1800,11 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
         unsigned int prev_sig[3] = {0xffffffffu, 0xffffffffu, 0xffffffffu};
         c->pb_built = false;    // the batch changed the graph
         const bool in_place = c->update_mode == DYNLP_UPDATE_IN_PLACE;
+        // dynlp_set_final_check: when V_aff has emptied, one more round over every updatable row; rows it moves by
+        // more than tol (and their neighbours) start Step 3 again.  check_round = index of the running check round.
+        int final_checks = 0, check_round = -1;
+        bool verified = !c->final_check;
+        for (;;) {
         while (known > 0 && it < c->max_iter) {
             const int G = choose_group(c, avg_len);
             // A stretch of ping-pong rounds starts when V_aff covers nearly every updatable vertex (one copy
@@ -1857,6 +1898,7 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
                 // inside a stretch the next V_aff is not counted: this round's size stands in for it while
                 // rows still move
                 known = pingpong && fused ? (rc.changed ? std::max(nq, 1u) : 0u) : rc.next_count + rc.next_long;
+                if (it + i == check_round) verified = rc.changed == 0u;  // the check round moved no row by more than tol
                 const unsigned int sig[3] = {nq, rc.changed, rc.resid_bits};
                 same_run = (!pingpong && std::memcmp(sig, prev_sig, sizeof sig) == 0) ? same_run + 1 : 0;
                 std::memcpy(prev_sig, sig, sizeof sig);
@@ -1867,7 +1909,21 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
             it += executed;
             if (executed < r) known = 0;  // a round found V_aff empty
         }
-        const unsigned int nq = known;
+        if (verified || known > 0 || it >= c->max_iter || universe.size() == 0) break;
+        // V_aff is empty: make every updatable vertex the frontier of round `it` (list into the current parity's
+        // array, sizes into the slot the round reads them from; a slot past the last executed round is all zero)
+        {
+            pingpong = false;  // the check round starts a stretch of its own (fresh bitmaps, partner buffer in step)
+            RoundCtr* slot = slot_of(c, it - 1);
+            HIPCHK(c, hipMemsetAsync(slot, 0, sizeof(RoundCtr), c->stream));
+            launch_compact(c, frontier_of(c, cur), &slot->next_count, &slot->next_long, 1);
+            known = universe.size();
+            check_round = it;
+            ++final_checks;
+        }
+        }
+        // not converged: max_iter cut the rounds, or cut them before a requested final check had passed
+        const unsigned int nq = known > 0 ? known : (verified || universe.size() == 0 ? 0u : 1u);
         HIPCHK(c, hipEventRecord(c->phase_ev[3], c->stream));
         HIPCHK(c, hipStreamSynchronize(c->stream));
         const float kernel_ms_total = c->time_kernels ? collect_kernel_ms(c) : 0.f;
@@ -1882,6 +1938,7 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
             stats->frontier_peak = peak;
             stats->rows_relocated = relocated;
             stats->update_launches = it;
+            stats->final_checks = final_checks;
             stats->ms_update_kernel = kernel_ms_total;
             (void)hipEventElapsedTime(&stats->ms_insert, c->phase_ev[0], c->phase_ev[1]);
             (void)hipEventElapsedTime(&stats->ms_seed, c->phase_ev[1], c->phase_ev[2]);
@@ -1913,14 +1970,20 @@ dynlp_status dynlp_get_labels(dynlp_ctx* c, float* soft, int32_t* hard) {
     dynlp_status st = DYNLP_OK;
     try {
         HIPCHK(c, hipSetDevice(c->device));
-        float* dst_soft = !soft ? nullptr : c->dev_ptrs ? soft : (d_soft = dev_alloc_n<float>(c, n * c->C));
-        int32_t* dst_hard = !hard ? nullptr : c->dev_ptrs ? hard : (d_hard = dev_alloc_n<int32_t>(c, n));
+        // staging of the packed outputs in host-pointer mode; without memory for it the call fails and the context
+        // stays usable
+        if (soft && !c->dev_ptrs) d_soft = Temp<float>(c, n * c->C).release();
+        if (hard && !c->dev_ptrs) d_hard = Temp<int32_t>(c, n).release();
+        float* dst_soft = !soft ? nullptr : c->dev_ptrs ? soft : d_soft;
+        int32_t* dst_hard = !hard ? nullptr : c->dev_ptrs ? hard : d_hard;
         launch_label_output(c, dst_soft, dst_hard);
         if (!c->dev_ptrs) {
             if (soft) HIPCHK(c, hipMemcpyAsync(soft, dst_soft, (size_t)n * c->C * sizeof(float), hipMemcpyDeviceToHost, c->stream));
             if (hard) HIPCHK(c, hipMemcpyAsync(hard, dst_hard, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
         }
         HIPCHK(c, hipStreamSynchronize(c->stream));
+    } catch (const SoftOom&) {
+        st = DYNLP_ERR_OOM;
     } catch (const Fail& f) {
         st = f.st;
     }
@@ -1989,8 +2052,8 @@ dynlp_status dynlp_export_graph(dynlp_ctx* c, int64_t* row_ptr, int32_t* col, fl
     try {
         HIPCHK(c, hipSetDevice(c->device));
         const int64_t nb = grid_for(n);
-        d_rp = dev_alloc_n<int64_t>(c, n + 1);
-        sums = dev_alloc_n<int64_t>(c, nb);
+        d_rp = Temp<int64_t>(c, n + 1).release();
+        sums = Temp<int64_t>(c, nb).release();
         int64_t total = 0;
         if (n > 0) {
             hipLaunchKernelGGL(k_row_lens, dim3(nb), dim3(kBlock), 0, c->stream, n, c->meta, d_rp, sums);
@@ -2005,8 +2068,8 @@ dynlp_status dynlp_export_graph(dynlp_ctx* c, int64_t* row_ptr, int32_t* col, fl
             throw Fail{DYNLP_ERR_STATE};
         }
         if (nnz > 0) {
-            int32_t* ocol = c->dev_ptrs ? col : (d_col = dev_alloc_n<int32_t>(c, nnz));
-            float* ow = c->dev_ptrs ? w : (d_w = dev_alloc_n<float>(c, nnz));
+            int32_t* ocol = c->dev_ptrs ? col : (d_col = Temp<int32_t>(c, nnz).release());
+            float* ow = c->dev_ptrs ? w : (d_w = Temp<float>(c, nnz).release());
             hipLaunchKernelGGL(k_export_rows, dim3(grid_for(n * 16)), dim3(kBlock), 0, c->stream, n, c->meta, c->pool, d_rp,
                                ocol, ow);
             HIPCHK(c, hipGetLastError());
@@ -2020,6 +2083,9 @@ dynlp_status dynlp_export_graph(dynlp_ctx* c, int64_t* row_ptr, int32_t* col, fl
         if (seed_class && n > 0)
             HIPCHK(c, hipMemcpyAsync(seed_class, c->seed_class, (size_t)n * sizeof(int32_t), kind, c->stream));
         HIPCHK(c, hipStreamSynchronize(c->stream));
+    } catch (const SoftOom&) {
+        (void)hipStreamSynchronize(c->stream);
+        st = DYNLP_ERR_OOM;
     } catch (const Fail& f) {
         st = f.st;
     }

@@ -36,7 +36,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_stats_and_options_layout_match_header():
     # field order and sizes as declared in include/dynlp.h (natural alignment)
-    assert ct.sizeof(B.Stats) == 4 + 4 + 4 + 4 + 8 * 6 + 4 * 5 + 4
+    assert ct.sizeof(B.Stats) == 4 + 4 + 4 + 4 + 8 * 6 + 4 * 5 + 4 + 8
     assert B.Stats.rows_updated.offset == 16
     assert B.Stats.ms_update_kernel.offset == 64
     assert B.Options.stream.offset == 8 and B.Options.slack_factor.offset == 20

@@ -6,7 +6,9 @@ import numpy as np
 import pytest
 import torch
 
+import certify as Cf
 import workloads as W
+from oracle import reference as R
 import paper_2604_06596_amd as P
 
 pytestmark = pytest.mark.gpu
@@ -106,4 +108,43 @@ def test_without_memory_for_the_binned_arrays_the_rounds_are_ordinary_ones():
     assert not a.live
     st2, s2, soft2, hard2, kinds2 = _run(p0, b, binary_scalar=True, binned_rounds=8)
     assert 3 in kinds2
-    assert np.max(np.abs(soft - soft2)) <= 2e-5
+    # ordinary rounds and binned rounds are two locally stopped runs on one graph: each within its own residual
+    # certificate of the exact labels, hence within the sum of the two of each other
+    g = R.Graph(p0.n, p0.row_ptr, p0.col, p0.w, 2, p0.seed_vertex, p0.seed_class)
+    g.insert(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+    rp, col, w = g.csr()
+    Cf.check_two_runs(soft, Cf.certificate(rp, col, w, g.seed_class, soft), soft2,
+                      Cf.certificate(rp, col, w, g.seed_class, soft2), "ordinary vs binned rounds")
+
+
+def test_calls_that_change_nothing_survive_an_allocator_without_memory():
+    """dynlp_get_labels, dynlp_export_graph, dynlp_mean_edge_weight and dynlp_compact_storage only need temporary
+    arrays (compaction: the new layout beside the old one).  When the allocator refuses them they return
+    DYNLP_ERR_OOM, hand back what they had already taken, and leave the context usable and unchanged."""
+    p0, b = _problem(10)
+    a = TorchAllocator()
+    with P.DynLP(p0.n, p0.row_ptr, p0.col, p0.w, p0.C, p0.seed_vertex, p0.seed_class, allocator=a) as d:
+        assert d.static_solve(TOL, 20000)[0] == 0
+        soft, hard = d.get_labels()
+        graph = d.export_graph()
+        mean = d.mean_edge_weight()
+        held = set(a.live)
+        for refuse in (lambda nbytes: True, lambda nbytes: nbytes > 100_000):  # nothing at all / only small arrays
+            a.refuse = refuse
+            for call in (d.get_labels, d.export_graph, d.mean_edge_weight, d.compact_storage):
+                if call == d.mean_edge_weight and not refuse(8192):
+                    continue  # its only array is a few KB
+                with pytest.raises(P.DynLPError) as ei:
+                    call()
+                assert ei.value.status == -2 and "allocation" in ei.value.message
+                assert set(a.live) == held, "a failed call hands back whatever it had already allocated"
+        a.refuse = lambda nbytes: False
+        soft2, hard2 = d.get_labels()
+        assert np.array_equal(soft, soft2) and np.array_equal(hard, hard2)
+        assert d.mean_edge_weight() == mean
+        d.compact_storage()
+        for x, y in zip(graph, d.export_graph()):
+            assert np.array_equal(x, y)
+        st, s = d.apply_batch(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+        assert st == 0
+    assert not a.live

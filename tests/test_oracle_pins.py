@@ -263,6 +263,7 @@ def test_neumann_solve_on_a_path_gives_the_gamblers_ruin_duration(oracle_native)
     x, sweeps, last = oracle_native.neumann_solve(rp, col, w, sc, ones, tol=1e-13)
     np.testing.assert_allclose(x, want, atol=1e-9)
     np.testing.assert_allclose(R.neumann_solve_cg(rp, col, w, sc, ones), want, atol=1e-9)
+    np.testing.assert_allclose(oracle_native.neumann_solve_cg(rp, col, w, sc, ones), want, atol=1e-9)
     assert x.max() == pytest.approx(L * L / 4)
 
 
@@ -275,7 +276,8 @@ def test_neumann_solve_three_ways_on_random_weighted_graphs(oracle_native):
     dense = R.neumann_solve_dense(p.row_ptr, p.col, w, sc, b)
     it, sweeps, last = oracle_native.neumann_solve(p.row_ptr, p.col, w, sc, b, tol=1e-14)
     cg = R.neumann_solve_cg(p.row_ptr, p.col, w, sc, b)
-    assert np.max(np.abs(dense - it)) < 1e-9 and np.max(np.abs(dense - cg)) < 1e-9
+    cg_c = oracle_native.neumann_solve_cg(p.row_ptr, p.col, w, sc, b)
+    assert np.max(np.abs(dense - it)) < 1e-9 and np.max(np.abs(dense - cg)) < 1e-9 and np.max(np.abs(dense - cg_c)) < 1e-9
     reach = R.seed_reachable(p.row_ptr, p.col, sc)
     upd = (sc < 0) & (np.diff(p.row_ptr) > 0) & reach
     assert np.all(dense[~upd] == 0) and dense[upd].min() > 0 and (~reach).sum() > 0
@@ -327,6 +329,8 @@ def test_harmonic_solve_by_conjugate_gradients_is_the_fixed_point_of_eq1(oracle_
     sc[p.seed_vertex] = p.seed_class
     w = p.w.astype(np.float64)
     cg = R.harmonic_solve_cg(p.row_ptr, p.col, w, sc, p.C)
+    cg_c = oracle_native.harmonic_solve_cg(p.row_ptr, p.col, w, sc, p.C)
+    assert np.max(np.abs(cg - cg_c)) < 1e-10
     reach = R.seed_reachable(p.row_ptr, p.col, sc)
     it, _, _ = oracle_native.itlp_solve(p.row_ptr, p.col, w, sc, p.C, tol=1e-14, max_iter=1_000_000)
     assert np.max(np.abs(cg - it)[reach]) < 1e-10
@@ -338,3 +342,4 @@ def test_harmonic_solve_by_conjugate_gradients_is_the_fixed_point_of_eq1(oracle_
     scq[q.seed_vertex] = q.seed_class
     dense = R.harmonic_closed_form(q.row_ptr, q.col, q.w.astype(np.float64), scq, q.C)
     np.testing.assert_allclose(R.harmonic_solve_cg(q.row_ptr, q.col, q.w.astype(np.float64), scq, q.C), dense, atol=1e-11)
+    np.testing.assert_allclose(oracle_native.harmonic_solve_cg(q.row_ptr, q.col, q.w.astype(np.float64), scq, q.C), dense, atol=1e-11)
