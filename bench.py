@@ -32,6 +32,16 @@ def algorithmic_bytes(rows: int, edges: int, C: int) -> int:
     return 8 * edges + 4 * C * (edges + 2 * rows) + 20 * rows
 
 
+def compulsory_bytes(rows: int, edges: int, C: int, launches: int, vertices: int) -> int:
+    """The same rounds if every needed label row moved once per round instead of once per gather: per launch
+    8 * entries + 4C * (distinct neighbours + 2 * rows) + 20 * rows.  The library counts rows and entries per
+    round, not distinct neighbours; they are taken as min(entries, vertices) per launch, which is exact for the
+    rounds over (nearly) all rows that dominate the timed region and an upper bound otherwise."""
+    per_launch_entries = edges / max(1, launches)
+    distinct = min(per_launch_entries, float(vertices)) * launches
+    return int(8 * edges + 4 * C * (distinct + 2 * rows) + 20 * rows)
+
+
 def build_workload(name: str, batch_frac: float, num_batches: int, batch_kind: str = "default", scale: float = 1.0):
     import workloads as W
 
@@ -152,6 +162,33 @@ def cpu_baseline(base, batches_applied, batch, F_before, tol, gpu_edges_traverse
                                                  if F_after is not None else None)))
 
 
+def residual_after(base, applied, F_last, tol, rounds_total):
+    """One float64 oracle sweep over the labels the GPU held after the last timed batch, on the updated graph as
+    the harness (not the library) builds it from the base graph and every applied batch.  Returns a dict."""
+    import workloads as W
+    from oracle import native as ON
+
+    t0 = time.perf_counter()
+    k = sum(b.num_new_vertices for b in applied)
+    allb = W.Batch(num_new_vertices=k, eu=np.concatenate([b.eu for b in applied]),
+                   ev=np.concatenate([b.ev for b in applied]), ew=np.concatenate([b.ew for b in applied]),
+                   seed_vertex=np.concatenate([b.seed_vertex for b in applied]),
+                   seed_class=np.concatenate([b.seed_class for b in applied]))
+    rp, col, w = W.csr_with_batch(base["n"], base["row_ptr"], base["col"], base["w"], allb)
+    sc = np.full(base["n"] + k, -1, dtype=np.int32)
+    sc[base["seed_vertex"]] = base["seed_class"]
+    sc[allb.seed_vertex] = allb.seed_class
+    t_build = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    _, res = ON.itlp_sweep(rp, col, w.astype(np.float64), F_last.astype(np.float64), sc)
+    t_sweep = time.perf_counter() - t0
+    return dict(state=f"GPU labels after the last timed batch ({len(applied)} batches applied), one float64 oracle sweep "
+                      f"over the harness-built updated graph ({int(rp[-1])} entries)",
+                max_change=res, seconds_graph_build=round(t_build, 1), seconds_sweep=round(t_sweep, 1),
+                # what row-by-row stopping allows (Alg. 2 Step 3): each of the batches' rounds may add tol
+                implied_by_stop_rule=(rounds_total + len(applied)) * tol + 2e-6)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -182,6 +219,11 @@ def main():
                          "replaced at once (Alg. 2's parallel loop taken literally)")
     ap.add_argument("--host-inputs", action="store_true",
                     help="hand the library host arrays (PCIe-inclusive timing; not the headline number)")
+    ap.add_argument("--final-check", action="store_true",
+                    help="dynlp_set_final_check: every batch ends with a round over all rows that moves none by more than tol")
+    ap.add_argument("--threshold-steps", type=int, default=2,
+                    help="after the timed steps, this many more batches at the paper's threshold delta = 1e-4 (reported "
+                         "under detail.delta_1e-4, not part of the metric; 0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (one process, no collectives); use --gpus 1", file=sys.stderr)
@@ -198,7 +240,11 @@ def main():
         P.build()
     dev = torch.device("cuda:0")
     t_gen = time.perf_counter()
-    cfg, base, batches, label = build_workload(args.workload, args.batch_frac, args.warmup + args.steps, args.batch_kind, args.scale)
+    extra = 0 if args.workload == "cfg6" else max(0, args.threshold_steps)
+    cfg, base, batches, label = build_workload(args.workload, args.batch_frac, args.warmup + args.steps + extra, args.batch_kind,
+                                               args.scale)
+    extra_batches = batches[args.warmup + args.steps:]
+    batches = batches[:args.warmup + args.steps]
     tol = float(args.tol if args.tol is not None else cfg["tol"])
     t_gen = time.perf_counter() - t_gen
 
@@ -232,8 +278,8 @@ def main():
         return dev_batch[id(b)]
 
     d_batches = [to_dev(b) for b in batches]
-    tot_v = sum(b.num_new_vertices for b in (batches[:1] if fresh else batches))
-    tot_e = sum(b.num_edges for b in (batches[:1] if fresh else batches))
+    tot_v = sum(b.num_new_vertices for b in (batches[:1] if fresh else batches + extra_batches))
+    tot_e = sum(b.num_edges for b in (batches[:1] if fresh else batches + extra_batches))
     d_base = [dv(base["row_ptr"], torch.int64), dv(base["col"], torch.int32), dv(base["w"], torch.float32),
               dv(base["seed_vertex"], torch.int32), dv(base["seed_class"], torch.int32)]
 
@@ -244,6 +290,7 @@ def main():
                       binned_rounds=args.binned_rounds)
         if args.update_mode == "in-place":
             ctx.set_update_mode(P.UPDATE_IN_PLACE)
+        ctx.set_final_check(args.final_check)
         st_, s_ = ctx.static_solve(tol, cfg["max_iter"])
         t_ = None
         if args.init == "supernode":
@@ -255,6 +302,10 @@ def main():
     d, st, s0, tau = new_context()
     # what plain streaming kernels sustain on this machine: 1 GiB copy (read + write) and 1 GiB read-only pass
     copy_gbs, read_gbs = d.stream_bandwidth(1 << 30, 10)
+    # ... and what random whole-row gathers of this workload's stored row size sustain in a table of its vertex count
+    CP_ = next(c for c in (1, 2, 4, 8, 16, 32, 64) if c >= Cs)
+    gather_rows_per_s, gather_gbs = d.gather_bandwidth(max(1, base["n"]), max(16, 4 * CP_),
+                                                       min(400_000_000, max(1_000_000, int(base["col"].shape[0]))), 5)
     cold = dict(status=st, sweeps=s0.iterations, ms=s0.ms_total, ms_update_kernel=s0.ms_update_kernel,
                 algorithmic_gbs=algorithmic_bytes(s0.rows_updated, s0.edges_traversed, Cs) / 1e6 /
                 max(s0.ms_update_kernel, 1e-9))
@@ -269,6 +320,7 @@ def main():
     per_step = []
     round_profile = []
     buckets = {}
+    rounds_all = 0  # rounds of every batch applied, warm-up included
     for i, b in enumerate(d_batches):
         timed = i >= args.warmup
         if i == args.warmup and args.cpu_budget > 0 and not fresh:
@@ -286,6 +338,7 @@ def main():
         _, hard = d.get_labels(soft=False, hard=True)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
+        rounds_all += s.iterations
         if timed:
             per_step.append(dict(ms=dt * 1e3, status=st, edges=batches[i].num_edges, **s.as_dict()))
             if tau is not None:
@@ -307,6 +360,47 @@ def main():
                 round_profile = [dict(round=int(j), frontier=int(info[j].rows_short + info[j].rows_long),
                                       staged=int(info[j].staged),
                                       kernel_us=round(float(info[j].ms_update) * 1e3, 1)) for j in pick]
+    # labels after the last timed batch, for the oracle's residual check
+    F_last = None
+    if args.cpu_budget > 0 and not fresh and args.delete_frac == 0:
+        F_last = d.get_labels(soft=True, hard=False)[0]
+        F_last = F_last if args.host_inputs else F_last.cpu().numpy()
+    # the paper's own threshold (delta = 1e-4, its "near optimal accuracy" choice): a few more batches on the same
+    # context, where V_aff stays a small part of the graph and the flag-marking rounds dominate
+    delta_block = None
+    if extra_batches:
+        d.set_params(1e-4, cfg["max_iter"])
+        xs, xb = [], {}
+        for b in extra_batches:
+            db = to_dev(b)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            st, s = d.apply_batch(db["k"], db["eu"], db["ev"], db["ew"], db["sv"], db["sc"])
+            _, hard = d.get_labels(soft=False, hard=True)
+            torch.cuda.synchronize()
+            xs.append(dict(ms=(time.perf_counter() - t0) * 1e3, status=st, edges=b.num_edges, **s.as_dict()))
+            for r in d.round_log_full():
+                q = xb.setdefault((int(r.staged), int(r.group_lanes)), [0, 0, 0, 0.0])
+                q[0] += 1
+                q[1] += int(r.rows_short + r.rows_long)
+                q[2] += int(r.entries_short + r.entries_long)
+                q[3] += float(r.ms_update)
+        CPx = next(c for c in (1, 2, 4, 8, 16, 32, 64) if c >= Cs)
+        kx = {}
+        for (staged, glanes), (cnt, rws, ent, ms) in xb.items():
+            name = ("k_pb_scatter + k_pb_gather" if staged == 3 else f"k_row_update_pull<{CPx}, {glanes}>" if staged == 2 else
+                    f"k_row_update<{CPx}, {glanes}, {'true' if staged else 'false'}>")
+            kx[name] = dict(launches=cnt, rows=rws, entries=ent, device_ms=round(ms, 3), avg_launch_us=round(ms * 1e3 / max(1, cnt), 1),
+                            algorithmic_GBs=round(algorithmic_bytes(rws, ent, Cs) / 1e6 / max(ms, 1e-9), 1))
+        delta_block = dict(tol=1e-4, batches=len(xs), ms_per_batch=[round(x["ms"], 2) for x in xs],
+                           inserted_edges_per_s=sum(x["edges"] for x in xs) / max(1e-9, sum(x["ms"] for x in xs) / 1e3),
+                           rounds=[x["iterations"] for x in xs], frontier_initial=[x["frontier_initial"] for x in xs],
+                           frontier_peak=[x["frontier_peak"] for x in xs],
+                           ms_insert=[round(x["ms_insert"], 3) for x in xs], ms_seed=[round(x["ms_seed"], 3) for x in xs],
+                           ms_iterate=[round(x["ms_iterate"], 3) for x in xs],
+                           ms_update_kernel=[round(x["ms_update_kernel"], 3) for x in xs], row_update_kernels=kx,
+                           note="same context after the timed batches; labels were converged at the workload's tol before")
+        d.set_params(tol, cfg["max_iter"])
     total_s = sum(x["ms"] for x in per_step) / 1e3
     edges_inserted = sum(x["edges"] for x in per_step)
     rows = sum(x["rows_updated"] for x in per_step)
@@ -328,14 +422,19 @@ def main():
     achieved = alg_bytes / 1e6 / max(k_ms, 1e-9)  # GB/s
     all_ms = sum(v["device_ms"] for v in kstats.values())
     all_bytes = sum(v["algorithmic_bytes"] for v in kstats.values())
+    # HBM-side bytes per launch by the counters: profiles/ stores, per kernel, the ratio of counter bytes (rocprofv3
+    # --pmc, request-size counters) to algorithmic bytes over a whole profiling run of the same workload; applied
+    # here to this run's algorithmic bytes per launch, so that the two figures describe the same rows and entries.
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"row_update_{args.workload}_hbm_traffic.md")  # from rocprofv3 --pmc runs
+    traffic_ratio = None
+    tpath = os.path.join(ROOT, "profiles", f"row_update_{args.workload}_hbm_traffic.md")
     if os.path.exists(tpath):
         import re
-        hit = re.search(r"hbm_bytes_per_launch = (\d+) for kernel `([^`]+)`", open(tpath).read())
-        # the stored figure belongs to one kernel instantiation at full-size launches
-        if hit and hit.group(2).endswith(dom):
-            traffic = float(hit.group(1))
+        for hit in re.finditer(r"hbm_bytes_per_algorithmic_byte = ([0-9.]+) for kernel `([^`]+)`", open(tpath).read()):
+            if hit.group(2).endswith(dom):
+                traffic_ratio = float(hit.group(1))
+                traffic = traffic_ratio * alg_bytes / max(1, launches)
+    comp_bytes = compulsory_bytes(kstats[dom]["rows"], kstats[dom]["entries"], Cs, launches, d.num_vertices)
     out = {
         "metric": "dynlp_batch_update_inserted_edges_per_s",
         "value": edges_inserted / total_s,
@@ -359,8 +458,16 @@ def main():
                      # what the counters say the same launch moves on the HBM side, as a rate (context: `frac`
                      # above is the algorithmic one)
                      "stream_copy_GBs": copy_gbs, "stream_read_GBs": read_gbs, "frac_of_stream_read": achieved / read_gbs,
+                     # gathers per second: this kernel's CSR entries per second against random whole-row reads of the
+                     # same stored row size with no other traffic
+                     "gather_yardstick": {"row_bytes": max(16, 4 * CP_), "table_rows": base["n"],
+                                          "rows_per_s": gather_rows_per_s, "GBs": gather_gbs},
+                     "gathers_per_s": kstats[dom]["entries"] / max(k_ms * 1e-3, 1e-12),
+                     "frac_of_gather_yardstick": kstats[dom]["entries"] / max(k_ms * 1e-3, 1e-12) / max(gather_rows_per_s, 1.0),
+                     "traffic_per_algorithmic_byte": traffic_ratio,
                      "traffic_GBs": (traffic / (k_ms * 1e6 / max(1, launches))) if traffic else None,
-                     "traffic_frac": (traffic / (k_ms * 1e6 / max(1, launches)) / HBM_PEAK_GBS) if traffic else None},
+                     "compulsory_bytes_per_launch": comp_bytes / max(1, launches),
+                     "compulsory_GBs": comp_bytes / 1e6 / max(k_ms, 1e-9)},
         "detail": {"rounds_per_step": [x["iterations"] for x in per_step],
                    "frontier_initial": [x["frontier_initial"] for x in per_step],
                    "frontier_peak": [x["frontier_peak"] for x in per_step],
@@ -376,7 +483,9 @@ def main():
                    "round_profile_first_step": round_profile,
                    "cold_start": cold, "gen_s": round(t_gen, 1),
                    "init": {"mode": args.init, "tau": tau, "per_step": init_info},
-                   "update_mode": args.update_mode,
+                   "update_mode": args.update_mode, "final_check": bool(args.final_check),
+                   "final_checks_per_step": [x["final_checks"] for x in per_step],
+                   "delta_1e-4": delta_block,
                    "deleted_per_step": [int(len(x)) for x in dels[args.warmup:]]},
     }
     if args.cpu_budget > 0 and per_step and not fresh:
@@ -384,6 +493,9 @@ def main():
                                            per_step[0]["edges_traversed"], args.cpu_budget, F_cold=F_cold, F_after=F_after)
     else:
         out["cpu_baseline"] = None
+    if out["cpu_baseline"] is not None and F_last is not None:
+        out["cpu_baseline"]["oracle_residual_after_last_batch"] = residual_after(
+            base, batches, F_last, tol, rounds_all)
     d.destroy()
     print(json.dumps(out))
 

@@ -315,6 +315,17 @@ dynlp_status dynlp_compact_storage(dynlp_ctx* ctx);
 dynlp_status dynlp_stream_bandwidth(dynlp_ctx* ctx, int64_t bytes, int32_t repetitions, double* copy_gb_per_s,
                                     double* read_gb_per_s);
 
+/*
+ * Yardstick for the neighbour-row gathers of the row update (Alg. 2 Step 3 reads one label row per CSR entry):
+ * `repetitions` launches of a kernel that reads `gathers` whole rows of `row_bytes` bytes (16, 32, 64, 128 or 256:
+ * the stored row sizes of 4 ... 64 label columns) at pseudo-random places of a temporary table of `table_rows` rows,
+ * eight rows in flight per lane group, with no other memory traffic.  *gathers_per_s = rows read per second,
+ * *gb_per_s = that times row_bytes; both host memory, either may be NULL.  With table_rows = the number of vertices
+ * it is the ceiling of a sweep over a graph without locality.
+ */
+dynlp_status dynlp_gather_bandwidth(dynlp_ctx* ctx, int64_t table_rows, int32_t row_bytes, int64_t gathers,
+                                    int32_t repetitions, double* gathers_per_s, double* gb_per_s);
+
 /* One propagation round of the last dynlp_static_solve / dynlp_apply_batch. */
 typedef struct dynlp_round_info {
     int64_t rows_short;    /* |V_aff| of the round, split by how the row was updated: rows of at most 128 */

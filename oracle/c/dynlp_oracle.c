@@ -203,6 +203,13 @@ int64_t oracle_laplacian_cg(int64_t n, const int64_t* row_ptr, const int32_t* co
     int live[64];
     for (int64_t u = 0; u < n; ++u)
         for (int64_t j = row_ptr[u]; j < row_ptr[u + 1]; ++j) diag[u] += w[j];
+    /* a system whose right-hand side is zero has the solution zero (the matrix is positive definite): take it
+       at once, the relative stopping rule has nothing to measure against there */
+    col_dots(n, in_U, k, B, B, bb);
+    for (int64_t u = 0; u < n; ++u)
+        if (in_U[u])
+            for (int c = 0; c < k; ++c)
+                if (bb[c] == 0.0) X[u * k + c] = 0.0;
     /* r = B - A X on U; z = r / diag; p = z */
     for (int64_t u = 0; u < n; ++u)
         if (in_U[u])
@@ -220,7 +227,6 @@ int64_t oracle_laplacian_cg(int64_t n, const int64_t* row_ptr, const int32_t* co
             }
         }
     }
-    col_dots(n, in_U, k, B, B, bb);
     col_dots(n, in_U, k, r, z, rz);
     col_dots(n, in_U, k, r, r, rr);
     int64_t it = 0;

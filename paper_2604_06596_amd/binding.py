@@ -70,7 +70,7 @@ EXPORTS = ["dynlp_default_options", "dynlp_create", "dynlp_static_solve", "dynlp
            "dynlp_round_log", "dynlp_last_error", "dynlp_destroy", "dynlp_set_initialiser",
            "dynlp_mean_edge_weight", "dynlp_last_components", "dynlp_set_update_mode", "dynlp_apply_update", "dynlp_storage_info",
            "dynlp_compact_storage", "dynlp_stream_bandwidth", "dynlp_get_labels_static", "dynlp_static_scratch_bytes",
-           "dynlp_set_final_check"]
+           "dynlp_set_final_check", "dynlp_gather_bandwidth"]
 
 _lib = None
 
@@ -124,6 +124,8 @@ def load_library(path: str | None = None):
     L.dynlp_storage_info.restype = ct.c_int
     L.dynlp_stream_bandwidth.argtypes = [p, i64, i32, ct.POINTER(ct.c_double), ct.POINTER(ct.c_double)]
     L.dynlp_stream_bandwidth.restype = ct.c_int
+    L.dynlp_gather_bandwidth.argtypes = [p, i64, i32, i64, i32, ct.POINTER(ct.c_double), ct.POINTER(ct.c_double)]
+    L.dynlp_gather_bandwidth.restype = ct.c_int
     L.dynlp_compact_storage.argtypes = [p]
     L.dynlp_compact_storage.restype = ct.c_int
     L.dynlp_set_update_mode.argtypes = [p, i32]
@@ -244,6 +246,13 @@ class DynLP:
         cp, rd = ct.c_double(0.0), ct.c_double(0.0)
         self._check(self._L.dynlp_stream_bandwidth(self._h, int(nbytes), int(repetitions), ct.byref(cp), ct.byref(rd)))
         return float(cp.value), float(rd.value)
+
+    def gather_bandwidth(self, table_rows, row_bytes, gathers, repetitions=5):
+        """dynlp_gather_bandwidth: (rows gathered per second, GB/s) for random whole-row reads of row_bytes bytes."""
+        per_s, gbs = ct.c_double(0.0), ct.c_double(0.0)
+        self._check(self._L.dynlp_gather_bandwidth(self._h, int(table_rows), int(row_bytes), int(gathers), int(repetitions),
+                                                   ct.byref(per_s), ct.byref(gbs)))
+        return float(per_s.value), float(gbs.value)
 
     def compact_storage(self):
         """dynlp_compact_storage."""

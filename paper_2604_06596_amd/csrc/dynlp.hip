@@ -1341,6 +1341,56 @@ dynlp_status dynlp_stream_bandwidth(dynlp_ctx* c, int64_t bytes, int32_t repetit
     }
 }
 
+dynlp_status dynlp_gather_bandwidth(dynlp_ctx* c, int64_t table_rows, int32_t row_bytes, int64_t gathers,
+                                    int32_t repetitions, double* gathers_per_s, double* gb_per_s) {
+    if (!c) return DYNLP_ERR_INVALID_ARG;
+    if (table_rows < 1 || table_rows > 0x7fffffffLL || gathers < 1 || repetitions < 1 ||
+        !(row_bytes == 16 || row_bytes == 32 || row_bytes == 64 || row_bytes == 128 || row_bytes == 256)) {
+        c->err = "table_rows in [1, 2^31), row_bytes one of 16, 32, 64, 128, 256, gathers >= 1, repetitions >= 1";
+        return DYNLP_ERR_INVALID_ARG;
+    }
+    hipEvent_t ev[2] = {nullptr, nullptr};
+    try {
+        HIPCHK(c, hipSetDevice(c->device));
+        const int lpn = row_bytes / 16;
+        const unsigned int blocks = (unsigned int)std::min<int64_t>(grid_for(ceil_div(gathers, 8) * lpn), (int64_t)c->num_cu * 32);
+        Temp<float4> table(c, table_rows * lpn);
+        Temp<float> sink(c, (int64_t)blocks * kBlock);
+        HIPCHK(c, hipMemsetAsync(table.ptr, 0, (size_t)table_rows * row_bytes, c->stream));
+        for (hipEvent_t& e : ev) HIPCHK(c, hipEventCreate(&e));
+        auto launch = [&]() {
+            switch (lpn) {
+                case 1: hipLaunchKernelGGL(k_gather_probe<1>, dim3(blocks), dim3(kBlock), 0, c->stream, table.ptr, (unsigned int)table_rows, (unsigned long long)gathers, sink.ptr); break;
+                case 2: hipLaunchKernelGGL(k_gather_probe<2>, dim3(blocks), dim3(kBlock), 0, c->stream, table.ptr, (unsigned int)table_rows, (unsigned long long)gathers, sink.ptr); break;
+                case 4: hipLaunchKernelGGL(k_gather_probe<4>, dim3(blocks), dim3(kBlock), 0, c->stream, table.ptr, (unsigned int)table_rows, (unsigned long long)gathers, sink.ptr); break;
+                case 8: hipLaunchKernelGGL(k_gather_probe<8>, dim3(blocks), dim3(kBlock), 0, c->stream, table.ptr, (unsigned int)table_rows, (unsigned long long)gathers, sink.ptr); break;
+                default: hipLaunchKernelGGL(k_gather_probe<16>, dim3(blocks), dim3(kBlock), 0, c->stream, table.ptr, (unsigned int)table_rows, (unsigned long long)gathers, sink.ptr); break;
+            }
+        };
+        launch();  // warm-up
+        HIPCHK(c, hipEventRecord(ev[0], c->stream));
+        for (int r = 0; r < repetitions; ++r) launch();
+        HIPCHK(c, hipEventRecord(ev[1], c->stream));
+        HIPCHK(c, hipGetLastError());
+        HIPCHK(c, hipEventSynchronize(ev[1]));
+        float ms = 0.f;
+        HIPCHK(c, hipEventElapsedTime(&ms, ev[0], ev[1]));
+        const double per_s = (double)gathers * repetitions / ((double)ms * 1e-3);
+        if (gathers_per_s) *gathers_per_s = per_s;
+        if (gb_per_s) *gb_per_s = per_s * row_bytes / 1e9;
+        for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+        return DYNLP_OK;
+    } catch (const SoftOom&) {
+        for (hipEvent_t e : ev)
+            if (e) (void)hipEventDestroy(e);
+        return DYNLP_ERR_OOM;
+    } catch (const Fail& f) {
+        for (hipEvent_t e : ev)
+            if (e) (void)hipEventDestroy(e);
+        return f.st;
+    }
+}
+
 dynlp_status dynlp_storage_info(const dynlp_ctx* c, int64_t* pool_used, int64_t* pool_capacity) {
     if (!c) return DYNLP_ERR_INVALID_ARG;
     if (pool_used) *pool_used = c->pool_tail;

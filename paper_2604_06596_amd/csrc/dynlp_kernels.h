@@ -689,6 +689,34 @@ __global__ void __launch_bounds__(kBlock) k_stream_read(int64_t n16, const float
     sink[(int64_t)blockIdx.x * kBlock + threadIdx.x] = acc;
 }
 
+// Yardstick for the gathers of the row update: every group of LPN adjacent lanes reads whole rows of 16 * LPN
+// bytes at pseudo-random places of a table (the row number is a multiplicative hash of a running index, so the
+// kernel reads no index array: its only memory traffic is the gathers), eight independent rows in flight per
+// group, the values summed so that the loads cannot be dropped.  What it sustains is the ceiling of "one
+// neighbour row per CSR entry" for rows of that size in a table of that footprint.
+template <int LPN>
+__global__ void __launch_bounds__(kBlock) k_gather_probe(const float4* __restrict__ table, unsigned int rows,
+                                                        unsigned long long gathers, float* __restrict__ sink) {
+    constexpr int UN = 8;
+    const unsigned long long groups = (unsigned long long)gridDim.x * (kBlock / LPN);
+    const unsigned long long g = (unsigned long long)blockIdx.x * (kBlock / LPN) + threadIdx.x / LPN;
+    const unsigned int part = threadIdx.x % LPN;
+    float acc = 0.f;
+    for (unsigned long long i = g; i < gathers; i += groups * UN) {
+        float4 v[UN];
+#pragma unroll
+        for (int t = 0; t < UN; ++t) {
+            const unsigned long long idx = i + (unsigned long long)t * groups;
+            const unsigned int h = (unsigned int)((idx * 0x9E3779B97F4A7C15ull) >> 32);
+            const unsigned int r = (unsigned int)(((unsigned long long)h * rows) >> 32);
+            v[t] = idx < gathers ? table[(unsigned long long)r * LPN + part] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int t = 0; t < UN; ++t) acc += (v[t].x + v[t].y) + (v[t].z + v[t].w);
+    }
+    sink[(unsigned long long)blockIdx.x * kBlock + threadIdx.x] = acc;
+}
+
 // =================================================================================================
 // Export (inspection / tests)
 // =================================================================================================

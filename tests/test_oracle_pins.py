@@ -337,6 +337,17 @@ def test_harmonic_solve_by_conjugate_gradients_is_the_fixed_point_of_eq1(oracle_
     _, moved = oracle_native.itlp_sweep(p.row_ptr, p.col, w, np.where(reach[:, None], cg, it), sc)
     assert moved < 1e-12
     assert np.array_equal(cg[~reach], R.initial_labels(sc, p.C)[~reach])  # left at the start values
+    # a class no vertex is labelled with: its column is identically zero (and the library solve must cope with the
+    # zero right-hand side)
+    z = W.small_random(300, 6, 4.0, 12, 51)
+    keep = z.seed_class != 4
+    scz = np.full(z.n, -1, dtype=np.int32)
+    scz[z.seed_vertex[keep]] = z.seed_class[keep]
+    Fz = oracle_native.harmonic_solve_cg(z.row_ptr, z.col, z.w.astype(np.float64), scz, 6)
+    Fz_it, _, _ = oracle_native.itlp_solve(z.row_ptr, z.col, z.w.astype(np.float64), scz, 6, tol=1e-14, max_iter=1_000_000)
+    rz = R.seed_reachable(z.row_ptr, z.col, scz)
+    upd = rz & (scz < 0) & (np.diff(z.row_ptr) > 0)
+    assert np.all(Fz[upd, 4] == 0.0) and np.max(np.abs(Fz - Fz_it)[rz]) < 1e-10
     q = W.small_random(120, 3, 3.0, 8, 49)
     scq = np.full(q.n, -1, dtype=np.int32)
     scq[q.seed_vertex] = q.seed_class
