@@ -69,7 +69,9 @@ typedef struct dynlp_stats {
     float ms_iterate;         /* the propagation loop */
     float ms_total;           /* whole call, host wall clock */
     int32_t final_checks;     /* rounds over all updatable rows that dynlp_set_final_check added (0 when it is off) */
-    int32_t reserved;
+    int32_t ingest_chunks;    /* chunks a host-resident edge list was sent in while earlier chunks were being validated
+                                 and counted (dynlp_options.ingest_chunk_edges); 0: one plain copy, or device pointers;
+                                 negative: the caller's arrays were pageable and went through the pinned staging */
 } dynlp_stats;
 
 typedef struct dynlp_options {
@@ -96,6 +98,12 @@ typedef struct dynlp_options {
                                 passes (scatter labels into bins of receivers, gather per bin) instead of row
                                 updates with random gathers.  0: the library decides (graphs of 2M updatable
                                 vertices or more); -1: never; 8..15: always, with 2^k receivers per bin */
+    int64_t ingest_chunk_edges; /* host pointers only: an insertion batch (no deletions) with more edges than this is
+                                sent to the device chunk by chunk on a second stream while the chunks that have
+                                arrived are validated and counted (the paper's overlap of batch transfer and Step 1
+                                kernels, "Overlapping subgraph transfer and kernel execution").  Arrays in pinned host
+                                memory are sent as they are; pageable arrays pass through two pinned staging buffers
+                                of 12 bytes per chunk edge.  0 selects the default, 4,194,304 edges */
 } dynlp_options;
 
 /* Fill *opt with the defaults (device 0, default stream, host pointers). */

@@ -18,7 +18,7 @@ def build(verbose: bool = False) -> str:
     """hipcc -> paper_2604_06596_amd/libdynlp.so.  Always recompiles."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [
-        hipcc, "-O3", "--offload-arch=gfx950", "-std=c++17", "-shared", "-fPIC",
+        hipcc, "-O3", "--offload-arch=gfx950", "-std=c++17", "-shared", "-fPIC", "-pthread",
         # packed-FP32 instruction selection is switched off for all device code
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-I", os.path.join(_ROOT, "include"), "-I", os.path.join(_HERE, "csrc"),

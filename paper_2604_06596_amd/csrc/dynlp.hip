@@ -10,6 +10,7 @@
 #include <mutex>
 #include <new>
 #include <string>
+#include <thread>
 #include <unordered_map>
 #include <unordered_set>
 #include <vector>
@@ -127,6 +128,14 @@ struct dynlp_ctx {
     int32_t *b_eu = nullptr, *b_ev = nullptr, *b_sv = nullptr, *b_sc = nullptr;
     float* b_ew = nullptr;
     int64_t b_edge_cap = 0, b_seed_cap = 0;
+
+    // pipelined ingest of host-resident batches (see ingest_edges)
+    int64_t ingest_chunk = 0;            // edges per chunk
+    hipStream_t copy_stream = nullptr;   // default priority, used only for the batch's host-to-device copies
+    hipEvent_t ingest_ev[2] = {nullptr, nullptr};
+    void* bounce[2] = {nullptr, nullptr};  // pinned staging for callers whose arrays are pageable, 12 bytes per chunk edge
+    int64_t bounce_edges = 0;
+    int ingest_chunks_last = 0, ingest_pinned_last = 0;  // what the last batch's ingest did (inspection)
 
     RoundCtr* ring = nullptr;  // kRing round slots + the start slot
     BatchCtr* bc = nullptr;
@@ -409,6 +418,96 @@ void ensure_batch_scratch(dynlp_ctx* c, int64_t m, int64_t s) {
             c->b_seed_cap = cap;
         }
     }
+}
+
+// ---- pipelined ingest of a host-resident batch --------------------------------------------------------------
+// The paper overlaps the transfer of a batch with the Step-1 kernels that only need what has already arrived.
+// Here the graph lives on the device and only the batch's edge list crosses PCIe; for a batch of more than one
+// chunk the list is sent chunk by chunk on a second stream while the main stream validates and counts the
+// chunks that have landed (k_validate_edges, k_count_halfedges: the part of Step 1 that needs nothing but the
+// chunk).  Caller arrays in pinned memory are sent as they are; pageable arrays go through two pinned staging
+// buffers filled by a few host threads, so that filling chunk i+1 overlaps the transfer of chunk i.
+constexpr int kIngestThreads = 6;
+
+bool host_pointer_is_pinned(const void* p) {
+    hipPointerAttribute_t a;
+    if (hipPointerGetAttributes(&a, p) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return a.type == hipMemoryTypeHost;
+}
+
+void parallel_copy(void* dst, const void* src, size_t bytes) {
+    if (bytes < ((size_t)4 << 20)) {
+        std::memcpy(dst, src, bytes);
+        return;
+    }
+    std::thread workers[kIngestThreads];
+    const size_t slice = round_up((int64_t)ceil_div((int64_t)bytes, kIngestThreads), 4096);
+    int started = 0;
+    for (int t = 0; t < kIngestThreads; ++t) {
+        const size_t lo = std::min(bytes, slice * t), hi = std::min(bytes, slice * (t + 1));
+        if (hi <= lo) break;
+        workers[t] = std::thread([=] { std::memcpy(static_cast<char*>(dst) + lo, static_cast<const char*>(src) + lo, hi - lo); });
+        ++started;
+    }
+    for (int t = 0; t < started; ++t) workers[t].join();
+}
+
+// Copies eu / ev / ew (host) into c->b_eu / b_ev / b_ew and, per chunk, launches validation and counting on the
+// main stream.  bc must have been reset on the main stream before the call.
+void ingest_edges(dynlp_ctx* c, int64_t m, int64_t n_total, const int32_t* eu, const int32_t* ev, const float* ew) {
+    const int64_t chunk = c->ingest_chunk;
+    if (!c->copy_stream) {
+        HIPCHK(c, hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
+        for (hipEvent_t& e : c->ingest_ev) HIPCHK(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    }
+    const bool pinned = host_pointer_is_pinned(eu) && host_pointer_is_pinned(ev) && host_pointer_is_pinned(ew);
+    if (!pinned && c->bounce_edges < chunk) {
+        for (void*& b : c->bounce) {
+            if (b) (void)hipHostFree(b);
+            b = nullptr;
+        }
+        c->bounce_edges = 0;
+        for (void*& b : c->bounce) HIPCHK(c, hipHostMalloc(&b, (size_t)chunk * 12, hipHostMallocDefault));
+        c->bounce_edges = chunk;
+    }
+    // the copies must not start before earlier work on the main stream that still reads the device buffers is done
+    // (there is none: the previous call ended with a synchronisation), nor before bc has been reset
+    HIPCHK(c, hipEventRecord(c->ingest_ev[0], c->stream));
+    HIPCHK(c, hipStreamWaitEvent(c->copy_stream, c->ingest_ev[0], 0));
+    int chunks = 0;
+    bool slot_used[2] = {false, false};
+    for (int64_t off = 0; off < m; off += chunk, ++chunks) {
+        const int64_t mc = std::min(chunk, m - off);
+        const int slot = chunks & 1;
+        const int32_t *s_eu = eu + off, *s_ev = ev + off;
+        const float* s_ew = ew + off;
+        if (!pinned) {
+            if (slot_used[slot]) HIPCHK(c, hipEventSynchronize(c->ingest_ev[slot]));  // its last transfer has left the buffer
+            char* b = static_cast<char*>(c->bounce[slot]);
+            parallel_copy(b, s_eu, (size_t)mc * 4);
+            parallel_copy(b + (size_t)chunk * 4, s_ev, (size_t)mc * 4);
+            parallel_copy(b + (size_t)chunk * 8, s_ew, (size_t)mc * 4);
+            s_eu = reinterpret_cast<const int32_t*>(b);
+            s_ev = reinterpret_cast<const int32_t*>(b + (size_t)chunk * 4);
+            s_ew = reinterpret_cast<const float*>(b + (size_t)chunk * 8);
+        }
+        HIPCHK(c, hipMemcpyAsync(c->b_eu + off, s_eu, (size_t)mc * 4, hipMemcpyHostToDevice, c->copy_stream));
+        HIPCHK(c, hipMemcpyAsync(c->b_ev + off, s_ev, (size_t)mc * 4, hipMemcpyHostToDevice, c->copy_stream));
+        HIPCHK(c, hipMemcpyAsync(c->b_ew + off, s_ew, (size_t)mc * 4, hipMemcpyHostToDevice, c->copy_stream));
+        HIPCHK(c, hipEventRecord(c->ingest_ev[slot], c->copy_stream));
+        slot_used[slot] = true;
+        HIPCHK(c, hipStreamWaitEvent(c->stream, c->ingest_ev[slot], 0));
+        hipLaunchKernelGGL(k_validate_edges, dim3(grid_for(mc)), dim3(kBlock), 0, c->stream, mc, n_total, c->b_eu + off,
+                           c->b_ev + off, c->b_ew + off, c->bc, off);
+        hipLaunchKernelGGL(k_count_halfedges, dim3(grid_for(ceil_div(2 * mc, kAppendItems))), dim3(kBlock), 0, c->stream, mc,
+                           n_total, c->b_eu + off, c->b_ev + off, c->add_cnt, c->touched, c->bc);
+        HIPCHK(c, hipGetLastError());
+    }
+    c->ingest_chunks_last = chunks;
+    c->ingest_pinned_last = pinned ? 1 : 0;
 }
 
 // ---- frontier launches ---------------------------------------------------------------------------
@@ -950,6 +1049,11 @@ void destroy_ctx(dynlp_ctx* c) {
         if (e) (void)hipEventDestroy(e);
     dev_free(c, c->ring);
     dev_free(c, c->bc);
+    for (void* b : c->bounce)
+        if (b) (void)hipHostFree(b);
+    for (hipEvent_t e : c->ingest_ev)
+        if (e) (void)hipEventDestroy(e);
+    if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
     if (c->h_slot) (void)hipHostFree(c->h_slot);
     if (c->h_bc) (void)hipHostFree(c->h_bc);
     for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
@@ -1121,6 +1225,7 @@ dynlp_status dynlp_create(dynlp_ctx** out, int64_t n, const int64_t* row_ptr, co
     if (!(o.slack_factor > 1.0f)) o.slack_factor = 1.25f;
     if (o.slack_factor > 8.0f) return bad("slack_factor must be <= 8");
     if (o.reserve_vertices < 0 || o.reserve_edges < 0) return bad("reserve counts must be >= 0");
+    if (o.ingest_chunk_edges < 0 || o.ingest_chunk_edges > ((int64_t)1 << 28)) return bad("ingest_chunk_edges must be in [0, 2^28]");
     if ((o.alloc == nullptr) != (o.dealloc == nullptr)) return bad("alloc and dealloc must be given together");
     if (o.binary_scalar != 0 && num_classes != 2) return bad("binary_scalar needs num_classes == 2");
     const int Cs = o.binary_scalar != 0 ? 1 : num_classes;  // stored columns
@@ -1165,6 +1270,7 @@ dynlp_status dynlp_create(dynlp_ctx** out, int64_t n, const int64_t* row_ptr, co
         c->time_kernels = o.time_kernels != 0;
         c->group_lanes = o.group_lanes;
         c->binned = o.binned_rounds;
+        c->ingest_chunk = o.ingest_chunk_edges > 0 ? o.ingest_chunk_edges : ((int64_t)4 << 20);
         c->alloc_fn = o.alloc;
         c->dealloc_fn = o.dealloc;
         c->alloc_user = o.alloc_user;
@@ -1668,9 +1774,12 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
     const int64_t n0 = c->n, n1 = c->n + k;
     if (n1 > 0x7ffffffeLL) return bad("vertex count would exceed 2^31-2");
     if (m > 0x3fffffffLL) return bad("too many edges in one batch");
+    // a host-resident edge list of more than one chunk is sent in a pipeline (ingest_edges) and checked on the
+    // device chunk by chunk as it arrives; a smaller one is checked here, before any device work
+    const bool pipelined = !c->dev_ptrs && nd == 0 && m > c->ingest_chunk;
     if (!c->dev_ptrs) {
         std::string e;
-        if (!host_check_edges(e, m, n1, eu, ev, ew)) return bad(e);
+        if (!pipelined && !host_check_edges(e, m, n1, eu, ev, ew)) return bad(e);
         if (!host_check_seeds(e, s, n1, c->C, sv, sc)) return bad(e);
         for (int64_t i = 0; i < nd; ++i)
             if (del[i] < 0 || del[i] >= n0) return bad(format_validation(kErrDeleted, i));
@@ -1686,8 +1795,9 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
         ensure_batch_scratch(c, m, s);
         const int32_t *d_eu = eu, *d_ev = ev, *d_sv = sv, *d_sc = sc;
         const float* d_ew = ew;
+        c->ingest_chunks_last = 0;
         if (!c->dev_ptrs) {
-            if (m > 0) {
+            if (m > 0 && !pipelined) {
                 HIPCHK(c, hipMemcpyAsync(c->b_eu, eu, (size_t)m * 4, hipMemcpyHostToDevice, c->stream));
                 HIPCHK(c, hipMemcpyAsync(c->b_ev, ev, (size_t)m * 4, hipMemcpyHostToDevice, c->stream));
                 HIPCHK(c, hipMemcpyAsync(c->b_ew, ew, (size_t)m * 4, hipMemcpyHostToDevice, c->stream));
@@ -1752,7 +1862,7 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
         std::memset(c->h_bc, 0, sizeof(BatchCtr));
         c->h_bc->pool_tail = (unsigned long long)c->pool_tail;
         HIPCHK(c, hipMemcpyAsync(c->bc, c->h_bc, sizeof(BatchCtr), hipMemcpyHostToDevice, c->stream));
-        if (m > 0)
+        if (m > 0 && !pipelined)
             hipLaunchKernelGGL(k_validate_edges, dim3(grid_for(m)), dim3(kBlock), 0, c->stream, m, n1, d_eu, d_ev, d_ew, c->bc);
         if (s > 0) {
             hipLaunchKernelGGL(k_validate_seeds, dim3(grid_for(s)), dim3(kBlock), 0, c->stream, s, n1, n0, c->C, d_sv,
@@ -1763,7 +1873,9 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
             hipLaunchKernelGGL(k_init_meta, dim3(grid_for(k)), dim3(kBlock), 0, c->stream, n0, n1, c->meta, c->deg);
             hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(k)), dim3(kBlock), 0, c->stream, n0, n1, c->seed_class, -1);
         }
-        if (m > 0)
+        if (pipelined)
+            ingest_edges(c, m, n1, eu, ev, ew);
+        else if (m > 0)
             hipLaunchKernelGGL(k_count_halfedges, dim3(grid_for(ceil_div(2 * m, kAppendItems))), dim3(kBlock), 0, c->stream, m, n1, d_eu, d_ev,
                                c->add_cnt, c->touched, c->bc);
         HIPCHK(c, hipGetLastError());
@@ -1989,6 +2101,7 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
             stats->rows_relocated = relocated;
             stats->update_launches = it;
             stats->final_checks = final_checks;
+            stats->ingest_chunks = c->ingest_pinned_last ? c->ingest_chunks_last : -c->ingest_chunks_last;
             stats->ms_update_kernel = kernel_ms_total;
             (void)hipEventElapsedTime(&stats->ms_insert, c->phase_ev[0], c->phase_ev[1]);
             (void)hipEventElapsedTime(&stats->ms_seed, c->phase_ev[1], c->phase_ev[2]);

@@ -259,16 +259,18 @@ __global__ void __launch_bounds__(kBlock) k_scalar_soft(int64_t n, const float* 
 // =================================================================================================
 // Edge insertion (Alg. 2 Step 1 for insertions) into the slack CSR
 // =================================================================================================
+// index_base: position of eu[0] in the caller's batch (the arrays may be one chunk of it), for the error report.
 __global__ void __launch_bounds__(kBlock) k_validate_edges(int64_t m, int64_t n_total, const int32_t* __restrict__ eu,
                                                           const int32_t* __restrict__ ev,
-                                                          const float* __restrict__ ew, BatchCtr* bc) {
+                                                          const float* __restrict__ ew, BatchCtr* bc,
+                                                          int64_t index_base = 0) {
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= m) return;
     const int32_t a = eu[i], b = ev[i];
     const float ww = ew[i];
-    if (a < 0 || a >= n_total || b < 0 || b >= n_total) { report_error(bc, kErrEndpoint, i); return; }
-    if (a == b) { report_error(bc, kErrSelfLoop, i); return; }
-    if (!(ww > 0.f) || !isfinite(ww)) report_error(bc, kErrWeight, i);
+    if (a < 0 || a >= n_total || b < 0 || b >= n_total) { report_error(bc, kErrEndpoint, index_base + i); return; }
+    if (a == b) { report_error(bc, kErrSelfLoop, index_base + i); return; }
+    if (!(ww > 0.f) || !isfinite(ww)) report_error(bc, kErrWeight, index_base + i);
 }
 
 // Half-edge i < m has source eu[i]; half-edge m + i has source ev[i].  Count the entries each row
