@@ -222,8 +222,13 @@ def main():
     ap.add_argument("--pinned-inputs", action="store_true",
                     help="with --host-inputs: keep the host arrays in pinned memory (the pipelined ingest then sends them "
                          "without staging)")
+    ap.add_argument("--persistent-rounds", type=int, default=0,
+                    help="1: many rounds per launch (a tuning knob for small graphs); 0: one launch per round")
     ap.add_argument("--final-check", action="store_true",
                     help="dynlp_set_final_check: every batch ends with a round over all rows that moves none by more than tol")
+    ap.add_argument("--other-mode-steps", type=int, default=1,
+                    help="after the timed steps, this many more batches in the OTHER update mode at the workload's tol "
+                         "(reported under detail.other_update_mode, not part of the metric; 0 = skip)")
     ap.add_argument("--threshold-steps", type=int, default=2,
                     help="after the timed steps, this many more batches at the paper's threshold delta = 1e-4 (reported "
                          "under detail.delta_1e-4, not part of the metric; 0 = skip)")
@@ -244,9 +249,11 @@ def main():
     dev = torch.device("cuda:0")
     t_gen = time.perf_counter()
     extra = 0 if args.workload == "cfg6" else max(0, args.threshold_steps)
-    cfg, base, batches, label = build_workload(args.workload, args.batch_frac, args.warmup + args.steps + extra, args.batch_kind,
-                                               args.scale)
-    extra_batches = batches[args.warmup + args.steps:]
+    extra_mode = 0 if args.workload == "cfg6" else max(0, args.other_mode_steps)
+    cfg, base, batches, label = build_workload(args.workload, args.batch_frac, args.warmup + args.steps + extra_mode + extra,
+                                               args.batch_kind, args.scale)
+    mode_batches = batches[args.warmup + args.steps:args.warmup + args.steps + extra_mode]
+    extra_batches = batches[args.warmup + args.steps + extra_mode:]
     batches = batches[:args.warmup + args.steps]
     tol = float(args.tol if args.tol is not None else cfg["tol"])
     t_gen = time.perf_counter() - t_gen
@@ -288,8 +295,8 @@ def main():
         return dev_batch[id(b)]
 
     d_batches = [to_dev(b) for b in batches]
-    tot_v = sum(b.num_new_vertices for b in (batches[:1] if fresh else batches + extra_batches))
-    tot_e = sum(b.num_edges for b in (batches[:1] if fresh else batches + extra_batches))
+    tot_v = sum(b.num_new_vertices for b in (batches[:1] if fresh else batches + mode_batches + extra_batches))
+    tot_e = sum(b.num_edges for b in (batches[:1] if fresh else batches + mode_batches + extra_batches))
     d_base = [dv(base["row_ptr"], torch.int64), dv(base["col"], torch.int32), dv(base["w"], torch.float32),
               dv(base["seed_vertex"], torch.int32), dv(base["seed_class"], torch.int32)]
 
@@ -297,7 +304,7 @@ def main():
         ctx = P.DynLP(base["n"], d_base[0], d_base[1], d_base[2], base["C"], d_base[3], d_base[4],
                       device_ptrs=not args.host_inputs, reserve_vertices=tot_v + 1024, reserve_edges=2 * tot_e + 1024,
                       time_kernels=not args.no_kernel_timing, group_lanes=args.group_lanes, binary_scalar=scalar,
-                      binned_rounds=args.binned_rounds)
+                      binned_rounds=args.binned_rounds, persistent_rounds=args.persistent_rounds)
         if args.update_mode == "in-place":
             ctx.set_update_mode(P.UPDATE_IN_PLACE)
         ctx.set_final_check(args.final_check)
@@ -375,6 +382,27 @@ def main():
     if args.cpu_budget > 0 and not fresh and args.delete_frac == 0:
         F_last = d.get_labels(soft=True, hard=False)[0]
         F_last = F_last if args.host_inputs else F_last.cpu().numpy()
+    # the same workload in the other update mode (the timed mode is the in-place one unless asked otherwise; the
+    # synchronous one is the reproducible one): a batch or two on the same context
+    mode_block = None
+    if mode_batches:
+        other = "synchronous" if args.update_mode == "in-place" else "in-place"
+        d.set_update_mode(P.UPDATE_SYNCHRONOUS if other == "synchronous" else P.UPDATE_IN_PLACE)
+        ms_, rounds_, kms_ = [], [], []
+        for b in mode_batches:
+            db = to_dev(b)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            st, s = d.apply_batch(db["k"], db["eu"], db["ev"], db["ew"], db["sv"], db["sc"])
+            _, hard = d.get_labels(soft=False, hard=True)
+            torch.cuda.synchronize()
+            ms_.append(round((time.perf_counter() - t0) * 1e3, 2))
+            rounds_.append(s.iterations)
+            kms_.append(round(s.ms_update_kernel, 2))
+            rounds_all += s.iterations
+        mode_block = dict(update_mode=other, batches=len(ms_), ms_per_batch=ms_, rounds=rounds_, ms_update_kernel=kms_,
+                          inserted_edges_per_s=sum(b.num_edges for b in mode_batches) / max(1e-9, sum(ms_) / 1e3))
+        d.set_update_mode(P.UPDATE_IN_PLACE if args.update_mode == "in-place" else P.UPDATE_SYNCHRONOUS)
     # the paper's own threshold (delta = 1e-4, its "near optimal accuracy" choice): a few more batches on the same
     # context, where V_aff stays a small part of the graph and the flag-marking rounds dominate
     delta_block = None
@@ -497,6 +525,7 @@ def main():
                    "update_mode": args.update_mode, "final_check": bool(args.final_check),
                    "final_checks_per_step": [x["final_checks"] for x in per_step],
                    "ingest_chunks_per_step": [x["ingest_chunks"] for x in per_step],
+                   "other_update_mode": mode_block,
                    "delta_1e-4": delta_block,
                    "deleted_per_step": [int(len(x)) for x in dels[args.warmup:]]},
     }

@@ -98,6 +98,14 @@ typedef struct dynlp_options {
                                 passes (scatter labels into bins of receivers, gather per bin) instead of row
                                 updates with random gathers.  0: the library decides (graphs of 2M updatable
                                 vertices or more); -1: never; 8..15: always, with 2^k receivers per bin */
+    int32_t persistent_rounds; /* tuning knob, off by default: 1 = run the rounds of a batch up to 32 per launch, with a
+                                barrier across a grid of workgroups that are all resident at once between rounds (for
+                                graphs so small that a round is shorter than a launch and its drain; the batch's
+                                rounds then all evaluate V_aff per row themselves).  0 or -1: one launch per round.
+                                On MI355X it does not pay yet: see the note at persistent_rounds_pay in the source */
+    int32_t persistent_spin_limit; /* polls a workgroup waits at that barrier before it gives up (0 = default 2^20, about
+                                a quarter of a second).  A workgroup that gives up makes the launch end after the round
+                                in progress; the batch continues with one launch per round */
     int64_t ingest_chunk_edges; /* host pointers only: an insertion batch (no deletions) with more edges than this is
                                 sent to the device chunk by chunk on a second stream while the chunks that have
                                 arrived are validated and counted (the paper's overlap of batch transfer and Step 1
@@ -351,7 +359,8 @@ typedef struct dynlp_round_info {
                               round ran over all updatable vertices and decided per row, from the previous
                               round's bitmap, whether the row is in V_aff (no frontier list in between); 3: as 2,
                               as a binned round (scalar labels: scatter pass + gather pass, see
-                              dynlp_options.binned_rounds) */
+                              dynlp_options.binned_rounds); 4: as 2, one of several rounds run by one launch
+                              (dynlp_options.persistent_rounds; ms_update is that launch's time divided by its rounds) */
     int32_t group_lanes;   /* lanes per row the short-row kernel ran with */
 } dynlp_round_info;
 

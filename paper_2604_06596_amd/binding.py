@@ -62,7 +62,8 @@ class Options(ct.Structure):
                 ("slack_factor", ct.c_float), ("reserve_vertices", ct.c_int64), ("reserve_edges", ct.c_int64),
                 ("time_kernels", ct.c_int32), ("group_lanes", ct.c_int32), ("alloc", _ALLOC_FN),
                 ("dealloc", _DEALLOC_FN), ("alloc_user", ct.c_void_p), ("binary_scalar", ct.c_int32),
-                ("binned_rounds", ct.c_int32), ("ingest_chunk_edges", ct.c_int64)]
+                ("binned_rounds", ct.c_int32), ("persistent_rounds", ct.c_int32), ("persistent_spin_limit", ct.c_int32),
+                ("ingest_chunk_edges", ct.c_int64)]
 
 
 EXPORTS = ["dynlp_default_options", "dynlp_create", "dynlp_static_solve", "dynlp_set_params", "dynlp_apply_batch",
@@ -156,7 +157,7 @@ class DynLP:
     def __init__(self, n, row_ptr, col, w, num_classes, seed_vertex, seed_class, *, device=0, stream=None,
                  device_ptrs=False, slack_factor=1.25, reserve_vertices=0, reserve_edges=0, time_kernels=False,
                  group_lanes=0, binary_scalar=False, binned_rounds=0, allocator=None, library=None,
-                 ingest_chunk_edges=0):
+                 ingest_chunk_edges=0, persistent_rounds=0, persistent_spin_limit=0):
         """``allocator``: optional object with ``alloc(nbytes) -> device address (0 = no memory)`` and
         ``free(address)``; the library then takes all its device arrays from it (dynlp_options.alloc / dealloc)."""
         self._L = load_library(library)
@@ -177,6 +178,8 @@ class DynLP:
         opt.binary_scalar = 1 if binary_scalar else 0
         opt.binned_rounds = int(binned_rounds)
         opt.ingest_chunk_edges = int(ingest_chunk_edges)
+        opt.persistent_rounds = int(persistent_rounds)
+        opt.persistent_spin_limit = int(persistent_spin_limit)
         if allocator is not None:
             # the callbacks must outlive the context
             self._alloc_cb = _ALLOC_FN(lambda nbytes, user: int(allocator.alloc(int(nbytes))) or None)

@@ -145,8 +145,15 @@ struct dynlp_ctx {
 
     int update_mode = DYNLP_UPDATE_SYNCHRONOUS;
     bool final_check = false;  // dynlp_set_final_check
+    // several rounds per launch (k_rounds_persistent)
+    int persist = 0;                  // option: 1 = whenever a stretch allows it, 0 / -1 = never
+    unsigned int persist_spin = 1u << 20;  // polls a workgroup waits at the grid barrier before it gives up
+    unsigned int* persist_ctl = nullptr;   // device: the words of the grid barrier (kBarWords; [1] = "given up")
+    bool persist_failed = false;      // a launch was refused or a barrier was given up: ordinary launches from then on
+    int persist_launches_last = 0, persist_aborts_last = 0;  // of the last batch (inspection)
     // binned rounds for scalar labels (dynlp_binned.h)
     int binned = 0;                 // option: 0 = automatic, -1 = never, 8..15 = always, with this many bin bits
+    int pb_parts_opt = 0;           // in-place mode: vertex ranges per binned round (0 = default 8)
     bool pb_built = false;          // the arrays below describe the graph as it stands
     int pb_bits = 0, pb_bins = 0;
     // per stored entry, rows in vertex order
@@ -169,6 +176,12 @@ struct dynlp_ctx {
     unsigned int* pb_bin = nullptr;  // bin_count | bin_off (+1), kPbMaxBins + 1 each
     unsigned int* pb_table = nullptr;  // entries per (chunk, bin) during the build
     int64_t pb_table_cap = 0;
+    // in-place mode: the vertices are cut into pb_parts ranges of whole bins that are updated one after the other
+    // within a round (range i: bins [pb_part_bin[i], pb_part_bin[i+1]), its rows' entries lie in chunks
+    // [pb_part_chunk[i][0], pb_part_chunk[i][1]))
+    int pb_parts = 1;
+    int pb_part_bin[kPbMaxParts + 1] = {};
+    int pb_part_chunk[kPbMaxParts][2] = {};
     // label initialisation of inserted vertices (dynlp_components.h)
     int init_mode = DYNLP_INIT_UNIFORM;
     float tau = 0.f;
@@ -187,8 +200,10 @@ struct dynlp_ctx {
     float tol = 1e-4f;
     int32_t max_iter = 100000;
     std::vector<dynlp_round_info> log;  // one entry per round of the last solve / batch
-    std::vector<hipEvent_t> events;
+    std::vector<hipEvent_t> events;   // pairs: events[2k], events[2k+1] bracket the k-th timed launch
     size_t events_used = 0;
+    std::vector<int> ev_round, ev_count;  // rounds [ev_round[k], ev_round[k] + ev_count[k]) ran inside the k-th launch;
+                                          // ev_round[k] < 0: the launch found nothing to do (queued past the end)
     hipEvent_t phase_ev[4] = {nullptr, nullptr, nullptr, nullptr};
     std::string err;
     bool poisoned = false;
@@ -595,21 +610,44 @@ void launch_update_cp(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& 
     launch_update_inst<CP, 64, STAGED>(c, f, a);
 }
 
+// With kernel timing on, two events bracket every row-update launch; `round` / `count` say which rounds it runs.
+hipEvent_t open_timed_span(dynlp_ctx* c, int round, int count) {
+    if (!c->time_kernels) return nullptr;
+    while (c->events.size() < c->events_used + 2) {
+        hipEvent_t e;
+        HIPCHK(c, hipEventCreate(&e));
+        c->events.push_back(e);
+    }
+    const size_t k = c->events_used / 2;
+    if (c->ev_round.size() <= k) {
+        c->ev_round.resize(k + 1);
+        c->ev_count.resize(k + 1);
+    }
+    c->ev_round[k] = round;
+    c->ev_count[k] = count;
+    hipEvent_t e0 = c->events[c->events_used++];
+    hipEvent_t e1 = c->events[c->events_used++];
+    HIPCHK(c, hipEventRecord(e0, c->stream));
+    return e1;
+}
+
+void close_timed_span(dynlp_ctx* c, hipEvent_t e1) {
+    if (e1) HIPCHK(c, hipEventRecord(e1, c->stream));
+}
+
+// After a chain has been read back: launches of rounds >= first_unexecuted did nothing.
+void trim_timed_spans(dynlp_ctx* c, size_t first_pair, int first_unexecuted) {
+    for (size_t k = first_pair; k < c->events_used / 2; ++k) {
+        if (c->ev_round[k] >= first_unexecuted) c->ev_round[k] = -1;
+        else c->ev_count[k] = std::min(c->ev_count[k], first_unexecuted - c->ev_round[k]);
+    }
+}
+
 // Row update of one frontier: one launch (long rows and short rows share the grid).  With kernel
 // timing on, two events per round bracket it.
 template <bool STAGED>
-void launch_update(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& a) {
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (c->time_kernels) {
-        while (c->events.size() < c->events_used + 2) {
-            hipEvent_t e;
-            HIPCHK(c, hipEventCreate(&e));
-            c->events.push_back(e);
-        }
-        e0 = c->events[c->events_used++];
-        e1 = c->events[c->events_used++];
-        HIPCHK(c, hipEventRecord(e0, c->stream));
-    }
+void launch_update(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& a, int round) {
+    hipEvent_t e1 = open_timed_span(c, round, 1);
     switch (c->CP) {
         case 1: launch_update_cp<1, STAGED>(c, G, f, a); break;
         case 2: launch_update_cp<2, STAGED>(c, G, f, a); break;
@@ -620,7 +658,7 @@ void launch_update(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& a) 
         default: launch_update_cp<64, STAGED>(c, G, f, a); break;
     }
     HIPCHK(c, hipGetLastError());
-    if (c->time_kernels) HIPCHK(c, hipEventRecord(e1, c->stream));
+    close_timed_span(c, e1);
 }
 
 // A ping-pong round that evaluates V_aff membership itself (k_row_update_pull): `universe` lists every
@@ -671,18 +709,8 @@ void launch_update_pull_cp(dynlp_ctx* c, int G, const Frontier& universe, const 
     launch_update_pull_inst<CP, 64>(c, universe, a);
 }
 
-void launch_update_pull(dynlp_ctx* c, int G, const Frontier& universe, const PullRoundArgs& a) {
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (c->time_kernels) {
-        while (c->events.size() < c->events_used + 2) {
-            hipEvent_t e;
-            HIPCHK(c, hipEventCreate(&e));
-            c->events.push_back(e);
-        }
-        e0 = c->events[c->events_used++];
-        e1 = c->events[c->events_used++];
-        HIPCHK(c, hipEventRecord(e0, c->stream));
-    }
+void launch_update_pull(dynlp_ctx* c, int G, const Frontier& universe, const PullRoundArgs& a, int round) {
+    hipEvent_t e1 = open_timed_span(c, round, 1);
     switch (c->CP) {
         case 1: launch_update_pull_cp<1>(c, G, universe, a); break;
         case 2: launch_update_pull_cp<2>(c, G, universe, a); break;
@@ -693,7 +721,86 @@ void launch_update_pull(dynlp_ctx* c, int G, const Frontier& universe, const Pul
         default: launch_update_pull_cp<64>(c, G, universe, a); break;
     }
     HIPCHK(c, hipGetLastError());
-    if (c->time_kernels) HIPCHK(c, hipEventRecord(e1, c->stream));
+    close_timed_span(c, e1);
+}
+
+// ---- several rounds per launch (k_rounds_persistent) ------------------------------------------------------------
+// Whether a stretch of rounds that evaluate V_aff themselves should run many rounds per launch.  Off unless asked
+// for: measured on MI355X on a 100,000-vertex kNN graph (10 classes, 2M stored entries) a round inside such a
+// launch takes 68 us against 52-58 us as a launch of its own - the label rows that cross the barrier must be
+// read past the per-XCD L2s, and a workgroup runs its share of a round's rows one after the other - so that the
+// fewer rounds an in-place batch then needs (370 against 500: fewer rows in flight at once) only tie the batch at
+// 26 ms, and a synchronous batch loses (46 against 38 ms).
+constexpr int kPersistRounds = 32;  // rounds per launch; the ring of counter slots holds kRing = 64
+
+bool persistent_rounds_pay(const dynlp_ctx* c, const Frontier& universe) {
+    (void)universe;
+    return c->persist > 0 && !c->persist_failed;
+}
+
+template <int CP, int G>
+bool launch_persistent_inst(dynlp_ctx* c, const Frontier& universe, PersistArgs& a) {
+    constexpr int GPB = kBlock / G;
+    static int per_cu_cache[64] = {};  // by device ordinal
+    int& per_cu = per_cu_cache[c->device & 63];
+    if (per_cu == 0) {
+        int v = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, k_rounds_persistent<CP, G>, kBlock, 0) != hipSuccess || v < 1) {
+            (void)hipGetLastError();
+            return false;
+        }
+        per_cu = v;
+    }
+    const int64_t resident = std::min<int64_t>((int64_t)c->num_cu * per_cu, (int64_t)kBarGroup * kBarMaxGroups);
+    const int64_t want = std::max<int64_t>(1, ceil_div((int64_t)universe.ns, GPB)) + std::min<int64_t>(universe.nl, resident / 2);
+    const unsigned int grid = (unsigned int)std::min<int64_t>(want, resident);
+    a.long_blocks_max = (unsigned int)std::min<int64_t>((int64_t)universe.nl, std::max<int64_t>(grid / 2, universe.ns ? 0 : grid));
+    if (a.long_blocks_max >= grid && universe.ns > 0) a.long_blocks_max = grid - 1;
+    a.ngroups = (unsigned int)ceil_div((int64_t)grid, (int64_t)kBarGroup);
+    // an ordinary launch of a grid that fits the device all at once (a cooperative launch costs milliseconds here);
+    // should the grid not be resident as a whole for any reason, the bounded wait at the barrier ends the launch
+    hipLaunchKernelGGL((k_rounds_persistent<CP, G>), dim3(grid), dim3(kBlock), 0, c->stream, a);
+    if (hipGetLastError() != hipSuccess) return false;
+    return true;
+}
+
+template <int CP>
+bool launch_persistent_cp(dynlp_ctx* c, int G, const Frontier& universe, PersistArgs& a) {
+    constexpr int LPN = CP >= 4 ? CP / 4 : 1;
+#define DYNLP_CASE(GV)                                                  \
+    case GV:                                                            \
+        if constexpr (GV >= LPN) return launch_persistent_inst<CP, GV>(c, universe, a); \
+        break;
+    switch (G) {
+        DYNLP_CASE(4)
+        DYNLP_CASE(8)
+        DYNLP_CASE(16)
+        DYNLP_CASE(32)
+        DYNLP_CASE(64)
+        default: break;
+    }
+#undef DYNLP_CASE
+    return launch_persistent_inst<CP, 64>(c, universe, a);
+}
+
+// Rounds [round, round + count) of a stretch in one launch.  False: the launch was refused (nothing was queued);
+// the caller queues ordinary rounds instead.
+bool launch_persistent(dynlp_ctx* c, int G, const Frontier& universe, PersistArgs& a, int round) {
+    HIPCHK(c, hipMemsetAsync(c->persist_ctl, 0, kBarWords * sizeof(unsigned int), c->stream));
+    hipEvent_t e1 = open_timed_span(c, round, a.rounds);
+    bool ok;
+    switch (c->CP) {
+        case 1: ok = launch_persistent_cp<1>(c, G, universe, a); break;
+        case 2: ok = launch_persistent_cp<2>(c, G, universe, a); break;
+        case 4: ok = launch_persistent_cp<4>(c, G, universe, a); break;
+        case 8: ok = launch_persistent_cp<8>(c, G, universe, a); break;
+        case 16: ok = launch_persistent_cp<16>(c, G, universe, a); break;
+        case 32: ok = launch_persistent_cp<32>(c, G, universe, a); break;
+        default: ok = launch_persistent_cp<64>(c, G, universe, a); break;
+    }
+    close_timed_span(c, e1);
+    if (!ok && c->time_kernels) c->ev_round[c->events_used / 2 - 1] = -1;
+    return ok;
 }
 
 // ---- binned rounds (dynlp_binned.h) -----------------------------------------------------------------
@@ -810,42 +917,87 @@ bool build_binned(dynlp_ctx* c) {
     c->pb_bits = bits;
     c->pb_bins = nbins;
     c->pb_chunks = chunks;
+    // In-place mode: the round updates the vertices range by range (whole bins each) and publishes a range's new
+    // labels before the next range is updated, which is what "a new row replaces the old one at once" means for
+    // two streaming passes; fewer rounds are needed than with all ranges updated from the round-start labels.
+    // Synchronous mode: one range.
+    const int want_parts = c->update_mode == DYNLP_UPDATE_IN_PLACE ? (c->pb_parts_opt > 0 ? c->pb_parts_opt : 8) : 1;
+    const int parts = std::max(1, std::min({want_parts, kPbMaxParts, nbins}));
+    c->pb_parts = parts;
+    std::vector<unsigned int> first_at(parts + 1, 0u);
+    for (int i = 0; i <= parts; ++i) {
+        const int b = (int)(((int64_t)nbins * i) / parts);
+        c->pb_part_bin[i] = b;
+        const int64_t v = std::min<int64_t>(c->n, (int64_t)b << bits);
+        HIPCHK(c, hipMemcpyAsync(&first_at[i], c->pb_first + v, sizeof(unsigned int), hipMemcpyDeviceToHost, c->stream));
+    }
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    for (int i = 0; i < parts; ++i) {
+        c->pb_part_chunk[i][0] = (int)(first_at[i] / kPbChunk);
+        c->pb_part_chunk[i][1] = (int)std::min<int64_t>(chunks, ceil_div((int64_t)first_at[i + 1], kPbChunk));
+        if (first_at[i + 1] == first_at[i]) c->pb_part_chunk[i][1] = c->pb_part_chunk[i][0];  // no entries: nothing to publish
+    }
     c->pb_built = true;
     return true;
 }
 
 // One binned round: scatter pass + gather pass (arguments as for the fused round).
-void launch_binned_round(dynlp_ctx* c, const PullRoundArgs& a) {
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (c->time_kernels) {
-        while (c->events.size() < c->events_used + 2) {
-            hipEvent_t e;
-            HIPCHK(c, hipEventCreate(&e));
-            c->events.push_back(e);
-        }
-        e0 = c->events[c->events_used++];
-        e1 = c->events[c->events_used++];
-        HIPCHK(c, hipEventRecord(e0, c->stream));
-    }
+void launch_pb_scatter(dynlp_ctx* c, const RoundCtr* prev, int chunk0, int nchunks, const float* F, const unsigned int* bits,
+                       unsigned int* moved_clear, RoundCtr* ctr_zero, const unsigned int* bits_also = nullptr) {
+    if (nchunks <= 0 && !ctr_zero && !moved_clear) return;
+    hipLaunchKernelGGL(k_pb_scatter, dim3(8 * (unsigned int)std::max<int64_t>(1, ceil_div(nchunks, 8))), dim3(kPbScatterThreads), 0,
+                       c->stream, prev, c->pb_first + c->n, (unsigned int)chunk0, (unsigned int)std::max(nchunks, 0), c->pb_src,
+                       c->pb_lpos, c->pb_oslot, F, bits, bits_also, moved_clear, (unsigned int)c->moved_words, c->pb_val, ctr_zero);
+}
+
+// One binned round (arguments as for the fused round).  `first_of_stretch`: no binned round has run since the slots
+// were last brought up to date with the labels.
+// One range (synchronous mode): scatter all labels, gather all bins: a Jacobi round.
+// Several ranges (in-place mode): the slots are kept up to date between rounds; the round updates range after range,
+// each gather followed by the scatter that publishes the range's new labels, so that later ranges of the same round
+// already read them.  A published label carries "the sender moved in this round or in the previous one": ranges that
+// come later in this round and ranges that come earlier in the next one both have to learn that it moved, and each
+// sees only one publication.  V_aff of a round is then a superset of Alg. 2's (a row may be updated once more than
+// needed), as with any in-place round that reads rows the same round has already replaced.
+void launch_binned_round(dynlp_ctx* c, const PullRoundArgs& a, int round, bool first_of_stretch) {
+    hipEvent_t e1 = open_timed_span(c, round, 1);
     const unsigned int* bin_off = c->pb_bin + (kPbMaxBins + 1);
-    hipLaunchKernelGGL(k_pb_scatter, dim3(8 * (unsigned int)ceil_div(c->pb_chunks, 8)), dim3(kPbScatterThreads), 0, c->stream, a.prev,
-                       c->pb_first + c->n, (unsigned int)c->pb_chunks, c->pb_src, c->pb_lpos, c->pb_oslot, a.F_in, a.moved_prev,
-                       a.moved_clear, (unsigned int)c->moved_words, c->pb_val, a.ctr_zero);
-    hipLaunchKernelGGL(k_pb_gather, dim3(c->pb_bins), dim3(kPbGatherThreads), 0, c->stream, a.prev, c->n, c->pb_bits, bin_off,
-                       c->pb_dst, c->pb_wn, c->pb_val, c->pb_len, a.F_in, a.F_out, a.moved_prev, a.moved_cur, a.tol, a.ctr);
+    if (c->pb_parts <= 1) {
+        launch_pb_scatter(c, a.prev, 0, c->pb_chunks, a.F_in, a.moved_prev, a.moved_clear, a.ctr_zero);
+        hipLaunchKernelGGL(k_pb_gather, dim3(c->pb_bins), dim3(kPbGatherThreads), 0, c->stream, a.prev, c->n, c->pb_bits, 0u,
+                           bin_off, c->pb_dst, c->pb_wn, c->pb_val, c->pb_len, a.F_in, a.F_out, a.moved_prev, a.moved_cur,
+                           a.tol, a.ctr);
+    } else {
+        // bring every slot up to date once (labels and "moved in the previous round" bits); this launch also clears
+        // the next round's counter slot and bitmap, as the first launch of every round does
+        if (first_of_stretch) launch_pb_scatter(c, a.prev, 0, c->pb_chunks, a.F_in, a.moved_prev, nullptr, nullptr);
+        for (int i = 0; i < c->pb_parts; ++i) {
+            const int b0 = c->pb_part_bin[i], b1 = c->pb_part_bin[i + 1];
+            if (i == 0) launch_pb_scatter(c, a.prev, 0, 0, a.F_in, a.moved_prev, a.moved_clear, a.ctr_zero);
+            if (b1 > b0)
+                hipLaunchKernelGGL(k_pb_gather, dim3(b1 - b0), dim3(kPbGatherThreads), 0, c->stream, a.prev, c->n, c->pb_bits,
+                                   (unsigned int)b0, bin_off, c->pb_dst, c->pb_wn, c->pb_val, c->pb_len, a.F_in, a.F_out,
+                                   a.moved_prev, a.moved_cur, a.tol, a.ctr);
+            launch_pb_scatter(c, a.prev, c->pb_part_chunk[i][0], c->pb_part_chunk[i][1] - c->pb_part_chunk[i][0], a.F_out,
+                              a.moved_cur, nullptr, nullptr, a.moved_prev);
+        }
+    }
     HIPCHK(c, hipGetLastError());
-    if (c->time_kernels) HIPCHK(c, hipEventRecord(e1, c->stream));
+    close_timed_span(c, e1);
 }
 
 // Resolve the per-round events into the round log; returns the summed device time of all
 // row-update launches.
 float collect_kernel_ms(dynlp_ctx* c) {
     float total = 0.f;
-    for (size_t i = 0, round = 0; i + 1 < c->events_used && round < c->log.size(); i += 2, ++round) {
+    for (size_t k = 0; 2 * k + 1 < c->events_used; ++k) {
         float a = 0.f;
-        (void)hipEventElapsedTime(&a, c->events[i], c->events[i + 1]);
-        c->log[round].ms_update = a;
+        (void)hipEventElapsedTime(&a, c->events[2 * k], c->events[2 * k + 1]);
         total += a;
+        const int first = c->ev_round[k];
+        if (first < 0) continue;
+        const int last = std::min<int>(first + c->ev_count[k], (int)c->log.size());
+        for (int t = first; t < last; ++t) c->log[t].ms_update += a / (float)std::max(1, last - first);
     }
     c->events_used = 0;
     return total;
@@ -1049,6 +1201,7 @@ void destroy_ctx(dynlp_ctx* c) {
         if (e) (void)hipEventDestroy(e);
     dev_free(c, c->ring);
     dev_free(c, c->bc);
+    dev_free(c, c->persist_ctl);
     for (void* b : c->bounce)
         if (b) (void)hipHostFree(b);
     for (hipEvent_t e : c->ingest_ev)
@@ -1225,6 +1378,8 @@ dynlp_status dynlp_create(dynlp_ctx** out, int64_t n, const int64_t* row_ptr, co
     if (!(o.slack_factor > 1.0f)) o.slack_factor = 1.25f;
     if (o.slack_factor > 8.0f) return bad("slack_factor must be <= 8");
     if (o.reserve_vertices < 0 || o.reserve_edges < 0) return bad("reserve counts must be >= 0");
+    if (o.persistent_rounds < -1 || o.persistent_rounds > 1) return bad("persistent_rounds must be -1, 0 or 1");
+    if (o.persistent_spin_limit < 0) return bad("persistent_spin_limit must be >= 0");
     if (o.ingest_chunk_edges < 0 || o.ingest_chunk_edges > ((int64_t)1 << 28)) return bad("ingest_chunk_edges must be in [0, 2^28]");
     if ((o.alloc == nullptr) != (o.dealloc == nullptr)) return bad("alloc and dealloc must be given together");
     if (o.binary_scalar != 0 && num_classes != 2) return bad("binary_scalar needs num_classes == 2");
@@ -1270,6 +1425,8 @@ dynlp_status dynlp_create(dynlp_ctx** out, int64_t n, const int64_t* row_ptr, co
         c->time_kernels = o.time_kernels != 0;
         c->group_lanes = o.group_lanes;
         c->binned = o.binned_rounds;
+        c->persist = o.persistent_rounds;
+        if (o.persistent_spin_limit > 0) c->persist_spin = (unsigned int)o.persistent_spin_limit;
         c->ingest_chunk = o.ingest_chunk_edges > 0 ? o.ingest_chunk_edges : ((int64_t)4 << 20);
         c->alloc_fn = o.alloc;
         c->dealloc_fn = o.dealloc;
@@ -1283,6 +1440,7 @@ dynlp_status dynlp_create(dynlp_ctx** out, int64_t n, const int64_t* row_ptr, co
         hipDeviceProp_t prop;
         HIPCHK(c, hipGetDeviceProperties(&prop, c->device));
         c->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+        c->persist_ctl = static_cast<unsigned int*>(dev_alloc(c, kBarWords * sizeof(unsigned int)));
         c->ring = static_cast<RoundCtr*>(dev_alloc(c, sizeof(RoundCtr) * (kRing + 1)));
         c->bc = static_cast<BatchCtr*>(dev_alloc(c, sizeof(BatchCtr)));
         HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_slot), sizeof(RoundCtr) * kRing, hipHostMallocDefault));
@@ -1684,6 +1842,7 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
         all_rows.nl = c->h_slot[0].next_long;
         c->pb_built = false;
         const bool binned = !converged && binned_rounds_pay(c, all_rows) && build_binned(c);
+        bool pb_fresh = true;  // the slots of the binned rounds do not yet hold the current labels
         if (binned) HIPCHK(c, hipMemsetAsync(c->moved[0], 0xff, (size_t)c->moved_words * sizeof(unsigned int), c->stream));
         while (!converged && it < max_iter) {
             // a chain of sweeps; each checks on the device whether its predecessor already met the stop rule
@@ -1694,15 +1853,22 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
                 if (chain_binned && t > 0) {
                     const PullRoundArgs a{slot_of(c, t - 1), buf[t & 1], buf[(t + 1) & 1], c->moved[0], c->moved[1], c->moved[2],
                                           tol, slot_of(c, t), slot_of(c, t + 1)};
-                    launch_binned_round(c, a);
+                    launch_binned_round(c, a, t, t == 1 || pb_fresh);
+                    pb_fresh = false;
                     continue;
                 }
                 const UpdateArgs a{slot_of(c, t - 1), t == 0 ? 1 : 2, buf[t & 1], buf[(t + 1) & 1], nullptr, tol,
                                    slot_of(c, t), slot_of(c, t + 1), (int64_t)nq, (int64_t)c->h_slot_start_long,
                                    lazy ? kRowLazy : 0};
-                launch_update<false>(c, G, f, a);
+                launch_update<false>(c, G, f, a, t);
             }
+            const size_t first_pair = c->events_used / 2 - (c->time_kernels ? (size_t)r : 0);
             read_slots(c, it, r);
+            {
+                int done = 0;
+                while (done < r && c->h_slot[done].executed) ++done;
+                if (c->time_kernels) trim_timed_spans(c, first_pair, it + done);
+            }
             if (!c->h_slot[0].executed) break;  // cannot happen while the stop rule is unmet; never spin on it
             for (int i = 0; i < r; ++i) {
                 const RoundCtr& rc = c->h_slot[i];
@@ -1961,6 +2127,8 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
         bool lazy = false;
         unsigned int prev_sig[3] = {0xffffffffu, 0xffffffffu, 0xffffffffu};
         c->pb_built = false;    // the batch changed the graph
+        c->persist_failed = false;
+        c->persist_launches_last = c->persist_aborts_last = 0;
         const bool in_place = c->update_mode == DYNLP_UPDATE_IN_PLACE;
         // dynlp_set_final_check: when V_aff has emptied, one more round over every updatable row; rows it moves by
         // more than tol (and their neighbours) start Step 3 again.  check_round = index of the running check round.
@@ -1981,7 +2149,11 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
                 bin_failed = true;  // no memory for the binned arrays: ordinary rounds for this batch
                 can_bin = false;
             }
-            if (!pingpong && (double)known >= (can_bin ? kBinnedEnter : kDenseEnter) * (double)universe.size()) {
+            // graphs whose rounds run many per launch stay in one stretch from the first round to the last: a round
+            // over a small V_aff costs them no more than a launch
+            // (not once rounds repeat themselves exactly: the averaged rows that end such a cycle are staged rounds)
+            const bool stay = !lazy && !can_bin && fused_rounds_pay(c, avg_len) && persistent_rounds_pay(c, universe);
+            if (!pingpong && (stay || (double)known >= (can_bin ? kBinnedEnter : kDenseEnter) * (double)universe.size())) {
                 if (!in_place) sync_partner(c);
                 for (unsigned int* mv : c->moved)
                     HIPCHK(c, hipMemsetAsync(mv, 0, (size_t)c->moved_words * sizeof(unsigned int), c->stream));
@@ -1989,7 +2161,8 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
                 stretch_start = it;
                 binned = can_bin;
                 fused = binned || fused_rounds_pay(c, avg_len);
-            } else if (pingpong && (double)known < (binned ? kBinnedLeave : kDenseLeave) * (double)universe.size()) {
+            } else if (pingpong && !(stay && fused && !binned) &&
+                       (double)known < (binned ? kBinnedLeave : kDenseLeave) * (double)universe.size()) {
                 pingpong = false;
                 if (fused) {
                     // rows of the last round are in F (the buffers were swapped to make it so)
@@ -1999,9 +2172,15 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
                                          in_place ? nullptr : c->F2, frontier_of(c, cur), &slot->next_count, &slot->next_long);
                 }
             }
-            const int r = std::min<int>(kChain, c->max_iter - it);
+            // a stretch of short rounds runs many rounds per launch (k_rounds_persistent); its first round, which still
+            // works on a frontier list, is an ordinary launch
+            const bool persist = pingpong && fused && !binned && persistent_rounds_pay(c, universe);
+            const int r = std::min<int>(persist ? kPersistRounds : kChain, c->max_iter - it);
+            const size_t first_pair = c->events_used / 2;
             // ping-pong: round it+i reads buf[i & 1], writes buf[(i + 1) & 1]; in place: always F
             float* const buf[2] = {c->F, in_place ? c->F : c->F2};
+            bool persist_launched = false;
+            int persist_first = r;  // chain position of the first round that ran inside a persistent launch
             for (int i = 0; i < r; ++i) {
                 const int t = it + i;
                 RoundCtr* slot = slot_of(c, t);
@@ -2014,7 +2193,7 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
                         unsigned int* mv = c->moved[q & 1];
                         const UpdateArgs a{slot_of(c, t - 1), 0, buf[i & 1], buf[(i + 1) & 1], mv, c->tol,
                                            slot, slot_of(c, t + 1), (int64_t)universe.size(), (int64_t)universe.nl};
-                        launch_update<false>(c, G, f, a);
+                        launch_update<false>(c, G, f, a, t);
                         launch_pull_frontier(c, universe, avg_len, mv, c->moved[(q + 1) & 1], buf[(i + 1) & 1],
                                              in_place ? nullptr : buf[i & 1], frontier_of(c, cur ^ 1), &slot->next_count,
                                              &slot->next_long);
@@ -2022,14 +2201,45 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
                     } else if (q == 0) {
                         const UpdateArgs a{slot_of(c, t - 1), 0, buf[i & 1], buf[(i + 1) & 1], c->moved[0], c->tol,
                                            slot, slot_of(c, t + 1), (int64_t)universe.size(), (int64_t)universe.nl};
-                        launch_update<false>(c, G, f, a);
+                        launch_update<false>(c, G, f, a, t);
                     } else {
+                        if (persist && !c->persist_failed) {
+                            // rounds t .. it + r - 1 in one launch
+                            PersistArgs pa;
+                            pa.ring = c->ring;
+                            pa.t0 = t;
+                            pa.rounds = r - i;
+                            pa.long_blocks_max = 0;
+                            pa.front = universe.front;
+                            pa.back = universe.back;
+                            pa.ns = universe.ns;
+                            pa.nl = universe.nl;
+                            pa.meta = c->meta;
+                            pa.pool = c->pool;
+                            pa.buf0 = buf[i & 1];
+                            pa.buf1 = buf[(i + 1) & 1];
+                            pa.moved0 = c->moved[0];
+                            pa.moved1 = c->moved[1];
+                            pa.moved2 = c->moved[2];
+                            pa.q0 = q;
+                            pa.words = (unsigned int)c->moved_words;
+                            pa.tol = c->tol;
+                            pa.barrier = c->persist_ctl;
+                            pa.spin_limit = c->persist_spin;
+                            if (launch_persistent(c, G, universe, pa, t)) {
+                                persist_launched = true;
+                                persist_first = i;
+                                ++c->persist_launches_last;
+                                break;
+                            }
+                            c->persist_failed = true;  // refused: ordinary rounds for the rest of the chain and the batch
+                        }
                         const PullRoundArgs a{slot_of(c, t - 1), buf[i & 1], buf[(i + 1) & 1], c->moved[(q - 1) % 3],
                                               c->moved[q % 3], c->moved[(q + 1) % 3], c->tol, slot, slot_of(c, t + 1)};
                         if (binned)
-                            launch_binned_round(c, a);
+                            launch_binned_round(c, a, t, q == 1);
                         else
-                            launch_update_pull(c, G, universe, a);
+                            launch_update_pull(c, G, universe, a, t);
                     }
                 } else {
                     // rows are staged by frontier position and committed after the kernel; rows that moved mark
@@ -2038,10 +2248,20 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
                     const UpdateArgs a{slot_of(c, t - 1), 0, c->F, in_place ? c->F : c->F2, nullptr, c->tol,
                                        slot, slot_of(c, t + 1), (int64_t)universe.size(), (int64_t)universe.nl,
                                        (in_place ? kRowByVertex : 0) | (lazy ? kRowLazy : 0)};
-                    launch_update<true>(c, G, f, a);
+                    launch_update<true>(c, G, f, a, t);
                     if (!in_place) launch_commit(c, f, slot_of(c, t - 1), (int64_t)universe.size());
                     launch_compact(c, frontier_of(c, cur ^ 1), &slot->next_count, &slot->next_long, 0);
                     cur ^= 1;
+                }
+            }
+            if (persist_launched) {
+                // did a workgroup give up at the barrier?  (the rounds whose slots say "executed" are complete either way)
+                unsigned int ctl[2] = {0, 0};
+                HIPCHK(c, hipMemcpyAsync(ctl, c->persist_ctl, sizeof ctl, hipMemcpyDeviceToHost, c->stream));
+                HIPCHK(c, hipStreamSynchronize(c->stream));
+                if (ctl[1] != 0u) {
+                    c->persist_failed = true;
+                    ++c->persist_aborts_last;
                 }
             }
             read_slots(c, it, r);
@@ -2056,19 +2276,23 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
                 edges += (int64_t)(rc.edges + rc.edges_long);
                 avg_len = nq ? (double)(rc.edges + rc.edges_long) / (double)nq : avg_len;
                 // the first round of a fused stretch still works on a frontier list
-                c->log.push_back(round_info(rc, !pingpong ? 1 : (fused && it + i > stretch_start ? (binned ? 3 : 2) : 0), G));
+                c->log.push_back(round_info(rc, !pingpong ? 1 : (fused && it + i > stretch_start ? (binned ? 3 : i >= persist_first ? 4 : 2) : 0), G));
                 // inside a stretch the next V_aff is not counted: this round's size stands in for it while
                 // rows still move
                 known = pingpong && fused ? (rc.changed ? std::max(nq, 1u) : 0u) : rc.next_count + rc.next_long;
                 if (it + i == check_round) verified = rc.changed == 0u;  // the check round moved no row by more than tol
                 const unsigned int sig[3] = {nq, rc.changed, rc.resid_bits};
-                same_run = (!pingpong && std::memcmp(sig, prev_sig, sizeof sig) == 0) ? same_run + 1 : 0;
+                same_run = std::memcmp(sig, prev_sig, sizeof sig) == 0 ? same_run + 1 : 0;
                 std::memcpy(prev_sig, sig, sizeof sig);
                 if (same_run >= 16) lazy = true;
                 peak = std::max<int64_t>(peak, known);
             }
             if (pingpong && !in_place && (executed & 1)) std::swap(c->F, c->F2);  // the output of the last executed round
+            if (c->time_kernels) trim_timed_spans(c, first_pair, it + executed);
+            // a persistent launch that gave up at a barrier stops short without V_aff being empty
+            const bool cut_short = persist_launched && executed < r && executed > 0 && c->h_slot[executed - 1].changed != 0u;
             it += executed;
+            if (cut_short) continue;
             if (executed < r) known = 0;  // a round found V_aff empty
         }
         if (verified || known > 0 || it >= c->max_iter || universe.size() == 0) break;

@@ -37,6 +37,7 @@ constexpr unsigned int kPbNone = 0xffffffffu;      // slot of an entry whose rec
 constexpr int kPbChunk = 16384;                    // entries per chunk: 64 KB of staged values (8K / 16K / 32K entries:
                                                    // 1.74 / 1.63 / 1.82 ms per round on 250M entries)
 constexpr float kPbUnit = 1073741824.0f;           // 2^30
+constexpr int kPbMaxParts = 16;                    // in-place mode: vertex ranges updated one after the other in a round
 
 // receivers: len[v] = row length if v is updatable (unlabelled, at least one entry), else 0; the same as one
 // bit per vertex in upd[] (the build passes test it for every entry; 1 bit per vertex stays in the L2).
@@ -263,13 +264,17 @@ constexpr int kPbScatterThreads = 1024;  // two workgroups of this size and 64 K
                                          // 2.25 / 1.75 / 1.63 ms per round on 250M entries)
 
 __global__ void __launch_bounds__(kPbScatterThreads) k_pb_scatter(const RoundCtr* __restrict__ prev,
-                                                      const unsigned int* __restrict__ num_entries, unsigned int chunks,
+                                                      const unsigned int* __restrict__ num_entries, unsigned int chunk0,
+                                                      unsigned int chunks,
                                                       const unsigned int* __restrict__ src,
                                                       const unsigned short* __restrict__ lpos,
                                                       const unsigned int* __restrict__ oslot, const float* F_in,
                                                       const unsigned int* __restrict__ moved_prev,
+                                                      const unsigned int* __restrict__ moved_also,
                                                       unsigned int* __restrict__ moved_clear, unsigned int words,
                                                       unsigned int* __restrict__ val, RoundCtr* __restrict__ ctr_zero) {
+    // chunks chunk0 .. chunk0 + chunks - 1; moved_prev (and moved_also, if not NULL): the bitmaps whose bits travel
+    // with the labels ("the sender moved"); moved_clear / ctr_zero may be NULL
     __shared__ unsigned int stage[kPbChunk];
     if (ctr_zero && blockIdx.x == 0) {
         if (threadIdx.x == 0) {
@@ -291,10 +296,12 @@ __global__ void __launch_bounds__(kPbScatterThreads) k_pb_scatter(const RoundCtr
     }
     if (!pb_round_runs(prev)) return;
     constexpr int T = kPbScatterThreads;
-    for (unsigned int w = blockIdx.x * T + threadIdx.x; w < words; w += gridDim.x * T) moved_clear[w] = 0u;
+    if (moved_clear)
+        for (unsigned int w = blockIdx.x * T + threadIdx.x; w < words; w += gridDim.x * T) moved_clear[w] = 0u;
     const unsigned int per_xcd = (chunks + 7u) / 8u;
-    const unsigned int chunk = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
-    if ((blockIdx.x >> 3) >= per_xcd || chunk >= chunks) return;
+    const unsigned int local = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    if ((blockIdx.x >> 3) >= per_xcd || local >= chunks) return;
+    const unsigned int chunk = chunk0 + local;
     const int64_t E = (int64_t)*num_entries;
     const int64_t base = (int64_t)chunk * kPbChunk;
     constexpr int UN = 4;
@@ -310,7 +317,8 @@ __global__ void __launch_bounds__(kPbScatterThreads) k_pb_scatter(const RoundCtr
 #pragma unroll
         for (int q = 0; q < UN; ++q)
             if (u[q] != 0xffffffffu)
-                stage[p[q]] = __float_as_uint(F_in[u[q]]) | (pb_bit(moved_prev, (int32_t)u[q]) ? 0x80000000u : 0u);
+                stage[p[q]] = __float_as_uint(F_in[u[q]]) |
+                              ((pb_bit(moved_prev, (int32_t)u[q]) || (moved_also && pb_bit(moved_also, (int32_t)u[q]))) ? 0x80000000u : 0u);
     }
     __syncthreads();
     for (int k0 = 0; k0 < kPbChunk; k0 += UN * T) {
@@ -328,6 +336,7 @@ __global__ void __launch_bounds__(kPbScatterThreads) k_pb_scatter(const RoundCtr
 constexpr int kPbGatherThreads = 1024;
 
 __global__ void __launch_bounds__(kPbGatherThreads) k_pb_gather(const RoundCtr* __restrict__ prev, int64_t n, int bin_bits,
+                                                               unsigned int bin0,
                                                                const unsigned int* __restrict__ bin_off,
                                                                const unsigned short* __restrict__ dst,
                                                                const float* __restrict__ wn,
@@ -344,17 +353,19 @@ __global__ void __launch_bounds__(kPbGatherThreads) k_pb_gather(const RoundCtr* 
     __shared__ unsigned long long sm_e[NW];
     __shared__ unsigned int sm_c[NW], sm_n[NW];
     // a static sweep finds the size of its row list in its predecessor's slot: hand it on (0 in batch rounds)
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
+    // (one workgroup per bin of the range that starts at bin0)
+    const unsigned int bin = bin0 + blockIdx.x;
+    if (bin == 0 && threadIdx.x == 0) {
         ctr->next_count = prev->next_count;
         ctr->next_long = prev->next_long;
     }
     if (!pb_round_runs(prev)) return;
-    if (blockIdx.x == 0 && threadIdx.x == 0) ctr->executed = 1;
+    if (bin == 0 && threadIdx.x == 0) ctr->executed = 1;
     const int size = 1 << bin_bits;
     for (int d = threadIdx.x; d < size; d += T) acc[d] = 0u;
     for (int d = threadIdx.x; d < size / 32; d += T) nb[d] = 0u;
     __syncthreads();
-    const unsigned int lo = bin_off[blockIdx.x], hi = bin_off[blockIdx.x + 1];
+    const unsigned int lo = bin_off[bin], hi = bin_off[bin + 1];
     constexpr int UN = 4;  // independent slot reads in flight per lane
     for (unsigned int i0 = lo; i0 < hi; i0 += UN * T) {
         unsigned int d[UN], x[UN];
@@ -376,7 +387,7 @@ __global__ void __launch_bounds__(kPbGatherThreads) k_pb_gather(const RoundCtr* 
         }
     }
     __syncthreads();
-    const int64_t first = (int64_t)blockIdx.x << bin_bits;
+    const int64_t first = (int64_t)bin << bin_bits;
     const int64_t n_words_end = (n + 31) & ~(int64_t)31;
     float rmax = 0.f;
     unsigned long long edges = 0;
@@ -426,7 +437,7 @@ __global__ void __launch_bounds__(kPbGatherThreads) k_pb_gather(const RoundCtr* 
             nchanged += sm_c[i];
             nrows += sm_n[i];
         }
-        RoundPart* p = &ctr->part[blockIdx.x & (kCtrLanes - 1)];
+        RoundPart* p = &ctr->part[bin & (kCtrLanes - 1)];
         if (rmax > 0.f) atomicMax(&p->resid_bits, __float_as_uint(rmax));
         if (edges) atomicAdd(&p->edges, edges);
         if (nchanged) atomicAdd(&p->changed, nchanged);

@@ -227,4 +227,49 @@ __device__ inline void store_vec<4>(float* p, const Vec<4>& a) {
     *reinterpret_cast<float4*>(p) = make_float4(a.v[0], a.v[1], a.v[2], a.v[3]);
 }
 
+// ---- the same row chunks, read and written coherently across the whole device -------------------------------
+// A kernel that runs several rounds (k_rounds_persistent) exchanges label rows between workgroups on different
+// XCDs, each of which has an L2 of its own.  Relaxed atomic accesses at device scope are served from / written
+// through to the point where the XCDs meet, so that a row written before a grid barrier is what every workgroup
+// reads after it, without writing back and invalidating whole caches at every barrier (measured: that costs ten
+// times the round itself).  A 16-byte chunk is two 8-byte accesses.
+template <int V, bool COH>
+__device__ inline Vec<V> load_row(const float* p) {
+    if constexpr (!COH) {
+        return load_vec<V>(p);
+    } else if constexpr (V == 1) {
+        Vec<1> r;
+        r.v[0] = __uint_as_float(__hip_atomic_load(reinterpret_cast<const unsigned int*>(p), __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT));
+        return r;
+    } else {
+        Vec<V> r;
+#pragma unroll
+        for (int k = 0; k < V; k += 2) {
+            const unsigned long long q = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p + k),
+                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            r.v[k] = __uint_as_float((unsigned int)q);
+            r.v[k + 1] = __uint_as_float((unsigned int)(q >> 32));
+        }
+        return r;
+    }
+}
+
+template <int V, bool COH>
+__device__ inline void store_row(float* p, const Vec<V>& a) {
+    if constexpr (!COH) {
+        store_vec<V>(p, a);
+    } else if constexpr (V == 1) {
+        __hip_atomic_store(reinterpret_cast<unsigned int*>(p), __float_as_uint(a.v[0]), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+#pragma unroll
+        for (int k = 0; k < V; k += 2) {
+            const unsigned long long q =
+                (unsigned long long)__float_as_uint(a.v[k]) | ((unsigned long long)__float_as_uint(a.v[k + 1]) << 32);
+            __hip_atomic_store(reinterpret_cast<unsigned long long*>(p + k), q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
 }  // namespace dynlp

@@ -159,6 +159,15 @@ __device__ inline bool moved_bit(const unsigned int* __restrict__ moved, int32_t
     return (moved[(unsigned int)v >> 5] >> ((unsigned int)v & 31u)) & 1u;
 }
 
+// COH: read past the caches (the bitmap was written by other workgroups earlier in the same launch)
+template <bool COH>
+__device__ inline bool moved_bit_c(const unsigned int* moved, int32_t v) {
+    if constexpr (!COH) return moved_bit(moved, v);
+    else
+        return (__hip_atomic_load(&moved[(unsigned int)v >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >>
+                ((unsigned int)v & 31u)) & 1u;
+}
+
 // kPullSub = sub-steps per workgroup chunk (one queue atomic per chunk of kPullSub * kBlock positions).
 // Small chunks mean more workgroups (the kernel is latency-bound on small and on low-degree graphs),
 // large chunks mean fewer atomics on the one queue counter (which run at about 1e8 per second and show
@@ -324,7 +333,7 @@ struct RowShape {
 // Accumulate the chunks first_chunk, first_chunk + chunk_step, ... (G entries each) of one row.
 // Lanes past the end of the row carry a stand-in entry (own row, weight 0).  On return e holds the
 // last chunk this group loaded (or the stand-in if it loaded none).
-template <int CP, int G>
+template <int CP, int G, bool COH = false>
 __device__ inline void accumulate_row(const Edge* __restrict__ row, int len, int first_chunk, int chunk_step,
                                       int32_t u, const float* F_in, int gl,
                                       Vec<RowShape<CP>::VEC>& acc, float& s, Edge& e) {
@@ -357,7 +366,7 @@ __device__ inline void accumulate_row(const Edge* __restrict__ row, int len, int
                     w[t] = __shfl(e.w, j0 + t * SLOTS + slot, G);
                 }
 #pragma unroll
-                for (int t = 0; t < UN; ++t) f[t] = load_vec<VEC>(F_in + (size_t)c[t] * CP + chunk * VEC);
+                for (int t = 0; t < UN; ++t) f[t] = load_row<VEC, COH>(F_in + (size_t)c[t] * CP + chunk * VEC);
 #pragma unroll
                 for (int t = 0; t < UN; ++t) {
 #pragma unroll
@@ -376,8 +385,9 @@ __device__ inline void accumulate_row(const Edge* __restrict__ row, int len, int
 }
 
 // Per-workgroup totals -> one set of atomics on one of the round's partial records.
-__device__ inline void flush_round_counters(float rmax, unsigned long long edges, unsigned int changed,
-                                            RoundCtr* __restrict__ ctr, bool long_rows, unsigned int rows = 0) {
+// Returns (in thread 0) the number of rows the workgroup moved.
+__device__ inline unsigned int flush_round_counters(float rmax, unsigned long long edges, unsigned int changed,
+                                                    RoundCtr* __restrict__ ctr, bool long_rows, unsigned int rows = 0) {
     __shared__ float sm_r[kBlock / kWave];
     __shared__ unsigned long long sm_e[kBlock / kWave];
     __shared__ unsigned int sm_c[kBlock / kWave];
@@ -406,6 +416,7 @@ __device__ inline void flush_round_counters(float rmax, unsigned long long edges
         if (changed) atomicAdd(&p->changed, changed);
         if (rows) atomicAdd(long_rows ? &p->rows_long : &p->rows_short, rows);
     }
+    return changed;
 }
 
 // Short rows: G lanes per row, grid-strided (body; k_row_update dispatches to it).
@@ -429,14 +440,14 @@ __device__ inline void flush_round_counters(float rmax, unsigned long long edges
 //            outside V_aff is copied to F_out when that is another buffer, so the two keep agreeing there.
 constexpr int kRowByVertex = 1, kRowLazy = 2;
 
-template <int CP, int G, bool STAGED, bool PULL = false>
-__device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, const int32_t* __restrict__ front,
+template <int CP, int G, bool STAGED, bool PULL = false, bool COH = false>
+__device__ inline unsigned int row_update_short(unsigned int bid, unsigned int nblocks, const int32_t* __restrict__ front,
                                         unsigned int ns, const RowMeta* __restrict__ meta,
                                         const Edge* __restrict__ pool, const float* F_in,
                                         float* F_out, int by_vertex, uint8_t* __restrict__ flag,
                                         unsigned int* __restrict__ moved, float tol,
                                         RoundCtr* __restrict__ ctr,
-                                        const unsigned int* __restrict__ moved_prev = nullptr) {
+                                        const unsigned int* moved_prev = nullptr) {
     constexpr int VEC = RowShape<CP>::VEC;
     constexpr int LPN = RowShape<CP>::LPN;
     constexpr int GPB = kBlock / G;
@@ -453,17 +464,17 @@ __device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, 
         const RowMeta m = meta[u];
         const Edge* __restrict__ row = pool + m.off;
         if (PULL) {
-            bool in_front = moved_bit(moved_prev, u);
+            bool in_front = moved_bit_c<COH>(moved_prev, u);
             for (int base = 0; base < m.len && !in_front; base += G) {  // uniform in the group
                 const int idx = base + gl;
-                const bool hit = idx < m.len && moved_bit(moved_prev, row[idx].col);
+                const bool hit = idx < m.len && moved_bit_c<COH>(moved_prev, row[idx].col);
                 const unsigned long long b = __ballot(hit);
                 const unsigned long long mine = G == kWave ? b : (b >> ((lane_id() / G) * G)) & ((1ull << (G & 63)) - 1ull);
                 in_front = mine != 0ull;
             }
             if (!in_front) {
                 if (F_out != F_in && slot == 0)
-                    store_vec<VEC>(F_out + (size_t)u * CP + chunk * VEC, load_vec<VEC>(F_in + (size_t)u * CP + chunk * VEC));
+                    store_row<VEC, COH>(F_out + (size_t)u * CP + chunk * VEC, load_row<VEC, COH>(F_in + (size_t)u * CP + chunk * VEC));
                 continue;
             }
             if (gl == 0) nrows += 1;
@@ -475,8 +486,8 @@ __device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, 
         Edge e;
         e.col = u;
         e.w = 0.f;
-        accumulate_row<CP, G>(row, m.len, 0, 1, u, F_in, gl, acc, s, e);
-        const Vec<VEC> old = load_vec<VEC>(F_in + (size_t)u * CP + chunk * VEC);
+        accumulate_row<CP, G, COH>(row, m.len, 0, 1, u, F_in, gl, acc, s, e);
+        const Vec<VEC> old = load_row<VEC, COH>(F_in + (size_t)u * CP + chunk * VEC);
         Vec<VEC> fn;
         float r = 0.f;
 #pragma unroll
@@ -487,7 +498,7 @@ __device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, 
         }
 #pragma unroll
         for (int d = 1; d < LPN; d <<= 1) r = fmaxf(r, __shfl_xor(r, d, G));
-        if (slot == 0) store_vec<VEC>(F_out + (size_t)(STAGED && !(by_vertex & kRowByVertex) ? g : (unsigned int)u) * CP + chunk * VEC, fn);
+        if (slot == 0) store_row<VEC, COH>(F_out + (size_t)(STAGED && !(by_vertex & kRowByVertex) ? g : (unsigned int)u) * CP + chunk * VEC, fn);
         const bool big = r > tol;
         if (STAGED) {
             if (big) {  // V_aff <- V_aff U {u} U N(u); the last chunk of the row is still in registers
@@ -505,20 +516,20 @@ __device__ inline void row_update_short(unsigned int bid, unsigned int nblocks, 
             nchanged += big ? 1u : 0u;
         }
     }
-    flush_round_counters(rmax, edges, nchanged, ctr, false, nrows);
+    return flush_round_counters(rmax, edges, nchanged, ctr, false, nrows);
 }
 
 // Long rows: one workgroup per row (body; k_row_update dispatches to it).  Its kBlock/G groups take the row's chunks round-robin; their
 // partial sums meet in LDS and are added in group order (a fixed order: results do not depend on
 // timing).  Position of long row j is pos_base + j.
-template <int CP, bool STAGED, bool PULL = false>
-__device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, const int32_t* __restrict__ back,
+template <int CP, bool STAGED, bool PULL = false, bool COH = false>
+__device__ inline unsigned int row_update_long(unsigned int bid, unsigned int nblocks, const int32_t* __restrict__ back,
                                        unsigned int nl, unsigned int pos_base, const RowMeta* __restrict__ meta,
                                        const Edge* __restrict__ pool, const float* F_in,
                                        float* F_out, int by_vertex, uint8_t* __restrict__ flag,
                                        unsigned int* __restrict__ moved, float tol,
                                        RoundCtr* __restrict__ ctr,
-                                       const unsigned int* __restrict__ moved_prev = nullptr) {
+                                       const unsigned int* moved_prev = nullptr) {
     constexpr int VEC = RowShape<CP>::VEC;
     constexpr int LPN = RowShape<CP>::LPN;
     constexpr int G = LPN > 16 ? LPN : 16;
@@ -540,14 +551,14 @@ __device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, c
         const RowMeta m = meta[u];
         const Edge* __restrict__ row = pool + m.off;
         if (PULL) {  // every decision below is uniform across the workgroup
-            bool in_front = moved_bit(moved_prev, u);
+            bool in_front = moved_bit_c<COH>(moved_prev, u);
             for (int base = 0; base < m.len && !in_front; base += kBlock) {
                 const int idx = base + (int)threadIdx.x;
-                in_front = __syncthreads_or(idx < m.len && moved_bit(moved_prev, row[idx].col)) != 0;
+                in_front = __syncthreads_or(idx < m.len && moved_bit_c<COH>(moved_prev, row[idx].col)) != 0;
             }
             if (!in_front) {
                 if (F_out != F_in && gi == 0 && slot == 0)
-                    store_vec<VEC>(F_out + (size_t)u * CP + chunk * VEC, load_vec<VEC>(F_in + (size_t)u * CP + chunk * VEC));
+                    store_row<VEC, COH>(F_out + (size_t)u * CP + chunk * VEC, load_row<VEC, COH>(F_in + (size_t)u * CP + chunk * VEC));
                 continue;
             }
             if (threadIdx.x == 0) nrows += 1;
@@ -559,7 +570,7 @@ __device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, c
         Edge e;
         e.col = u;
         e.w = 0.f;
-        accumulate_row<CP, G>(row, m.len, gi, NG, u, F_in, gl, acc, s, e);
+        accumulate_row<CP, G, COH>(row, m.len, gi, NG, u, F_in, gl, acc, s, e);
         if (slot == 0) {
 #pragma unroll
             for (int k = 0; k < VEC; ++k) part[gi][chunk * VEC + k] = acc.v[k];
@@ -576,7 +587,7 @@ __device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, c
                 for (int k = 0; k < VEC; ++k) tot.v[k] += part[q][chunk * VEC + k];
                 st += part_s[q];
             }
-            const Vec<VEC> old = load_vec<VEC>(F_in + (size_t)u * CP + chunk * VEC);
+            const Vec<VEC> old = load_row<VEC, COH>(F_in + (size_t)u * CP + chunk * VEC);
             Vec<VEC> fn;
             float r = 0.f;
 #pragma unroll
@@ -587,7 +598,7 @@ __device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, c
             }
 #pragma unroll
             for (int d = 1; d < LPN; d <<= 1) r = fmaxf(r, __shfl_xor(r, d, G));
-            store_vec<VEC>(F_out + (size_t)(STAGED && !(by_vertex & kRowByVertex) ? pos_base + j : (unsigned int)u) * CP + chunk * VEC, fn);
+            store_row<VEC, COH>(F_out + (size_t)(STAGED && !(by_vertex & kRowByVertex) ? pos_base + j : (unsigned int)u) * CP + chunk * VEC, fn);
             if (gl == 0) {
                 const bool big = r > tol;
                 sh_big = big ? 1 : 0;
@@ -604,7 +615,7 @@ __device__ inline void row_update_long(unsigned int bid, unsigned int nblocks, c
         }
         __syncthreads();
     }
-    flush_round_counters(rmax, edges, nchanged, ctr, true, nrows);
+    return flush_round_counters(rmax, edges, nchanged, ctr, true, nrows);
 }
 
 // One launch per round.  The frontier's size comes from the previous round's counter slot (prev), so
@@ -729,6 +740,206 @@ __global__ void __launch_bounds__(kBlock) k_row_update_pull(const RoundCtr* __re
     else
         row_update_short<CP, G, false, true>(blockIdx.x - long_blocks, gridDim.x - long_blocks, front, ns, meta, pool,
                                              F_in, F_out, 1, nullptr, moved_cur, tol, ctr, moved_prev);
+}
+
+// =================================================================================================
+// Several rounds in one launch, for graphs whose rounds are too short to be worth a launch each
+// =================================================================================================
+// On a graph of a few hundred thousand rows a round over all rows takes tens of microseconds, of which the
+// work is a small part: the rest is the launch, the ramp-up of thousands of short-lived workgroups and the
+// drain before the next launch may start.  k_rounds_persistent runs up to `rounds` consecutive rounds of the kind
+// k_row_update_pull runs (every updatable vertex decides from the previous round's bitmap whether it is in V_aff)
+// with a grid of workgroups that are all resident at once and a barrier across the grid between rounds.
+//
+// What crosses the barrier (label rows, bitmap words, counters) is read and written with device-scope accesses
+// (load_row / store_row / moved_bit_c with COH): every XCD has an L2 of its own, and writing back and invalidating
+// whole caches at every barrier costs ten times the round.
+//
+// The barrier is a two-level tree, so that no address is polled by more than kBarGroup workgroups (a word polled by
+// a thousand workgroups answers so slowly that the barrier alone took 100 us): a workgroup arrives at its group's
+// counter; the last arrival of a group arrives at the global counter; the last arrival there writes the release
+// word of every group, and every workgroup waits for the release word of its group only.  The arrivals carry along
+// whether the workgroup moved a row in the round, so that the release word also says whether any row moved at all:
+// if none did, V_aff is empty and every workgroup leaves the kernel.
+//
+// The wait is bounded.  After spin_limit polls a workgroup tries to give the barrier up for the whole grid: a
+// compare-and-swap sets the top bit of the global counter, and only succeeds while the last group has not arrived
+// there; the last arrival, in turn, does not release when it finds that bit set.  So either every workgroup is
+// released from barrier k or none is, and no round is ever run by a part of the grid.  Every workgroup completes the
+// work of a round before it looks at the barrier; whenever the kernel ends - all rounds done, V_aff empty, or a
+// barrier given up - the rounds whose counter slots say "executed" have been executed in full, and the host goes
+// on from there with ordinary launches.
+constexpr unsigned int kBarGroup = 32;              // workgroups per group
+constexpr unsigned int kBarWordsPerLine = 16;       // every counter and release word has a 64-byte line of its own
+constexpr unsigned int kBarMaxGroups = 128;
+constexpr unsigned int kBarGivenUp = 0x80000000u;   // global counter: the barrier was given up
+constexpr unsigned int kBarMovedUnit = 0x10000u;    // counters: arrivals in the low 16 bits, arrivals that moved rows above
+constexpr unsigned int kRelStop = 0x40000000u;      // release word: no row moved in the round
+constexpr unsigned int kRelFail = 0x80000000u;      // release word: the barrier was given up
+// words: [0] global counter, [1] "a barrier was given up" for the host, then one line per group counter, then one
+// line per release word
+constexpr unsigned int kBarWords = kBarWordsPerLine * (1 + 2 * kBarMaxGroups);
+
+struct PersistArgs {
+    RoundCtr* ring;               // kRing slots
+    int t0;                       // round number of the first round (>= 1)
+    int rounds;
+    unsigned int long_blocks_max;
+    const int32_t* front;         // list of all updatable vertices: short rows from the front, long rows from the back
+    const int32_t* back;
+    unsigned int ns, nl;
+    const RowMeta* meta;
+    const Edge* pool;
+    float* buf0;                  // round t0 + r reads buf[r & 1] and writes buf[(r + 1) & 1] (one array in place)
+    float* buf1;
+    unsigned int* moved0;         // the three bitmaps; the round with stretch index q reads (q - 1) % 3, sets q % 3
+    unsigned int* moved1;         // and clears (q + 1) % 3
+    unsigned int* moved2;
+    int q0;                       // stretch index of the first round (>= 1)
+    unsigned int words;
+    float tol;
+    unsigned int* barrier;        // kBarWords words, all zero at launch
+    unsigned int ngroups;         // ceil(gridDim.x / kBarGroup) <= kBarMaxGroups
+    unsigned int spin_limit;
+};
+
+__device__ inline unsigned int load_fresh(const unsigned int* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ inline void store_through(unsigned int* p, unsigned int v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Barrier number k (1, 2, ...) of the launch.  moved: this workgroup moved at least one row in the round (thread 0's
+// value counts).  Returns 1: released, some row moved; 2: released, no row moved anywhere; 0: given up.
+__device__ inline int grid_barrier(unsigned int* bar, unsigned int k, unsigned int ngroups, bool moved,
+                                   unsigned int spin_limit) {
+    __shared__ int sh_res;
+    // every wave: its stores and atomics of this round (all of them device-scope, write-through accesses) have been
+    // acknowledged before the workgroup reports its arrival
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned int g = blockIdx.x / kBarGroup;
+        const unsigned int first = g * kBarGroup;
+        const unsigned int gsize = gridDim.x - first < kBarGroup ? gridDim.x - first : kBarGroup;
+        unsigned int* global = bar;
+        unsigned int* gctr = bar + kBarWordsPerLine * (1 + g);
+        unsigned int* rel = bar + kBarWordsPerLine * (1 + ngroups + g);
+        auto release_all = [&](unsigned int word) {
+            for (unsigned int i = 0; i < ngroups; ++i) store_through(bar + kBarWordsPerLine * (1 + ngroups + i), word);
+        };
+        const unsigned int add = 1u + (moved ? kBarMovedUnit : 0u);
+        const unsigned int in_group = atomicAdd(gctr, add) + add;
+        if ((in_group & 0xffffu) == gsize * k) {
+            // last of the group: take the group's "moved" count out again and arrive at the global counter
+            const unsigned int group_moved = in_group & 0xffff0000u;
+            if (group_moved) atomicSub(gctr, group_moved);
+            const unsigned int gadd = 1u + (group_moved ? kBarMovedUnit : 0u);
+            const unsigned int old = atomicAdd(global, gadd);
+            const unsigned int now = old + gadd;
+            if (old & kBarGivenUp) {
+                release_all(kRelFail | k);
+            } else if ((now & 0xffffu) == ngroups * k) {
+                // last of all: nobody else touches the global counter until the next round's arrivals
+                const unsigned int any_moved = now & 0x7fff0000u;
+                if (any_moved) atomicSub(global, any_moved);
+                release_all(k | (any_moved ? 0u : kRelStop));
+            }
+        }
+        int res = -1;
+        unsigned int spins = 0;
+        while (res < 0) {
+            const unsigned int w = load_fresh(rel);
+            if (w & kRelFail) {
+                res = 0;
+            } else if ((w & 0xffffu) == k) {
+                res = (w & kRelStop) ? 2 : 1;
+            } else if (++spins > spin_limit) {
+                // give up for everybody, unless the last group has arrived by now (then the release is on its way)
+                const unsigned int v = load_fresh(global);
+                if (v & kBarGivenUp) {
+                    res = 0;
+                } else if ((v & 0xffffu) >= ngroups * k) {
+                    spins = 0;
+                } else if (atomicCAS(global, v, v | kBarGivenUp) == v) {
+                    release_all(kRelFail | k);
+                    res = 0;
+                }
+            } else {
+                __builtin_amdgcn_s_sleep(16);
+            }
+        }
+        if (res == 0) store_through(&bar[1], 1u);  // for the host
+        sh_res = res;
+    }
+    __syncthreads();
+    const int res = sh_res;
+    __syncthreads();  // sh_res may be rewritten by the next barrier
+    return res;
+}
+
+template <int CP, int G>
+__global__ void __launch_bounds__(kBlock) k_rounds_persistent(PersistArgs a) {
+    __shared__ unsigned int sh_go;
+    unsigned int* const moved[3] = {a.moved0, a.moved1, a.moved2};
+    float* const buf[2] = {a.buf0, a.buf1};
+    const unsigned int long_blocks = a.nl < a.long_blocks_max ? a.nl : a.long_blocks_max;
+    {
+        // the round before the launch: did it run, and did it move a row?  (every later round learns this from the
+        // barrier)
+        const RoundCtr* prev = a.ring + ((a.t0 - 1) % kRing);
+        if (threadIdx.x < kWave) {
+            unsigned int prev_changed = lane_id() < kCtrLanes ? load_fresh(&prev->part[lane_id()].changed) : 0u;
+            prev_changed = wave_sum(prev_changed);
+            if (threadIdx.x == 0) sh_go = (load_fresh(&prev->executed) != 0u && prev_changed != 0u) ? 1u : 0u;
+        }
+        __syncthreads();
+        if (sh_go == 0u) return;  // the same for every workgroup
+    }
+    for (int r = 0; r < a.rounds; ++r) {
+        const int t = a.t0 + r;
+        RoundCtr* ctr = a.ring + (t % kRing);
+        RoundCtr* ctr_zero = a.ring + ((t + 1) % kRing);
+        if (blockIdx.x == 0) {  // write-through stores: the slot's next user may sit on another XCD
+            auto put64 = [](unsigned long long* p, unsigned long long v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+            if (threadIdx.x == 0) {
+                store_through(&ctr_zero->next_count, 0u);
+                store_through(&ctr_zero->next_long, 0u);
+                store_through(&ctr_zero->executed, 0u);
+                store_through(&ctr_zero->rows_short, 0u);
+                store_through(&ctr_zero->rows_long, 0u);
+                store_through(&ctr->executed, 1u);
+            }
+            if (threadIdx.x < kCtrLanes) {
+                RoundPart* p = &ctr_zero->part[threadIdx.x];
+                store_through(&p->resid_bits, 0u);
+                store_through(&p->changed, 0u);
+                put64(&p->edges, 0ull);
+                put64(&p->edges_long, 0ull);
+                store_through(&p->rows_short, 0u);
+                store_through(&p->rows_long, 0u);
+            }
+        }
+        const int q = a.q0 + r;
+        unsigned int* moved_clear = moved[(q + 1) % 3];
+        for (unsigned int w = blockIdx.x * kBlock + threadIdx.x; w < a.words; w += gridDim.x * kBlock)
+            store_through(&moved_clear[w], 0u);
+        const float* F_in = buf[r & 1];
+        float* F_out = buf[(r + 1) & 1];
+        unsigned int block_moved;
+        if (blockIdx.x < long_blocks)
+            block_moved = row_update_long<CP, false, true, true>(blockIdx.x, long_blocks, a.back, a.nl, a.ns, a.meta, a.pool,
+                                                                 F_in, F_out, 1, nullptr, moved[q % 3], a.tol, ctr,
+                                                                 moved[(q + 2) % 3]);
+        else
+            block_moved = row_update_short<CP, G, false, true, true>(blockIdx.x - long_blocks, gridDim.x - long_blocks, a.front,
+                                                                     a.ns, a.meta, a.pool, F_in, F_out, 1, nullptr,
+                                                                     moved[q % 3], a.tol, ctr, moved[(q + 2) % 3]);
+        if (r + 1 == a.rounds) return;
+        if (grid_barrier(a.barrier, (unsigned int)(r + 1), a.ngroups, block_moved != 0u, a.spin_limit) != 1) return;
+    }
 }
 
 }  // namespace dynlp

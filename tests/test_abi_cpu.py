@@ -40,7 +40,7 @@ def test_stats_and_options_layout_match_header():
     assert B.Stats.rows_updated.offset == 16
     assert B.Stats.ms_update_kernel.offset == 64
     assert B.Options.stream.offset == 8 and B.Options.slack_factor.offset == 20
-    assert B.Options.alloc.offset == 48 and B.Options.binary_scalar.offset == 72 and ct.sizeof(B.Options) == 88 and B.Options.ingest_chunk_edges.offset == 80
+    assert B.Options.alloc.offset == 48 and B.Options.binary_scalar.offset == 72 and ct.sizeof(B.Options) == 96 and B.Options.persistent_rounds.offset == 80 and B.Options.ingest_chunk_edges.offset == 88
 
 
 def _tiny():

@@ -318,17 +318,18 @@ def test_first_rounds_of_a_batch_match_the_oracle_step_by_step(kind, C, R_):
 
 
 @pytest.mark.parametrize("tol", [TOL, 2e-5])
-@pytest.mark.parametrize("deg,C,kinds", [(9.0, 10, {0, 2}), (40.0, 50, {0})])
-def test_rounds_over_nearly_all_vertices_match_the_oracle_round_by_round(deg, C, kinds, tol):
+@pytest.mark.parametrize("deg,C,kinds,persistent", [(9.0, 10, {0, 2}, -1), (9.0, 10, {0, 4}, 1), (40.0, 50, {0}, -1)])
+def test_rounds_over_nearly_all_vertices_match_the_oracle_round_by_round(deg, C, kinds, persistent, tol):
     """Once V_aff holds nearly every vertex the library stops keeping a frontier list.  Light rows (few bytes per
-    update): the rounds decide membership per row themselves; heavy rows: row update and pull stay two launches.
-    Either way every round must work on exactly the oracle's V_aff."""
+    update): the rounds decide membership per row themselves (kind 2), on small graphs many rounds per launch from
+    the batch's first round on (kind 4); heavy rows: row update and pull stay two launches.  Either way every round
+    must work on exactly the oracle's V_aff."""
     R_ = 30 if tol == TOL else 2000
     p = W.small_random(3000, C, deg, 150, 4100 + C)
     p0 = W.small_random(3000, C, deg, 150, 4100 + C)
     b = W.small_random_batch(p, 300, int(deg), 5, num_extra_edges=40, num_revealed=2)
     g = _oracle_graph(p0)
-    with _make(p0) as d:
+    with _make(p0, persistent_rounds=persistent) as d:
         st, _ = d.static_solve(TOL, 20000)
         assert st == 0
         soft0, _ = d.get_labels()
