@@ -24,6 +24,22 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+_T0 = time.perf_counter()
+
+
+def progress(msg: str) -> None:
+    """One line per finished phase on stderr (stdout carries only the JSON line)."""
+    print(f"[bench {time.perf_counter() - _T0:7.1f} s] {msg}", file=sys.stderr, flush=True)
+
+
+def counted(n: int, what: str):
+    """range(n) that reports on stderr whenever 20 s have passed since its last line."""
+    last = time.perf_counter()
+    for i in range(n):
+        yield i
+        if time.perf_counter() - last > 20.0:
+            progress(f"{what}: {i + 1}/{n}")
+            last = time.perf_counter()
 
 
 def algorithmic_bytes(rows: int, edges: int, C: int) -> int:
@@ -46,7 +62,9 @@ def build_workload(name: str, batch_frac: float, num_batches: int, batch_kind: s
     import workloads as W
 
     cfg = W.CONFIGS[name]
+    progress(f"generating the base graph of {name}")
     p = W.make_config(name, scale)
+    progress(f"base graph: n = {p.n}, {int(p.row_ptr[-1])} entries; generating {num_batches} batches")
     base = dict(n=p.n, C=p.C, row_ptr=p.row_ptr, col=p.col, w=p.w, seed_vertex=p.seed_vertex,
                 seed_class=p.seed_class)
     batches = []
@@ -56,7 +74,7 @@ def build_workload(name: str, batch_frac: float, num_batches: int, batch_kind: s
         k = max(1, int(round(batch_frac * cfg["n"])))
         deg = int(cfg.get("batch_degree", cfg.get("mean_degree", cfg.get("k", 10))))
         intra, cross = max(1, deg // 5), max(1, deg // 10)
-        for _ in range(num_batches):
+        for _ in counted(num_batches, 'batches generated'):
             batches.append(W.clustered_batch(p, k, 8.0, intra, cross, max(1, deg - intra - cross),
                                              max(1, int(round(cfg["seed_frac"] * k)))))
         label = (f"{name}: base graph n={cfg['n']} C={cfg['C']}, clustered batches of {k} new vertices "
@@ -64,21 +82,21 @@ def build_workload(name: str, batch_frac: float, num_batches: int, batch_kind: s
                  f"{max(1, deg - intra - cross)} among old vertices)")
     elif cfg["kind"] == "sbm":
         k = max(1, int(round(batch_frac * cfg["n"])))
-        for _ in range(num_batches):
+        for _ in counted(num_batches, 'batches generated'):
             batches.append(W.sbm_vertex_batch(p, k, cfg["batch_degree"], cfg["seed_frac"]))
         label = f"{name}: SBM n={cfg['n']} C={cfg['C']} mean degree {cfg['mean_degree']:g}, batches of {k} new vertices x degree {cfg['batch_degree']}"
     elif cfg["kind"] == "sbm-edge-stream":
-        for _ in range(num_batches):
+        for _ in counted(num_batches, 'batches generated'):
             batches.append(W.sbm_edge_batch(p, cfg["edges_per_batch"], cfg["intra_frac"], cfg["revealed_per_batch"]))
         label = f"{name}: SBM n={cfg['n']} C={cfg['C']}, edge-only batches of {cfg['edges_per_batch']} edges + {cfg['revealed_per_batch']} revealed seeds"
     elif cfg["kind"] == "knn":
         k = max(1, int(round(batch_frac * cfg["n"])))
-        for _ in range(num_batches):
+        for _ in counted(num_batches, 'batches generated'):
             batches.append(W.knn_mixture_batch(p, k, max(1, int(round(cfg["seed_frac"] * k)))))
         label = f"{name}: kNN mixture n={cfg['n']} C={cfg['C']} k={cfg['k']}, batches of {k} new points"
     elif cfg["kind"] == "chung_lu":
         k = max(1, int(round(batch_frac * cfg["n"])))
-        for _ in range(num_batches):
+        for _ in counted(num_batches, 'batches generated'):
             batches.append(W.chung_lu_vertex_batch(p, k, cfg["seed_frac"]))
         label = f"{name}: Chung-Lu n={cfg['n']} C={cfg['C']} mean degree {cfg['mean_degree']:g}, batches of {k} new vertices"
     elif cfg["kind"] == "er-single-batch":
@@ -112,6 +130,7 @@ def cpu_baseline(base, batches_applied, batch, F_before, tol, gpu_edges_traverse
         t0 = time.perf_counter()
         F, _ = ON.itlp_sweep(base["row_ptr"], base["col"], w64, F, sc)
         probe = time.perf_counter() - t0
+        progress(f"oracle: one sweep of the base graph takes {probe:.2f} s")
         sweeps = int(max(1, min(1000, 0.8 * budget_s / max(probe, 1e-3))))
         t0 = time.perf_counter()
         for _ in range(sweeps):
@@ -135,6 +154,7 @@ def cpu_baseline(base, batches_applied, batch, F_before, tol, gpu_edges_traverse
     n_old = g.n
     g.insert(batch.num_new_vertices, batch.eu, batch.ev, batch.ew, batch.seed_vertex, batch.seed_class)
     rp, col, w = g.csr()
+    progress("oracle: graph with the first timed batch built")
     F = np.concatenate([F_before.astype(np.float64), np.full((batch.num_new_vertices, g.C), 1.0 / g.C)])
     s = np.asarray(batch.seed_vertex, dtype=np.int64)
     F[s] = 0
@@ -179,6 +199,7 @@ def residual_after(base, applied, F_last, tol, rounds_total):
     sc[base["seed_vertex"]] = base["seed_class"]
     sc[allb.seed_vertex] = allb.seed_class
     t_build = time.perf_counter() - t0
+    progress(f"harness-built updated graph ready ({t_build:.1f} s)")
     t0 = time.perf_counter()
     _, res = ON.itlp_sweep(rp, col, w.astype(np.float64), F_last.astype(np.float64), sc)
     t_sweep = time.perf_counter() - t0
@@ -257,6 +278,7 @@ def main():
     batches = batches[:args.warmup + args.steps]
     tol = float(args.tol if args.tol is not None else cfg["tol"])
     t_gen = time.perf_counter() - t_gen
+    progress(f"workload ready ({t_gen:.1f} s)")
 
     pinned_keep = []
 
@@ -317,6 +339,7 @@ def main():
         return ctx, st_, s_, t_
 
     d, st, s0, tau = new_context()
+    progress(f"cold start: {s0.iterations} sweeps, {s0.ms_total:.1f} ms")
     # what plain streaming kernels sustain on this machine: 1 GiB copy (read + write) and 1 GiB read-only pass
     copy_gbs, read_gbs = d.stream_bandwidth(1 << 30, 10)
     # ... and what random whole-row gathers of this workload's stored row size sustain in a table of its vertex count
@@ -356,6 +379,7 @@ def main():
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         rounds_all += s.iterations
+        progress(f"batch {i + 1}/{len(d_batches)} ({'timed' if timed else 'warm-up'}): {dt * 1e3:.1f} ms, {s.iterations} rounds")
         if timed:
             per_step.append(dict(ms=dt * 1e3, status=st, edges=batches[i].num_edges, **s.as_dict()))
             if tau is not None:
@@ -400,6 +424,7 @@ def main():
             rounds_.append(s.iterations)
             kms_.append(round(s.ms_update_kernel, 2))
             rounds_all += s.iterations
+        progress(f"{len(ms_)} batches in the {other} mode: {ms_} ms")
         mode_block = dict(update_mode=other, batches=len(ms_), ms_per_batch=ms_, rounds=rounds_, ms_update_kernel=kms_,
                           inserted_edges_per_s=sum(b.num_edges for b in mode_batches) / max(1e-9, sum(ms_) / 1e3))
         d.set_update_mode(P.UPDATE_IN_PLACE if args.update_mode == "in-place" else P.UPDATE_SYNCHRONOUS)
@@ -423,6 +448,7 @@ def main():
                 q[1] += int(r.rows_short + r.rows_long)
                 q[2] += int(r.entries_short + r.entries_long)
                 q[3] += float(r.ms_update)
+        progress(f"{len(xs)} batches at delta = 1e-4: {[round(x['ms'], 1) for x in xs]} ms")
         CPx = next(c for c in (1, 2, 4, 8, 16, 32, 64) if c >= Cs)
         kx = {}
         for (staged, glanes), (cnt, rws, ent, ms) in xb.items():
@@ -530,15 +556,18 @@ def main():
                    "deleted_per_step": [int(len(x)) for x in dels[args.warmup:]]},
     }
     if args.cpu_budget > 0 and per_step and not fresh:
+        progress("CPU oracle baseline")
         out["cpu_baseline"] = cpu_baseline(base, batches[:args.warmup], batches[args.warmup], F_before, tol,
                                            per_step[0]["edges_traversed"], args.cpu_budget, F_cold=F_cold, F_after=F_after)
     else:
         out["cpu_baseline"] = None
     if out["cpu_baseline"] is not None and F_last is not None:
+        progress("oracle sweep over the labels after the last batch")
         out["cpu_baseline"]["oracle_residual_after_last_batch"] = residual_after(
             base, batches, F_last, tol, rounds_all)
     d.destroy()
-    print(json.dumps(out))
+    progress("done")
+    print(json.dumps(out), flush=True)
 
 
 if __name__ == "__main__":
