@@ -124,6 +124,8 @@ struct dynlp_ctx {
 
     int32_t* touched = nullptr;
     int64_t* reloc_off = nullptr;
+    int32_t* he_rank = nullptr;  // per half-edge of the batch: its place among the entries appended to its row (or NULL)
+    int64_t he_rank_cap = 0;
     int64_t touched_cap = 0;
     int32_t *b_eu = nullptr, *b_ev = nullptr, *b_sv = nullptr, *b_sc = nullptr;
     float* b_ew = nullptr;
@@ -158,7 +160,6 @@ struct dynlp_ctx {
     // per stored entry, rows in vertex order
     unsigned int* pb_src = nullptr;    // its row
     unsigned short* pb_lpos = nullptr;  // its position in its chunk once sorted by slot
-    unsigned int* pb_oslot = nullptr;  // per chunk position: the slot behind it
     float* pb_tmp = nullptr;           // build scratch: the entries' weights in stream order
     // per slot
     unsigned short* pb_dst = nullptr;
@@ -409,6 +410,13 @@ void ensure_batch_scratch(dynlp_ctx* c, int64_t m, int64_t s) {
         c->reloc_off = dev_alloc_n<int64_t>(c, cap);
         c->touched_cap = cap;
     }
+    // optional (the insertion falls back to a second atomic per half-edge without it)
+    if (2 * m > c->he_rank_cap) {
+        dev_free(c, c->he_rank);
+        c->he_rank_cap = 0;
+        c->he_rank = static_cast<int32_t*>(dev_try_alloc(c, (size_t)(3 * m) * sizeof(int32_t)));
+        if (c->he_rank) c->he_rank_cap = 3 * m;
+    }
     if (!c->dev_ptrs) {
         if (m > c->b_edge_cap) {
             dev_free(c, c->b_eu);
@@ -517,7 +525,8 @@ void ingest_edges(dynlp_ctx* c, int64_t m, int64_t n_total, const int32_t* eu, c
         hipLaunchKernelGGL(k_validate_edges, dim3(grid_for(mc)), dim3(kBlock), 0, c->stream, mc, n_total, c->b_eu + off,
                            c->b_ev + off, c->b_ew + off, c->bc, off);
         hipLaunchKernelGGL(k_count_halfedges, dim3(grid_for(ceil_div(2 * mc, kAppendItems))), dim3(kBlock), 0, c->stream, mc,
-                           n_total, c->b_eu + off, c->b_ev + off, c->add_cnt, c->touched, c->bc);
+                           n_total, c->b_eu + off, c->b_ev + off, c->add_cnt, c->touched, c->bc,
+                           c->he_rank ? c->he_rank + off : nullptr, c->he_rank ? c->he_rank + m + off : nullptr);
         HIPCHK(c, hipGetLastError());
     }
     c->ingest_chunks_last = chunks;
@@ -821,10 +830,10 @@ bool binned_rounds_pay(const dynlp_ctx* c, const Frontier& universe) {
 
 // Free every array of the binned rounds.
 void free_binned(dynlp_ctx* c) {
-    void* all[] = {c->pb_src, c->pb_lpos, c->pb_oslot, c->pb_tmp, c->pb_dst, c->pb_wn, c->pb_val,
+    void* all[] = {c->pb_src, c->pb_lpos, c->pb_tmp, c->pb_dst, c->pb_wn, c->pb_val,
                    c->pb_len, c->pb_upd, c->pb_first, c->pb_block, c->pb_bin, c->pb_table};
     for (void* q : all) dev_free(c, q);
-    c->pb_src = c->pb_oslot = c->pb_val = c->pb_upd = c->pb_first = c->pb_block = c->pb_bin = c->pb_table = nullptr;
+    c->pb_src = c->pb_val = c->pb_upd = c->pb_first = c->pb_block = c->pb_bin = c->pb_table = nullptr;
     c->pb_lpos = c->pb_dst = nullptr;
     c->pb_tmp = c->pb_wn = nullptr;
     c->pb_len = nullptr;
@@ -838,6 +847,14 @@ bool try_alloc_n(dynlp_ctx* c, T*& p, int64_t count) {
     return p != nullptr;
 }
 
+// Lanes that share one (chunk, bin) run when it is written out (log2): the mean run length rounded up to a power of
+// two, 16 .. 1,024 (8 / 16 / 32 lanes on runs of 11 entries: 1.79 / 1.71 / 1.73 ms per round).
+int pb_run_lanes(int nbins) {
+    int lg = 4;
+    while (lg < 10 && ((int64_t)nbins << lg) < kPbChunk) ++lg;
+    return lg;
+}
+
 // Slots, per-slot receiver offsets and normalised weights for the graph as it stands.  False (and nothing kept)
 // when the arrays cannot be allocated: the caller then runs ordinary rounds.
 bool build_binned(dynlp_ctx* c) {
@@ -846,14 +863,14 @@ bool build_binned(dynlp_ctx* c) {
     const int chunks = (int)ceil_div(std::max<int64_t>(c->entries, 1), kPbChunk);
     bool ok = true;
     if ((int64_t)chunks * kPbChunk > c->pb_ent_cap) {
-        void* old[] = {c->pb_src, c->pb_lpos, c->pb_oslot, c->pb_tmp, c->pb_dst, c->pb_wn, c->pb_val};
+        void* old[] = {c->pb_src, c->pb_lpos, c->pb_tmp, c->pb_dst, c->pb_wn, c->pb_val};
         for (void* q : old) dev_free(c, q);
-        c->pb_src = c->pb_oslot = c->pb_val = nullptr;
+        c->pb_src = c->pb_val = nullptr;
         c->pb_lpos = c->pb_dst = nullptr;
         c->pb_tmp = c->pb_wn = nullptr;
         c->pb_ent_cap = 0;
         const int64_t cap = round_up(c->entries + c->entries / 8 + 1, kPbChunk);
-        ok = try_alloc_n(c, c->pb_src, cap) && try_alloc_n(c, c->pb_lpos, cap) && try_alloc_n(c, c->pb_oslot, cap) &&
+        ok = try_alloc_n(c, c->pb_src, cap) && try_alloc_n(c, c->pb_lpos, cap) &&
              try_alloc_n(c, c->pb_tmp, cap) && try_alloc_n(c, c->pb_dst, cap) && try_alloc_n(c, c->pb_wn, cap) &&
              try_alloc_n(c, c->pb_val, cap);
         if (ok) c->pb_ent_cap = cap;
@@ -869,11 +886,12 @@ bool build_binned(dynlp_ctx* c) {
         if (ok) c->pb_vcap = c->n_cap;
     }
     if (ok && !c->pb_bin) ok = try_alloc_n(c, c->pb_bin, 2 * (kPbMaxBins + 1));
-    if (ok && (int64_t)chunks * nbins > c->pb_table_cap) {
+    // rows 0 .. chunks of the table, then kPbSegs rows of segment sums
+    if (ok && ((int64_t)chunks + 1 + kPbSegs) * nbins > c->pb_table_cap) {
         dev_free(c, c->pb_table);
         c->pb_table = nullptr;
         c->pb_table_cap = 0;
-        const int64_t cap = (int64_t)chunks * nbins + (int64_t)chunks * nbins / 8;
+        const int64_t cap = ((int64_t)chunks + 1 + kPbSegs) * nbins + (int64_t)chunks * nbins / 8;
         ok = try_alloc_n(c, c->pb_table, cap);
         if (ok) c->pb_table_cap = cap;
     }
@@ -906,12 +924,17 @@ bool build_binned(dynlp_ctx* c) {
                        c->pb_src, ecol, c->pb_tmp);
     hipLaunchKernelGGL(k_pb_count, dim3(chunks), dim3(kBlock), 0, c->stream, num_entries, bits, nbins, ecol, c->pb_upd,
                        c->pb_table);
-    hipLaunchKernelGGL(k_pb_chunk_bases, dim3(grid_for(nbins)), dim3(kBlock), 0, c->stream, nbins, chunks, c->pb_table,
+    unsigned int* seg = c->pb_table + ((size_t)chunks + 1) * nbins;
+    const dim3 col_grid(grid_for(nbins), kPbSegs);
+    hipLaunchKernelGGL(k_pb_seg_sums, col_grid, dim3(kBlock), 0, c->stream, nbins, chunks, c->pb_table, seg);
+    hipLaunchKernelGGL(k_pb_seg_scan, dim3(grid_for(nbins)), dim3(kBlock), 0, c->stream, nbins, chunks, seg, c->pb_table,
                        bin_count);
+    hipLaunchKernelGGL(k_pb_chunk_bases, col_grid, dim3(kBlock), 0, c->stream, nbins, chunks, seg, c->pb_table);
     hipLaunchKernelGGL(k_pb_offsets, dim3(1), dim3(kBlock), 0, c->stream, nbins, bin_count, bin_off);
-    hipLaunchKernelGGL(k_pb_place, dim3(chunks), dim3(kBlock), 0, c->stream, num_entries, bits, nbins, ecol, c->pb_tmp,
-                       c->pb_upd, c->pb_table, bin_off, c->pb_lpos, c->pb_oslot, c->pb_dst, c->pb_wn);
-    hipLaunchKernelGGL(k_pb_normalise, dim3(nbins), dim3(kBlock), 0, c->stream, bits, bin_off, c->pb_dst, c->deg, c->pb_wn);
+    hipLaunchKernelGGL(k_pb_place, dim3(chunks), dim3(kPbPlaceThreads), 0, c->stream, num_entries, bits, nbins,
+                       pb_run_lanes(nbins), ecol, c->pb_tmp, c->pb_upd, c->pb_table, bin_off, c->pb_lpos, c->pb_dst, c->pb_wn);
+    hipLaunchKernelGGL(k_pb_normalise, dim3(nbins * kPbNormParts), dim3(kBlock), 0, c->stream, bits, bin_off, c->pb_dst,
+                       c->deg, c->pb_wn);
     HIPCHK(c, hipGetLastError());
     c->pb_bits = bits;
     c->pb_bins = nbins;
@@ -947,9 +970,19 @@ bool build_binned(dynlp_ctx* c) {
 void launch_pb_scatter(dynlp_ctx* c, const RoundCtr* prev, int chunk0, int nchunks, const float* F, const unsigned int* bits,
                        unsigned int* moved_clear, RoundCtr* ctr_zero, const unsigned int* bits_also = nullptr) {
     if (nchunks <= 0 && !ctr_zero && !moved_clear) return;
-    hipLaunchKernelGGL(k_pb_scatter, dim3(8 * (unsigned int)std::max<int64_t>(1, ceil_div(nchunks, 8))), dim3(kPbScatterThreads), 0,
-                       c->stream, prev, c->pb_first + c->n, (unsigned int)chunk0, (unsigned int)std::max(nchunks, 0), c->pb_src,
-                       c->pb_lpos, c->pb_oslot, F, bits, bits_also, moved_clear, (unsigned int)c->moved_words, c->pb_val, ctr_zero);
+    const int lg = pb_run_lanes(c->pb_bins);
+    const dim3 grid(8 * (unsigned int)std::max<int64_t>(1, ceil_div(nchunks, 8)));
+    const unsigned int* bin_off = c->pb_bin + (kPbMaxBins + 1);
+    if (c->pb_bins <= 2048)
+        hipLaunchKernelGGL(k_pb_scatter<2048>, grid, dim3(kPbScatterThreads), 0, c->stream, prev, c->pb_first + c->n,
+                           (unsigned int)chunk0, (unsigned int)std::max(nchunks, 0), c->pb_bins, lg, c->pb_src, c->pb_lpos,
+                           c->pb_table, bin_off, F, bits, bits_also, moved_clear, (unsigned int)c->moved_words, c->pb_val,
+                           ctr_zero);
+    else
+        hipLaunchKernelGGL(k_pb_scatter<kPbMaxBins>, grid, dim3(kPbScatterThreads), 0, c->stream, prev, c->pb_first + c->n,
+                           (unsigned int)chunk0, (unsigned int)std::max(nchunks, 0), c->pb_bins, lg, c->pb_src, c->pb_lpos,
+                           c->pb_table, bin_off, F, bits, bits_also, moved_clear, (unsigned int)c->moved_words, c->pb_val,
+                           ctr_zero);
 }
 
 // One binned round (arguments as for the fused round).  `first_of_stretch`: no binned round has run since the slots
@@ -961,14 +994,18 @@ void launch_pb_scatter(dynlp_ctx* c, const RoundCtr* prev, int chunk0, int nchun
 // come later in this round and ranges that come earlier in the next one both have to learn that it moved, and each
 // sees only one publication.  V_aff of a round is then a superset of Alg. 2's (a row may be updated once more than
 // needed), as with any in-place round that reads rows the same round has already replaced.
+void launch_pb_gather(dynlp_ctx* c, const PullRoundArgs& a, int b0, int b1) {
+    const unsigned int* bin_off = c->pb_bin + (kPbMaxBins + 1);
+    hipLaunchKernelGGL(k_pb_gather, dim3(b1 - b0), dim3(kPbGatherThreads), 0, c->stream, a.prev, c->n, c->pb_bits, (unsigned int)b0,
+                       bin_off, c->pb_dst, c->pb_wn, c->pb_val, c->pb_len, a.F_in, a.F_out, a.moved_prev, a.moved_cur, a.tol,
+                       a.ctr);
+}
+
 void launch_binned_round(dynlp_ctx* c, const PullRoundArgs& a, int round, bool first_of_stretch) {
     hipEvent_t e1 = open_timed_span(c, round, 1);
-    const unsigned int* bin_off = c->pb_bin + (kPbMaxBins + 1);
     if (c->pb_parts <= 1) {
         launch_pb_scatter(c, a.prev, 0, c->pb_chunks, a.F_in, a.moved_prev, a.moved_clear, a.ctr_zero);
-        hipLaunchKernelGGL(k_pb_gather, dim3(c->pb_bins), dim3(kPbGatherThreads), 0, c->stream, a.prev, c->n, c->pb_bits, 0u,
-                           bin_off, c->pb_dst, c->pb_wn, c->pb_val, c->pb_len, a.F_in, a.F_out, a.moved_prev, a.moved_cur,
-                           a.tol, a.ctr);
+        launch_pb_gather(c, a, 0, c->pb_bins);
     } else {
         // bring every slot up to date once (labels and "moved in the previous round" bits); this launch also clears
         // the next round's counter slot and bitmap, as the first launch of every round does
@@ -976,10 +1013,7 @@ void launch_binned_round(dynlp_ctx* c, const PullRoundArgs& a, int round, bool f
         for (int i = 0; i < c->pb_parts; ++i) {
             const int b0 = c->pb_part_bin[i], b1 = c->pb_part_bin[i + 1];
             if (i == 0) launch_pb_scatter(c, a.prev, 0, 0, a.F_in, a.moved_prev, a.moved_clear, a.ctr_zero);
-            if (b1 > b0)
-                hipLaunchKernelGGL(k_pb_gather, dim3(b1 - b0), dim3(kPbGatherThreads), 0, c->stream, a.prev, c->n, c->pb_bits,
-                                   (unsigned int)b0, bin_off, c->pb_dst, c->pb_wn, c->pb_val, c->pb_len, a.F_in, a.F_out,
-                                   a.moved_prev, a.moved_cur, a.tol, a.ctr);
+            if (b1 > b0) launch_pb_gather(c, a, b0, b1);
             launch_pb_scatter(c, a.prev, c->pb_part_chunk[i][0], c->pb_part_chunk[i][1] - c->pb_part_chunk[i][0], a.F_out,
                               a.moved_cur, nullptr, nullptr, a.moved_prev);
         }
@@ -1190,9 +1224,9 @@ void destroy_ctx(dynlp_ctx* c) {
     (void)hipSetDevice(c->device);
     if (c->stream || c->meta) (void)hipStreamSynchronize(c->stream);
     void* ptrs[] = {c->meta, c->pool, c->F, c->F2, c->seed_class, c->flag, c->queue[0], c->queue[1], c->queue[2], c->moved[0], c->moved[1], c->moved[2], c->add_cnt,
-                    c->deg, c->touched, c->reloc_off, c->b_eu, c->b_ev, c->b_ew, c->b_sv, c->b_sc,
+                    c->deg, c->touched, c->reloc_off, c->he_rank, c->b_eu, c->b_ev, c->b_ew, c->b_sv, c->b_sc,
                     c->cc_par, c->cc_dense, c->cc_comp, c->cc_block, c->cc_kept, c->cc_W,
-                    c->pb_src, c->pb_lpos, c->pb_oslot, c->pb_tmp, c->pb_dst, c->pb_wn, c->pb_val, c->pb_len, c->pb_upd,
+                    c->pb_src, c->pb_lpos, c->pb_tmp, c->pb_dst, c->pb_wn, c->pb_val, c->pb_len, c->pb_upd,
                     c->pb_first, c->pb_block, c->pb_bin, c->pb_table};
     for (void* p : ptrs) dev_free(c, p);
     const std::vector<void*> left(c->live.begin(), c->live.end());  // arrays an interrupted call never got to free
@@ -1961,6 +1995,7 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
         // ---- capacity for new vertices; their rows start empty, unlabelled, uniform ----
         if (n1 > c->n_cap) alloc_vertex_arrays(c, n1 + std::max<int64_t>(n1 / 2, 1024));
         ensure_batch_scratch(c, m, s);
+        const bool use_rank = c->he_rank != nullptr;
         const int32_t *d_eu = eu, *d_ev = ev, *d_sv = sv, *d_sc = sc;
         const float* d_ew = ew;
         c->ingest_chunks_last = 0;
@@ -2045,7 +2080,8 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
             ingest_edges(c, m, n1, eu, ev, ew);
         else if (m > 0)
             hipLaunchKernelGGL(k_count_halfedges, dim3(grid_for(ceil_div(2 * m, kAppendItems))), dim3(kBlock), 0, c->stream, m, n1, d_eu, d_ev,
-                               c->add_cnt, c->touched, c->bc);
+                               c->add_cnt, c->touched, c->bc, use_rank ? c->he_rank : nullptr,
+                               use_rank ? c->he_rank + m : nullptr);
         HIPCHK(c, hipGetLastError());
         read_bc(c);
         unsigned int nt = c->h_bc->touched;
@@ -2055,12 +2091,14 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
             return bad(format_validation(c->h_bc->err_code, c->h_bc->err_index));
         }
         if (nt) {
-            hipLaunchKernelGGL(k_plan_sum, dim3(grid_for(nt)), dim3(kBlock), 0, c->stream, nt, c->touched, c->meta,
-                               c->add_cnt, c->slack, c->bc);
+            // room at the pool tail for the rows whose slack is too small: planned on the device (no row is touched
+            // yet), then the pool is made large enough for the plan
+            hipLaunchKernelGGL(k_plan_reserve, dim3(grid_for(nt)), dim3(kBlock), 0, c->stream, nt, c->touched, c->meta,
+                               c->add_cnt, c->slack, c->reloc_off, c->bc);
             HIPCHK(c, hipGetLastError());
             read_bc(c);
-            const int64_t need = (int64_t)c->h_bc->reloc_need;
-            if (c->pool_tail + need > c->pool_cap) grow_pool(c, c->pool_tail + need + need / 2);
+            const int64_t tail = (int64_t)c->h_bc->pool_tail;
+            if (tail > c->pool_cap) grow_pool(c, tail + (tail - c->pool_tail) / 2);
         }
         // ---- from here on the graph changes ----
         mutated = true;
@@ -2068,21 +2106,20 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
             hipLaunchKernelGGL(k_init_labels, dim3(grid_for(k * c->CP)), dim3(kBlock), 0, c->stream, n0, n1, c->C, c->Cs, c->coff,
                                c->CP, c->seed_class, c->F);
         if (nt) {
-            hipLaunchKernelGGL(k_plan_reserve, dim3(grid_for(nt)), dim3(kBlock), 0, c->stream, nt, c->touched, c->meta,
-                               c->add_cnt, c->slack, c->reloc_off, c->bc);
-            hipLaunchKernelGGL(k_relocate, dim3(grid_for((int64_t)nt * 16)), dim3(kBlock), 0, c->stream, nt, c->touched,
-                               c->meta, c->add_cnt, c->slack, c->reloc_off, c->pool);
+            hipLaunchKernelGGL(k_relocate, dim3(grid_for(nt)), dim3(kBlock), 0, c->stream, nt, c->touched, c->meta, c->add_cnt,
+                               c->slack, c->reloc_off, c->pool);
+            const int32_t* rank = use_rank ? c->he_rank : nullptr;
             hipLaunchKernelGGL(k_write_halfedges, dim3(grid_for(2 * m)), dim3(kBlock), 0, c->stream, m, d_eu, d_ev, d_ew,
-                               c->meta, c->pool);
-            // the batch's entries of every row in a fixed order (the relocation offsets are no longer needed:
-            // their array holds the list of rows with long appended segments)
+                               c->meta, c->pool, rank);
+            // the batch's entries of every row in a fixed order, then degree, scratch and V_aff flag of the row (the
+            // relocation offsets are no longer needed: their array holds the list of rows with long appended segments)
             int32_t* long_list = reinterpret_cast<int32_t*>(c->reloc_off);
-            hipLaunchKernelGGL(k_sort_segments, dim3(grid_for((int64_t)nt * 16)), dim3(kBlock), 0, c->stream, nt, c->touched,
-                               c->meta, c->pool, c->add_cnt, long_list, c->bc);
+            hipLaunchKernelGGL(k_sort_finish, dim3(grid_for((int64_t)nt * 16)), dim3(kBlock), 0, c->stream, nt, c->touched,
+                               c->meta, c->pool, c->add_cnt, use_rank ? 1 : 0, long_list, c->bc, c->deg, c->flag);
             hipLaunchKernelGGL(k_sort_long_segments, dim3(std::min<unsigned int>(nt, 512u)), dim3(kBlock), 0, c->stream,
                                long_list, c->meta, c->pool, c->add_cnt, c->bc);
-            hipLaunchKernelGGL(k_finish_rows, dim3(grid_for((int64_t)nt * 16)), dim3(kBlock), 0, c->stream, nt, c->touched,
-                               c->meta, c->pool, c->add_cnt, c->deg, c->flag);
+            hipLaunchKernelGGL(k_finish_rows, dim3(std::min<unsigned int>(grid_for((int64_t)nt * 16), 512u)), dim3(kBlock), 0,
+                               c->stream, long_list, c->bc, c->meta, c->pool, c->add_cnt, c->deg, c->flag);
             HIPCHK(c, hipGetLastError());
         }
         c->n = n1;

@@ -66,7 +66,6 @@ struct __attribute__((aligned(64))) RoundCtr {
 // Scalars of the insertion step and error reporting.
 struct __attribute__((aligned(64))) BatchCtr {
     unsigned long long pool_tail;    // first free pool entry
-    unsigned long long reloc_need;   // pool entries the planned relocations will take
     unsigned int touched;            // rows that receive at least one new entry
     unsigned int relocated;          // rows moved by the last insertion
     int err_code;                    // 0 = none; first validation error wins

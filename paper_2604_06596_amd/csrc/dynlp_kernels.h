@@ -277,10 +277,13 @@ __global__ void __launch_bounds__(kBlock) k_validate_edges(int64_t m, int64_t n_
 // will receive and list every row that receives any ("touched" rows).  Out-of-range sources are
 // skipped (the validation kernel reports them).  A workgroup takes kAppendItems * kBlock half-edges
 // and appends its first-touched rows with one counter atomic.
+// rank_u / rank_v (both or neither): what the counting atomic returned for half-edge i / m + i, i.e. the
+// half-edge's place among the entries this batch appends to its row; k_write_halfedges then needs no second atomic.
 __global__ void __launch_bounds__(kBlock) k_count_halfedges(int64_t m, int64_t n_total, const int32_t* __restrict__ eu,
                                                            const int32_t* __restrict__ ev,
                                                            int32_t* __restrict__ add_cnt,
-                                                           int32_t* __restrict__ touched, BatchCtr* bc) {
+                                                           int32_t* __restrict__ touched, BatchCtr* bc,
+                                                           int32_t* __restrict__ rank_u, int32_t* __restrict__ rank_v) {
     __shared__ unsigned int smem[kBlock / kWave + 1];
     const int64_t base = (int64_t)blockIdx.x * kBlock * kAppendItems;
     int32_t srcs[kAppendItems];
@@ -291,7 +294,11 @@ __global__ void __launch_bounds__(kBlock) k_count_halfedges(int64_t m, int64_t n
         int32_t src = -1;
         if (i < 2 * m) {
             src = i < m ? eu[i] : ev[i - m];
-            if (src >= 0 && src < n_total && atomicAdd(&add_cnt[src], 1) == 0) firstmask |= 1u << k;
+            if (src >= 0 && src < n_total) {
+                const int32_t r = atomicAdd(&add_cnt[src], 1);
+                if (r == 0) firstmask |= 1u << k;
+                if (rank_u) (i < m ? rank_u[i] : rank_v[i - m]) = r;
+            }
         }
         srcs[k] = src;
     }
@@ -301,33 +308,9 @@ __global__ void __launch_bounds__(kBlock) k_count_halfedges(int64_t m, int64_t n
         if ((firstmask >> k) & 1u) touched[slot++] = srcs[k];
 }
 
-// Rows whose slack cannot take the new entries: total capacity they need at the pool tail (one
-// counter atomic per workgroup: atomics on one address run at about 1e8 per second).
-__global__ void __launch_bounds__(kBlock) k_plan_sum(unsigned int nt, const int32_t* __restrict__ touched,
-                                                    const RowMeta* __restrict__ meta,
-                                                    const int32_t* __restrict__ add_cnt, float slack,
-                                                    BatchCtr* bc) {
-    __shared__ unsigned long long part[kBlock / kWave];
-    const unsigned int t = blockIdx.x * kBlock + threadIdx.x;
-    unsigned long long need_cap = 0;
-    if (t < nt) {
-        const int32_t u = touched[t];
-        const RowMeta m = meta[u];
-        const int64_t need = (int64_t)m.len + add_cnt[u];
-        if (need > m.cap) need_cap = (unsigned long long)row_capacity(need, slack);
-    }
-    need_cap = wave_sum(need_cap);
-    if (lane_id() == 0) part[threadIdx.x / kWave] = need_cap;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        unsigned long long tot = 0;
-        for (int i = 0; i < kBlock / kWave; ++i) tot += part[i];
-        if (tot) atomicAdd(&bc->reloc_need, tot);
-    }
-}
-
-// Reserve tail space for every overflowing touched row (one tail atomic per workgroup); reloc_off[t]
-// is the new offset or -1.
+// Rows whose slack cannot take the new entries get room at the pool tail (one tail atomic per workgroup: atomics
+// on one address run at about 1e8 per second); reloc_off[t] is the new offset or -1.  Touches no row: bc->pool_tail
+// afterwards tells the host how large the pool has to be before k_relocate may run.
 __global__ void __launch_bounds__(kBlock) k_plan_reserve(unsigned int nt, const int32_t* __restrict__ touched,
                                                         const RowMeta* __restrict__ meta,
                                                         const int32_t* __restrict__ add_cnt, float slack,
@@ -353,52 +336,68 @@ __global__ void __launch_bounds__(kBlock) k_plan_reserve(unsigned int nt, const 
     if (t < nt) reloc_off[t] = cap ? (int64_t)(sbase + ex) : -1;
 }
 
-// Move the valid entries of every relocated row to its new place (16 lanes per row).
+// Give every relocated row its new place.  One lane per touched row; rows that already hold entries (few, but
+// hubs among them) are copied by the whole wave, one row after the other.
 __global__ void __launch_bounds__(kBlock) k_relocate(unsigned int nt, const int32_t* __restrict__ touched,
                                                     RowMeta* __restrict__ meta, const int32_t* __restrict__ add_cnt,
                                                     float slack, const int64_t* __restrict__ reloc_off,
                                                     Edge* __restrict__ pool) {
-    constexpr int G = 16;
-    const unsigned int t = (blockIdx.x * kBlock + threadIdx.x) / G;
-    const int gl = threadIdx.x % G;
-    if (t >= nt) return;
-    const int64_t noff = reloc_off[t];
-    if (noff < 0) return;
-    const int32_t u = touched[t];
-    const RowMeta m = meta[u];
-    for (int j = gl; j < m.len; j += G) pool[noff + j] = pool[m.off + j];
-    if (gl == 0) {
+    const unsigned int t = blockIdx.x * kBlock + threadIdx.x;
+    const int64_t noff = t < nt ? reloc_off[t] : -1;
+    int64_t ooff = 0;
+    int len = 0;
+    if (noff >= 0) {
+        const int32_t u = touched[t];
+        const RowMeta m = meta[u];
+        ooff = m.off;
+        len = m.len;
         RowMeta r;
         r.off = noff;
         r.len = m.len;
         r.cap = row_capacity((int64_t)m.len + add_cnt[u], slack);
         meta[u] = r;
     }
+    unsigned long long todo = __ballot(len > 0);
+    const int lane = lane_id();
+    while (todo) {
+        const int l = __ffsll((long long)todo) - 1;
+        todo &= todo - 1;
+        const int64_t from = __shfl(ooff, l), to = __shfl(noff, l);
+        const int n = __shfl(len, l);
+        for (int j = lane; j < n; j += kWave) pool[to + j] = pool[from + j];
+    }
 }
 
-// Append both directions of every new edge; the slot inside the row comes from an atomic on its
-// length, so the order of one batch's entries inside a row is unspecified.
+// Append both directions of every new edge.  With ranks (k_count_halfedges): the entry goes to position
+// len + rank of its row and the row's length stays as it was (k_sort_finish adds the batch's count); without: the
+// position comes from an atomic on the length.  Either way the order of one batch's entries inside a row is
+// unspecified until they are sorted.
 __global__ void __launch_bounds__(kBlock) k_write_halfedges(int64_t m, const int32_t* __restrict__ eu,
                                                            const int32_t* __restrict__ ev,
                                                            const float* __restrict__ ew, RowMeta* __restrict__ meta,
-                                                           Edge* __restrict__ pool) {
+                                                           Edge* __restrict__ pool, const int32_t* __restrict__ rank) {
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= 2 * m) return;
     const int64_t k = i < m ? i : i - m;
     const int32_t src = i < m ? eu[k] : ev[k];
     const int32_t dst = i < m ? ev[k] : eu[k];
-    const int slot = atomicAdd(&meta[src].len, 1);
     Edge e;
     e.col = dst;
     e.w = ew[k];
-    pool[meta[src].off + slot] = e;
+    if (rank) {
+        const RowMeta r = meta[src];
+        pool[r.off + r.len + rank[i]] = e;
+    } else {
+        const int slot = atomicAdd(&meta[src].len, 1);
+        pool[meta[src].off + slot] = e;
+    }
 }
 
 // The entries one batch appends to a row land in the order their atomics happened to take.  Sorting
 // the appended segment by (neighbour id, weight bits) makes the stored row, and with it every sum
 // over the row, a function of the batch alone.  16 lanes per touched row; segments of up to
 // 16 * kSortRegs entries are rank-sorted in registers (every key is broadcast to the group once),
-// longer ones are queued for k_sort_long_segments.
+// longer ones are queued for k_sort_long_segments (and finished by k_finish_rows afterwards).
 __device__ inline unsigned long long edge_key(const Edge& e) {
     return ((unsigned long long)(unsigned int)e.col << 32) | (unsigned long long)__float_as_uint(e.w);
 }
@@ -410,53 +409,97 @@ __device__ inline Edge key_edge(unsigned long long k) {
     return e;
 }
 
-__global__ void __launch_bounds__(kBlock) k_sort_segments(unsigned int nt, const int32_t* __restrict__ touched,
-                                                         const RowMeta* __restrict__ meta, Edge* __restrict__ pool,
-                                                         const int32_t* __restrict__ add_cnt,
-                                                         int32_t* __restrict__ long_list, BatchCtr* bc) {
+// ... and, for the same rows, what ends Step 1: d(u) recomputed from the stored row (entries added in position
+// order, lane j mod 16 takes entry j), the counting scratch cleared, the row put into V_aff (both endpoints of every
+// inserted edge are affected).  The sorted weights go through LDS so that the sum needs no second pass over the row.
+// len_is_old: the rows' lengths do not yet include the appended entries (k_write_halfedges with ranks); the kernel
+// then stores the new length.  Rows with long appended segments only get their length and are listed.
+__global__ void __launch_bounds__(kBlock) k_sort_finish(unsigned int nt, const int32_t* __restrict__ touched,
+                                                       RowMeta* __restrict__ meta, Edge* __restrict__ pool,
+                                                       int32_t* __restrict__ add_cnt, int len_is_old,
+                                                       int32_t* __restrict__ long_list, BatchCtr* bc,
+                                                       float* __restrict__ deg, uint8_t* __restrict__ flag) {
     constexpr int G = 16;
+    __shared__ float sorted_w[kBlock / G][G * kSortRegs];
     const unsigned int t = (blockIdx.x * kBlock + threadIdx.x) / G;
+    const int grp = threadIdx.x / G;
     const int gl = threadIdx.x % G;
-    if (t >= nt) return;
-    const int32_t u = touched[t];
-    const int a = add_cnt[u];
-    if (a <= 1) return;
-    const RowMeta m = meta[u];
-    Edge* seg = pool + m.off + (m.len - a);
-    if (a > G * kSortRegs) {
-        if (gl == 0) long_list[atomicAdd(&bc->sort_long, 1u)] = u;
-        return;
+    int32_t u = 0;
+    int a = 0, len_old = 0;
+    RowMeta m;
+    m.off = 0;
+    m.len = 0;
+    m.cap = 0;
+    bool is_long = false;
+    if (t < nt) {
+        u = touched[t];
+        a = add_cnt[u];
+        m = meta[u];
+        len_old = len_is_old ? m.len : m.len - a;
+        is_long = a > G * kSortRegs;
     }
-    const int slots = (a + G - 1) / G;  // uniform in the group
-    unsigned long long key[kSortRegs];
+    const bool sorts = t < nt && !is_long;
+    Edge* seg = pool + m.off + len_old;
+    if (sorts) {
+        const int slots = (a + G - 1) / G;  // uniform in the group
+        unsigned long long key[kSortRegs];
 #pragma unroll
-    for (int r = 0; r < kSortRegs; ++r) {
-        const int j = r * G + gl;
-        key[r] = (r < slots && j < a) ? edge_key(seg[j]) : ~0ull;
-    }
-    int rank[kSortRegs];
+        for (int r = 0; r < kSortRegs; ++r) {
+            const int j = r * G + gl;
+            key[r] = (r < slots && j < a) ? edge_key(seg[j]) : ~0ull;
+        }
+        int rank[kSortRegs];
 #pragma unroll
-    for (int r = 0; r < kSortRegs; ++r) rank[r] = 0;
+        for (int r = 0; r < kSortRegs; ++r) rank[r] = r * G + gl;
+        if (a > 1) {
 #pragma unroll
-    for (int r2 = 0; r2 < kSortRegs; ++r2) {
-        if (r2 < slots) {
-            for (int l = 0; l < G; ++l) {
-                const unsigned int hi = __shfl((unsigned int)(key[r2] >> 32), l, G);
-                const unsigned int lo = __shfl((unsigned int)(key[r2] & 0xffffffffull), l, G);
-                const unsigned long long other = ((unsigned long long)hi << 32) | lo;
-                const int oj = r2 * G + l;
+            for (int r = 0; r < kSortRegs; ++r) rank[r] = 0;
 #pragma unroll
-                for (int r = 0; r < kSortRegs; ++r) {
-                    const int j = r * G + gl;
-                    rank[r] += (other < key[r] || (other == key[r] && oj < j)) ? 1 : 0;
+            for (int r2 = 0; r2 < kSortRegs; ++r2) {
+                if (r2 < slots) {
+                    for (int l = 0; l < G; ++l) {
+                        const unsigned int hi = __shfl((unsigned int)(key[r2] >> 32), l, G);
+                        const unsigned int lo = __shfl((unsigned int)(key[r2] & 0xffffffffull), l, G);
+                        const unsigned long long other = ((unsigned long long)hi << 32) | lo;
+                        const int oj = r2 * G + l;
+#pragma unroll
+                        for (int r = 0; r < kSortRegs; ++r) {
+                            const int j = r * G + gl;
+                            rank[r] += (other < key[r] || (other == key[r] && oj < j)) ? 1 : 0;
+                        }
+                    }
                 }
             }
         }
-    }
 #pragma unroll
-    for (int r = 0; r < kSortRegs; ++r) {
-        const int j = r * G + gl;
-        if (r < slots && j < a) seg[rank[r]] = key_edge(key[r]);
+        for (int r = 0; r < kSortRegs; ++r) {
+            const int j = r * G + gl;
+            if (r < slots && j < a) {
+                const Edge e = key_edge(key[r]);
+                if (a > 1) seg[rank[r]] = e;
+                sorted_w[grp][rank[r]] = e.w;
+            }
+        }
+    }
+    __syncthreads();
+    if (t >= nt) return;
+    if (is_long) {
+        if (gl == 0) {
+            if (len_is_old) meta[u].len = len_old + a;
+            long_list[atomicAdd(&bc->sort_long, 1u)] = u;
+        }
+        return;
+    }
+    const int len_new = len_old + a;
+    float s = 0.f;
+    for (int j = gl; j < len_new; j += G) s += j < len_old ? pool[m.off + j].w : sorted_w[grp][j - len_old];
+#pragma unroll
+    for (int d = G / 2; d > 0; d >>= 1) s += __shfl_xor(s, d, G);
+    if (gl == 0) {
+        if (len_is_old) meta[u].len = len_new;
+        deg[u] = s;
+        add_cnt[u] = 0;
+        if (flag) flag[u] = 1;
     }
 }
 
@@ -494,26 +537,27 @@ __global__ void __launch_bounds__(kBlock) k_sort_long_segments(const int32_t* __
     }
 }
 
-// Touched rows: recompute d(u) from the stored row, clear the counting scratch, and put the row
-// into V_aff (both endpoints of every inserted edge are affected).
-__global__ void __launch_bounds__(kBlock) k_finish_rows(unsigned int nt, const int32_t* __restrict__ touched,
+// The rows k_sort_long_segments has sorted (their number is bc->sort_long): recompute d(u) from the stored row in
+// the same order as k_sort_finish, clear the counting scratch, and put the row into V_aff.
+__global__ void __launch_bounds__(kBlock) k_finish_rows(const int32_t* __restrict__ list, const BatchCtr* bc,
                                                        const RowMeta* __restrict__ meta,
                                                        const Edge* __restrict__ pool, int32_t* __restrict__ add_cnt,
                                                        float* __restrict__ deg, uint8_t* __restrict__ flag) {
     constexpr int G = 16;
-    const unsigned int t = (blockIdx.x * kBlock + threadIdx.x) / G;
+    const unsigned int count = bc->sort_long;
     const int gl = threadIdx.x % G;
-    if (t >= nt) return;
-    const int32_t u = touched[t];
-    const RowMeta m = meta[u];
-    float s = 0.f;
-    for (int j = gl; j < m.len; j += G) s += pool[m.off + j].w;
+    for (unsigned int t = (blockIdx.x * kBlock + threadIdx.x) / G; t < count; t += gridDim.x * (kBlock / G)) {
+        const int32_t u = list[t];
+        const RowMeta m = meta[u];
+        float s = 0.f;
+        for (int j = gl; j < m.len; j += G) s += pool[m.off + j].w;
 #pragma unroll
-    for (int d = G / 2; d > 0; d >>= 1) s += __shfl_xor(s, d, G);
-    if (gl == 0) {
-        deg[u] = s;
-        add_cnt[u] = 0;
-        if (flag) flag[u] = 1;
+        for (int d = G / 2; d > 0; d >>= 1) s += __shfl_xor(s, d, G);
+        if (gl == 0) {
+            deg[u] = s;
+            add_cnt[u] = 0;
+            if (flag) flag[u] = 1;
+        }
     }
 }
 

@@ -90,7 +90,14 @@ def _unique(keys: np.ndarray) -> np.ndarray:
 def _searchsorted_right(cum: np.ndarray, vals: np.ndarray) -> np.ndarray:
     t = _gpu() if vals.shape[0] >= _BIG else None
     if t is None:
-        return np.searchsorted(cum, vals, side="right")
+        if vals.shape[0] < 100_000:
+            return np.searchsorted(cum, vals, side="right")
+        # same answers, looked up in ascending order of the queries: neighbouring binary searches then share their
+        # path through ``cum`` instead of missing the cache at every level
+        order = np.argsort(vals)
+        out = np.empty(vals.shape[0], dtype=np.int64)
+        out[order] = np.searchsorted(cum, vals[order], side="right")
+        return out
     return t.searchsorted(t.from_numpy(cum).cuda(), t.from_numpy(vals).cuda(), right=True).cpu().numpy()
 
 
