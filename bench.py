@@ -344,7 +344,8 @@ def main():
     copy_gbs, read_gbs = d.stream_bandwidth(1 << 30, 10)
     # ... and what random whole-row gathers of this workload's stored row size sustain in a table of its vertex count
     CP_ = next(c for c in (1, 2, 4, 8, 16, 32, 64) if c >= Cs)
-    gather_rows_per_s, gather_gbs = d.gather_bandwidth(max(1, base["n"]), max(16, 4 * CP_),
+    table_rows = max(1, base["n"] + tot_v)  # the vertex count the timed batches work on
+    gather_rows_per_s, gather_gbs = d.gather_bandwidth(table_rows, max(16, 4 * CP_),
                                                        min(400_000_000, max(1_000_000, int(base["col"].shape[0]))), 5)
     cold = dict(status=st, sweeps=s0.iterations, ms=s0.ms_total, ms_update_kernel=s0.ms_update_kernel,
                 algorithmic_gbs=algorithmic_bytes(s0.rows_updated, s0.edges_traversed, Cs) / 1e6 /
@@ -525,7 +526,7 @@ def main():
                      "stream_copy_GBs": copy_gbs, "stream_read_GBs": read_gbs, "frac_of_stream_read": achieved / read_gbs,
                      # gathers per second: this kernel's CSR entries per second against random whole-row reads of the
                      # same stored row size with no other traffic
-                     "gather_yardstick": {"row_bytes": max(16, 4 * CP_), "table_rows": base["n"],
+                     "gather_yardstick": {"row_bytes": max(16, 4 * CP_), "table_rows": table_rows,
                                           "rows_per_s": gather_rows_per_s, "GBs": gather_gbs},
                      "gathers_per_s": kstats[dom]["entries"] / max(k_ms * 1e-3, 1e-12),
                      "frac_of_gather_yardstick": kstats[dom]["entries"] / max(k_ms * 1e-3, 1e-12) / max(gather_rows_per_s, 1.0),
