@@ -117,6 +117,31 @@ def test_without_memory_for_the_binned_arrays_the_rounds_are_ordinary_ones():
                       Cf.certificate(rp, col, w, g.seed_class, soft2), "ordinary vs binned rounds")
 
 
+def test_without_memory_for_the_half_edge_ranks_the_insertion_takes_its_second_atomic():
+    """The insertion keeps, per half-edge, what the counting atomic returned (its place among the entries appended to
+    its row) so that the writing pass needs no atomic of its own.  That array is optional: refused, the writing pass
+    counts again.  Either way the appended entries are sorted afterwards, so graph and labels agree bit for bit."""
+    p0, b = _problem(10)
+    m = int(b.eu.shape[0])
+    a = TorchAllocator()
+    with P.DynLP(p0.n, p0.row_ptr, p0.col, p0.w, p0.C, p0.seed_vertex, p0.seed_class, allocator=a) as d:
+        assert d.static_solve(TOL, 20000)[0] == 0
+        a.refuse = lambda nbytes: nbytes == 3 * m * 4
+        st, s = d.apply_batch(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+        soft, hard = d.get_labels()
+        graph = d.export_graph()
+    assert st == 0 and a.refused == 1 and not a.live
+    with P.DynLP(p0.n, p0.row_ptr, p0.col, p0.w, p0.C, p0.seed_vertex, p0.seed_class) as d2:
+        assert d2.static_solve(TOL, 20000)[0] == 0
+        st2, s2 = d2.apply_batch(b.num_new_vertices, b.eu, b.ev, b.ew, b.seed_vertex, b.seed_class)
+        soft2, hard2 = d2.get_labels()
+        graph2 = d2.export_graph()
+    assert st2 == 0 and s.iterations == s2.iterations and s.frontier_initial == s2.frontier_initial
+    for x, y in zip(graph, graph2):
+        assert np.array_equal(x, y)
+    assert np.array_equal(soft, soft2) and np.array_equal(hard, hard2)
+
+
 def test_calls_that_change_nothing_survive_an_allocator_without_memory():
     """dynlp_get_labels, dynlp_export_graph, dynlp_mean_edge_weight and dynlp_compact_storage only need temporary
     arrays (compaction: the new layout beside the old one).  When the allocator refuses them they return

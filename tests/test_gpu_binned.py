@@ -120,6 +120,49 @@ def test_binned_rounds_converge_to_the_exact_labels(kind, mode):
     assert np.array_equal(out["soft"][s_idx], R.initial_labels(g.seed_class, 2)[s_idx].astype(np.float32))
 
 
+def _many_bins_case():
+    mk = lambda: W.small_random(600_001, 2, 4.0, 6000, 5400)
+    p, p0 = mk(), mk()
+    b = W.small_random_batch(p, 60_000, 7, 600, num_extra_edges=3000, num_revealed=30)
+    return p0, b, np.zeros(0, dtype=np.int32)
+
+
+def test_many_bins_match_the_oracle_round_by_round():
+    """660,001 vertices in bins of 256 receivers: 2,579 bins (the scatter pass's per-bin tables in their wide
+    instantiation, for more than 2,048 bins) and about 180 chunks of entries; synchronous mode, 10 rounds."""
+    p0, b, dead = _many_bins_case()
+    R_ = 10
+    out = _run(p0, b, dead, R_, 8)
+    g, rp, col, w, F, A0 = _oracle_after(p0, b, dead, out["soft0"])
+    o2 = ON.step3_propagate(rp, col, w, F, g.seed_class, A0, TOL, R_)
+    print("round kinds", out["kinds"], "sizes", out["sizes"].tolist())
+    assert out["kinds"].count(3) >= R_ - 2, "the case is meant to run binned rounds"
+    assert out["s"].frontier_initial == len(A0) and out["s"].iterations == o2["rounds"] == R_
+    assert out["sizes"].tolist() == o2["frontier_sizes"].tolist()
+    assert np.max(np.abs(out["soft"] - o2["F"])) <= ROUNDS_ATOL
+    np.testing.assert_allclose(out["deltas"], o2["max_changes"], atol=1e-6)
+    assert out["s"].rows_updated == o2["rows_updated"] and out["s"].edges_traversed == o2["edges_traversed"]
+
+
+def test_many_bins_in_place_rounds_of_several_ranges_reach_the_exact_labels():
+    """The same graph in the in-place mode: more bins than compute units, so a binned round goes through the graph in
+    several ranges, each reading what the ranges before it published in the same round.  Converged labels against
+    the exact ones (row-wise residual certificate), and fewer rounds than the synchronous run needs."""
+    p0, b, dead = _many_bins_case()
+    out = _run(p0, b, dead, 20000, 8, mode=P.UPDATE_IN_PLACE)
+    sync = _run(p0, b, dead, 20000, 8, mode=P.UPDATE_SYNCHRONOUS)
+    g, rp, col, w, F, A0 = _oracle_after(p0, b, dead, out["soft0"])
+    assert out["st"] == 0 and sync["st"] == 0 and 3 in out["kinds"] and 3 in sync["kinds"]
+    exact, exact_moved = Cf.exact_labels(rp, col, w, g.seed_class, 2)
+    for name, o in (("in-place", out), ("synchronous", sync)):
+        cert = Cf.certificate(rp, col, w, g.seed_class, o["soft"])
+        err = Cf.check_against_exact(o["soft"], exact, exact_moved, cert, f"many bins, {name}")
+        Cf.check_hard(o["hard"], exact, cert)
+        assert cert.res <= Cf.local_stop_residual(TOL, o["s"].iterations, Cf.stop_rule_residual(TOL))
+        print(f"{name}: {o['s'].iterations} rounds ({o['kinds'].count(3)} binned), err vs exact {err:.2e}")
+    assert out["s"].iterations < sync["s"].iterations
+
+
 @pytest.mark.parametrize("n,deg,new", [(3, 1.0, 1), (50, 3.0, 5), (257, 4.0, 40), (700, 2.2, 300)])
 def test_binned_rounds_on_tiny_and_ragged_graphs(n, deg, new):
     """One bin or a few, a last bin that is mostly empty, rows of one entry, vertices without edges: the binned
