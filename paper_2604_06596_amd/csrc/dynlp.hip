@@ -1121,9 +1121,12 @@ bool fused_rounds_pay(const dynlp_ctx* c, double avg_len) {
 // Ping-pong stretches begin when V_aff holds at least kDenseEnter of the updatable vertices and end
 // when it falls below kDenseLeave (the pull over all updatable vertices stops paying off).
 constexpr double kDenseEnter = 0.90, kDenseLeave = 0.75;
-// A binned round costs the same whatever the size of V_aff (two streams over the whole graph), about a third of an
-// ordinary round over all rows: such stretches begin and end at smaller V_aff.
-constexpr double kBinnedEnter = 0.50, kBinnedLeave = 0.35;
+// A binned round costs the same whatever the size of V_aff (two streams over the whole graph), about a quarter of an
+// ordinary round over all rows, and a flag-marking round over a third of the rows already costs more: such stretches
+// begin and end at smaller V_aff.  50M-vertex random graph, one batch, enter / leave at 0.50 / 0.35 against 0.35 / 0.20:
+// synchronous 762 -> 738 ms, with supernode initialisation 367 -> 342 ms, in place with it 332 -> 270 ms (in place
+// from uniform rows V_aff collapses within one chain of rounds and nothing changes); 0.20 / 0.10 is no better.
+constexpr double kBinnedEnter = 0.35, kBinnedLeave = 0.20;
 
 // The ping-pong partner must agree with F on every row a full sweep does not write (seeds,
 // isolated vertices) before it can receive one.
