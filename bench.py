@@ -531,7 +531,7 @@ def main():
                      "gathers_per_s": kstats[dom]["entries"] / max(k_ms * 1e-3, 1e-12),
                      "frac_of_gather_yardstick": kstats[dom]["entries"] / max(k_ms * 1e-3, 1e-12) / max(gather_rows_per_s, 1.0),
                      "traffic_per_algorithmic_byte": traffic_ratio,
-                     "traffic_GBs": (traffic / (k_ms * 1e6 / max(1, launches))) if traffic else None,
+                     "traffic_GBs": (traffic / (k_ms * 1e6 / max(1, launches))) if traffic and k_ms > 0 else None,
                      "compulsory_bytes_per_launch": comp_bytes / max(1, launches),
                      "compulsory_GBs": comp_bytes / 1e6 / max(k_ms, 1e-9)},
         "detail": {"rounds_per_step": [x["iterations"] for x in per_step],

@@ -201,7 +201,10 @@ struct dynlp_ctx {
     int32_t max_iter = 100000;
     std::vector<dynlp_round_info> log;  // one entry per round of the last solve / batch
     std::vector<hipEvent_t> events;   // pairs: events[2k], events[2k+1] bracket the k-th timed launch
-    size_t events_used = 0;
+    size_t events_used = 0;               // 2 x the number of timed spans
+    size_t events_next = 0;               // events handed out (a span that directly follows another shares its event)
+    std::vector<int> ev_first, ev_last;   // event indices of span k
+    bool ev_adjacent = false;             // set by a caller: nothing was queued since the previous span was closed
     std::vector<int> ev_round, ev_count;  // rounds [ev_round[k], ev_round[k] + ev_count[k]) ran inside the k-th launch;
                                           // ev_round[k] < 0: the launch found nothing to do (queued past the end)
     hipEvent_t phase_ev[4] = {nullptr, nullptr, nullptr, nullptr};
@@ -619,9 +622,14 @@ void launch_update_cp(dynlp_ctx* c, int G, const Frontier& f, const UpdateArgs& 
 }
 
 // With kernel timing on, two events bracket every row-update launch; `round` / `count` say which rounds it runs.
+// A launch that directly follows the previous timed launch (c->ev_adjacent, set by the caller for this one call)
+// takes that launch's closing event as its opening one: an event record costs a few microseconds on the stream,
+// which shows once a round takes 40 of them.
 hipEvent_t open_timed_span(dynlp_ctx* c, int round, int count) {
+    const bool adjacent = c->ev_adjacent && c->events_used > 0;
+    c->ev_adjacent = false;
     if (!c->time_kernels) return nullptr;
-    while (c->events.size() < c->events_used + 2) {
+    while (c->events.size() < c->events_next + 2) {
         hipEvent_t e;
         HIPCHK(c, hipEventCreate(&e));
         c->events.push_back(e);
@@ -630,17 +638,30 @@ hipEvent_t open_timed_span(dynlp_ctx* c, int round, int count) {
     if (c->ev_round.size() <= k) {
         c->ev_round.resize(k + 1);
         c->ev_count.resize(k + 1);
+        c->ev_first.resize(k + 1);
+        c->ev_last.resize(k + 1);
     }
     c->ev_round[k] = round;
     c->ev_count[k] = count;
-    hipEvent_t e0 = c->events[c->events_used++];
-    hipEvent_t e1 = c->events[c->events_used++];
-    HIPCHK(c, hipEventRecord(e0, c->stream));
-    return e1;
+    c->events_used += 2;
+    if (adjacent) {
+        c->ev_first[k] = c->ev_last[k - 1];
+    } else {
+        c->ev_first[k] = (int)c->events_next;
+        HIPCHK(c, hipEventRecord(c->events[c->events_next++], c->stream));
+    }
+    c->ev_last[k] = (int)c->events_next;
+    return c->events[c->events_next++];
 }
 
 void close_timed_span(dynlp_ctx* c, hipEvent_t e1) {
     if (e1) HIPCHK(c, hipEventRecord(e1, c->stream));
+}
+
+void reset_timed_spans(dynlp_ctx* c) {
+    c->events_used = 0;
+    c->events_next = 0;
+    c->ev_adjacent = false;
 }
 
 // After a chain has been read back: launches of rounds >= first_unexecuted did nothing.
@@ -1028,14 +1049,14 @@ float collect_kernel_ms(dynlp_ctx* c) {
     float total = 0.f;
     for (size_t k = 0; 2 * k + 1 < c->events_used; ++k) {
         float a = 0.f;
-        (void)hipEventElapsedTime(&a, c->events[2 * k], c->events[2 * k + 1]);
+        (void)hipEventElapsedTime(&a, c->events[c->ev_first[k]], c->events[c->ev_last[k]]);
         total += a;
         const int first = c->ev_round[k];
         if (first < 0) continue;
         const int last = std::min<int>(first + c->ev_count[k], (int)c->log.size());
         for (int t = first; t < last; ++t) c->log[t].ms_update += a / (float)std::max(1, last - first);
     }
-    c->events_used = 0;
+    reset_timed_spans(c);
     return total;
 }
 
@@ -1850,7 +1871,7 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
     try {
         HIPCHK(c, hipSetDevice(c->device));
         c->log.clear();
-        c->events_used = 0;
+        reset_timed_spans(c);
         const bool in_place = c->update_mode == DYNLP_UPDATE_IN_PLACE;
         if (!in_place) sync_partner(c);
         zero_ring(c);
@@ -1889,6 +1910,7 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
             const bool chain_binned = binned && !lazy;  // the averaged sweeps of a limit cycle are ordinary ones
             for (int i = 0; i < r; ++i) {
                 const int t = it + i;
+                c->ev_adjacent = i > 0;  // a chain of sweeps is nothing but these launches
                 if (chain_binned && t > 0) {
                     const PullRoundArgs a{slot_of(c, t - 1), buf[t & 1], buf[(t + 1) & 1], c->moved[0], c->moved[1], c->moved[2],
                                           tol, slot_of(c, t), slot_of(c, t + 1)};
@@ -1944,7 +1966,7 @@ dynlp_status dynlp_static_solve(dynlp_ctx* c, float tol, int32_t max_iter, dynlp
             stats->ms_update_kernel = kernel_ms_total;
             stats->ms_total = ms_since(t0);
         }
-        c->events_used = 0;
+        reset_timed_spans(c);
         return converged ? DYNLP_OK : DYNLP_NOT_CONVERGED;
     } catch (const Fail& f) {
         return f.st;
@@ -1994,7 +2016,7 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
     try {
         HIPCHK(c, hipSetDevice(c->device));
         c->log.clear();
-        c->events_used = 0;
+        reset_timed_spans(c);
         // ---- capacity for new vertices; their rows start empty, unlabelled, uniform ----
         if (n1 > c->n_cap) alloc_vertex_arrays(c, n1 + std::max<int64_t>(n1 / 2, 1024));
         ensure_batch_scratch(c, m, s);
@@ -2245,6 +2267,7 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
                                            slot, slot_of(c, t + 1), (int64_t)universe.size(), (int64_t)universe.nl};
                         launch_update<false>(c, G, f, a, t);
                     } else {
+                        c->ev_adjacent = i > 0;  // fused rounds of one chain follow each other with nothing in between
                         if (persist && !c->persist_failed) {
                             // rounds t .. it + r - 1 in one launch
                             PersistArgs pa;
@@ -2374,7 +2397,7 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
             (void)hipEventElapsedTime(&stats->ms_iterate, c->phase_ev[2], c->phase_ev[3]);
             stats->ms_total = ms_since(t0);
         }
-        c->events_used = 0;
+        reset_timed_spans(c);
         return nq == 0 ? DYNLP_OK : DYNLP_NOT_CONVERGED;
     } catch (const Fail& f) {
         if (mutated) c->poisoned = true;

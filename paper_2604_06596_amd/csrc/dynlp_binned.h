@@ -349,11 +349,7 @@ __global__ void __launch_bounds__(kBlock) k_pb_normalise(int bin_bits, const uns
 }
 
 // Early-exit test shared by both passes: a round runs iff the previous one ran and moved at least one row.
-__device__ inline bool pb_round_runs(const RoundCtr* __restrict__ prev) {
-    unsigned int prev_changed = lane_id() < kCtrLanes ? prev->part[lane_id()].changed : 0u;
-    prev_changed = wave_sum(prev_changed);
-    return prev->executed && prev_changed != 0u;
-}
+__device__ inline bool pb_round_runs(const RoundCtr* __restrict__ prev) { return prev->executed && prev->any_moved != 0u; }
 
 // Scatter pass, one workgroup per chunk: stage[lpos[i]] = F[src[i]] (sign bit: src[i] moved in the previous round)
 // for the chunk's entries i; then the staged values of bin b (positions loff[b] .. loff[b + 1] - 1, loff = running
@@ -397,6 +393,7 @@ __global__ void __launch_bounds__(kPbScatterThreads) k_pb_scatter(const RoundCtr
             ctr_zero->executed = 0;
             ctr_zero->rows_short = 0;
             ctr_zero->rows_long = 0;
+            ctr_zero->any_moved = 0;
         }
         if (threadIdx.x < kCtrLanes) {
             RoundPart* p = &ctr_zero->part[threadIdx.x];
@@ -572,7 +569,10 @@ __global__ void __launch_bounds__(kPbGatherThreads) k_pb_gather(const RoundCtr* 
         RoundPart* p = &ctr->part[bin & (kCtrLanes - 1)];
         if (rmax > 0.f) atomicMax(&p->resid_bits, __float_as_uint(rmax));
         if (edges) atomicAdd(&p->edges, edges);
-        if (nchanged) atomicAdd(&p->changed, nchanged);
+        if (nchanged) {
+            atomicAdd(&p->changed, nchanged);
+            ctr->any_moved = 1u;
+        }
         if (nrows) atomicAdd(&p->rows_short, nrows);
     }
 }

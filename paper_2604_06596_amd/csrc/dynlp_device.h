@@ -59,7 +59,9 @@ struct __attribute__((aligned(64))) RoundCtr {
     unsigned int executed;     // 1 if the round updated anything (0: frontier was empty / already converged)
     unsigned int rows_short;   // the frontier this round worked on
     unsigned int rows_long;
-    unsigned int pad[5];
+    unsigned int any_moved;    // set (plain store of 1) by every workgroup that moved a row: "did the round move
+                               // anything" for the next round without folding the partial records
+    unsigned int pad[4];
     RoundPart part[kCtrLanes];
 };
 

@@ -413,7 +413,10 @@ __device__ inline unsigned int flush_round_counters(float rmax, unsigned long lo
         RoundPart* p = &ctr->part[blockIdx.x & (kCtrLanes - 1)];
         if (rmax > 0.f) atomicMax(&p->resid_bits, __float_as_uint(rmax));
         if (edges) atomicAdd(long_rows ? &p->edges_long : &p->edges, edges);
-        if (changed) atomicAdd(&p->changed, changed);
+        if (changed) {
+            atomicAdd(&p->changed, changed);
+            ctr->any_moved = 1u;
+        }
         if (rows) atomicAdd(long_rows ? &p->rows_long : &p->rows_short, rows);
     }
     return changed;
@@ -507,8 +510,22 @@ __device__ inline unsigned int row_update_short(unsigned int bid, unsigned int n
                 const int last_base = ((m.len - 1) / G) * G;
                 for (int idx = gl; idx < last_base; idx += G) mark(flag, row[idx].col);
             }
-        } else if (moved && big && gl == 0) {
-            atomicOr(&moved[(unsigned int)u >> 5], 1u << ((unsigned int)u & 31u));
+        } else if (moved) {
+            // one atomic per distinct bitmap word among the rows of this wave (consecutive list positions are mostly
+            // consecutive vertices: the wave's kWave / G rows usually share a word)
+            const unsigned int word = (unsigned int)u >> 5;
+            unsigned int bits = (big && gl == 0) ? 1u << ((unsigned int)u & 31u) : 0u;
+            bool lowest = true;
+#pragma unroll
+            for (int k = 0; k < kWave / G; ++k) {
+                const unsigned int ow = __shfl(word, k * G);
+                const unsigned int ob = __shfl((big && gl == 0) ? 1u << ((unsigned int)u & 31u) : 0u, k * G);
+                if (ow == word && k * G != (lane_id() / G) * G) {
+                    bits |= ob;
+                    if (k * G < (lane_id() / G) * G && ob) lowest = false;
+                }
+            }
+            if (gl == 0 && big && lowest) atomicOr(&moved[word], bits);
         }
         if (gl == 0) {
             rmax = fmaxf(rmax, r);
@@ -643,6 +660,7 @@ __global__ void __launch_bounds__(kBlock) k_row_update(const RoundCtr* __restric
             ctr_zero->executed = 0;
             ctr_zero->rows_short = 0;
             ctr_zero->rows_long = 0;
+            ctr_zero->any_moved = 0;
         }
         if (threadIdx.x < kCtrLanes) {
             RoundPart* p = &ctr_zero->part[threadIdx.x];
@@ -716,6 +734,7 @@ __global__ void __launch_bounds__(kBlock) k_row_update_pull(const RoundCtr* __re
             ctr_zero->executed = 0;
             ctr_zero->rows_short = 0;
             ctr_zero->rows_long = 0;
+            ctr_zero->any_moved = 0;
         }
         if (threadIdx.x < kCtrLanes) {
             RoundPart* p = &ctr_zero->part[threadIdx.x];
@@ -727,10 +746,9 @@ __global__ void __launch_bounds__(kBlock) k_row_update_pull(const RoundCtr* __re
             p->rows_long = 0;
         }
     }
-    // rows the previous round moved: the sum over its partial records
-    unsigned int prev_changed = lane_id() < kCtrLanes ? prev->part[lane_id()].changed : 0u;
-    prev_changed = wave_sum(prev_changed);
-    if (!prev->executed || prev_changed == 0u) return;
+    // did the previous round move a row?  (one word of its header instead of its 32 partial records: thousands of
+    // short-lived workgroups each reading 32 lines was a fifth of the launch on a 100K-vertex graph)
+    if (!prev->executed || prev->any_moved == 0u) return;
     for (unsigned int w = blockIdx.x * kBlock + threadIdx.x; w < words; w += gridDim.x * kBlock) moved_clear[w] = 0u;
     if (blockIdx.x == 0 && threadIdx.x == 0) ctr->executed = 1;
     const unsigned int long_blocks = nl < long_blocks_max ? nl : long_blocks_max;
@@ -910,6 +928,7 @@ __global__ void __launch_bounds__(kBlock) k_rounds_persistent(PersistArgs a) {
                 store_through(&ctr_zero->executed, 0u);
                 store_through(&ctr_zero->rows_short, 0u);
                 store_through(&ctr_zero->rows_long, 0u);
+                store_through(&ctr_zero->any_moved, 0u);
                 store_through(&ctr->executed, 1u);
             }
             if (threadIdx.x < kCtrLanes) {
