@@ -159,6 +159,9 @@ struct dynlp_ctx {
     int pb_bits = 0, pb_bins = 0;
     // per stored entry, rows in vertex order
     unsigned int* pb_src = nullptr;    // its row
+    unsigned int* pb_sp = nullptr;     // row as an offset from pb_row0 of its chunk << 16 | pb_lpos: what the scatter pass reads
+    unsigned int* pb_row0 = nullptr;   // per chunk: the row of its first entry; [chunk capacity]: "an offset needs > 16 bits"
+    bool pb_packed_ok = false;
     unsigned short* pb_lpos = nullptr;  // its position in its chunk once sorted by slot
     float* pb_tmp = nullptr;           // build scratch: the entries' weights in stream order
     // per slot
@@ -851,10 +854,10 @@ bool binned_rounds_pay(const dynlp_ctx* c, const Frontier& universe) {
 
 // Free every array of the binned rounds.
 void free_binned(dynlp_ctx* c) {
-    void* all[] = {c->pb_src, c->pb_lpos, c->pb_tmp, c->pb_dst, c->pb_wn, c->pb_val,
+    void* all[] = {c->pb_src, c->pb_sp, c->pb_row0, c->pb_lpos, c->pb_tmp, c->pb_dst, c->pb_wn, c->pb_val,
                    c->pb_len, c->pb_upd, c->pb_first, c->pb_block, c->pb_bin, c->pb_table};
     for (void* q : all) dev_free(c, q);
-    c->pb_src = c->pb_val = c->pb_upd = c->pb_first = c->pb_block = c->pb_bin = c->pb_table = nullptr;
+    c->pb_src = c->pb_val = c->pb_upd = c->pb_first = c->pb_block = c->pb_bin = c->pb_table = c->pb_row0 = c->pb_sp = nullptr;
     c->pb_lpos = c->pb_dst = nullptr;
     c->pb_tmp = c->pb_wn = nullptr;
     c->pb_len = nullptr;
@@ -884,14 +887,15 @@ bool build_binned(dynlp_ctx* c) {
     const int chunks = (int)ceil_div(std::max<int64_t>(c->entries, 1), kPbChunk);
     bool ok = true;
     if ((int64_t)chunks * kPbChunk > c->pb_ent_cap) {
-        void* old[] = {c->pb_src, c->pb_lpos, c->pb_tmp, c->pb_dst, c->pb_wn, c->pb_val};
+        void* old[] = {c->pb_src, c->pb_sp, c->pb_row0, c->pb_lpos, c->pb_tmp, c->pb_dst, c->pb_wn, c->pb_val};
         for (void* q : old) dev_free(c, q);
-        c->pb_src = c->pb_val = nullptr;
+        c->pb_src = c->pb_val = c->pb_row0 = c->pb_sp = nullptr;
         c->pb_lpos = c->pb_dst = nullptr;
         c->pb_tmp = c->pb_wn = nullptr;
         c->pb_ent_cap = 0;
         const int64_t cap = round_up(c->entries + c->entries / 8 + 1, kPbChunk);
-        ok = try_alloc_n(c, c->pb_src, cap) && try_alloc_n(c, c->pb_lpos, cap) &&
+        ok = try_alloc_n(c, c->pb_src, cap) && try_alloc_n(c, c->pb_sp, cap) &&
+             try_alloc_n(c, c->pb_row0, cap / kPbChunk + 1) && try_alloc_n(c, c->pb_lpos, cap) &&
              try_alloc_n(c, c->pb_tmp, cap) && try_alloc_n(c, c->pb_dst, cap) && try_alloc_n(c, c->pb_wn, cap) &&
              try_alloc_n(c, c->pb_val, cap);
         if (ok) c->pb_ent_cap = cap;
@@ -941,8 +945,11 @@ bool build_binned(dynlp_ctx* c) {
         throw Fail{DYNLP_ERR_STATE};
     }
     unsigned int* ecol = c->pb_val;  // scratch until the first scatter pass overwrites it
+    unsigned int* too_wide = c->pb_row0 + c->pb_ent_cap / kPbChunk;  // the word after the last chunk's
+    HIPCHK(c, hipMemsetAsync(too_wide, 0, sizeof(unsigned int), c->stream));
     hipLaunchKernelGGL(k_pb_expand, dim3(grid_for(c->n * 16)), dim3(kBlock), 0, c->stream, c->n, c->meta, c->pool, c->pb_first,
-                       c->pb_src, ecol, c->pb_tmp);
+                       c->pb_src, ecol, c->pb_tmp, c->pb_row0);
+
     hipLaunchKernelGGL(k_pb_count, dim3(chunks), dim3(kBlock), 0, c->stream, num_entries, bits, nbins, ecol, c->pb_upd,
                        c->pb_table);
     unsigned int* seg = c->pb_table + ((size_t)chunks + 1) * nbins;
@@ -954,6 +961,8 @@ bool build_binned(dynlp_ctx* c) {
     hipLaunchKernelGGL(k_pb_offsets, dim3(1), dim3(kBlock), 0, c->stream, nbins, bin_count, bin_off);
     hipLaunchKernelGGL(k_pb_place, dim3(chunks), dim3(kPbPlaceThreads), 0, c->stream, num_entries, bits, nbins,
                        pb_run_lanes(nbins), ecol, c->pb_tmp, c->pb_upd, c->pb_table, bin_off, c->pb_lpos, c->pb_dst, c->pb_wn);
+    hipLaunchKernelGGL(k_pb_pack, dim3(grid_for(c->entries)), dim3(kBlock), 0, c->stream, num_entries, c->pb_src, c->pb_lpos,
+                       c->pb_row0, c->pb_sp, too_wide);
     hipLaunchKernelGGL(k_pb_normalise, dim3(nbins * kPbNormParts), dim3(kBlock), 0, c->stream, bits, bin_off, c->pb_dst,
                        c->deg, c->pb_wn);
     HIPCHK(c, hipGetLastError());
@@ -971,6 +980,8 @@ bool build_binned(dynlp_ctx* c) {
     const int parts = std::max(1, std::min({want_parts, kPbMaxParts, nbins}));
     c->pb_parts = parts;
     std::vector<unsigned int> first_at(parts + 1, 0u);
+    unsigned int wide = 1;
+    HIPCHK(c, hipMemcpyAsync(&wide, too_wide, sizeof wide, hipMemcpyDeviceToHost, c->stream));
     for (int i = 0; i <= parts; ++i) {
         const int b = (int)(((int64_t)nbins * i) / parts);
         c->pb_part_bin[i] = b;
@@ -983,6 +994,7 @@ bool build_binned(dynlp_ctx* c) {
         c->pb_part_chunk[i][1] = (int)std::min<int64_t>(chunks, ceil_div((int64_t)first_at[i + 1], kPbChunk));
         if (first_at[i + 1] == first_at[i]) c->pb_part_chunk[i][1] = c->pb_part_chunk[i][0];  // no entries: nothing to publish
     }
+    c->pb_packed_ok = wide == 0;
     c->pb_built = true;
     return true;
 }
@@ -994,16 +1006,16 @@ void launch_pb_scatter(dynlp_ctx* c, const RoundCtr* prev, int chunk0, int nchun
     const int lg = pb_run_lanes(c->pb_bins);
     const dim3 grid(8 * (unsigned int)std::max<int64_t>(1, ceil_div(nchunks, 8)));
     const unsigned int* bin_off = c->pb_bin + (kPbMaxBins + 1);
-    if (c->pb_bins <= 2048)
-        hipLaunchKernelGGL(k_pb_scatter<2048>, grid, dim3(kPbScatterThreads), 0, c->stream, prev, c->pb_first + c->n,
-                           (unsigned int)chunk0, (unsigned int)std::max(nchunks, 0), c->pb_bins, lg, c->pb_src, c->pb_lpos,
-                           c->pb_table, bin_off, F, bits, bits_also, moved_clear, (unsigned int)c->moved_words, c->pb_val,
-                           ctr_zero);
-    else
-        hipLaunchKernelGGL(k_pb_scatter<kPbMaxBins>, grid, dim3(kPbScatterThreads), 0, c->stream, prev, c->pb_first + c->n,
-                           (unsigned int)chunk0, (unsigned int)std::max(nchunks, 0), c->pb_bins, lg, c->pb_src, c->pb_lpos,
-                           c->pb_table, bin_off, F, bits, bits_also, moved_clear, (unsigned int)c->moved_words, c->pb_val,
-                           ctr_zero);
+#define DYNLP_SCATTER(NB, PACKED, SRC)                                                                                     \
+    hipLaunchKernelGGL((k_pb_scatter<NB, PACKED>), grid, dim3(kPbScatterThreads), 0, c->stream, prev, c->pb_first + c->n,      \
+                       (unsigned int)chunk0, (unsigned int)std::max(nchunks, 0), c->pb_bins, lg, SRC, c->pb_row0, c->pb_lpos,  \
+                       c->pb_table, bin_off, F, bits, bits_also, moved_clear, (unsigned int)c->moved_words, c->pb_val,         \
+                       ctr_zero)
+    if (c->pb_bins <= 2048 && c->pb_packed_ok) DYNLP_SCATTER(2048, true, c->pb_sp);
+    else if (c->pb_bins <= 2048) DYNLP_SCATTER(2048, false, c->pb_src);
+    else if (c->pb_packed_ok) DYNLP_SCATTER(kPbMaxBins, true, c->pb_sp);
+    else DYNLP_SCATTER(kPbMaxBins, false, c->pb_src);
+#undef DYNLP_SCATTER
 }
 
 // One binned round (arguments as for the fused round).  `first_of_stretch`: no binned round has run since the slots
@@ -1250,7 +1262,7 @@ void destroy_ctx(dynlp_ctx* c) {
     void* ptrs[] = {c->meta, c->pool, c->F, c->F2, c->seed_class, c->flag, c->queue[0], c->queue[1], c->queue[2], c->moved[0], c->moved[1], c->moved[2], c->add_cnt,
                     c->deg, c->touched, c->reloc_off, c->he_rank, c->b_eu, c->b_ev, c->b_ew, c->b_sv, c->b_sc,
                     c->cc_par, c->cc_dense, c->cc_comp, c->cc_block, c->cc_kept, c->cc_W,
-                    c->pb_src, c->pb_lpos, c->pb_tmp, c->pb_dst, c->pb_wn, c->pb_val, c->pb_len, c->pb_upd,
+                    c->pb_src, c->pb_sp, c->pb_row0, c->pb_lpos, c->pb_tmp, c->pb_dst, c->pb_wn, c->pb_val, c->pb_len, c->pb_upd,
                     c->pb_first, c->pb_block, c->pb_bin, c->pb_table};
     for (void* p : ptrs) dev_free(c, p);
     const std::vector<void*> left(c->live.begin(), c->live.end());  // arrays an interrupted call never got to free

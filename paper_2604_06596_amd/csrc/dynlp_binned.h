@@ -93,12 +93,13 @@ __global__ void __launch_bounds__(kBlock) k_pb_row_first(int64_t n, const RowMet
     if (v == n - 1) first[n] = block_off[blockIdx.x] + ex + l;
 }
 
-// Entry i of the stream (rows in vertex order): its row, its neighbour and its weight.  16 lanes per row.
+// Entry i of the stream (rows in vertex order): its row, its neighbour and its weight; and for every chunk of the
+// stream the row of its first entry.  16 lanes per row.
 __global__ void __launch_bounds__(kBlock) k_pb_expand(int64_t n, const RowMeta* __restrict__ meta,
                                                      const Edge* __restrict__ pool,
                                                      const unsigned int* __restrict__ first,
                                                      unsigned int* __restrict__ src, unsigned int* __restrict__ ecol,
-                                                     float* __restrict__ ew) {
+                                                     float* __restrict__ ew, unsigned int* __restrict__ chunk_row0) {
     constexpr int G = 16;
     const int gl = threadIdx.x % G;
     const int64_t u = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / G;
@@ -110,7 +111,27 @@ __global__ void __launch_bounds__(kBlock) k_pb_expand(int64_t n, const RowMeta* 
         src[a + j] = (unsigned int)u;
         ecol[a + j] = (unsigned int)e.col;
         ew[a + j] = e.w;
+        if ((a + j) % kPbChunk == 0) chunk_row0[(a + j) / kPbChunk] = (unsigned int)u;
     }
+}
+
+// What the scatter pass reads per entry, in one word: the entry's row as a 16-bit offset from the row of its
+// chunk's first entry (high half) and its position in the sorted chunk (low half): 4 instead of 6 bytes per entry
+// and round, and one load instead of two (two-byte loads alone, row offsets next to positions, were slower than the
+// 32-bit rows: 1.72 against 1.59 ms per round on 250M entries).  A chunk whose 16,384 entries span 65,536 rows or
+// more (long runs of vertices without entries) cannot be written that way: *too_wide is set and the scatter pass
+// reads the 32-bit rows and the positions instead.
+__global__ void __launch_bounds__(kBlock) k_pb_pack(const unsigned int* __restrict__ num_entries,
+                                                   const unsigned int* __restrict__ src,
+                                                   const unsigned short* __restrict__ lpos,
+                                                   const unsigned int* __restrict__ chunk_row0,
+                                                   unsigned int* __restrict__ packed, unsigned int* __restrict__ too_wide) {
+    const int64_t E = (int64_t)*num_entries;
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= E) return;
+    const unsigned int off = src[i] - chunk_row0[i / kPbChunk];
+    packed[i] = (off << 16) | (unsigned int)lpos[i];
+    if (off > 0xffffu) *too_wide = 1u;
 }
 
 // The build step orders a bin's slots by chunk: a table of entry counts per (chunk, bin) is turned into the
@@ -366,11 +387,12 @@ __device__ inline bool pb_round_runs(const RoundCtr* __restrict__ prev) { return
 constexpr int kPbScatterThreads = 1024;  // two workgroups of this size and 64 KB fill a CU (256 / 512 / 1024 threads:
                                          // 2.25 / 1.75 / 1.63 ms per round on 250M entries)
 
-template <int NB>
+template <int NB, bool PACKED>
 __global__ void __launch_bounds__(kPbScatterThreads) k_pb_scatter(const RoundCtr* __restrict__ prev,
                                                       const unsigned int* __restrict__ num_entries, unsigned int chunk0,
                                                       unsigned int chunks, int nbins, int lg_group,
                                                       const unsigned int* __restrict__ src,
+                                                      const unsigned int* __restrict__ chunk_row0,
                                                       const unsigned short* __restrict__ lpos,
                                                       const unsigned int* __restrict__ table,
                                                       const unsigned int* __restrict__ bin_off, const float* F_in,
@@ -416,14 +438,17 @@ __global__ void __launch_bounds__(kPbScatterThreads) k_pb_scatter(const RoundCtr
     const int64_t base = (int64_t)chunk * kPbChunk;
     pb_chunk_runs<T>(nbins, table + (size_t)chunk * nbins, bin_off, loff, first_slot, wave_tot);
     constexpr int UN = 4;
+    // PACKED: src holds (row - row of the chunk's first entry) << 16 | position; else rows in src, positions in lpos
+    const unsigned int row0 = PACKED ? chunk_row0[chunk] : 0u;
     for (int k0 = 0; k0 < kPbChunk; k0 += UN * T) {
         unsigned int u[UN], p[UN];
 #pragma unroll
         for (int q = 0; q < UN; ++q) {
             const int64_t i = base + k0 + q * T + threadIdx.x;
             const bool ok = i < E;
-            u[q] = ok ? src[i] : 0xffffffffu;
-            p[q] = ok ? lpos[i] : 0u;
+            const unsigned int x = ok ? src[i] : 0u;
+            u[q] = ok ? (PACKED ? row0 + (x >> 16) : x) : 0xffffffffu;
+            p[q] = PACKED ? (x & 0xffffu) : (ok ? lpos[i] : 0u);
         }
 #pragma unroll
         for (int q = 0; q < UN; ++q)
@@ -485,7 +510,9 @@ __global__ void __launch_bounds__(kPbGatherThreads) k_pb_gather(const RoundCtr* 
     }
     __syncthreads();
     const unsigned int lo = bin_off[bin], hi = bin_off[bin + 1];
-    constexpr int UN = 4;  // independent slot reads in flight per lane (2 / 4 / 8: 1.74 / 1.71 / 1.72 ms per round)
+    // independent slot reads in flight per lane: 2 / 4 / 8 give 1.74 / 1.71 / 1.72 ms per round; two neighbouring slots
+    // per lane with 4- and 8-byte loads instead of 2- and 4-byte ones: no gain either (1.52 against 1.51 ms)
+    constexpr int UN = 4;
     for (unsigned int i0 = lo; i0 < hi; i0 += UN * T) {
         unsigned int d[UN], x[UN];
         float w[UN];

@@ -186,6 +186,54 @@ def test_binned_rounds_on_tiny_and_ragged_graphs(n, deg, new):
     assert np.max(np.abs(a["soft"] - exact)[reach]) <= O1_ATOL
 
 
+def test_binned_rounds_across_long_runs_of_vertices_without_entries():
+    """Two islands of 400 vertices at the two ends of 180,000 vertex ids, nothing in between: one chunk of entries
+    spans far more than 65,535 rows, so the scatter pass cannot address its senders by 16-bit offsets from the chunk's
+    first row and reads the 32-bit rows instead.  Round by round against the oracle, then to convergence."""
+    rng = np.random.default_rng(5500)
+    n, k = 180_000, 400
+    isl = [np.arange(k), np.arange(n - k, n)]
+    eu, ev = [], []
+    for ids in isl:
+        a, b = rng.integers(0, k, 1400), rng.integers(0, k, 1400)
+        path = rng.permutation(k)
+        eu += [ids[a], ids[path[:-1]]]
+        ev += [ids[b], ids[path[1:]]]
+    eu.append(isl[0][rng.integers(0, k, 6)])
+    ev.append(isl[1][rng.integers(0, k, 6)])
+    eu, ev = np.concatenate(eu), np.concatenate(ev)
+    keep = eu != ev
+    key = np.unique(np.minimum(eu, ev)[keep] * n + np.maximum(eu, ev)[keep])
+    lo, hi = key // n, key % n
+    ew = rng.uniform(0.1, 1.0, lo.shape[0]).astype(np.float32)
+    rp, col, w = W.edges_to_csr(n, lo, hi, ew)
+    sv = np.sort(np.concatenate([rng.choice(isl[0], 20, replace=False), rng.choice(isl[1], 20, replace=False)])).astype(np.int32)
+    sc = (sv >= n // 2).astype(np.int32)
+    p0 = W.Problem(n, 2, rp, col, w, sv, sc, np.zeros(n, np.int32))
+    new = 60
+    bu = np.repeat(np.arange(n, n + new), 4)
+    bv = np.concatenate([rng.choice(np.concatenate(isl), 4, replace=False) for _ in range(new)])
+    b = W.Batch(new, bu.astype(np.int32), bv.astype(np.int32), rng.uniform(0.1, 1.0, bu.shape[0]).astype(np.float32),
+                np.zeros(0, np.int32), np.zeros(0, np.int32))
+    none = np.zeros(0, np.int32)
+    R_ = 12
+    out = _run(p0, b, none, R_, 8)
+    g, rp2, col2, w2, F, A0 = _oracle_after(p0, b, none, out["soft0"])
+    o2 = ON.step3_propagate(rp2, col2, w2, F, g.seed_class, A0, TOL, R_)
+    print("round kinds", out["kinds"], "sizes", out["sizes"].tolist())
+    assert 3 in out["kinds"], "the case is meant to reach binned rounds"
+    assert out["s"].iterations == o2["rounds"] == R_ and out["sizes"].tolist() == o2["frontier_sizes"].tolist()
+    assert np.max(np.abs(out["soft"] - o2["F"])) <= ROUNDS_ATOL
+    assert out["s"].rows_updated == o2["rows_updated"] and out["s"].edges_traversed == o2["edges_traversed"]
+    full = _run(p0, b, none, 20000, 8)
+    assert full["st"] == 0
+    exact, _, _ = ON.itlp_solve(rp2, col2, w2, g.seed_class, 2, tol=1e-12, max_iter=5_000_000)
+    reach = R.seed_reachable(rp2, col2, g.seed_class)
+    cert = Cf.certificate(rp2, col2, w2, g.seed_class, full["soft"])
+    Cf.check_against_exact(full["soft"], exact, 1e-12, cert, "islands, converged")
+    assert np.all(full["soft"][~reach] == np.float32(0.5))
+
+
 @pytest.mark.parametrize("kind", ["random", "hub"])
 def test_static_solve_with_binned_sweeps(kind):
     """The cold start on scalar labels: every sweep after the first is a binned round over all updatable vertices.
