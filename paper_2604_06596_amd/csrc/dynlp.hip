@@ -2153,7 +2153,7 @@ dynlp_status dynlp_apply_update(dynlp_ctx* c, int64_t nd, const int32_t* del, in
             int32_t* long_list = reinterpret_cast<int32_t*>(c->reloc_off);
             hipLaunchKernelGGL(k_sort_finish, dim3(grid_for((int64_t)nt * 16)), dim3(kBlock), 0, c->stream, nt, c->touched,
                                c->meta, c->pool, c->add_cnt, use_rank ? 1 : 0, long_list, c->bc, c->deg, c->flag);
-            hipLaunchKernelGGL(k_sort_long_segments, dim3(std::min<unsigned int>(nt, 512u)), dim3(kBlock), 0, c->stream,
+            hipLaunchKernelGGL(k_sort_long_segments, dim3(std::min<unsigned int>(nt, 512u)), dim3(kSortThreads), 0, c->stream,
                                long_list, c->meta, c->pool, c->add_cnt, c->bc);
             hipLaunchKernelGGL(k_finish_rows, dim3(std::min<unsigned int>(grid_for((int64_t)nt * 16), 512u)), dim3(kBlock), 0,
                                c->stream, long_list, c->bc, c->meta, c->pool, c->add_cnt, c->deg, c->flag);

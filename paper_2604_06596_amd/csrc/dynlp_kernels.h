@@ -492,7 +492,19 @@ __global__ void __launch_bounds__(kBlock) k_sort_finish(unsigned int nt, const i
     }
     const int len_new = len_old + a;
     float s = 0.f;
-    for (int j = gl; j < len_new; j += G) s += j < len_old ? pool[m.off + j].w : sorted_w[grp][j - len_old];
+    // (a row may be a hub of tens of thousands of entries that received a few: several loads in flight, added in order)
+    constexpr int UN = 4;
+    for (int j0 = gl; j0 < len_new; j0 += UN * G) {
+        float wv[UN];
+#pragma unroll
+        for (int q = 0; q < UN; ++q) {
+            const int j = j0 + q * G;
+            wv[q] = j < len_old ? pool[m.off + j].w : (j < len_new ? sorted_w[grp][j - len_old] : 0.f);
+        }
+#pragma unroll
+        for (int q = 0; q < UN; ++q)
+            if (j0 + q * G < len_new) s += wv[q];
+    }
 #pragma unroll
     for (int d = G / 2; d > 0; d >>= 1) s += __shfl_xor(s, d, G);
     if (gl == 0) {
@@ -503,35 +515,99 @@ __global__ void __launch_bounds__(kBlock) k_sort_finish(unsigned int nt, const i
     }
 }
 
-// Long appended segments: one workgroup per row sorts the segment in place with a bitonic network
-// whose compare-exchanges all point the same way (the first step of every merge pairs i with its
-// mirror image inside the block), so positions past the end act as +infinity without being stored.
-__global__ void __launch_bounds__(kBlock) k_sort_long_segments(const int32_t* __restrict__ long_list,
-                                                              const RowMeta* __restrict__ meta, Edge* pool,
-                                                              const int32_t* __restrict__ add_cnt,
-                                                              const BatchCtr* bc) {
+// Long appended segments: one workgroup of kSortThreads per row sorts the segment with a bitonic network whose
+// compare-exchanges all point the same way (the first step of every merge pairs i with its mirror image inside
+// the block), so positions past the end act as +infinity.  The network runs on tiles of kSortTile keys in LDS:
+// a segment of one tile (a power-law hub that receives a few thousand entries from one batch) never goes to memory
+// in between; a longer one (a new hub vertex arriving with tens of thousands of entries) is first sorted tile by
+// tile, and of every later merge only the steps whose partners lie in different tiles run in memory (6 of 136 steps
+// for 50,000 entries), UN disjoint pairs in flight per lane.
+constexpr int kSortThreads = 1024;
+constexpr int kSortTile = 8192;
+
+// steps j = j_first, j_first / 2, ..., 1 of the network on the first `len` positions (a power of two) of a tile held
+// in LDS; mirror: the first of them pairs i with its mirror image inside blocks of 2 * j_first
+__device__ inline void sort_tile_steps(unsigned long long* keys, unsigned int len, unsigned int j_first, bool mirror) {
+    for (unsigned int j = j_first; j > 0; j >>= 1) {
+        const unsigned int mask = (mirror && j == j_first) ? (2 * j_first - 1) : j;
+        for (unsigned int i = threadIdx.x; i < len; i += kSortThreads) {
+            const unsigned int l = i ^ mask;
+            if (l > i) {
+                const unsigned long long x = keys[i], y = keys[l];
+                if (y < x) {
+                    keys[i] = y;
+                    keys[l] = x;
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+__global__ void __launch_bounds__(kSortThreads) k_sort_long_segments(const int32_t* __restrict__ long_list,
+                                                                    const RowMeta* __restrict__ meta, Edge* pool,
+                                                                    const int32_t* __restrict__ add_cnt,
+                                                                    const BatchCtr* bc) {
+    __shared__ unsigned long long keys[kSortTile];
+    constexpr unsigned int T = kSortTile;
     const unsigned int count = bc->sort_long;
     for (unsigned int q = blockIdx.x; q < count; q += gridDim.x) {  // uniform per workgroup
         const int32_t u = long_list[q];
-        const int a = add_cnt[u];
+        const unsigned int a = (unsigned int)add_cnt[u];
         const RowMeta m = meta[u];
-        Edge* seg = pool + m.off + (m.len - a);
-        unsigned int P = 1;
-        while (P < (unsigned int)a) P <<= 1;
-        for (unsigned int k = 2; k <= P; k <<= 1) {
-            for (unsigned int j = k >> 1; j > 0; j >>= 1) {
+        Edge* seg = pool + m.off + (m.len - (int)a);
+        unsigned int P = 2;
+        while (P < a) P <<= 1;
+        const unsigned int L = P < T ? P : T;  // positions of a tile the network works on (all of it from T keys on)
+        const unsigned int tiles = (a + T - 1) / T;
+        auto load_tile = [&](unsigned int t) {
+            for (unsigned int i = threadIdx.x; i < L; i += kSortThreads)
+                keys[i] = t * T + i < a ? edge_key(seg[t * T + i]) : ~0ull;
+            __syncthreads();
+        };
+        auto store_tile = [&](unsigned int t) {
+            for (unsigned int i = threadIdx.x; i < L; i += kSortThreads)
+                if (t * T + i < a) seg[t * T + i] = key_edge(keys[i]);
+            __syncthreads();
+        };
+        // every tile on its own: merges of blocks of 2, 4, ..., L keys
+        for (unsigned int t = 0; t < tiles; ++t) {
+            load_tile(t);
+            for (unsigned int k = 2; k <= L; k <<= 1) sort_tile_steps(keys, L, k >> 1, true);
+            store_tile(t);
+        }
+        // merges of blocks of 2T, 4T, ..., P keys: partners in different tiles meet in memory, the rest in LDS
+        for (unsigned int k = 2 * T; k <= P; k <<= 1) {
+            for (unsigned int j = k >> 1; j >= T; j >>= 1) {
                 const unsigned int mask = (j == (k >> 1)) ? (k - 1) : j;
-                for (unsigned int i = threadIdx.x; i < (unsigned int)a; i += kBlock) {
-                    const unsigned int l = i ^ mask;
-                    if (l > i && l < (unsigned int)a) {
-                        const Edge x = seg[i], y = seg[l];
-                        if (edge_key(y) < edge_key(x)) {
-                            seg[i] = y;
-                            seg[l] = x;
+                constexpr int UN = 8;
+                for (unsigned int i0 = threadIdx.x; i0 < a; i0 += UN * kSortThreads) {
+                    Edge x[UN], y[UN];
+                    bool pair[UN];
+#pragma unroll
+                    for (int r = 0; r < UN; ++r) {
+                        const unsigned int i = i0 + r * kSortThreads, l = i ^ mask;
+                        pair[r] = i < a && l > i && l < a;
+                        if (pair[r]) {
+                            x[r] = seg[i];
+                            y[r] = seg[l];
+                        }
+                    }
+#pragma unroll
+                    for (int r = 0; r < UN; ++r) {
+                        const unsigned int i = i0 + r * kSortThreads, l = i ^ mask;
+                        if (pair[r] && edge_key(y[r]) < edge_key(x[r])) {
+                            seg[i] = y[r];
+                            seg[l] = x[r];
                         }
                     }
                 }
                 __syncthreads();
+            }
+            for (unsigned int t = 0; t < tiles; ++t) {
+                load_tile(t);
+                sort_tile_steps(keys, T, T >> 1, false);
+                store_tile(t);
             }
         }
     }
@@ -550,7 +626,16 @@ __global__ void __launch_bounds__(kBlock) k_finish_rows(const int32_t* __restric
         const int32_t u = list[t];
         const RowMeta m = meta[u];
         float s = 0.f;
-        for (int j = gl; j < m.len; j += G) s += pool[m.off + j].w;
+        // these are hub rows of up to tens of thousands of entries: 8 loads in flight per lane, added in order
+        constexpr int UN = 8;
+        for (int j0 = gl; j0 < m.len; j0 += UN * G) {
+            float wv[UN];
+#pragma unroll
+            for (int q = 0; q < UN; ++q) wv[q] = j0 + q * G < m.len ? pool[m.off + j0 + q * G].w : 0.f;
+#pragma unroll
+            for (int q = 0; q < UN; ++q)
+                if (j0 + q * G < m.len) s += wv[q];
+        }
 #pragma unroll
         for (int d = G / 2; d > 0; d >>= 1) s += __shfl_xor(s, d, G);
         if (gl == 0) {

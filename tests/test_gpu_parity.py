@@ -134,6 +134,43 @@ def test_hub_row_receives_many_edges_in_one_batch():
         _check_graph_equals_oracle(d, g)
 
 
+def test_rows_that_receive_tens_of_thousands_of_entries_in_one_batch():
+    """A new hub vertex arriving with 40,001 edges, another with 9,000, an existing vertex that receives 12,345 and
+    one that receives 8,192: appended segments of several sorting tiles, of exactly one tile, and of a ragged tile.
+    Stored rows against the oracle's graph; every appended segment must come out in ascending (neighbour, weight)
+    order; a second, identical context must store identical rows."""
+    n0 = 60_000
+    p = W.small_random(n0, 3, 4.0, 600, 31)
+    g = _oracle_graph(p)
+    rng = np.random.default_rng(77)
+    old_len = np.diff(p.row_ptr)
+    parts = []
+    for src, cnt in ((n0, 40_001), (n0 + 1, 9_000), (11, 12_345), (12, 8_192)):
+        dst = rng.choice(np.setdiff1d(np.arange(n0), [11, 12]), size=cnt, replace=False)
+        parts.append((np.full(cnt, src), dst))
+    eu = np.concatenate([a for a, _ in parts]).astype(np.int32)
+    ev = np.concatenate([b for _, b in parts]).astype(np.int32)
+    ew = rng.uniform(0.1, 1.0, eu.shape[0]).astype(np.float32)
+    order = rng.permutation(eu.shape[0])  # the batch lists its edges in no particular order
+    eu, ev, ew = eu[order], ev[order], ew[order]
+    g.insert(2, eu, ev, ew, [], [])
+    exports = []
+    for _ in range(2):
+        with _make(p) as d:
+            d.set_params(1e-3, 2)
+            st, s = d.apply_batch(2, eu, ev, ew)
+            _check_graph_equals_oracle(d, g)
+            exports.append(d.export_graph())
+    rp, col, w = exports[0][:3]
+    for u, first in ((n0, 0), (n0 + 1, 0), (11, int(old_len[11])), (12, int(old_len[12]))):
+        seg_c = col[rp[u] + first:rp[u + 1]].astype(np.int64)
+        seg_w = w[rp[u] + first:rp[u + 1]].view(np.uint32).astype(np.int64)
+        key = seg_c * (1 << 32) + seg_w
+        assert np.all(np.diff(key) > 0), f"row {u}: appended entries out of order"
+    for x, y in zip(exports[0], exports[1]):
+        assert np.array_equal(x, y)
+
+
 # ---------------------------------------------------------------------------------------------
 # row update: one sweep, static solve
 # ---------------------------------------------------------------------------------------------
