@@ -741,22 +741,38 @@ __global__ void __launch_bounds__(kBlock) k_drop_deleted_entries(unsigned int nt
     const int32_t v = touched[t];
     const RowMeta m = meta[v];
     int out = 0;
-    for (int base = 0; base < m.len; base += G) {
-        const int j = base + gl;
-        Edge e;
-        e.col = 0;
-        e.w = 0.f;
-        bool keep = false;
-        if (j < m.len) {
-            e = pool[m.off + j];
-            keep = seed_class[e.col] != kDeletedMark;
+    // UN chunks of G entries per step (the row may be a hub of tens of thousands of entries): their loads and the
+    // lookups of their neighbours are in flight together; the kept ones are written in order, always to positions
+    // that lie before everything the step has read
+    constexpr int UN = 4;
+    for (int base = 0; base < m.len; base += UN * G) {
+        Edge e[UN];
+        bool keep[UN];
+#pragma unroll
+        for (int q = 0; q < UN; ++q) {
+            const int j = base + q * G + gl;
+            e[q].col = 0;
+            e[q].w = 0.f;
+            if (j < m.len) e[q] = pool[m.off + j];
         }
-        const unsigned int mask = (unsigned int)((__ballot(keep) >> gshift) & 0xffffull);
-        if (keep) pool[m.off + out + __popc(mask & ((1u << gl) - 1u))] = e;
-        out += __popc(mask);
+#pragma unroll
+        for (int q = 0; q < UN; ++q) keep[q] = base + q * G + gl < m.len && seed_class[e[q].col] != kDeletedMark;
+#pragma unroll
+        for (int q = 0; q < UN; ++q) {
+            const unsigned int mask = (unsigned int)((__ballot(keep[q]) >> gshift) & 0xffffull);
+            if (keep[q]) pool[m.off + out + __popc(mask & ((1u << gl) - 1u))] = e[q];
+            out += __popc(mask);
+        }
     }
     float s = 0.f;
-    for (int j = gl; j < out; j += G) s += pool[m.off + j].w;
+    for (int j0 = gl; j0 < out; j0 += 8 * G) {  // the same order of additions as k_sort_finish / k_finish_rows
+        float wv[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) wv[q] = j0 + q * G < out ? pool[m.off + j0 + q * G].w : 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (j0 + q * G < out) s += wv[q];
+    }
 #pragma unroll
     for (int d = G / 2; d > 0; d >>= 1) s += __shfl_xor(s, d, G);
     if (gl == 0) {
